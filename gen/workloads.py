@@ -1,0 +1,232 @@
+"""Seeded generators for Criteo-shaped embedding workloads.
+
+The paper trains on Criteo Kaggle and Criteo Terabyte (its experiments
+section; model shapes in its model-architecture table: 26 tables, at most
+about 10 M rows per table, embedding width 16 or 64).  Neither dataset is
+available here, so these generators stand in for them: same table count, same
+widths, a comparable spread of table sizes (3 rows up to 10 M rows), totals
+chosen so that the fp32 model sizes match the paper's 2.16 GB / 12.58 GB, and
+power-law (Zipf) row popularity as in click logs.
+
+Everything is a pure function of (config, seed, batch number); all draws use
+``numpy.random.Generator(PCG64(SeedSequence([...])))`` so that any piece can be
+regenerated independently and in parallel.  No quantisation, pooling,
+deduplication or update arithmetic lives here.
+"""
+from __future__ import annotations
+
+import math
+from concurrent.futures import ThreadPoolExecutor
+from dataclasses import dataclass, field
+from typing import Dict, Optional, Tuple
+
+import numpy as np
+
+# name -> shape of the workload.  ``rows`` is the total over tables.
+CONFIGS: Dict[str, dict] = {
+    # 4 tables x 1000 rows x dim 16, batch 128, uniform indices
+    "tiny": dict(T=4, D=16, B=128, alpha=None, rows=4000, fixed_card=1000, seed=1001),
+    # 1 table, 1 M rows x dim 16, batch 2048, Zipf 1.05
+    "single": dict(T=1, D=16, B=2048, alpha=1.05, rows=1_000_000, fixed_card=1_000_000, seed=1002),
+    # Kaggle-shaped: 26 tables, ~33.77 M rows (2.161 GB fp32), dim 16, batch 2048
+    "kaggle": dict(T=26, D=16, B=2048, alpha=1.05, rows=33_770_000, fixed_card=None, seed=1003),
+    # Terabyte-shaped: 26 tables, ~49.12 M rows (12.575 GB fp32), dim 64, batch 8192
+    "terabyte": dict(T=26, D=64, B=8192, alpha=1.1, rows=49_120_000, fixed_card=None, seed=1004),
+}
+
+CARD_MIN = 3
+CARD_MAX = 10_000_000
+
+_STREAM_CARDS, _STREAM_TABLE, _STREAM_MAP, _STREAM_BATCH, _STREAM_GRAD = 1, 2, 3, 4, 5
+
+
+def _rng(*key: int) -> np.random.Generator:
+    return np.random.Generator(np.random.PCG64(np.random.SeedSequence(list(key))))
+
+
+def cardinalities(T: int, total_rows: int, seed: int) -> np.ndarray:
+    """Table sizes: log-uniform in [3, 1e7], rescaled to ``total_rows`` with a cap.
+
+    Tables that hit the cap stay there; the others are scaled by a common
+    factor until the total matches, then rounded, and the rounding residue is
+    absorbed by the largest uncapped table.
+    """
+    rng = _rng(seed, _STREAM_CARDS)
+    c = np.exp(rng.uniform(math.log(CARD_MIN), math.log(CARD_MAX), size=T))
+    for _ in range(64):
+        c = np.clip(c, CARD_MIN, CARD_MAX)
+        free = c < CARD_MAX
+        need = total_rows - c[~free].sum()
+        have = c[free].sum()
+        if have <= 0 or abs(c.sum() - total_rows) < 0.5:
+            break
+        c[free] *= need / have
+    cards = np.clip(np.rint(c), CARD_MIN, CARD_MAX).astype(np.int64)
+    free_idx = np.flatnonzero(cards < CARD_MAX)
+    if free_idx.size:
+        j = free_idx[np.argmax(cards[free_idx])]
+        cards[j] = min(CARD_MAX, max(CARD_MIN, cards[j] + (total_rows - int(cards.sum()))))
+    return cards
+
+
+def _fill_table(out: np.ndarray, rows: int, seed: int, t: int, chunk_rows: int = 1 << 18) -> None:
+    """U(-1/sqrt(rows), +1/sqrt(rows)) in fp32, written in place (the paper
+    says tables start from a uniform initialisation; the bound is the usual
+    embedding-table one)."""
+    rng = _rng(seed, _STREAM_TABLE, t)
+    bound = np.float32(1.0 / math.sqrt(rows))
+    D = out.shape[1]
+    for r0 in range(0, rows, chunk_rows):
+        r1 = min(rows, r0 + chunk_rows)
+        u = rng.random((r1 - r0, D), dtype=np.float32)
+        np.multiply(u, np.float32(2.0), out=u)
+        np.subtract(u, np.float32(1.0), out=u)
+        np.multiply(u, bound, out=out[r0:r1])
+
+
+def make_tables(cards: np.ndarray, D: int, seed: int, threads: int = 8,
+                out: Optional[np.ndarray] = None) -> np.ndarray:
+    """All tables concatenated, [sum(cards), D] fp32, row-major."""
+    R = int(cards.sum())
+    if out is None:
+        out = np.empty((R, D), dtype=np.float32)
+    offs = np.concatenate([[0], np.cumsum(cards)])
+    jobs = [(out[offs[t]:offs[t + 1]], int(cards[t]), seed, t) for t in range(len(cards))]
+    if threads <= 1:
+        for j in jobs:
+            _fill_table(*j)
+    else:
+        with ThreadPoolExecutor(max_workers=threads) as ex:
+            list(ex.map(lambda j: _fill_table(*j), jobs))
+    return out
+
+
+def _coprime_multiplier(rows: int, rng: np.random.Generator) -> int:
+    if rows <= 2:
+        return 1
+    a = int(rng.integers(1, rows))
+    while math.gcd(a, rows) != 1:
+        a += 1
+        if a >= rows:
+            a = 1
+    return a
+
+
+@dataclass
+class Workload:
+    name: str
+    T: int
+    D: int
+    B: int
+    alpha: Optional[float]
+    seed: int
+    cards: np.ndarray
+    row_offsets: np.ndarray = field(init=False)
+    _cdf: dict = field(default_factory=dict, repr=False)
+    _map: dict = field(default_factory=dict, repr=False)
+
+    def __post_init__(self) -> None:
+        self.cards = np.asarray(self.cards, dtype=np.int64)
+        self.row_offsets = np.concatenate([[0], np.cumsum(self.cards)]).astype(np.int64)
+
+    @property
+    def R(self) -> int:
+        return int(self.row_offsets[-1])
+
+    def tables(self, threads: int = 8) -> np.ndarray:
+        return make_tables(self.cards, self.D, self.seed, threads=threads)
+
+    # ---- index batches -------------------------------------------------
+    def _zipf_cdf(self, t: int) -> np.ndarray:
+        cdf = self._cdf.get(t)
+        if cdf is None:
+            rows = int(self.cards[t])
+            w = np.arange(1, rows + 1, dtype=np.float64) ** (-float(self.alpha))
+            cdf = np.cumsum(w)
+            cdf /= cdf[-1]
+            self._cdf[t] = cdf
+        return cdf
+
+    def _rank_to_row(self, t: int) -> Tuple[int, int]:
+        ab = self._map.get(t)
+        if ab is None:
+            rows = int(self.cards[t])
+            rng = _rng(self.seed, _STREAM_MAP, t)
+            a = _coprime_multiplier(rows, rng)
+            b = int(rng.integers(0, rows))
+            ab = (a, b)
+            self._map[t] = ab
+        return ab
+
+    def _draw_rows(self, t: int, n: int, rng: np.random.Generator) -> np.ndarray:
+        rows = int(self.cards[t])
+        if self.alpha is None:
+            return rng.integers(0, rows, size=n, dtype=np.int64)
+        cdf = self._zipf_cdf(t)
+        k = np.searchsorted(cdf, rng.random(n), side="right")
+        k = np.minimum(k, rows - 1).astype(np.int64)  # rank-1 in [0, rows)
+        a, b = self._rank_to_row(t)
+        return (a * k + b) % rows
+
+    def batch(self, k: int, pooling: str = "one", max_len: int = 4) -> Tuple[np.ndarray, np.ndarray]:
+        """Batch number ``k``: ``(indices [N] int64 table-major, offsets [T*B+1] int64)``.
+
+        ``pooling="one"``: exactly one index per bag (all of the paper-shaped
+        configs).  ``pooling="ragged"``: bag lengths uniform in [0, max_len],
+        so empty bags and uneven bags occur.
+        """
+        rng = _rng(self.seed, _STREAM_BATCH, k)
+        T, B = self.T, self.B
+        if pooling == "one":
+            lens = np.ones(T * B, dtype=np.int64)
+        elif pooling == "ragged":
+            lens = rng.integers(0, max_len + 1, size=T * B, dtype=np.int64)
+        else:
+            raise ValueError(pooling)
+        offsets = np.concatenate([[0], np.cumsum(lens)]).astype(np.int64)
+        parts = []
+        for t in range(T):
+            n_t = int(offsets[(t + 1) * B] - offsets[t * B])
+            parts.append(self._draw_rows(t, n_t, rng))
+        indices = np.concatenate(parts) if parts else np.empty(0, np.int64)
+        return np.ascontiguousarray(indices, dtype=np.int64), offsets
+
+    # ---- upstream gradients -------------------------------------------
+    def grad_dyadic(self, k: int) -> np.ndarray:
+        return grad_dyadic(self.B, self.T, self.D, self.seed, k)
+
+    def grad_normal(self, k: int) -> np.ndarray:
+        return grad_normal(self.B, self.T, self.D, self.seed, k)
+
+
+def make_workload(name: str, **override) -> Workload:
+    cfg = dict(CONFIGS[name])
+    cfg.update(override)
+    T = cfg["T"]
+    if cfg.get("fixed_card"):
+        cards = np.full(T, cfg["fixed_card"], dtype=np.int64)
+    else:
+        cards = cardinalities(T, cfg["rows"], cfg["seed"])
+    return Workload(name=name, T=T, D=cfg["D"], B=cfg["B"], alpha=cfg["alpha"], seed=cfg["seed"], cards=cards)
+
+
+def index_batch(wl: Workload, k: int, **kw):
+    return wl.batch(k, **kw)
+
+
+def grad_dyadic(B: int, T: int, D: int, seed: int, k: int) -> np.ndarray:
+    """Gradient w.r.t. the pooled output, [B, T, D] fp32, on the grid m * 2^-24
+    with integer m uniform in [-1024, 1024].  Any sum of at most 8192 such
+    values is exactly representable in fp32, so every summation order gives
+    the same bits and the sum has an integer closed form."""
+    rng = _rng(seed, _STREAM_GRAD, 0, k)
+    m = rng.integers(-1024, 1025, size=(B, T, D), dtype=np.int32)
+    return (m.astype(np.float32) * np.float32(2.0 ** -24)).astype(np.float32)
+
+
+def grad_normal(B: int, T: int, D: int, seed: int, k: int) -> np.ndarray:
+    """Gradient w.r.t. the pooled output, [B, T, D] fp32, N(0, 1e-4^2)."""
+    rng = _rng(seed, _STREAM_GRAD, 1, k)
+    g = rng.standard_normal(size=(B, T, D), dtype=np.float32)
+    g *= np.float32(1e-4)
+    return g

@@ -1,0 +1,142 @@
+"""ctypes front end of the CPU oracle (``dqrm_oracle.c``).
+
+TEST INFRASTRUCTURE ONLY: imported by ``tests/``, by the smoke check and by the
+benchmark's ``cpu_baseline`` leg.  The product package never imports this.
+All arrays are host numpy arrays; nothing here touches a GPU.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+import subprocess
+from typing import Optional, Tuple
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "dqrm_oracle.c")
+_LIB = os.path.join(_HERE, "libdqrm_oracle.so")
+_lib: Optional[C.CDLL] = None
+
+
+def build(force: bool = False) -> str:
+    """Compile the oracle with gcc (one rounding per operation: no contraction)."""
+    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+        cmd = ["gcc", "-O2", "-ffp-contract=off", "-fno-fast-math", "-std=c11", "-shared", "-fPIC",
+               "-o", _LIB, _SRC, "-lm"]
+        subprocess.run(cmd, check=True)
+    return _LIB
+
+
+def _p(a: Optional[np.ndarray], ct):
+    if a is None:
+        return None
+    assert a.flags["C_CONTIGUOUS"], "oracle arrays must be contiguous"
+    return a.ctypes.data_as(C.POINTER(ct))
+
+
+def lib() -> C.CDLL:
+    global _lib
+    if _lib is None:
+        _lib = C.CDLL(build())
+        _lib.oracle_quantize_code.restype = C.c_int
+        _lib.oracle_quantize_code.argtypes = [C.c_float, C.c_float, C.c_int]
+        _lib.oracle_scale_from_absmax.restype = C.c_float
+        _lib.oracle_scale_from_absmax.argtypes = [C.c_float, C.c_int]
+        _lib.oracle_seg_chunk.restype = C.c_int
+        _lib.oracle_embbag_bwd.restype = C.c_int64
+    return _lib
+
+
+def quantize_code(x: float, scale: float, bits: int) -> int:
+    return int(lib().oracle_quantize_code(x, scale, bits))
+
+
+def scale_from_absmax(absmax: float, bits: int) -> float:
+    return float(lib().oracle_scale_from_absmax(absmax, bits))
+
+
+def seg_chunk() -> int:
+    return int(lib().oracle_seg_chunk())
+
+
+def find_scale(W: np.ndarray, row_offsets: np.ndarray) -> np.ndarray:
+    T = len(row_offsets) - 1
+    D = W.shape[1]
+    s = np.empty(T, np.float32)
+    lib().oracle_find_scale(_p(W, C.c_float), _p(row_offsets, C.c_int64), C.c_int(T), C.c_int(D),
+                            _p(s, C.c_float))
+    return s
+
+
+def pack_int4(W: np.ndarray, row_offsets: np.ndarray, w_scale: np.ndarray) -> np.ndarray:
+    T = len(row_offsets) - 1
+    R, D = W.shape
+    packed = np.empty((R, D // 2), np.uint8)
+    lib().oracle_pack_int4(_p(W, C.c_float), _p(row_offsets, C.c_int64), C.c_int(T), C.c_int(D),
+                           _p(w_scale, C.c_float), _p(packed, C.c_uint8))
+    return packed
+
+
+def unpack_int4(packed: np.ndarray) -> np.ndarray:
+    R, half = packed.shape
+    codes = np.empty((R, 2 * half), np.int8)
+    lib().oracle_unpack_int4(_p(packed, C.c_uint8), C.c_int64(R), C.c_int(2 * half), _p(codes, C.c_int8))
+    return codes
+
+
+def embbag_fwd(W: Optional[np.ndarray], packed: Optional[np.ndarray], row_offsets: np.ndarray,
+               w_scale: Optional[np.ndarray], B: int, indices: np.ndarray, offsets: np.ndarray,
+               mode: int = 0, quantise: bool = True, want_codes: bool = True
+               ) -> Tuple[np.ndarray, Optional[np.ndarray]]:
+    T = len(row_offsets) - 1
+    D = W.shape[1] if W is not None else packed.shape[1] * 2
+    N = len(indices)
+    out = np.empty((B, T, D), np.float32)
+    codes = np.zeros((N, D), np.int8) if want_codes else None
+    lib().oracle_embbag_fwd(_p(W, C.c_float), _p(packed, C.c_uint8), _p(row_offsets, C.c_int64),
+                            _p(w_scale, C.c_float), C.c_int(T), C.c_int(D), C.c_int(B),
+                            _p(indices, C.c_int64), _p(offsets, C.c_int64), C.c_int(mode),
+                            C.c_int(1 if quantise else 0), _p(out, C.c_float), _p(codes, C.c_int8))
+    return out, codes
+
+
+def embbag_bwd(T: int, D: int, B: int, indices: np.ndarray, offsets: np.ndarray, grad_out: np.ndarray):
+    """Returns dict with sorted_pos, uniq_rows, seg_offsets, table_uniq_offsets, values, g_absmax, U
+    (arrays trimmed to U)."""
+    N = len(indices)
+    sorted_pos = np.empty(N, np.int32)
+    uniq_rows = np.empty(max(N, 1), np.int64)
+    seg_offsets = np.empty(N + 1, np.int32)
+    tuo = np.empty(T + 1, np.int32)
+    values = np.empty((max(N, 1), D), np.float32)
+    g_absmax = np.empty(T, np.float32)
+    U = lib().oracle_embbag_bwd(C.c_int(T), C.c_int(D), C.c_int(B), _p(indices, C.c_int64),
+                                _p(offsets, C.c_int64), _p(grad_out, C.c_float), _p(sorted_pos, C.c_int32),
+                                _p(uniq_rows, C.c_int64), _p(seg_offsets, C.c_int32), _p(tuo, C.c_int32),
+                                _p(values, C.c_float), _p(g_absmax, C.c_float))
+    U = int(U)
+    return dict(U=U, sorted_pos=sorted_pos, uniq_rows=uniq_rows[:U].copy(), seg_offsets=seg_offsets[:U + 1].copy(),
+                table_uniq_offsets=tuo, values=values[:U].copy(), g_absmax=g_absmax)
+
+
+def grad_quant_int8(T: int, D: int, values: np.ndarray, table_uniq_offsets: np.ndarray, g_absmax: np.ndarray):
+    U = values.shape[0]
+    gq = np.empty((max(U, 1), D), np.int8)
+    g_scale = np.empty(T, np.float32)
+    lib().oracle_grad_quant_int8(C.c_int(T), C.c_int(D), _p(values, C.c_float), _p(table_uniq_offsets, C.c_int32),
+                                 _p(g_absmax, C.c_float), _p(gq, C.c_int8), _p(g_scale, C.c_float))
+    return gq[:U], g_scale
+
+
+def sparse_update(W: np.ndarray, packed: Optional[np.ndarray], row_offsets: np.ndarray, w_scale: np.ndarray,
+                  uniq_rows: np.ndarray, table_uniq_offsets: np.ndarray, gq: np.ndarray, g_scale: np.ndarray,
+                  lr: float) -> None:
+    """In place on W (and packed)."""
+    T = len(row_offsets) - 1
+    D = W.shape[1]
+    gq = np.ascontiguousarray(gq)
+    lib().oracle_sparse_update(_p(W, C.c_float), _p(packed, C.c_uint8), _p(row_offsets, C.c_int64),
+                               _p(w_scale, C.c_float), C.c_int(T), C.c_int(D), _p(uniq_rows, C.c_int64),
+                               _p(table_uniq_offsets, C.c_int32), _p(gq, C.c_int8), _p(g_scale, C.c_float),
+                               C.c_float(lr))

@@ -1,0 +1,171 @@
+/*
+ * dqrm.h -- C ABI of the MI355X (gfx950) library for the embedding-table hot path
+ * of DQRM (arXiv 2410.20046): quantisation-aware training of DLRM embedding
+ * tables with INT4 weights and INT8 sparse gradients.
+ *
+ * One training step of the path, in call order:
+ *
+ *   dqrm_find_scale      every P steps   per-table weight scale      (Sec. 3.2)
+ *   dqrm_pack_int4       after the above packed INT4 mirror          (Sec. 4.2, sizes; demo appendix)
+ *   dqrm_embbag_fwd      every step      gather -> INT4 fake-quant -> sum-pool   (Sec. 3.1, Sec. 4.1)
+ *   dqrm_embbag_bwd      every step      dedupe -> segment-sum = sparse gradient (Sec. 4.3, "specified sparsity")
+ *   dqrm_grad_quant_int8 every step      INT8 codes of the gradient values       (Appendix, gradient quantisation)
+ *   dqrm_sparse_update   every step      dequantise + SGD on touched rows        (same appendix)
+ *
+ * Conventions common to every entry point
+ *   - Returns 0 (DQRM_OK) or a negative DQRM_ERR_* code.  Never throws, never aborts.
+ *   - Arguments are validated on the host BEFORE anything is launched; on a
+ *     validation error nothing is enqueued and no buffer is written.
+ *   - Unless a parameter is documented as "host", every pointer is a DEVICE
+ *     pointer owned by the caller.  The library allocates nothing, frees
+ *     nothing, and keeps no pointer after the call returns.
+ *   - `stream` is a hipStream_t passed as void*.  Every call only enqueues work
+ *     on that stream and returns; only dqrm_check_status() synchronises.
+ *   - Data-dependent problems (an index outside its table, offsets that go
+ *     backwards, more lookups in one table than the dedupe kernel holds) cannot
+ *     be seen by the host.  Kernels never act on such data (the lookup is
+ *     skipped, so every access stays inside the caller's buffers); they record
+ *     the first problem in a per-device status word that dqrm_check_status()
+ *     reads and clears.
+ *   - All floating point is IEEE binary32, one rounding per operation (no fused
+ *     multiply-add), true division.
+ *
+ * The quantiser (the paper states "uniform", "one scale per table"; the formula
+ * is this library's reading): scale = max(absmax / (2^(b-1) - 1), 1e-8),
+ * code = clamp(round_half_even(x / scale), -2^(b-1), 2^(b-1) - 1), value =
+ * scale * code; b = 4 for weights, b = 8 for gradients.
+ */
+#ifndef DQRM_H
+#define DQRM_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define DQRM_OK 0
+#define DQRM_ERR_INVALID_ARG (-1)         /* null pointer, negative size, unknown mode */
+#define DQRM_ERR_UNSUPPORTED (-2)         /* dim, table count or table size outside the limits below */
+#define DQRM_ERR_WORKSPACE_TOO_SMALL (-3) /* workspace_bytes below dqrm_embbag_bwd_workspace_bytes() */
+#define DQRM_ERR_INDEX_OUT_OF_RANGE (-4)  /* (device status) an index < 0 or >= its table's rows */
+#define DQRM_ERR_HIP (-5)                 /* a HIP runtime call failed; see dqrm_last_hip_error() */
+#define DQRM_ERR_CAPACITY (-6)            /* (device status) one table has > DQRM_MAX_TABLE_LOOKUPS lookups in a batch */
+#define DQRM_ERR_BAD_OFFSETS (-7)         /* (device status) offsets decrease or leave [0, num_indices] */
+
+#define DQRM_MAX_DIM 256             /* dim must be a multiple of 8 in [8, 256] */
+#define DQRM_MAX_TABLES 1024
+#define DQRM_MAX_TABLE_ROWS 2147483646LL /* rows of one table */
+#define DQRM_MAX_TABLE_LOOKUPS 16384 /* lookups one table may receive in one batch (dedupe sorts them in LDS) */
+
+/* Order of a segment's floating-point sum (the paper does not fix one; results
+ * must be reproducible bit for bit, because the INT8 scale and codes depend on
+ * the last bit): contributions in ascending lookup position are cut into
+ * consecutive chunks of DQRM_SEG_CHUNK; each chunk is summed left to right
+ * starting from its first element; the chunk sums are summed left to right. */
+#define DQRM_SEG_CHUNK 32
+
+#define DQRM_FWD_MASTER 0 /* forward quantises the fp32 master rows */
+#define DQRM_FWD_PACKED 1 /* forward reads the packed INT4 mirror */
+
+/* The embedding layer.  T tables are stored back to back: table t owns rows
+ * row_offsets[t] .. row_offsets[t+1]-1 of `master` ([R][dim] fp32, row-major)
+ * and of `packed` ([R][dim/2] bytes; byte k of a row = element 2k in bits 0..3,
+ * element 2k+1 in bits 4..7, 4-bit two's complement).  `packed` may be NULL if
+ * no call uses it.  The struct itself is read on the host during the call. */
+typedef struct {
+    int32_t num_tables;              /* T, 1 .. DQRM_MAX_TABLES */
+    int32_t dim;                     /* D */
+    const int64_t *row_offsets_host; /* HOST [T+1], row_offsets[0] = 0, non-decreasing */
+    const int64_t *row_offsets_dev;  /* device copy of the same [T+1] */
+    float *master;                   /* device [R][D] */
+    uint8_t *packed;                 /* device [R][D/2] or NULL */
+    float *w_scale;                  /* device [T] per-table weight scale (the cached scale of Sec. 3.2) */
+} dqrm_tables_t;
+
+/* Sec. 3.2 (find the quantisation scale by traversing the table):
+ * w_scale[t] = max(max|master_t| / 7, 1e-8).  Reads all of `master`. */
+int32_t dqrm_find_scale(const dqrm_tables_t *tables, void *stream);
+
+/* Packed INT4 storage (2 codes per byte: the 8x model-size reduction of the
+ * results tables): re-encodes every row of `master` into `packed` with the
+ * current w_scale.  Requires tables->packed. */
+int32_t dqrm_pack_int4(const dqrm_tables_t *tables, void *stream);
+
+/* Sec. 3.1 + Sec. 4.1: lookup first, quantise only the gathered rows, sum-pool.
+ *   indices [num_indices] int64  table-local row ids, table-major: bags
+ *                                t*batch .. t*batch+batch-1 belong to table t
+ *   offsets [T*batch+1]   int64  bag i = lookups offsets[i] .. offsets[i+1]-1;
+ *                                offsets[0] = 0, offsets[T*batch] = num_indices;
+ *                                empty bags are legal (their output is zero)
+ *   out     [batch][T][D] fp32   out[b][t] = sum over the bag, in lookup order, of
+ *                                w_scale[t] * code
+ *   codes_dbg [num_indices][D] int8 or NULL: the INT4 code of every gathered element
+ *   mode    DQRM_FWD_MASTER: code = quantise(master row);  DQRM_FWD_PACKED: code =
+ *           stored nibble (identical results when `packed` is in sync) */
+int32_t dqrm_embbag_fwd(const dqrm_tables_t *tables, const int64_t *indices, const int64_t *offsets,
+                        int32_t batch, int64_t num_indices, int32_t mode, float *out, int8_t *codes_dbg,
+                        void *stream);
+
+/* Scratch for dqrm_embbag_bwd.  The workspace must be cleared ONCE with
+ * dqrm_workspace_init() after it is allocated (and again after any call that
+ * was aborted); the kernels leave it ready for the next call.  Two calls that
+ * may overlap in time need two workspaces.  Returns 0 for invalid arguments. */
+size_t dqrm_embbag_bwd_workspace_bytes(int32_t num_tables, int32_t dim, int32_t batch, int64_t num_indices);
+int32_t dqrm_workspace_init(void *workspace, size_t workspace_bytes, void *stream);
+
+/* Sec. 4.3 / distributed-training appendix: the table gradient in sparse
+ * (indices, values) form over the touched rows only -- lossless "specified
+ * sparsity", coalesced.  The backward of the quantiser is the identity, so the
+ * gradient of row r of table t is the sum of grad_out[bag(i)] over the lookups
+ * i of table t with indices[i] == r.
+ *   grad_out [batch][T][D] fp32        gradient w.r.t. `out` of the forward
+ *   sorted_pos [num_indices] int32     lookup positions ordered by (table, row, position)
+ *   uniq_rows  [num_indices] int64     first U entries: table-local row of each segment,
+ *                                      ascending inside a table, tables in order
+ *   seg_offsets [num_indices+1] int32  first U+1 entries: start of each segment in
+ *                                      sorted_pos; seg_offsets[U] = num_indices
+ *   table_uniq_offsets [T+1] int32     table t's segments are [tuo[t], tuo[t+1])
+ *   num_unique [1] int32               U (stays on the device: the following calls read it there)
+ *   values [num_indices][D] fp32       first U rows: the summed row gradients (order: DQRM_SEG_CHUNK)
+ *   g_absmax [T] fp32                  max |values| over the table's segments, 0 if none
+ * Entries past U (U+1) of the capacity-sized outputs are left untouched. */
+int32_t dqrm_embbag_bwd(const dqrm_tables_t *tables, const int64_t *indices, const int64_t *offsets,
+                        int32_t batch, int64_t num_indices, const float *grad_out, int32_t *sorted_pos,
+                        int64_t *uniq_rows, int32_t *seg_offsets, int32_t *table_uniq_offsets,
+                        int32_t *num_unique, float *values, float *g_absmax, void *workspace,
+                        size_t workspace_bytes, void *stream);
+
+/* Distributed-training appendix (only the values of the sparse gradient are
+ * quantised; the indices are left alone): one scale per table per step,
+ * g_scale[t] = max(g_absmax[t] / 127, 1e-8); gq = clamp(round_half_even(values /
+ * g_scale[t]), -128, 127).  `capacity` = rows allocated in values / gq (>= U). */
+int32_t dqrm_grad_quant_int8(int32_t num_tables, int32_t dim, int64_t capacity, const float *values,
+                             const int32_t *table_uniq_offsets, const float *g_absmax, int8_t *gq,
+                             float *g_scale, void *stream);
+
+/* Same appendix (dequantise, then the local parameter update): for every
+ * segment u of table t, master[row] -= lr * (g_scale[t] * gq[u]) (two
+ * roundings); if tables->packed is not NULL the row's nibbles are re-encoded
+ * from the new master row with the cached w_scale[t]. */
+int32_t dqrm_sparse_update(const dqrm_tables_t *tables, int64_t capacity, const int64_t *uniq_rows,
+                           const int32_t *table_uniq_offsets, const int8_t *gq, const float *g_scale,
+                           float lr, void *stream);
+
+/* Synchronises `stream`, returns the first data-dependent problem recorded on
+ * the current device since the last call (DQRM_OK if none) and clears it.
+ * first_bad_table / first_bad_index (host pointers, may be NULL) receive the
+ * table and the offending value (index value, lookup count or bag number). */
+int32_t dqrm_check_status(void *stream, int32_t *first_bad_table, int64_t *first_bad_index);
+
+/* Text of the last HIP error seen by this thread's DQRM calls ("" if none). */
+const char *dqrm_last_hip_error(void);
+
+/* Library version, "major.minor". */
+const char *dqrm_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* DQRM_H */

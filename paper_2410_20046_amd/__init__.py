@@ -1,0 +1,14 @@
+"""MI355X-native embedding-table hot path of DQRM (arXiv 2410.20046).
+
+The product is the C-ABI library ``libdqrm.so`` (``include/dqrm.h``), built from
+the HIP sources under ``csrc/``.  This package is its thin ctypes binding.
+"""
+from .binding import (  # noqa: F401
+    DqrmError, Tables, StepBuffers, lib, EXPORTS,
+    OK, ERR_INVALID_ARG, ERR_UNSUPPORTED, ERR_WORKSPACE_TOO_SMALL, ERR_INDEX_OUT_OF_RANGE, ERR_HIP, ERR_CAPACITY,
+    ERR_BAD_OFFSETS, FWD_MASTER, FWD_PACKED, SEG_CHUNK, MAX_TABLE_LOOKUPS,
+    dqrm_version, dqrm_find_scale, dqrm_pack_int4, dqrm_embbag_fwd, dqrm_embbag_bwd_workspace_bytes,
+    dqrm_workspace_init, dqrm_embbag_bwd, dqrm_grad_quant_int8, dqrm_sparse_update, dqrm_check_status,
+    dqrm_fwd_bwd_step,
+)
+from .build import build_library  # noqa: F401

@@ -1,0 +1,221 @@
+"""Thin ctypes binding of libdqrm.so: argument marshalling only.
+
+Every function has the name of the C entry point it calls (``include/dqrm.h``)
+and passes device pointers of torch tensors plus the current HIP stream.  No
+step of the path runs in Python or in torch; torch only owns device memory and
+streams.  There is no CPU fallback: if the library is missing, loading raises.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from typing import Optional, Tuple
+
+import numpy as np
+import torch
+
+from . import build as _build
+
+OK = 0
+ERR_INVALID_ARG = -1
+ERR_UNSUPPORTED = -2
+ERR_WORKSPACE_TOO_SMALL = -3
+ERR_INDEX_OUT_OF_RANGE = -4
+ERR_HIP = -5
+ERR_CAPACITY = -6
+ERR_BAD_OFFSETS = -7
+_NAMES = {0: "OK", -1: "INVALID_ARG", -2: "UNSUPPORTED", -3: "WORKSPACE_TOO_SMALL", -4: "INDEX_OUT_OF_RANGE",
+          -5: "HIP_ERROR", -6: "CAPACITY", -7: "BAD_OFFSETS"}
+
+FWD_MASTER = 0
+FWD_PACKED = 1
+SEG_CHUNK = 32
+MAX_TABLE_LOOKUPS = 16384
+
+EXPORTS = ("dqrm_find_scale", "dqrm_pack_int4", "dqrm_embbag_fwd", "dqrm_embbag_bwd_workspace_bytes",
+           "dqrm_workspace_init", "dqrm_embbag_bwd", "dqrm_grad_quant_int8", "dqrm_sparse_update",
+           "dqrm_check_status", "dqrm_last_hip_error", "dqrm_version")
+
+
+class DqrmError(RuntimeError):
+    def __init__(self, code: int, where: str, detail: str = ""):
+        self.code = code
+        super().__init__(f"{where}: DQRM_ERR_{_NAMES.get(code, code)}" + (f" ({detail})" if detail else ""))
+
+
+class dqrm_tables_t(C.Structure):
+    _fields_ = [("num_tables", C.c_int32), ("dim", C.c_int32), ("row_offsets_host", C.c_void_p),
+                ("row_offsets_dev", C.c_void_p), ("master", C.c_void_p), ("packed", C.c_void_p),
+                ("w_scale", C.c_void_p)]
+
+
+_lib: Optional[C.CDLL] = None
+
+
+def lib() -> C.CDLL:
+    """The loaded C-ABI library.  Builds it only if no built library is present."""
+    global _lib
+    if _lib is None:
+        path = _build.LIB
+        if not os.path.exists(path):
+            _build.build_library(force=True)
+        L = C.CDLL(path)
+        vp, i32, i64, sz = C.c_void_p, C.c_int32, C.c_int64, C.c_size_t
+        tp = C.POINTER(dqrm_tables_t)
+        L.dqrm_find_scale.argtypes = [tp, vp]
+        L.dqrm_pack_int4.argtypes = [tp, vp]
+        L.dqrm_embbag_fwd.argtypes = [tp, vp, vp, i32, i64, i32, vp, vp, vp]
+        L.dqrm_embbag_bwd_workspace_bytes.argtypes = [i32, i32, i32, i64]
+        L.dqrm_embbag_bwd_workspace_bytes.restype = sz
+        L.dqrm_workspace_init.argtypes = [vp, sz, vp]
+        L.dqrm_embbag_bwd.argtypes = [tp, vp, vp, i32, i64, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+        L.dqrm_grad_quant_int8.argtypes = [i32, i32, i64, vp, vp, vp, vp, vp, vp]
+        L.dqrm_sparse_update.argtypes = [tp, i64, vp, vp, vp, vp, C.c_float, vp]
+        L.dqrm_check_status.argtypes = [vp, C.POINTER(i32), C.POINTER(i64)]
+        for n in ("dqrm_find_scale", "dqrm_pack_int4", "dqrm_embbag_fwd", "dqrm_workspace_init", "dqrm_embbag_bwd",
+                  "dqrm_grad_quant_int8", "dqrm_sparse_update", "dqrm_check_status"):
+            getattr(L, n).restype = i32
+        L.dqrm_last_hip_error.restype = C.c_char_p
+        L.dqrm_version.restype = C.c_char_p
+        _lib = L
+    return _lib
+
+
+def _ptr(t: Optional[torch.Tensor]) -> Optional[int]:
+    if t is None:
+        return None
+    assert t.is_contiguous(), "DQRM buffers must be contiguous"
+    return t.data_ptr()
+
+
+def _stream(stream) -> Optional[int]:
+    if stream is None:
+        stream = torch.cuda.current_stream()
+    return stream.cuda_stream if hasattr(stream, "cuda_stream") else int(stream)
+
+
+def _check(rc: int, where: str) -> None:
+    if rc != OK:
+        detail = lib().dqrm_last_hip_error().decode() if rc == ERR_HIP else ""
+        raise DqrmError(rc, where, detail)
+
+
+class Tables:
+    """Owns the device buffers of the embedding layer and the C descriptor."""
+
+    def __init__(self, row_offsets: np.ndarray, dim: int, master: torch.Tensor, packed: Optional[torch.Tensor] = None,
+                 w_scale: Optional[torch.Tensor] = None):
+        self.row_offsets_host = np.ascontiguousarray(row_offsets, dtype=np.int64)
+        self.T = len(self.row_offsets_host) - 1
+        self.D = int(dim)
+        self.R = int(self.row_offsets_host[-1])
+        dev = master.device
+        assert master.dtype == torch.float32 and tuple(master.shape) == (self.R, self.D)
+        self.master = master
+        self.packed = packed
+        if packed is not None:
+            assert packed.dtype == torch.uint8 and tuple(packed.shape) == (self.R, self.D // 2)
+        self.w_scale = w_scale if w_scale is not None else torch.ones(self.T, dtype=torch.float32, device=dev)
+        self.row_offsets_dev = torch.from_numpy(self.row_offsets_host).to(dev)
+        self.c = dqrm_tables_t(self.T, self.D, self.row_offsets_host.ctypes.data, _ptr(self.row_offsets_dev),
+                               _ptr(self.master), _ptr(self.packed), _ptr(self.w_scale))
+
+    @property
+    def ref(self):
+        return C.byref(self.c)
+
+
+def dqrm_version() -> str:
+    return lib().dqrm_version().decode()
+
+
+def dqrm_find_scale(tables: Tables, stream=None) -> None:
+    _check(lib().dqrm_find_scale(tables.ref, _stream(stream)), "dqrm_find_scale")
+
+
+def dqrm_pack_int4(tables: Tables, stream=None) -> None:
+    _check(lib().dqrm_pack_int4(tables.ref, _stream(stream)), "dqrm_pack_int4")
+
+
+def dqrm_embbag_fwd(tables: Tables, indices: torch.Tensor, offsets: torch.Tensor, batch: int, mode: int,
+                    out: torch.Tensor, codes_dbg: Optional[torch.Tensor] = None, stream=None) -> None:
+    _check(lib().dqrm_embbag_fwd(tables.ref, _ptr(indices), _ptr(offsets), batch, indices.numel(), mode, _ptr(out),
+                                 _ptr(codes_dbg), _stream(stream)), "dqrm_embbag_fwd")
+
+
+def dqrm_embbag_bwd_workspace_bytes(num_tables: int, dim: int, batch: int, num_indices: int) -> int:
+    return int(lib().dqrm_embbag_bwd_workspace_bytes(num_tables, dim, batch, num_indices))
+
+
+def dqrm_workspace_init(workspace: torch.Tensor, stream=None) -> None:
+    _check(lib().dqrm_workspace_init(_ptr(workspace), workspace.numel() * workspace.element_size(), _stream(stream)),
+           "dqrm_workspace_init")
+
+
+def dqrm_embbag_bwd(tables: Tables, indices: torch.Tensor, offsets: torch.Tensor, batch: int, grad_out: torch.Tensor,
+                    sorted_pos: torch.Tensor, uniq_rows: torch.Tensor, seg_offsets: torch.Tensor,
+                    table_uniq_offsets: torch.Tensor, num_unique: torch.Tensor, values: torch.Tensor,
+                    g_absmax: torch.Tensor, workspace: torch.Tensor, stream=None) -> None:
+    _check(lib().dqrm_embbag_bwd(tables.ref, _ptr(indices), _ptr(offsets), batch, indices.numel(), _ptr(grad_out),
+                                 _ptr(sorted_pos), _ptr(uniq_rows), _ptr(seg_offsets), _ptr(table_uniq_offsets),
+                                 _ptr(num_unique), _ptr(values), _ptr(g_absmax), _ptr(workspace),
+                                 workspace.numel() * workspace.element_size(), _stream(stream)), "dqrm_embbag_bwd")
+
+
+def dqrm_grad_quant_int8(num_tables: int, dim: int, capacity: int, values: torch.Tensor,
+                         table_uniq_offsets: torch.Tensor, g_absmax: torch.Tensor, gq: torch.Tensor,
+                         g_scale: torch.Tensor, stream=None) -> None:
+    _check(lib().dqrm_grad_quant_int8(num_tables, dim, capacity, _ptr(values), _ptr(table_uniq_offsets),
+                                      _ptr(g_absmax), _ptr(gq), _ptr(g_scale), _stream(stream)),
+           "dqrm_grad_quant_int8")
+
+
+def dqrm_sparse_update(tables: Tables, capacity: int, uniq_rows: torch.Tensor, table_uniq_offsets: torch.Tensor,
+                       gq: torch.Tensor, g_scale: torch.Tensor, lr: float, stream=None) -> None:
+    _check(lib().dqrm_sparse_update(tables.ref, capacity, _ptr(uniq_rows), _ptr(table_uniq_offsets), _ptr(gq),
+                                    _ptr(g_scale), lr, _stream(stream)), "dqrm_sparse_update")
+
+
+def dqrm_check_status(stream=None) -> Tuple[int, int, int]:
+    """(code, table, value); code 0 = no data-dependent problem since the last call.  Synchronises."""
+    t, v = C.c_int32(-1), C.c_int64(-1)
+    rc = lib().dqrm_check_status(_stream(stream), C.byref(t), C.byref(v))
+    if rc == ERR_HIP:
+        _check(rc, "dqrm_check_status")
+    return int(rc), int(t.value), int(v.value)
+
+
+class StepBuffers:
+    """Device buffers one training step needs, allocated once (the library itself allocates nothing)."""
+
+    def __init__(self, T: int, D: int, B: int, N: int, device, want_codes: bool = False):
+        cap = max(N, 1)
+        i32, i64, f32 = torch.int32, torch.int64, torch.float32
+        self.T, self.D, self.B, self.N, self.cap = T, D, B, N, cap
+        self.out = torch.empty((B, T, D), dtype=f32, device=device)
+        self.codes = torch.empty((cap, D), dtype=torch.int8, device=device) if want_codes else None
+        self.sorted_pos = torch.empty(cap, dtype=i32, device=device)
+        self.uniq_rows = torch.empty(cap, dtype=i64, device=device)
+        self.seg_offsets = torch.empty(cap + 1, dtype=i32, device=device)
+        self.table_uniq_offsets = torch.empty(T + 1, dtype=i32, device=device)
+        self.num_unique = torch.empty(1, dtype=i32, device=device)
+        self.values = torch.empty((cap, D), dtype=f32, device=device)
+        self.g_absmax = torch.empty(T, dtype=f32, device=device)
+        self.gq = torch.empty((cap, D), dtype=torch.int8, device=device)
+        self.g_scale = torch.empty(T, dtype=f32, device=device)
+        nbytes = dqrm_embbag_bwd_workspace_bytes(T, D, B, N)
+        if nbytes == 0:
+            raise DqrmError(ERR_UNSUPPORTED, "dqrm_embbag_bwd_workspace_bytes")
+        self.workspace = torch.empty(nbytes, dtype=torch.uint8, device=device)
+        dqrm_workspace_init(self.workspace)
+
+
+def dqrm_fwd_bwd_step(tables: Tables, bufs: StepBuffers, indices: torch.Tensor, offsets: torch.Tensor,
+                      grad_out: torch.Tensor, lr: float, mode: int = FWD_MASTER, stream=None) -> None:
+    """One pass of the whole hot path: the five per-step C calls in order, on one stream, no host sync."""
+    dqrm_embbag_fwd(tables, indices, offsets, bufs.B, mode, bufs.out, bufs.codes, stream)
+    dqrm_embbag_bwd(tables, indices, offsets, bufs.B, grad_out, bufs.sorted_pos, bufs.uniq_rows, bufs.seg_offsets,
+                    bufs.table_uniq_offsets, bufs.num_unique, bufs.values, bufs.g_absmax, bufs.workspace, stream)
+    dqrm_grad_quant_int8(bufs.T, bufs.D, bufs.cap, bufs.values, bufs.table_uniq_offsets, bufs.g_absmax, bufs.gq,
+                         bufs.g_scale, stream)
+    dqrm_sparse_update(tables, bufs.cap, bufs.uniq_rows, bufs.table_uniq_offsets, bufs.gq, bufs.g_scale, lr, stream)

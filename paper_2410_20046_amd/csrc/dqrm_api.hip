@@ -1,0 +1,402 @@
+// C ABI of the DQRM embedding hot path: host-side validation and kernel dispatch.
+// Every entry point validates on the host first and enqueues nothing on error.
+#include <hip/hip_runtime.h>
+
+#include <cstdio>
+#include <cstring>
+
+#include "dqrm.h"
+#include "dqrm_device.hpp"
+#include "dqrm_fwd.hpp"
+#include "dqrm_bwd.hpp"
+#include "dqrm_update.hpp"
+
+namespace {
+
+thread_local char t_hip_error[256] = "";
+
+int32_t hip_fail(hipError_t e, const char *what)
+{
+    std::snprintf(t_hip_error, sizeof(t_hip_error), "%s: %s", what, hipGetErrorString(e));
+    return DQRM_ERR_HIP;
+}
+
+#define DQRM_HIP_CHECK(expr)                                 \
+    do {                                                     \
+        hipError_t e_ = (expr);                              \
+        if (e_ != hipSuccess) return hip_fail(e_, #expr);    \
+    } while (0)
+
+inline bool aligned(const void *p, size_t a) { return (reinterpret_cast<uintptr_t>(p) & (a - 1)) == 0; }
+
+int pow2ceil(int x)
+{
+    int p = 1;
+    while (p < x) p <<= 1;
+    return p;
+}
+
+// Checks the table descriptor; *total_rows receives R.
+int32_t check_tables(const dqrm_tables_t *tb, bool need_packed, int64_t *total_rows)
+{
+    if (!tb) return DQRM_ERR_INVALID_ARG;
+    if (tb->num_tables < 1 || tb->dim < 1) return DQRM_ERR_INVALID_ARG;
+    if (!tb->row_offsets_host || !tb->row_offsets_dev || !tb->master || !tb->w_scale) return DQRM_ERR_INVALID_ARG;
+    if (need_packed && !tb->packed) return DQRM_ERR_INVALID_ARG;
+    if (tb->num_tables > DQRM_MAX_TABLES) return DQRM_ERR_UNSUPPORTED;
+    if (tb->dim % 8 != 0 || tb->dim > DQRM_MAX_DIM) return DQRM_ERR_UNSUPPORTED;
+    if (!aligned(tb->master, 16) || (tb->packed && !aligned(tb->packed, 4))) return DQRM_ERR_INVALID_ARG;
+    const int64_t *ro = tb->row_offsets_host;
+    if (ro[0] != 0) return DQRM_ERR_INVALID_ARG;
+    for (int t = 0; t < tb->num_tables; ++t) {
+        if (ro[t + 1] < ro[t]) return DQRM_ERR_INVALID_ARG;
+        if (ro[t + 1] - ro[t] > DQRM_MAX_TABLE_ROWS) return DQRM_ERR_UNSUPPORTED;
+    }
+    *total_rows = ro[tb->num_tables];
+    return DQRM_OK;
+}
+
+constexpr int64_t kMaxIndices = 2147483647LL - 2 * DQRM_MAX_TABLES - 64;
+
+int32_t check_batch(const dqrm_tables_t *tb, const int64_t *indices, const int64_t *offsets, int32_t batch,
+                    int64_t num_indices)
+{
+    if (!offsets || batch < 1 || num_indices < 0) return DQRM_ERR_INVALID_ARG;
+    if (num_indices > 0 && !indices) return DQRM_ERR_INVALID_ARG;
+    if (num_indices > kMaxIndices) return DQRM_ERR_UNSUPPORTED;
+    if ((int64_t)batch * tb->num_tables > kMaxIndices) return DQRM_ERR_UNSUPPORTED;
+    return DQRM_OK;
+}
+
+// ---- workspace layout of dqrm_embbag_bwd -------------------------------------
+struct WsLayout {
+    size_t off_ticket, off_seg_counter, off_table_base, off_table_nuniq, off_table_nchunk, off_tco, off_bag_of_pos,
+        off_sorted_bag, off_seg_row, off_seg_start, off_chunk_start, off_chunk_seg, off_partial_full, off_partial_last,
+        zero_bytes, total;
+};
+
+size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+
+WsLayout ws_layout(int32_t T, int32_t D, int64_t N)
+{
+    WsLayout L{};
+    size_t o = 0;
+    const size_t n = (size_t)N, t = (size_t)T, slots = (size_t)(N / DQRM_SEG_CHUNK + 2);
+    auto take = [&](size_t bytes) {
+        size_t at = o;
+        o = align_up(o + bytes, 256);
+        return at;
+    };
+    // the part that must be zero before the first call comes first
+    L.off_ticket = take(sizeof(unsigned));
+    L.off_seg_counter = take(slots * sizeof(unsigned));
+    L.zero_bytes = o;
+    L.off_table_base = take(t * sizeof(int));
+    L.off_table_nuniq = take(t * sizeof(int));
+    L.off_table_nchunk = take(t * sizeof(int));
+    L.off_tco = take((t + 1) * sizeof(int));
+    L.off_bag_of_pos = take(n * sizeof(int));
+    L.off_sorted_bag = take(n * sizeof(int));
+    L.off_seg_row = take((n + t + 1) * sizeof(unsigned));
+    L.off_seg_start = take((n + t + 1) * sizeof(int));
+    L.off_chunk_start = take(n * sizeof(int));
+    L.off_chunk_seg = take(n * sizeof(int));
+    L.off_partial_full = take(slots * (size_t)D * sizeof(float));
+    L.off_partial_last = take(slots * (size_t)D * sizeof(float));
+    L.total = o;
+    return L;
+}
+
+dqrm::BwdWs ws_views(void *workspace, const WsLayout &L)
+{
+    char *b = static_cast<char *>(workspace);
+    dqrm::BwdWs w;
+    w.ticket = reinterpret_cast<unsigned *>(b + L.off_ticket);
+    w.seg_counter = reinterpret_cast<unsigned *>(b + L.off_seg_counter);
+    w.table_base = reinterpret_cast<int *>(b + L.off_table_base);
+    w.table_nuniq = reinterpret_cast<int *>(b + L.off_table_nuniq);
+    w.table_nchunk = reinterpret_cast<int *>(b + L.off_table_nchunk);
+    w.table_chunk_offsets = reinterpret_cast<int *>(b + L.off_tco);
+    w.bag_of_pos = reinterpret_cast<int *>(b + L.off_bag_of_pos);
+    w.sorted_bag = reinterpret_cast<int *>(b + L.off_sorted_bag);
+    w.seg_row = reinterpret_cast<unsigned *>(b + L.off_seg_row);
+    w.seg_start = reinterpret_cast<int *>(b + L.off_seg_start);
+    w.chunk_start = reinterpret_cast<int *>(b + L.off_chunk_start);
+    w.chunk_seg = reinterpret_cast<int *>(b + L.off_chunk_seg);
+    w.partial_full = reinterpret_cast<float *>(b + L.off_partial_full);
+    w.partial_last = reinterpret_cast<float *>(b + L.off_partial_last);
+    return w;
+}
+
+int num_cus()
+{
+    static thread_local int cached_dev = -1, cached = 0;
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess) return 256;
+    if (dev != cached_dev) {
+        int v = 0;
+        if (hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || v <= 0) v = 256;
+        cached = v;
+        cached_dev = dev;
+    }
+    return cached;
+}
+
+int grid_for(int64_t work_items, int threads, int blocks_per_cu)
+{
+    int64_t want = (work_items + threads - 1) / threads;
+    int64_t cap = (int64_t)num_cus() * blocks_per_cu;
+    if (want > cap) want = cap;
+    if (want < 1) want = 1;
+    return (int)want;
+}
+
+template <bool PACKED>
+void launch_fwd(int G, dim3 grid, hipStream_t st, const dqrm::FwdArgs &a)
+{
+    using namespace dqrm;
+    switch (G) {
+    case 2: hipLaunchKernelGGL((embbag_fwd_kernel<2, PACKED>), grid, dim3(kFwdThreads), 0, st, a); break;
+    case 4: hipLaunchKernelGGL((embbag_fwd_kernel<4, PACKED>), grid, dim3(kFwdThreads), 0, st, a); break;
+    case 8: hipLaunchKernelGGL((embbag_fwd_kernel<8, PACKED>), grid, dim3(kFwdThreads), 0, st, a); break;
+    case 16: hipLaunchKernelGGL((embbag_fwd_kernel<16, PACKED>), grid, dim3(kFwdThreads), 0, st, a); break;
+    case 32: hipLaunchKernelGGL((embbag_fwd_kernel<32, PACKED>), grid, dim3(kFwdThreads), 0, st, a); break;
+    default: hipLaunchKernelGGL((embbag_fwd_kernel<64, PACKED>), grid, dim3(kFwdThreads), 0, st, a); break;
+    }
+}
+
+void launch_segsum(int G, dim3 grid, hipStream_t st, const dqrm::SegArgs &a)
+{
+    using namespace dqrm;
+    switch (G) {
+    case 2: hipLaunchKernelGGL((segsum_kernel<2>), grid, dim3(kSegThreads), 0, st, a); break;
+    case 4: hipLaunchKernelGGL((segsum_kernel<4>), grid, dim3(kSegThreads), 0, st, a); break;
+    case 8: hipLaunchKernelGGL((segsum_kernel<8>), grid, dim3(kSegThreads), 0, st, a); break;
+    case 16: hipLaunchKernelGGL((segsum_kernel<16>), grid, dim3(kSegThreads), 0, st, a); break;
+    case 32: hipLaunchKernelGGL((segsum_kernel<32>), grid, dim3(kSegThreads), 0, st, a); break;
+    default: hipLaunchKernelGGL((segsum_kernel<64>), grid, dim3(kSegThreads), 0, st, a); break;
+    }
+}
+
+} // namespace
+
+extern "C" {
+
+const char *dqrm_version(void) { return "0.1"; }
+
+const char *dqrm_last_hip_error(void) { return t_hip_error; }
+
+int32_t dqrm_find_scale(const dqrm_tables_t *tables, void *stream)
+{
+    int64_t R = 0;
+    int32_t rc = check_tables(tables, false, &R);
+    if (rc != DQRM_OK) return rc;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    const int T = tables->num_tables, D = tables->dim;
+    // w_scale doubles as the absmax accumulator (bit pattern of a non-negative float)
+    hipLaunchKernelGGL(dqrm::fill_u32_kernel, dim3((T + 255) / 256), dim3(256), 0, st,
+                       reinterpret_cast<unsigned *>(tables->w_scale), 0u, T);
+    const int64_t f4 = R * (D / 4);
+    if (f4 > 0) {
+        hipLaunchKernelGGL(dqrm::table_absmax_kernel, dim3(grid_for(f4, dqrm::kEwThreads * 4, 16)),
+                           dim3(dqrm::kEwThreads), 0, st, tables->master, tables->row_offsets_dev, T, D, tables->w_scale);
+    }
+    hipLaunchKernelGGL(dqrm::finalize_scale_kernel, dim3((T + 255) / 256), dim3(256), 0, st, tables->w_scale, T);
+    DQRM_HIP_CHECK(hipGetLastError());
+    return DQRM_OK;
+}
+
+int32_t dqrm_pack_int4(const dqrm_tables_t *tables, void *stream)
+{
+    int64_t R = 0;
+    int32_t rc = check_tables(tables, true, &R);
+    if (rc != DQRM_OK) return rc;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    const int T = tables->num_tables, D = tables->dim;
+    const int64_t g8 = R * (D / 8);
+    if (g8 > 0) {
+        hipLaunchKernelGGL(dqrm::pack_int4_kernel, dim3(grid_for(g8, dqrm::kEwThreads * 2, 16)), dim3(dqrm::kEwThreads),
+                           0, st, tables->master, tables->row_offsets_dev, tables->w_scale, T, D, tables->packed);
+    }
+    DQRM_HIP_CHECK(hipGetLastError());
+    return DQRM_OK;
+}
+
+int32_t dqrm_embbag_fwd(const dqrm_tables_t *tables, const int64_t *indices, const int64_t *offsets, int32_t batch,
+                        int64_t num_indices, int32_t mode, float *out, int8_t *codes_dbg, void *stream)
+{
+    int64_t R = 0;
+    if (mode != DQRM_FWD_MASTER && mode != DQRM_FWD_PACKED) return DQRM_ERR_INVALID_ARG;
+    int32_t rc = check_tables(tables, mode == DQRM_FWD_PACKED, &R);
+    if (rc != DQRM_OK) return rc;
+    rc = check_batch(tables, indices, offsets, batch, num_indices);
+    if (rc != DQRM_OK) return rc;
+    if (!out || !aligned(out, 16) || (codes_dbg && !aligned(codes_dbg, 4))) return DQRM_ERR_INVALID_ARG;
+
+    dqrm::FwdArgs a;
+    a.master = tables->master;
+    a.packed = tables->packed;
+    a.w_scale = tables->w_scale;
+    a.row_offsets = tables->row_offsets_dev;
+    a.indices = indices;
+    a.offsets = offsets;
+    a.out = out;
+    a.codes = codes_dbg;
+    a.num_indices = num_indices;
+    a.T = tables->num_tables;
+    a.B = batch;
+    a.D = tables->dim;
+    a.num_bags = (int64_t)a.T * a.B;
+
+    const int G = pow2ceil(a.D / 4);
+    const int64_t groups = (a.num_bags + dqrm::kBagsPerGroup - 1) / dqrm::kBagsPerGroup;
+    const int64_t threads = groups * G;
+    const int64_t blocks = (threads + dqrm::kFwdThreads - 1) / dqrm::kFwdThreads;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    if (mode == DQRM_FWD_PACKED)
+        launch_fwd<true>(G, dim3((unsigned)blocks), st, a);
+    else
+        launch_fwd<false>(G, dim3((unsigned)blocks), st, a);
+    DQRM_HIP_CHECK(hipGetLastError());
+    return DQRM_OK;
+}
+
+size_t dqrm_embbag_bwd_workspace_bytes(int32_t num_tables, int32_t dim, int32_t batch, int64_t num_indices)
+{
+    if (num_tables < 1 || num_tables > DQRM_MAX_TABLES || dim < 8 || dim > DQRM_MAX_DIM || dim % 8 != 0 || batch < 1 ||
+        num_indices < 0 || num_indices > kMaxIndices)
+        return 0;
+    return ws_layout(num_tables, dim, num_indices).total;
+}
+
+int32_t dqrm_workspace_init(void *workspace, size_t workspace_bytes, void *stream)
+{
+    if (!workspace || !aligned(workspace, 256) || workspace_bytes < 512) return DQRM_ERR_INVALID_ARG;
+    // Only the leading counters need to be zero, but their extent depends on the
+    // call's sizes, which are not known here: clear everything (one-off cost).
+    const size_t words = workspace_bytes / 4;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    const size_t per_launch = (size_t)1 << 30; // words per launch, keeps the int index of the fill kernel in range
+    for (size_t done = 0; done < words; done += per_launch) {
+        const size_t n = words - done < per_launch ? words - done : per_launch;
+        hipLaunchKernelGGL(dqrm::fill_u32_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st,
+                           static_cast<unsigned *>(workspace) + done, 0u, (int)n);
+    }
+    DQRM_HIP_CHECK(hipGetLastError());
+    return DQRM_OK;
+}
+
+int32_t dqrm_embbag_bwd(const dqrm_tables_t *tables, const int64_t *indices, const int64_t *offsets, int32_t batch,
+                        int64_t num_indices, const float *grad_out, int32_t *sorted_pos, int64_t *uniq_rows,
+                        int32_t *seg_offsets, int32_t *table_uniq_offsets, int32_t *num_unique, float *values,
+                        float *g_absmax, void *workspace, size_t workspace_bytes, void *stream)
+{
+    int64_t R = 0;
+    int32_t rc = check_tables(tables, false, &R);
+    if (rc != DQRM_OK) return rc;
+    rc = check_batch(tables, indices, offsets, batch, num_indices);
+    if (rc != DQRM_OK) return rc;
+    if (!grad_out || !sorted_pos || !uniq_rows || !seg_offsets || !table_uniq_offsets || !num_unique || !values ||
+        !g_absmax || !workspace)
+        return DQRM_ERR_INVALID_ARG;
+    if (!aligned(grad_out, 16) || !aligned(values, 16) || !aligned(workspace, 256)) return DQRM_ERR_INVALID_ARG;
+    const int T = tables->num_tables, D = tables->dim;
+    const WsLayout L = ws_layout(T, D, num_indices);
+    if (workspace_bytes < L.total) return DQRM_ERR_WORKSPACE_TOO_SMALL;
+
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    dqrm::BwdWs ws = ws_views(workspace, L);
+    hipLaunchKernelGGL(dqrm::dedupe_kernel, dim3(T), dim3(dqrm::kDdThreads), 0, st, indices, offsets,
+                       tables->row_offsets_dev, T, (int)batch, num_indices, ws, sorted_pos, seg_offsets,
+                       table_uniq_offsets, num_unique, g_absmax);
+
+    dqrm::SegArgs sa;
+    sa.grad_out = grad_out;
+    sa.ws = ws;
+    sa.tuo = table_uniq_offsets;
+    sa.uniq_rows = uniq_rows;
+    sa.seg_offsets = seg_offsets;
+    sa.values = values;
+    sa.g_absmax = g_absmax;
+    sa.T = T;
+    sa.B = batch;
+    sa.D = D;
+    const int G = pow2ceil(D / 4);
+    // at most one lane group per possible chunk, at least one block
+    const int grid = grid_for(num_indices * G, dqrm::kSegThreads, 8);
+    launch_segsum(G, dim3(grid), st, sa);
+    DQRM_HIP_CHECK(hipGetLastError());
+    return DQRM_OK;
+}
+
+int32_t dqrm_grad_quant_int8(int32_t num_tables, int32_t dim, int64_t capacity, const float *values,
+                             const int32_t *table_uniq_offsets, const float *g_absmax, int8_t *gq, float *g_scale,
+                             void *stream)
+{
+    if (num_tables < 1 || dim < 1 || capacity < 0) return DQRM_ERR_INVALID_ARG;
+    if (!values || !table_uniq_offsets || !g_absmax || !gq || !g_scale) return DQRM_ERR_INVALID_ARG;
+    if (num_tables > DQRM_MAX_TABLES || dim % 8 != 0 || dim > DQRM_MAX_DIM) return DQRM_ERR_UNSUPPORTED;
+    if (capacity > kMaxIndices) return DQRM_ERR_UNSUPPORTED;
+    if (!aligned(values, 16) || !aligned(gq, 4)) return DQRM_ERR_INVALID_ARG;
+    dqrm::QuantArgs a;
+    a.values = values;
+    a.tuo = table_uniq_offsets;
+    a.g_absmax = g_absmax;
+    a.gq = gq;
+    a.g_scale = g_scale;
+    a.capacity = capacity;
+    a.T = num_tables;
+    a.D = dim;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    hipLaunchKernelGGL(dqrm::grad_quant_kernel, dim3(grid_for(capacity * (dim / 4), dqrm::kEwThreads, 8)),
+                       dim3(dqrm::kEwThreads), 0, st, a);
+    DQRM_HIP_CHECK(hipGetLastError());
+    return DQRM_OK;
+}
+
+int32_t dqrm_sparse_update(const dqrm_tables_t *tables, int64_t capacity, const int64_t *uniq_rows,
+                           const int32_t *table_uniq_offsets, const int8_t *gq, const float *g_scale, float lr,
+                           void *stream)
+{
+    int64_t R = 0;
+    int32_t rc = check_tables(tables, false, &R);
+    if (rc != DQRM_OK) return rc;
+    if (capacity < 0 || !uniq_rows || !table_uniq_offsets || !gq || !g_scale) return DQRM_ERR_INVALID_ARG;
+    if (capacity > kMaxIndices) return DQRM_ERR_UNSUPPORTED;
+    if (!aligned(gq, 4)) return DQRM_ERR_INVALID_ARG;
+    dqrm::UpdateArgs a;
+    a.master = tables->master;
+    a.packed = tables->packed;
+    a.w_scale = tables->w_scale;
+    a.row_offsets = tables->row_offsets_dev;
+    a.uniq_rows = uniq_rows;
+    a.tuo = table_uniq_offsets;
+    a.gq = gq;
+    a.g_scale = g_scale;
+    a.capacity = capacity;
+    a.lr = lr;
+    a.T = tables->num_tables;
+    a.D = tables->dim;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    hipLaunchKernelGGL(dqrm::sparse_update_kernel, dim3(grid_for(capacity * (a.D / 4), dqrm::kEwThreads, 8)),
+                       dim3(dqrm::kEwThreads), 0, st, a);
+    DQRM_HIP_CHECK(hipGetLastError());
+    return DQRM_OK;
+}
+
+int32_t dqrm_check_status(void *stream, int32_t *first_bad_table, int64_t *first_bad_index)
+{
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    DQRM_HIP_CHECK(hipStreamSynchronize(st));
+    dqrm::DeviceStatus h;
+    DQRM_HIP_CHECK(hipMemcpyFromSymbol(&h, HIP_SYMBOL(dqrm::g_status), sizeof(h), 0, hipMemcpyDeviceToHost));
+    if (h.code != 0) {
+        dqrm::DeviceStatus z{0, 0, 0};
+        DQRM_HIP_CHECK(hipMemcpyToSymbol(HIP_SYMBOL(dqrm::g_status), &z, sizeof(z), 0, hipMemcpyHostToDevice));
+    }
+    if (first_bad_table) *first_bad_table = h.code ? h.table : -1;
+    if (first_bad_index) *first_bad_index = h.code ? h.value : -1;
+    return h.code;
+}
+
+} // extern "C"

@@ -1,0 +1,224 @@
+"""GPU parity: the HIP path, called through the C ABI, against the CPU oracle on the same
+seeded inputs.  Bit-exact on codes / indices / offsets / packed bytes; floats to
+|a-b| <= 1e-6 + 1e-5*|b| (and, because both sides use the same documented summation order and
+one rounding per operation, the float outputs are also expected to agree bit for bit)."""
+import numpy as np
+import pytest
+
+from gen import make_workload, Workload
+from helpers import GpuRun, assert_exact, assert_float_close, compare_bwd, full_step_parity
+
+pytestmark = pytest.mark.gpu
+
+
+def _say(msg):
+    print(msg, flush=True)
+
+
+# --------------------------------------------------------------------------
+# the BASELINE configurations
+# --------------------------------------------------------------------------
+@pytest.mark.parametrize("grad", ["dyadic", "normal"])
+def test_config_tiny(oracle, grad):
+    wl = make_workload("tiny")
+    _say(f"tiny grad={grad}")
+    W = wl.tables(threads=1)
+    idx, off = wl.batch(0)
+    g = wl.grad_dyadic(0) if grad == "dyadic" else wl.grad_normal(0)
+    full_step_parity(oracle, wl, W, idx, off, g, what=f"tiny/{grad}")
+
+
+def test_config_single_table(oracle):
+    wl = make_workload("single")
+    _say("single table 1M x 16, batch 2048, Zipf 1.05")
+    W = wl.tables()
+    idx, off = wl.batch(0)
+    full_step_parity(oracle, wl, W, idx, off, wl.grad_normal(0), what="single")
+
+
+def test_config_kaggle_full_size(oracle):
+    wl = make_workload("kaggle")
+    _say(f"kaggle-shaped full size: R={wl.R}")
+    W = wl.tables()
+    idx, off = wl.batch(0)
+    full_step_parity(oracle, wl, W, idx, off, wl.grad_normal(0), what="kaggle")
+
+
+def test_config_terabyte_full_size(oracle):
+    """The benchmark workload at full size, in the launch configuration bench.py times."""
+    wl = make_workload("terabyte")
+    _say(f"terabyte-shaped full size: R={wl.R} ({wl.R * wl.D * 4 / 1e9:.2f} GB fp32)")
+    W = wl.tables()
+    idx, off = wl.batch(0)
+    run = full_step_parity(oracle, wl, W, idx, off, wl.grad_normal(0), what="terabyte")
+    del run
+
+
+# --------------------------------------------------------------------------
+# shapes that span several tiles, ragged tails, degenerate cases
+# --------------------------------------------------------------------------
+@pytest.mark.parametrize("D", [8, 16, 24, 64, 128, 256])
+def test_dims_ragged_bags(oracle, D):
+    """every lane-group width, bags of 0..5 lookups (empty bags included), a stale weight scale."""
+    wl = make_workload("tiny", T=5, D=D, B=333, fixed_card=211, rows=5 * 211)
+    wl.seed += D
+    _say(f"ragged D={D}")
+    W = wl.tables(threads=1)
+    idx, off = wl.batch(1, pooling="ragged", max_len=5)
+    full_step_parity(oracle, wl, W, idx, off, wl.grad_normal(1), stale=0.5, what=f"ragged D={D}")
+
+
+def test_hot_segments_long_chunks(oracle):
+    """tiny tables: segments of several hundred to several thousand lookups (many chunks per segment,
+    the last-arrival combine), next to a table with no duplicates at all."""
+    cards = np.array([3, 1, 17, 5000, 40], np.int64)
+    wl = Workload(name="hot", T=5, D=64, B=4096, alpha=1.2, seed=77, cards=cards)
+    _say("hot segments")
+    W = wl.tables(threads=1)
+    idx, off = wl.batch(0)
+    run = full_step_parity(oracle, wl, W, idx, off, wl.grad_normal(0), what="hot")
+    # the same call again on the same workspace: the self-resetting counters must be ready
+    g1 = run.bwd()
+    o = oracle.embbag_bwd(wl.T, wl.D, wl.B, idx, off, wl.grad_normal(0))
+    compare_bwd(g1, o, "hot/second call")
+    assert_exact(g1["values"].view(np.uint32), o["values"].view(np.uint32), "hot/second call values bits")
+
+
+def test_max_table_lookups(oracle):
+    """a table that receives exactly the maximum number of lookups the dedupe kernel holds (16384),
+    with bags of two, next to an empty table (no lookups) and a small one."""
+    import paper_2410_20046_amd as dq
+
+    B = dq.MAX_TABLE_LOOKUPS // 2
+    cards = np.array([100000, 50, 9], np.int64)
+    wl = Workload(name="cap", T=3, D=16, B=B, alpha=1.05, seed=5, cards=cards)
+    rng = np.random.default_rng(3)
+    lens = np.concatenate([np.full(B, 2), np.zeros(B, np.int64), (np.arange(B) % 3 == 0).astype(np.int64)])
+    off = np.concatenate([[0], np.cumsum(lens)]).astype(np.int64)
+    idx = np.concatenate([rng.integers(0, 100000, 2 * B), rng.integers(0, 9, int(lens[2 * B:].sum()))]).astype(np.int64)
+    _say(f"capacity case N={len(idx)}")
+    W = wl.tables(threads=1)
+    full_step_parity(oracle, wl, W, idx, off, wl.grad_dyadic(0), what="cap")
+
+
+def test_zero_lookups_and_single_table(oracle):
+    wl = make_workload("tiny", T=1, B=7, fixed_card=5, rows=5)
+    W = wl.tables(threads=1)
+    off = np.zeros(wl.T * wl.B + 1, np.int64)
+    idx = np.zeros(0, np.int64)
+    _say("empty batch")
+    full_step_parity(oracle, wl, W, idx, off, wl.grad_normal(0), what="empty")
+
+
+def test_all_zero_gradient_and_all_zero_table(oracle):
+    """the scale floor: an all-zero table and an all-zero gradient give all-zero codes."""
+    wl = make_workload("tiny")
+    W = wl.tables(threads=1)
+    W[wl.row_offsets[1]:wl.row_offsets[2]] = 0.0
+    g = wl.grad_normal(0)
+    g[:, 2, :] = 0.0
+    idx, off = wl.batch(2)
+    _say("zero table / zero gradient")
+    run = full_step_parity(oracle, wl, W, idx, off, g, what="zeros")
+    assert run.tables.w_scale.cpu().numpy()[1] == np.float32(1e-8)
+    assert run.bufs.g_scale.cpu().numpy()[2] == np.float32(1e-8)
+
+
+# --------------------------------------------------------------------------
+# properties that hold at any size (checked on the benchmark-shaped dimension)
+# --------------------------------------------------------------------------
+def test_dyadic_integer_closed_form(oracle):
+    """on the dyadic grid every summation order is exact: GPU values == int64 closed form."""
+    cards = np.array([13, 900, 30000], np.int64)
+    wl = Workload(name="dy", T=3, D=64, B=8192, alpha=1.1, seed=11, cards=cards)
+    idx, off = wl.batch(0)
+    g = wl.grad_dyadic(0)
+    _say("dyadic closed form")
+    W = np.zeros((wl.R, wl.D), np.float32)
+    run = GpuRun(wl.row_offsets, wl.D, W, wl.B, len(idx), with_packed=False, want_codes=False)
+    run.upload_batch(idx, off, g)
+    r = run.bwd()
+    m = np.rint(g.astype(np.float64) * 2.0 ** 24).astype(np.int64)  # [B, T, D] integers
+    tuo = r["table_uniq_offsets"]
+    for t in range(wl.T):
+        dense = np.zeros((int(cards[t]), wl.D), np.int64)
+        np.add.at(dense, idx[t * wl.B:(t + 1) * wl.B], m[:, t, :])
+        rows = r["uniq_rows"][tuo[t]:tuo[t + 1]]
+        got = np.rint(r["values"][tuo[t]:tuo[t + 1]].astype(np.float64) * 2.0 ** 24).astype(np.int64)
+        assert_exact(got, dense[rows], f"dyadic table {t}")
+        assert set(rows.tolist()) == set(idx[t * wl.B:(t + 1) * wl.B].tolist())
+    assert run.status()[0] == 0
+
+
+def test_determinism(oracle):
+    """same inputs, repeated launches: byte-identical outputs (no dependence on scheduling)."""
+    cards = np.array([7, 300, 100000, 2], np.int64)
+    wl = Workload(name="det", T=4, D=64, B=8192, alpha=1.1, seed=21, cards=cards)
+    idx, off = wl.batch(0)
+    W = wl.tables(threads=1)
+    run = GpuRun(wl.row_offsets, wl.D, W, wl.B, len(idx), with_packed=False, want_codes=False)
+    run.upload_batch(idx, off, wl.grad_normal(0))
+    _say("determinism")
+    first = run.bwd()
+    gq0, gs0 = run.quant()
+    for _ in range(10):
+        r = run.bwd()
+        gq, gs = run.quant()
+        for k in ("sorted_pos", "uniq_rows", "seg_offsets", "table_uniq_offsets"):
+            assert_exact(r[k], first[k], k)
+        assert_exact(r["values"].view(np.uint32), first["values"].view(np.uint32), "values bits")
+        assert_exact(r["g_absmax"].view(np.uint32), first["g_absmax"].view(np.uint32), "g_absmax bits")
+        assert_exact(gq, gq0, "gq")
+    assert run.status()[0] == 0
+
+
+# --------------------------------------------------------------------------
+# data-dependent errors: reported, never acted upon
+# --------------------------------------------------------------------------
+def test_out_of_range_index_is_reported_not_used(oracle):
+    import paper_2410_20046_amd as dq
+
+    wl = make_workload("tiny")
+    W = wl.tables(threads=1)
+    idx, off = wl.batch(0)
+    bad = idx.copy()
+    bad[200] = 1000  # table 1 has rows 0..999
+    bad[300] = -1
+    _say("out-of-range index")
+    run = GpuRun(wl.row_offsets, wl.D, W, wl.B, len(idx))
+    run.upload_batch(bad, off, wl.grad_normal(0))
+    run.find_scale()
+    out, _ = run.fwd(0)
+    code, tb, val = run.status()
+    assert code == dq.ERR_INDEX_OUT_OF_RANGE and tb in (1, 2) and val in (1000, -1)
+    # the bad lookups were skipped: their bags are empty, everything else is as with valid input
+    s = oracle.find_scale(W, wl.row_offsets)
+    good_out, _ = oracle.embbag_fwd(W, None, wl.row_offsets, s, wl.B, idx, off)
+    good_out[200 - 128, 1] = 0.0
+    good_out[300 - 256, 2] = 0.0
+    assert_exact(out.view(np.uint32), good_out.view(np.uint32), "out with skipped lookups")
+    r = run.bwd()
+    code, tb, val = run.status()
+    assert code == dq.ERR_INDEX_OUT_OF_RANGE
+    exp_u = 0
+    for t in range(wl.T):
+        rows = bad[t * wl.B:(t + 1) * wl.B]
+        exp_u += len(np.unique(rows[(rows >= 0) & (rows < wl.cards[t])]))
+    assert r["U"] == exp_u
+    assert run.status()[0] == 0  # cleared by the read
+
+
+def test_capacity_overflow_is_reported(oracle):
+    import paper_2410_20046_amd as dq
+
+    B = dq.MAX_TABLE_LOOKUPS + 1
+    wl = make_workload("tiny", T=2, B=B, fixed_card=50, rows=100)
+    W = wl.tables(threads=1)
+    idx, off = wl.batch(0)
+    _say("capacity overflow")
+    run = GpuRun(wl.row_offsets, wl.D, W, wl.B, len(idx), with_packed=False, want_codes=False)
+    run.upload_batch(idx, off, wl.grad_normal(0))
+    r = run.bwd()
+    code, tb, val = run.status()
+    assert code == dq.ERR_CAPACITY and val == B
+    assert r["U"] == 0

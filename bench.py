@@ -1,0 +1,247 @@
+#!/usr/bin/env python3
+"""Benchmark of the DQRM embedding hot path on one MI355X.
+
+A step = one pass of the whole hot path over one synthetic batch, all through the C ABI:
+  dqrm_embbag_fwd (gather -> INT4 fake-quant -> sum-pool) ->
+  dqrm_embbag_bwd (dedupe -> segment-sum)                 ->
+  dqrm_grad_quant_int8 -> dqrm_sparse_update (SGD on master rows + packed re-encode).
+Workload: the Terabyte-shaped embedding layer (26 tables, ~49.12 M rows, dim 64, batch 8192,
+one Zipf(1.1) index per table per sample), tables and batches resident in HBM before timing.
+Prints ONE JSON line.  The CPU oracle is used only for the "cpu_baseline" leg.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0  # MI355X HBM3E, vendor figure
+
+
+def log(*a):
+    print(*a, file=sys.stderr, flush=True)
+
+
+def algorithmic_bytes(T, D, B, N, U, packed_fwd, packed_mirror):
+    """Bytes the method itself has to move per step (duplicates of a row within a step count once)."""
+    bags = T * B
+    b = {
+        "fwd": 8 * N + (D // 2 if packed_fwd else 4 * D) * U + 4 * D * bags,
+        "dedupe": 64 * N,
+        "segsum": 4 * D * bags + (8 + 4 * D) * U,
+        "quant": (4 * D + D) * U,
+        "update": (D + 8 * D) * U + (D // 2 * U if packed_mirror else 0),
+    }
+    b["step"] = sum(b.values())
+    return b
+
+
+def read_traffic(kernel):
+    """HBM bytes per launch of `kernel` from the committed rocprofv3 --pmc summary, or None."""
+    path = os.path.join(ROOT, "profiles", "terabyte_pmc_traffic.txt")
+    if not os.path.exists(path):
+        return None
+    for line in open(path):
+        p = line.split()
+        if len(p) >= 3 and p[0] == "traffic_bytes_per_launch" and p[1] == kernel:
+            return float(p[2])
+    return None
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=2000)
+    ap.add_argument("--warmup", type=int, default=100)
+    ap.add_argument("--workload", default="terabyte", choices=["terabyte", "kaggle", "single", "tiny"])
+    ap.add_argument("--mode", default="packed", choices=["packed", "master"])
+    ap.add_argument("--pool", type=int, default=64, help="distinct index batches cycled")
+    ap.add_argument("--grad-pool", type=int, default=8, help="distinct grad_out buffers cycled")
+    ap.add_argument("--lr", type=float, default=0.1)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-seconds", type=float, default=12.0)
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.exit("bench.py: this build runs on ONE GPU (no collectives, no sharding); use --gpus 1. "
+                 "DESIGN.md says how the path would shard.")
+
+    import numpy as np
+    import torch
+
+    import paper_2410_20046_amd as dq
+    from gen import make_workload
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+    dq.lib()  # fail loudly if the HIP library is missing
+
+    wl = make_workload(args.workload)
+    T, D, B = wl.T, wl.D, wl.B
+    t0 = time.time()
+    W = wl.tables(threads=16)
+    log(f"[bench] {args.workload}: T={T} D={D} B={B} R={wl.R} ({W.nbytes / 1e9:.2f} GB fp32), tables in {time.time() - t0:.1f}s")
+    master = torch.from_numpy(W).to(dev)
+    packed = torch.empty((wl.R, D // 2), dtype=torch.uint8, device=dev)
+    tables = dq.Tables(wl.row_offsets, D, master, packed)
+
+    t0 = time.time()
+    pool = [wl.batch(k) for k in range(args.pool)]
+    N = len(pool[0][0])
+    idx_d = [torch.from_numpy(i).to(dev) for i, _ in pool]
+    off_d = [torch.from_numpy(o).to(dev) for _, o in pool]
+    grads = [wl.grad_normal(k) for k in range(args.grad_pool)]
+    grad_d = [torch.from_numpy(g).to(dev) for g in grads]
+    log(f"[bench] {args.pool} batches of {N} lookups + {args.grad_pool} grad_out in {time.time() - t0:.1f}s")
+
+    bufs = dq.StepBuffers(T, D, B, N, dev, want_codes=False)
+    mode = dq.FWD_PACKED if args.mode == "packed" else dq.FWD_MASTER
+    dq.dqrm_find_scale(tables)
+    dq.dqrm_pack_int4(tables)
+    torch.cuda.synchronize()
+
+    def step(k):
+        dq.dqrm_fwd_bwd_step(tables, bufs, idx_d[k % args.pool], off_d[k % args.pool], grad_d[k % args.grad_pool],
+                             args.lr, mode)
+
+    # ---- warm-up, then the timed region: exactly K steps, one stream, no host sync inside ----
+    for k in range(args.warmup):
+        step(k)
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    t_start = time.perf_counter()
+    e0.record()
+    for k in range(args.steps):
+        step(args.warmup + k)
+    e1.record()
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t_start
+    ev_ms = e0.elapsed_time(e1)
+    ms_per_step = wall * 1e3 / args.steps
+    code, tb, val = dq.dqrm_check_status()
+    assert code == 0, f"device status {code} (table {tb}, value {val})"
+    log(f"[bench] timed {args.steps} steps: wall {wall * 1e3:.2f} ms, events {ev_ms:.2f} ms, {ms_per_step * 1e3:.1f} us/step")
+
+    # ---- unique rows per batch (for the algorithmic byte counts) ----
+    us = []
+    for k in range(min(args.pool, 16)):
+        dq.dqrm_embbag_bwd(tables, idx_d[k], off_d[k], B, grad_d[0], bufs.sorted_pos, bufs.uniq_rows,
+                           bufs.seg_offsets, bufs.table_uniq_offsets, bufs.num_unique, bufs.values, bufs.g_absmax,
+                           bufs.workspace)
+        us.append(int(bufs.num_unique.cpu().item()))
+    U = float(np.mean(us))
+    ab = algorithmic_bytes(T, D, B, N, U, packed_fwd=(mode == dq.FWD_PACKED), packed_mirror=True)
+
+    # ---- per-stage HIP-event timing over the same K steps (events on the launch stream) ----
+    stages = ["fwd", "bwd", "quant", "update"]
+    calls = {
+        "fwd": lambda k: dq.dqrm_embbag_fwd(tables, idx_d[k % args.pool], off_d[k % args.pool], B, mode, bufs.out, None),
+        "bwd": lambda k: dq.dqrm_embbag_bwd(tables, idx_d[k % args.pool], off_d[k % args.pool], B,
+                                            grad_d[k % args.grad_pool], bufs.sorted_pos, bufs.uniq_rows,
+                                            bufs.seg_offsets, bufs.table_uniq_offsets, bufs.num_unique, bufs.values,
+                                            bufs.g_absmax, bufs.workspace),
+        "quant": lambda k: dq.dqrm_grad_quant_int8(T, D, bufs.cap, bufs.values, bufs.table_uniq_offsets,
+                                                   bufs.g_absmax, bufs.gq, bufs.g_scale),
+        "update": lambda k: dq.dqrm_sparse_update(tables, bufs.cap, bufs.uniq_rows, bufs.table_uniq_offsets, bufs.gq,
+                                                  bufs.g_scale, args.lr),
+    }
+    n_ev = min(args.steps, 500)
+    evs = [[torch.cuda.Event(enable_timing=True) for _ in range(len(stages) + 1)] for _ in range(n_ev)]
+    for k in range(n_ev):
+        evs[k][0].record()
+        for s, name in enumerate(stages):
+            calls[name](args.warmup + k)
+            evs[k][s + 1].record()
+    torch.cuda.synchronize()
+    stage_us = {name: 1e3 * float(np.mean([evs[k][s].elapsed_time(evs[k][s + 1]) for k in range(n_ev)]))
+                for s, name in enumerate(stages)}
+    log("[bench] per-call HIP-event time (us): " + ", ".join(f"{k}={v:.1f}" for k, v in stage_us.items()))
+
+    # the dominant kernel: the forward kernel or the segment-sum kernel (bwd = dedupe + segsum launches)
+    dom = "fwd" if stage_us["fwd"] >= stage_us["bwd"] else "bwd"
+    dom_kernel = "embbag_fwd_kernel" if dom == "fwd" else "dedupe_kernel+segsum_kernel"
+    dom_bytes = ab["fwd"] if dom == "fwd" else ab["dedupe"] + ab["segsum"]
+    dom_gbs = dom_bytes / (stage_us[dom] * 1e-6) / 1e9
+    roofline = {"bound": "hbm", "kernel": dom_kernel, "achieved": round(dom_gbs, 1), "peak": HBM_PEAK_GBS,
+                "unit": "GB/s", "frac": round(dom_gbs / HBM_PEAK_GBS, 4), "traffic": read_traffic(dom_kernel),
+                "algorithmic_bytes_per_launch": int(dom_bytes), "avg_launch_us": round(stage_us[dom], 2)}
+
+    # ---- device-to-device copy bandwidth, for context ----
+    a = torch.empty(1 << 28, dtype=torch.float32, device=dev)
+    b = torch.empty_like(a)
+    for _ in range(3):
+        b.copy_(a)
+    torch.cuda.synchronize()
+    c0, c1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    c0.record()
+    for _ in range(10):
+        b.copy_(a)
+    c1.record()
+    torch.cuda.synchronize()
+    copy_gbs = 10 * 2 * a.numel() * 4 / (c0.elapsed_time(c1) * 1e-3) / 1e9
+    del a, b
+
+    lookups_per_s = N * args.steps / wall
+    step_gbs = ab["step"] / (ms_per_step * 1e-3) / 1e9
+
+    # ---- CPU baseline: the oracle as it stands, on a bounded sample of the same workload ----
+    cpu = None
+    if not args.no_cpu_baseline:
+        import oracle
+
+        oracle.build()
+        Wo = W  # the oracle updates the host copy in place, as the GPU does on the device
+        s = oracle.find_scale(Wo, wl.row_offsets)  # the cached scale is an input of a step: not timed
+        # packed mirror: only the rows a step touches are re-encoded, so an empty mirror gives the same work
+        pk = np.zeros((wl.R, D // 2), np.uint8)
+        done, t_cpu = 0, 0.0
+        while t_cpu < args.cpu_seconds and done < args.pool:
+            idx, off = pool[done]
+            g = grads[done % args.grad_pool]
+            t1 = time.perf_counter()
+            oracle.embbag_fwd(Wo, None, wl.row_offsets, s, B, idx, off, mode=0, want_codes=False)
+            r = oracle.embbag_bwd(T, D, B, idx, off, g)
+            gq, gs = oracle.grad_quant_int8(T, D, r["values"], r["table_uniq_offsets"], r["g_absmax"])
+            oracle.sparse_update(Wo, pk, wl.row_offsets, s, r["uniq_rows"], r["table_uniq_offsets"], gq, gs, args.lr)
+            t_cpu += time.perf_counter() - t1
+            done += 1
+        cpu = {"value": round(N * done / t_cpu, 1), "unit": "lookups/s", "cores": 1, "kind": "oracle",
+               "sample": f"{done} steps of the same {args.workload} workload (batches 0..{done - 1}), "
+                         f"{t_cpu:.1f} s of single-threaded C oracle (fwd master mode + bwd + quant + update)"}
+        log(f"[bench] oracle: {done} steps in {t_cpu:.1f}s")
+
+    out = {
+        "metric": "embedding lookups/s for INT4-QAT fwd+bwd; achieved HBM GB/s vs peak",
+        "value": round(lookups_per_s, 1),
+        "unit": "lookups/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 5),
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "f32",
+        "data": "synthetic",
+        "config": {"workload": f"{args.workload}-shaped embedding layer: {T} tables, {wl.R} rows, dim {D}, batch {B}, "
+                               f"1 Zipf index per table per sample, {args.mode}-mode forward, INT8 sparse grads, "
+                               f"SGD lr {args.lr}",
+                   "lookups_per_step": N, "unique_rows_per_step": round(U, 1), "fwd_mode": args.mode},
+        "roofline": roofline,
+        "cpu_baseline": cpu,
+        "step_algorithmic_bytes": int(ab["step"]),
+        "step_hbm_gbs": round(step_gbs, 1),
+        "step_hbm_frac_of_peak": round(step_gbs / HBM_PEAK_GBS, 4),
+        "stage_us": {k: round(v, 2) for k, v in stage_us.items()},
+        "event_ms_per_step": round(ev_ms / args.steps, 5),
+        "copy_bw_gbs": round(copy_gbs, 1),
+    }
+    print(json.dumps(out), flush=True)
+
+
+if __name__ == "__main__":
+    main()

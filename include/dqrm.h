@@ -108,12 +108,10 @@ int32_t dqrm_embbag_fwd(const dqrm_tables_t *tables, const int64_t *indices, con
                         int32_t batch, int64_t num_indices, int32_t mode, float *out, int8_t *codes_dbg,
                         void *stream);
 
-/* Scratch for dqrm_embbag_bwd.  The workspace must be cleared ONCE with
- * dqrm_workspace_init() after it is allocated (and again after any call that
- * was aborted); the kernels leave it ready for the next call.  Two calls that
+/* Scratch for dqrm_embbag_bwd, in bytes (256-byte aligned device memory; needs
+ * no initialisation; its contents mean nothing between calls).  Two calls that
  * may overlap in time need two workspaces.  Returns 0 for invalid arguments. */
 size_t dqrm_embbag_bwd_workspace_bytes(int32_t num_tables, int32_t dim, int32_t batch, int64_t num_indices);
-int32_t dqrm_workspace_init(void *workspace, size_t workspace_bytes, void *stream);
 
 /* Sec. 4.3 / distributed-training appendix: the table gradient in sparse
  * (indices, values) form over the touched rows only -- lossless "specified

@@ -33,7 +33,7 @@ SEG_CHUNK = 32
 MAX_TABLE_LOOKUPS = 16384
 
 EXPORTS = ("dqrm_find_scale", "dqrm_pack_int4", "dqrm_embbag_fwd", "dqrm_embbag_bwd_workspace_bytes",
-           "dqrm_workspace_init", "dqrm_embbag_bwd", "dqrm_grad_quant_int8", "dqrm_sparse_update",
+           "dqrm_embbag_bwd", "dqrm_grad_quant_int8", "dqrm_sparse_update",
            "dqrm_check_status", "dqrm_last_hip_error", "dqrm_version")
 
 
@@ -67,12 +67,11 @@ def lib() -> C.CDLL:
         L.dqrm_embbag_fwd.argtypes = [tp, vp, vp, i32, i64, i32, vp, vp, vp]
         L.dqrm_embbag_bwd_workspace_bytes.argtypes = [i32, i32, i32, i64]
         L.dqrm_embbag_bwd_workspace_bytes.restype = sz
-        L.dqrm_workspace_init.argtypes = [vp, sz, vp]
         L.dqrm_embbag_bwd.argtypes = [tp, vp, vp, i32, i64, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
         L.dqrm_grad_quant_int8.argtypes = [i32, i32, i64, vp, vp, vp, vp, vp, vp]
         L.dqrm_sparse_update.argtypes = [tp, i64, vp, vp, vp, vp, C.c_float, vp]
         L.dqrm_check_status.argtypes = [vp, C.POINTER(i32), C.POINTER(i64)]
-        for n in ("dqrm_find_scale", "dqrm_pack_int4", "dqrm_embbag_fwd", "dqrm_workspace_init", "dqrm_embbag_bwd",
+        for n in ("dqrm_find_scale", "dqrm_pack_int4", "dqrm_embbag_fwd", "dqrm_embbag_bwd",
                   "dqrm_grad_quant_int8", "dqrm_sparse_update", "dqrm_check_status"):
             getattr(L, n).restype = i32
         L.dqrm_last_hip_error.restype = C.c_char_p
@@ -147,11 +146,6 @@ def dqrm_embbag_bwd_workspace_bytes(num_tables: int, dim: int, batch: int, num_i
     return int(lib().dqrm_embbag_bwd_workspace_bytes(num_tables, dim, batch, num_indices))
 
 
-def dqrm_workspace_init(workspace: torch.Tensor, stream=None) -> None:
-    _check(lib().dqrm_workspace_init(_ptr(workspace), workspace.numel() * workspace.element_size(), _stream(stream)),
-           "dqrm_workspace_init")
-
-
 def dqrm_embbag_bwd(tables: Tables, indices: torch.Tensor, offsets: torch.Tensor, batch: int, grad_out: torch.Tensor,
                     sorted_pos: torch.Tensor, uniq_rows: torch.Tensor, seg_offsets: torch.Tensor,
                     table_uniq_offsets: torch.Tensor, num_unique: torch.Tensor, values: torch.Tensor,
@@ -207,7 +201,6 @@ class StepBuffers:
         if nbytes == 0:
             raise DqrmError(ERR_UNSUPPORTED, "dqrm_embbag_bwd_workspace_bytes")
         self.workspace = torch.empty(nbytes, dtype=torch.uint8, device=device)
-        dqrm_workspace_init(self.workspace)
 
 
 def dqrm_fwd_bwd_step(tables: Tables, bufs: StepBuffers, indices: torch.Tensor, offsets: torch.Tensor,

@@ -70,9 +70,8 @@ int32_t check_batch(const dqrm_tables_t *tb, const int64_t *indices, const int64
 
 // ---- workspace layout of dqrm_embbag_bwd -------------------------------------
 struct WsLayout {
-    size_t off_ticket, off_seg_counter, off_table_base, off_table_nuniq, off_table_nchunk, off_tco, off_bag_of_pos,
-        off_sorted_bag, off_seg_row, off_seg_start, off_chunk_start, off_chunk_seg, off_partial_full, off_partial_last,
-        zero_bytes, total;
+    size_t off_table_base, off_table_nuniq, off_table_nchunk, off_tco, off_bag_of_pos, off_sorted_bag, off_seg_row,
+        off_seg_start, off_chunk_start, off_chunk_seg, off_partial_full, off_partial_last, off_absmax_slots, total;
 };
 
 size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
@@ -87,10 +86,6 @@ WsLayout ws_layout(int32_t T, int32_t D, int64_t N)
         o = align_up(o + bytes, 256);
         return at;
     };
-    // the part that must be zero before the first call comes first
-    L.off_ticket = take(sizeof(unsigned));
-    L.off_seg_counter = take(slots * sizeof(unsigned));
-    L.zero_bytes = o;
     L.off_table_base = take(t * sizeof(int));
     L.off_table_nuniq = take(t * sizeof(int));
     L.off_table_nchunk = take(t * sizeof(int));
@@ -103,6 +98,7 @@ WsLayout ws_layout(int32_t T, int32_t D, int64_t N)
     L.off_chunk_seg = take(n * sizeof(int));
     L.off_partial_full = take(slots * (size_t)D * sizeof(float));
     L.off_partial_last = take(slots * (size_t)D * sizeof(float));
+    L.off_absmax_slots = take(t * dqrm::kAbsmaxSlots * dqrm::kAbsmaxStride * sizeof(float));
     L.total = o;
     return L;
 }
@@ -111,8 +107,6 @@ dqrm::BwdWs ws_views(void *workspace, const WsLayout &L)
 {
     char *b = static_cast<char *>(workspace);
     dqrm::BwdWs w;
-    w.ticket = reinterpret_cast<unsigned *>(b + L.off_ticket);
-    w.seg_counter = reinterpret_cast<unsigned *>(b + L.off_seg_counter);
     w.table_base = reinterpret_cast<int *>(b + L.off_table_base);
     w.table_nuniq = reinterpret_cast<int *>(b + L.off_table_nuniq);
     w.table_nchunk = reinterpret_cast<int *>(b + L.off_table_nchunk);
@@ -125,6 +119,7 @@ dqrm::BwdWs ws_views(void *workspace, const WsLayout &L)
     w.chunk_seg = reinterpret_cast<int *>(b + L.off_chunk_seg);
     w.partial_full = reinterpret_cast<float *>(b + L.off_partial_full);
     w.partial_last = reinterpret_cast<float *>(b + L.off_partial_last);
+    w.absmax_slots = reinterpret_cast<float *>(b + L.off_absmax_slots);
     return w;
 }
 
@@ -165,17 +160,26 @@ void launch_fwd(int G, dim3 grid, hipStream_t st, const dqrm::FwdArgs &a)
     }
 }
 
-void launch_segsum(int G, dim3 grid, hipStream_t st, const dqrm::SegArgs &a)
+void launch_segsum(int G, dim3 grid_sum, dim3 grid_comb, hipStream_t st, const dqrm::SegArgs &a)
 {
     using namespace dqrm;
+#define DQRM_SEG_CASE(g)                                                                        \
+    case g:                                                                                     \
+        hipLaunchKernelGGL((chunk_sum_kernel<g>), grid_sum, dim3(kSegThreads), 0, st, a);       \
+        hipLaunchKernelGGL((combine_kernel<g>), grid_comb, dim3(kSegThreads), 0, st, a);        \
+        break;
     switch (G) {
-    case 2: hipLaunchKernelGGL((segsum_kernel<2>), grid, dim3(kSegThreads), 0, st, a); break;
-    case 4: hipLaunchKernelGGL((segsum_kernel<4>), grid, dim3(kSegThreads), 0, st, a); break;
-    case 8: hipLaunchKernelGGL((segsum_kernel<8>), grid, dim3(kSegThreads), 0, st, a); break;
-    case 16: hipLaunchKernelGGL((segsum_kernel<16>), grid, dim3(kSegThreads), 0, st, a); break;
-    case 32: hipLaunchKernelGGL((segsum_kernel<32>), grid, dim3(kSegThreads), 0, st, a); break;
-    default: hipLaunchKernelGGL((segsum_kernel<64>), grid, dim3(kSegThreads), 0, st, a); break;
+        DQRM_SEG_CASE(2)
+        DQRM_SEG_CASE(4)
+        DQRM_SEG_CASE(8)
+        DQRM_SEG_CASE(16)
+        DQRM_SEG_CASE(32)
+    default:
+        hipLaunchKernelGGL((chunk_sum_kernel<64>), grid_sum, dim3(kSegThreads), 0, st, a);
+        hipLaunchKernelGGL((combine_kernel<64>), grid_comb, dim3(kSegThreads), 0, st, a);
+        break;
     }
+#undef DQRM_SEG_CASE
 }
 
 } // namespace
@@ -269,23 +273,6 @@ size_t dqrm_embbag_bwd_workspace_bytes(int32_t num_tables, int32_t dim, int32_t 
     return ws_layout(num_tables, dim, num_indices).total;
 }
 
-int32_t dqrm_workspace_init(void *workspace, size_t workspace_bytes, void *stream)
-{
-    if (!workspace || !aligned(workspace, 256) || workspace_bytes < 512) return DQRM_ERR_INVALID_ARG;
-    // Only the leading counters need to be zero, but their extent depends on the
-    // call's sizes, which are not known here: clear everything (one-off cost).
-    const size_t words = workspace_bytes / 4;
-    hipStream_t st = static_cast<hipStream_t>(stream);
-    const size_t per_launch = (size_t)1 << 30; // words per launch, keeps the int index of the fill kernel in range
-    for (size_t done = 0; done < words; done += per_launch) {
-        const size_t n = words - done < per_launch ? words - done : per_launch;
-        hipLaunchKernelGGL(dqrm::fill_u32_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st,
-                           static_cast<unsigned *>(workspace) + done, 0u, (int)n);
-    }
-    DQRM_HIP_CHECK(hipGetLastError());
-    return DQRM_OK;
-}
-
 int32_t dqrm_embbag_bwd(const dqrm_tables_t *tables, const int64_t *indices, const int64_t *offsets, int32_t batch,
                         int64_t num_indices, const float *grad_out, int32_t *sorted_pos, int64_t *uniq_rows,
                         int32_t *seg_offsets, int32_t *table_uniq_offsets, int32_t *num_unique, float *values,
@@ -307,13 +294,14 @@ int32_t dqrm_embbag_bwd(const dqrm_tables_t *tables, const int64_t *indices, con
     hipStream_t st = static_cast<hipStream_t>(stream);
     dqrm::BwdWs ws = ws_views(workspace, L);
     hipLaunchKernelGGL(dqrm::dedupe_kernel, dim3(T), dim3(dqrm::kDdThreads), 0, st, indices, offsets,
-                       tables->row_offsets_dev, T, (int)batch, num_indices, ws, sorted_pos, seg_offsets,
-                       table_uniq_offsets, num_unique, g_absmax);
+                       tables->row_offsets_dev, T, (int)batch, num_indices, ws, sorted_pos);
 
     dqrm::SegArgs sa;
     sa.grad_out = grad_out;
     sa.ws = ws;
     sa.tuo = table_uniq_offsets;
+    sa.num_unique = num_unique;
+    sa.N = num_indices;
     sa.uniq_rows = uniq_rows;
     sa.seg_offsets = seg_offsets;
     sa.values = values;
@@ -322,9 +310,12 @@ int32_t dqrm_embbag_bwd(const dqrm_tables_t *tables, const int64_t *indices, con
     sa.B = batch;
     sa.D = D;
     const int G = pow2ceil(D / 4);
-    // at most one lane group per possible chunk, at least one block
-    const int grid = grid_for(num_indices * G, dqrm::kSegThreads, 8);
-    launch_segsum(G, dim3(grid), st, sa);
+    // at most one lane group per possible chunk / segment, at least one block
+    const int grid_sum = grid_for(num_indices * G, dqrm::kSegThreads, 8);
+    const int grid_comb = grid_for(num_indices * G, dqrm::kSegThreads, 4);
+    launch_segsum(G, dim3(grid_sum), dim3(grid_comb), st, sa);
+    hipLaunchKernelGGL(dqrm::absmax_finalize_kernel, dim3((T + 255) / 256), dim3(256), 0, st, ws.absmax_slots, T,
+                       g_absmax);
     DQRM_HIP_CHECK(hipGetLastError());
     return DQRM_OK;
 }
@@ -398,5 +389,16 @@ int32_t dqrm_check_status(void *stream, int32_t *first_bad_table, int64_t *first
     if (first_bad_index) *first_bad_index = h.code ? h.value : -1;
     return h.code;
 }
+
+#ifdef DQRM_PHASE_TIMING
+// developer builds only: clock stamps of one dedupe workgroup (see dqrm_bwd.hpp)
+int32_t dqrm_debug_phase_ticks(long long *out16)
+{
+    DQRM_HIP_CHECK(hipDeviceSynchronize());
+    DQRM_HIP_CHECK(hipMemcpyFromSymbol(out16, HIP_SYMBOL(dqrm::g_phase_ticks), 16 * sizeof(long long), 0,
+                                       hipMemcpyDeviceToHost));
+    return DQRM_OK;
+}
+#endif
 
 } // extern "C"

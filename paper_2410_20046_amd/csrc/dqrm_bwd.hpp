@@ -5,13 +5,16 @@
 //   table's lookups in LDS with a stable 8-bit LSD radix sort (keys stay in
 //   registers between passes; ranks come from per-wave digit counters and a
 //   wave-wide match of equal digits), marks segment heads and chunk heads,
-//   and writes table-local segment / chunk lists.  The last workgroup to
-//   finish turns the per-table counts into global offsets.
-// Kernel 2 (segsum_kernel): one lane group per chunk (<= DQRM_SEG_CHUNK
-//   consecutive contributions of one segment) sums its gradient rows left to
-//   right.  Segments of one chunk are final at once; for longer segments every
-//   chunk stores its partial and the group that arrives last adds the partials
-//   in chunk order, so the result does not depend on scheduling.
+//   and writes table-local segment / chunk lists plus the table's counts.
+// Kernel 2 (chunk_sum_kernel): every workgroup first turns the per-table counts
+//   into offsets (T is small), then one lane group per chunk (<= DQRM_SEG_CHUNK
+//   consecutive contributions of one segment) adds its gradient rows left to
+//   right.  A segment of one chunk is final; chunks of longer segments store
+//   their partial sums.
+// Kernel 3 (combine_kernel): one lane group per long segment adds the chunk
+//   partials in chunk order.
+// Kernel boundaries are the only synchronisation between workgroups, so the
+// result never depends on scheduling.
 #pragma once
 
 #include "dqrm_device.hpp"
@@ -19,40 +22,65 @@
 namespace dqrm {
 
 constexpr int kDdThreads = 1024;
-constexpr int kDdWaves = kDdThreads / kWave;            // 16
+constexpr int kDdWaves = kDdThreads / kWave;                      // 16
 constexpr int kDdMaxRounds = DQRM_MAX_TABLE_LOOKUPS / kDdThreads; // 16 items per thread at most
 constexpr int kDdCap = DQRM_MAX_TABLE_LOOKUPS;
 constexpr int kSegThreads = 256;
 
 // Views into the caller's workspace (all device pointers).
 struct BwdWs {
-    unsigned *ticket;          // [1]   workgroups of kernel 1 that have finished
-    unsigned *seg_counter;     // [N/32 + 2] chunks of a long segment that have arrived (self-resetting)
-    int *table_base;           // [T]   first lookup position of the table
-    int *table_nuniq;          // [T]
-    int *table_nchunk;         // [T]
-    int *table_chunk_offsets;  // [T+1]
-    int *bag_of_pos;           // [N]   bag (within its table) of every lookup position
-    int *sorted_bag;           // [N]   bag of every sorted lookup
-    unsigned *seg_row;         // [N+T+1] table-local: row of segment
-    int *seg_start;            // [N+T+1] table-local: first sorted index of segment (+ end sentinel)
-    int *chunk_start;          // [N]   table-local: first sorted index of chunk
-    int *chunk_seg;            // [N]   table-local: segment of chunk
-    float *partial_full;       // [(N/32 + 2) * D] partial of a full chunk of a long segment
-    float *partial_last;       // [(N/32 + 2) * D] partial of the last chunk of a long segment
+    int *table_base;          // [T]   first lookup position of the table
+    int *table_nuniq;         // [T]
+    int *table_nchunk;        // [T]
+    int *table_chunk_offsets; // [T+1]
+    int *bag_of_pos;          // [N]   bag (within its table) of every lookup position
+    int *sorted_bag;          // [N]   bag of every sorted lookup
+    unsigned *seg_row;        // [N+T+1] table-local: row of segment
+    int *seg_start;           // [N+T+1] table-local: first sorted index of segment (+ end sentinel)
+    int *chunk_start;         // [N]   table-local: first sorted index of chunk
+    int *chunk_seg;           // [N]   table-local: segment of chunk
+    float *partial_full;      // [(N/32 + 2) * D] partial of a full chunk of a long segment
+    float *partial_last;      // [(N/32 + 2) * D] partial of the last chunk of a long segment
+    float *absmax_slots;      // [T][kAbsmaxSlots] running maxima, one 128-byte line per entry
 };
 
-// exclusive prefix sum over the 1024 threads of the block; *total = sum of all
+// Per-table maxima are first gathered in kAbsmaxSlots separate cache lines per
+// table (workgroups pick a slot by their index), so that atomics from thousands
+// of workgroups do not all queue on one line; a last small kernel folds them.
+constexpr int kAbsmaxSlots = 16;
+constexpr int kAbsmaxStride = 32; // floats between slots = 128 bytes
+
+__device__ __forceinline__ float *absmax_slot(float *slots, int t, int k)
+{
+    return slots + ((int64_t)t * kAbsmaxSlots + k) * kAbsmaxStride;
+}
+
+// Optional per-phase clock stamps of one workgroup of the dedupe kernel (developer
+// builds only: -DDQRM_PHASE_TIMING=<table>; the stamps are 100 MHz ticks).
+#ifdef DQRM_PHASE_TIMING
+__device__ long long g_phase_ticks[16];
+#define DQRM_TICK(k)                                                                                           \
+    do {                                                                                                       \
+        if (blockIdx.x == DQRM_PHASE_TIMING && threadIdx.x == 0) g_phase_ticks[k] = (long long)wall_clock64(); \
+    } while (0)
+#else
+#define DQRM_TICK(k) \
+    do {             \
+    } while (0)
+#endif
+
+// exclusive prefix sum over the threads of a block of kWaves waves; *total = sum of all
+template <int kWaves>
 __device__ __forceinline__ int block_excl_scan_add(int v, int lane, int wave, int *s_w, int *total)
 {
-    int incl = wave_incl_scan_add(v, lane);
+    const int incl = wave_incl_scan_add(v, lane);
     __syncthreads(); // s_w may still be read from a previous use
     if (lane == kWave - 1) s_w[wave] = incl;
     __syncthreads();
     int base = 0, tot = 0;
 #pragma unroll
-    for (int w = 0; w < kDdWaves; ++w) {
-        int x = s_w[w];
+    for (int w = 0; w < kWaves; ++w) {
+        const int x = s_w[w];
         if (w < wave) base += x;
         tot += x;
     }
@@ -63,17 +91,13 @@ __device__ __forceinline__ int block_excl_scan_add(int v, int lane, int wave, in
 __global__ __launch_bounds__(kDdThreads) void dedupe_kernel(const int64_t *__restrict__ indices,
                                                             const int64_t *__restrict__ offsets,
                                                             const int64_t *__restrict__ row_offsets, int T, int B,
-                                                            int64_t N, BwdWs ws, int32_t *__restrict__ sorted_pos,
-                                                            int32_t *__restrict__ seg_offsets,
-                                                            int32_t *__restrict__ tuo, int32_t *__restrict__ num_unique,
-                                                            float *__restrict__ g_absmax)
+                                                            int64_t N, BwdWs ws, int32_t *__restrict__ sorted_pos)
 {
-    __shared__ unsigned skey[kDdCap];             // 64 KB
-    __shared__ unsigned short spos[kDdCap];       // 32 KB
-    __shared__ unsigned cnt[kDdWaves * 256];      // 16 KB, cnt[wave * 256 + digit]
+    __shared__ unsigned skey[kDdCap];        // 64 KB
+    __shared__ unsigned short spos[kDdCap];  // 32 KB
+    __shared__ unsigned cnt[kDdWaves * 256]; // 16 KB, cnt[wave * 256 + digit]
     __shared__ int s_w[kDdWaves];
     __shared__ int s_w2[kDdWaves];
-    __shared__ int s_last;
 
     const int t = blockIdx.x;
     const int tid = threadIdx.x;
@@ -100,17 +124,43 @@ __global__ __launch_bounds__(kDdThreads) void dedupe_kernel(const int64_t *__res
     const int base = (int)lo;
 
     // ---- phase 0: bag of every lookup position ---------------------------
+    // When every bag of the table holds exactly one lookup (the usual DLRM
+    // batch) the bag of position p is p itself and nothing needs to be stored.
+    DQRM_TICK(0);
+    constexpr int kBagBatch = 8;
+    bool one_each = !disabled && (n == B);
     if (!disabled) {
+        for (int b0 = 0; b0 < B; b0 += kDdThreads * kBagBatch) {
+            long long s[kBagBatch], e[kBagBatch];
+#pragma unroll
+            for (int q = 0; q < kBagBatch; ++q) {
+                const int b = b0 + q * kDdThreads + tid;
+                s[q] = lo + b;
+                e[q] = s[q] + 1;
+                if (b < B) {
+                    s[q] = offsets[(long long)t * B + b];
+                    e[q] = offsets[(long long)t * B + b + 1];
+                }
+            }
+#pragma unroll
+            for (int q = 0; q < kBagBatch; ++q) {
+                const int b = b0 + q * kDdThreads + tid;
+                if (b < B && (s[q] < lo || e[q] > hi || s[q] > e[q]))
+                    report(DQRM_ERR_BAD_OFFSETS, t, (long long)t * B + b);
+                if (s[q] != lo + b || e[q] != s[q] + 1) one_each = false;
+            }
+        }
+    }
+    one_each = __syncthreads_and(one_each ? 1 : 0) != 0;
+    if (!disabled && !one_each) {
         for (int b = tid; b < B; b += kDdThreads) {
             long long s = offsets[(long long)t * B + b], e = offsets[(long long)t * B + b + 1];
-            if (s < lo || e > hi || s > e) {
-                report(DQRM_ERR_BAD_OFFSETS, t, (long long)t * B + b);
-                s = s < lo ? lo : (s > hi ? hi : s);
-                e = e < s ? s : (e > hi ? hi : e);
-            }
+            s = s < lo ? lo : (s > hi ? hi : s);
+            e = e < s ? s : (e > hi ? hi : e);
             for (long long p = s; p < e; ++p) ws.bag_of_pos[p] = b;
         }
     }
+    DQRM_TICK(1);
 
     // ---- phase 1: keys into registers, wave-striped ----------------------
     const int rounds = (n + kDdThreads - 1) / kDdThreads; // 0..16, same for the whole block
@@ -134,11 +184,13 @@ __global__ __launch_bounds__(kDdThreads) void dedupe_kernel(const int64_t *__res
         }
     }
 
+    DQRM_TICK(2);
     // ---- phase 2: stable LSD radix sort, 8 bits per pass -----------------
     const int nbits = 32 - __clz(rows_t | 1u); // bit width of the sentinel (>= 1)
     const int passes = (nbits + 7) / 8;
     for (int p = 0; p < passes; ++p) {
         const int shift = 8 * p;
+        DQRM_TICK(8 + p);
         for (int k = tid; k < kDdWaves * 256; k += kDdThreads) cnt[k] = 0;
         __syncthreads();
         unsigned lrank[kDdMaxRounds];
@@ -161,7 +213,7 @@ __global__ __launch_bounds__(kDdThreads) void dedupe_kernel(const int64_t *__res
             unsigned c0 = cnt[(w0 + 0) * 256 + d], c1 = cnt[(w0 + 1) * 256 + d], c2 = cnt[(w0 + 2) * 256 + d],
                      c3 = cnt[(w0 + 3) * 256 + d];
             int total;
-            int ex = block_excl_scan_add((int)(c0 + c1 + c2 + c3), lane, wave, s_w, &total);
+            int ex = block_excl_scan_add<kDdWaves>((int)(c0 + c1 + c2 + c3), lane, wave, s_w, &total);
             cnt[(w0 + 0) * 256 + d] = (unsigned)ex;
             cnt[(w0 + 1) * 256 + d] = (unsigned)ex + c0;
             cnt[(w0 + 2) * 256 + d] = (unsigned)ex + c0 + c1;
@@ -191,6 +243,7 @@ __global__ __launch_bounds__(kDdThreads) void dedupe_kernel(const int64_t *__res
         // the next pass clears cnt and synchronises before anything is overwritten
     }
 
+    DQRM_TICK(3);
     // ---- phase 3: segment heads and chunk heads ---------------------------
     // (skey / spos now hold the table's rounds*1024 items in sorted order;
     //  entries that are padding or had a bad index carry the sentinel key.)
@@ -210,8 +263,8 @@ __global__ __launch_bounds__(kDdThreads) void dedupe_kernel(const int64_t *__res
             const bool head = valid && (i == 0 || skey[i - 1] != k);
             const int h = wave_incl_scan_add(head ? 1 : 0, lane) + carry_heads;
             const int st = max(wave_incl_scan_max(head ? i : -1, lane), carry_start);
-            carry_heads = __shfl(h, kWave - 1, kWave);
-            carry_start = __shfl(st, kWave - 1, kWave);
+            carry_heads = wave_last(h);
+            carry_start = wave_last(st);
             carry_valid += __popcll(__ballot(valid));
             seg_of[r] = h;
             start_of[r] = st;
@@ -254,7 +307,7 @@ __global__ __launch_bounds__(kDdThreads) void dedupe_kernel(const int64_t *__res
             const bool valid = flags[r] & 1;
             const bool chead = valid && (((i - start_of[r]) % DQRM_SEG_CHUNK) == 0);
             const int c = wave_incl_scan_add(chead ? 1 : 0, lane) + carry_chunks;
-            carry_chunks = __shfl(c, kWave - 1, kWave);
+            carry_chunks = wave_last(c);
             chunk_of[r] = c;
             if (chead) flags[r] |= 4;
         }
@@ -270,7 +323,18 @@ __global__ __launch_bounds__(kDdThreads) void dedupe_kernel(const int64_t *__res
     }
 
     // ---- phase 4: write the table-local lists -------------------------------
+    DQRM_TICK(5);
     const int sb = base + t; // the table's slice of seg_row / seg_start has n + 1 slots
+    int bag_of_item[kDdMaxRounds];
+#pragma unroll
+    for (int r = 0; r < kDdMaxRounds; ++r) { // all gathers first, so that they overlap
+        bag_of_item[r] = 0;
+        if (r < rounds) {
+            const int i = wave * per_wave + r * kWave + lane;
+            const int p = spos[i];
+            if (flags[r] & 1) bag_of_item[r] = one_each ? p : ws.bag_of_pos[base + p];
+        }
+    }
 #pragma unroll
     for (int r = 0; r < kDdMaxRounds; ++r) {
         if (r < rounds) {
@@ -278,7 +342,7 @@ __global__ __launch_bounds__(kDdThreads) void dedupe_kernel(const int64_t *__res
             const int p = spos[i];
             if (i < n) sorted_pos[base + i] = base + p;
             if (flags[r] & 1) {
-                int b = ws.bag_of_pos[base + p];
+                int b = bag_of_item[r];
                 b = b < 0 ? 0 : (b >= B ? B - 1 : b);
                 ws.sorted_bag[base + i] = b;
             }
@@ -298,36 +362,9 @@ __global__ __launch_bounds__(kDdThreads) void dedupe_kernel(const int64_t *__res
         ws.table_base[t] = base;
         ws.table_nuniq[t] = n_uniq;
         ws.table_nchunk[t] = n_chunk;
-        g_absmax[t] = 0.0f;
     }
-
-    // ---- phase 5: the last workgroup turns counts into offsets --------------
-    __threadfence();
-    __syncthreads();
-    if (tid == 0) s_last = (atomicAdd(ws.ticket, 1u) == (unsigned)(T - 1)) ? 1 : 0;
-    __syncthreads();
-    if (s_last) {
-        __threadfence();
-        int u = 0, c = 0;
-        if (tid < T) {
-            u = __hip_atomic_load(ws.table_nuniq + tid, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            c = __hip_atomic_load(ws.table_nchunk + tid, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        }
-        int tot_u, tot_c;
-        const int eu = block_excl_scan_add(u, lane, wave, s_w, &tot_u);
-        const int ec = block_excl_scan_add(c, lane, wave, s_w2, &tot_c);
-        if (tid < T) {
-            tuo[tid] = eu;
-            ws.table_chunk_offsets[tid] = ec;
-        }
-        if (tid == 0) {
-            tuo[T] = tot_u;
-            ws.table_chunk_offsets[T] = tot_c;
-            *num_unique = tot_u;
-            seg_offsets[tot_u] = (int32_t)N;
-            *ws.ticket = 0u;
-        }
-    }
+    if (tid < kAbsmaxSlots) *absmax_slot(ws.absmax_slots, t, tid) = 0.0f;
+    DQRM_TICK(6);
 }
 
 // ---------------------------------------------------------------------------
@@ -335,11 +372,13 @@ __global__ __launch_bounds__(kDdThreads) void dedupe_kernel(const int64_t *__res
 struct SegArgs {
     const float *grad_out;
     BwdWs ws;
-    const int32_t *tuo;
+    int32_t *tuo;
+    int32_t *num_unique;
     int64_t *uniq_rows;
     int32_t *seg_offsets;
     float *values;
     float *g_absmax;
+    int64_t N;
     int T, B, D;
 };
 
@@ -348,29 +387,101 @@ __device__ __forceinline__ float4 f4_add(float4 a, float4 b)
     return make_float4(a.x + b.x, a.y + b.y, a.z + b.z, a.w + b.w);
 }
 
-__device__ __forceinline__ float4 load_coherent_f4(const float *p)
+__device__ __forceinline__ float f4_absmax(float4 a)
 {
-    float4 v;
-    v.x = __hip_atomic_load(p + 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    v.y = __hip_atomic_load(p + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    v.z = __hip_atomic_load(p + 2, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    v.w = __hip_atomic_load(p + 3, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    return v;
+    return fmaxf(fmaxf(fabsf(a.x), fabsf(a.y)), fmaxf(fabsf(a.z), fabsf(a.w)));
+}
+
+// Per-block maxima of |values| by table, kept in LDS (bit patterns of
+// non-negative floats order like unsigned integers) and flushed once per block.
+struct BlockAbsmax {
+    unsigned *s_max; // [T] in LDS
+    __device__ __forceinline__ void init(unsigned *lds, int T)
+    {
+        s_max = lds;
+        for (int k = threadIdx.x; k < T; k += blockDim.x) s_max[k] = 0u;
+        // the caller synchronises before the first add()
+    }
+    __device__ __forceinline__ void add(int t, float v)
+    {
+        const unsigned b = __float_as_uint(v);
+        if (b > s_max[t]) atomicMax(s_max + t, b);
+    }
+    // all threads of the block; publishes the block's maxima
+    __device__ __forceinline__ void flush(float *slots, int T)
+    {
+        __syncthreads();
+        for (int k = threadIdx.x; k < T; k += blockDim.x) {
+            const unsigned b = s_max[k];
+            if (b != 0u)
+                atomicMax(reinterpret_cast<unsigned *>(absmax_slot(slots, k, blockIdx.x & (kAbsmaxSlots - 1))), b);
+        }
+    }
+};
+
+// Turns the per-table counts into offsets in LDS (every block does this; T is
+// small).  s_tuo / s_tco receive T+1 entries, s_base T.
+__device__ __forceinline__ void table_offsets_to_lds(const BwdWs &ws, int T, int *s_tuo, int *s_tco, int *s_base,
+                                                     int *s_w)
+{
+    // kSegThreads threads, each owns a run of consecutive tables
+    constexpr int kPer = (DQRM_MAX_TABLES + kSegThreads - 1) / kSegThreads; // 4
+    const int tid = threadIdx.x, lane = tid & (kWave - 1), wave = tid / kWave;
+    int u[kPer], c[kPer], su = 0, sc = 0;
+#pragma unroll
+    for (int q = 0; q < kPer; ++q) {
+        const int t = tid * kPer + q;
+        u[q] = c[q] = 0;
+        if (t < T) {
+            u[q] = ws.table_nuniq[t];
+            c[q] = ws.table_nchunk[t];
+            s_base[t] = ws.table_base[t];
+        }
+        su += u[q];
+        sc += c[q];
+    }
+    int tot_u, tot_c;
+    int eu = block_excl_scan_add<kSegThreads / kWave>(su, lane, wave, s_w, &tot_u);
+    int ec = block_excl_scan_add<kSegThreads / kWave>(sc, lane, wave, s_w, &tot_c);
+#pragma unroll
+    for (int q = 0; q < kPer; ++q) {
+        const int t = tid * kPer + q;
+        if (t < T) {
+            s_tuo[t] = eu;
+            s_tco[t] = ec;
+        }
+        eu += u[q];
+        ec += c[q];
+    }
+    if (tid == 0) {
+        s_tuo[T] = tot_u;
+        s_tco[T] = tot_c;
+    }
+    __syncthreads();
 }
 
 template <int G>
-__global__ __launch_bounds__(kSegThreads) void segsum_kernel(SegArgs a)
+__global__ __launch_bounds__(kSegThreads) void chunk_sum_kernel(SegArgs a)
 {
     __shared__ int s_tco[DQRM_MAX_TABLES + 1];
     __shared__ int s_tuo[DQRM_MAX_TABLES + 1];
     __shared__ int s_base[DQRM_MAX_TABLES];
+    __shared__ int s_w[kSegThreads / kWave];
+    __shared__ unsigned s_max[DQRM_MAX_TABLES];
     const int T = a.T, D = a.D;
-    for (int k = threadIdx.x; k <= T; k += kSegThreads) {
-        s_tco[k] = a.ws.table_chunk_offsets[k];
-        s_tuo[k] = a.tuo[k];
-        if (k < T) s_base[k] = a.ws.table_base[k];
+    BlockAbsmax amax;
+    amax.init(s_max, T);
+    table_offsets_to_lds(a.ws, T, s_tuo, s_tco, s_base, s_w);
+    if (blockIdx.x == 0) { // publish the offsets: outputs of the call, and inputs of the next kernels
+        for (int k = threadIdx.x; k <= T; k += kSegThreads) {
+            a.tuo[k] = s_tuo[k];
+            a.ws.table_chunk_offsets[k] = s_tco[k];
+        }
+        if (threadIdx.x == 0) {
+            *a.num_unique = s_tuo[T];
+            a.seg_offsets[s_tuo[T]] = (int32_t)a.N;
+        }
     }
-    __syncthreads();
 
     const int lg = threadIdx.x & (G - 1);
     const int grp = threadIdx.x / G;
@@ -381,9 +492,8 @@ __global__ __launch_bounds__(kSegThreads) void segsum_kernel(SegArgs a)
     const int per_block = (C + (int)gridDim.x - 1) / (int)gridDim.x;
     const int c_begin = (int)blockIdx.x * per_block;
     const int c_end = min(C, c_begin + per_block);
-
-    int cur_t = -1;
-    float cur_max = 0.0f;
+    const int leader = (threadIdx.x & (kWave - 1)) & ~(G - 1);
+    const int64_t tD = (int64_t)T * D;
 
     for (int c = c_begin + grp; c < c_end; c += kGroups) {
         const int t = table_of(s_tco, T, c);
@@ -399,72 +509,136 @@ __global__ __launch_bounds__(kSegThreads) void segsum_kernel(SegArgs a)
         const int nchunks = (s1 - s0 + DQRM_SEG_CHUNK - 1) / DQRM_SEG_CHUNK;
         const int kchunk = (start - s0) / DQRM_SEG_CHUNK;
         const int *bags = a.ws.sorted_bag + base + start;
-        const int64_t tD = (int64_t)T * D;
         const float *g0 = a.grad_out + (int64_t)t * D + col;
 
+        // bag of every contribution: each lane fetches its share of the chunk's
+        // bag list once, the group then passes them round with shuffles
+        constexpr int kIdsPerLane = (DQRM_SEG_CHUNK + G - 1) / G;
+        int my_bags[kIdsPerLane];
+#pragma unroll
+        for (int q = 0; q < kIdsPerLane; ++q) {
+            const int i = q * G + lg;
+            my_bags[q] = (i < len) ? bags[i] : 0;
+        }
         float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
-        if (col_ok && len > 0) {
-            acc = *reinterpret_cast<const float4 *>(g0 + (int64_t)bags[0] * tD);
-#pragma unroll 4
-            for (int i = 1; i < len; ++i) {
-                float4 g = *reinterpret_cast<const float4 *>(g0 + (int64_t)bags[i] * tD);
-                acc = f4_add(acc, g);
+        constexpr int kBatch = 8; // rows requested before the first is added
+#pragma unroll
+        for (int i0 = 0; i0 < DQRM_SEG_CHUNK; i0 += kBatch) {
+            if (i0 < len) {
+                float4 g[kBatch];
+#pragma unroll
+                for (int q = 0; q < kBatch; ++q) {
+                    const int i = i0 + q;
+                    g[q] = make_float4(0.f, 0.f, 0.f, 0.f);
+                    if (i < len) {
+                        const int b = __shfl(my_bags[i / G], leader + (i % G), kWave);
+                        if (col_ok) g[q] = *reinterpret_cast<const float4 *>(g0 + (int64_t)b * tD);
+                    }
+                }
+#pragma unroll
+                for (int q = 0; q < kBatch; ++q) {
+                    const int i = i0 + q;
+                    if (i < len) acc = (i == 0) ? g[q] : f4_add(acc, g[q]);
+                }
             }
         }
 
-        const int j = s_tuo[t] + seg; // global segment
-        bool final_here = true;
         if (nchunks > 1) {
-            // long segment: publish this chunk's partial, the last arrival combines
-            const int gpos = base + s0; // global sorted position of the segment's head
-            const int slot_seg = gpos / DQRM_SEG_CHUNK;
-            const bool is_last_chunk = (kchunk == nchunks - 1);
-            float *pslot = is_last_chunk ? a.ws.partial_last + (int64_t)slot_seg * D
-                                         : a.ws.partial_full + (int64_t)((base + start) / DQRM_SEG_CHUNK) * D;
+            // chunk of a long segment: store the partial sum for the combine kernel.
+            // Full chunks are disjoint runs of DQRM_SEG_CHUNK sorted positions, so
+            // (position / DQRM_SEG_CHUNK) names them uniquely; the last chunk of a
+            // segment is filed under the slot of the segment's first chunk.
+            const int gpos = base + s0;
+            float *pslot = (kchunk == nchunks - 1)
+                               ? a.ws.partial_last + (int64_t)(gpos / DQRM_SEG_CHUNK) * D
+                               : a.ws.partial_full + (int64_t)((base + start) / DQRM_SEG_CHUNK) * D;
             if (col_ok) *reinterpret_cast<float4 *>(pslot + col) = acc;
-            __threadfence();
-            unsigned arrived = 0;
-            if (lg == 0) arrived = atomicAdd(a.ws.seg_counter + slot_seg, 1u);
-            arrived = __shfl(arrived, (threadIdx.x & (kWave - 1)) & ~(G - 1), kWave);
-            final_here = (arrived == (unsigned)(nchunks - 1));
-            if (final_here) {
-                __threadfence();
-                if (col_ok) {
-                    for (int k = 0; k < nchunks; ++k) {
-                        const float *ps = (k == nchunks - 1)
-                                              ? a.ws.partial_last + (int64_t)slot_seg * D
-                                              : a.ws.partial_full + (int64_t)((gpos + k * DQRM_SEG_CHUNK) / DQRM_SEG_CHUNK) * D;
-                        float4 pv = load_coherent_f4(ps + col);
-                        acc = (k == 0) ? pv : f4_add(acc, pv);
-                    }
-                }
-                if (lg == 0) a.ws.seg_counter[slot_seg] = 0u; // ready for the next call
-            }
-        }
-        if (final_here) {
+        } else {
+            const int j = s_tuo[t] + seg; // global segment
             if (col_ok) *reinterpret_cast<float4 *>(a.values + (int64_t)j * D + col) = acc;
             if (lg == 0) {
                 a.uniq_rows[j] = (int64_t)a.ws.seg_row[sb + seg];
                 a.seg_offsets[j] = base + s0;
             }
-            float m = fmaxf(fmaxf(fabsf(acc.x), fabsf(acc.y)), fmaxf(fabsf(acc.z), fabsf(acc.w)));
-            if (t != cur_t) {
-                if (cur_t >= 0 && cur_max > 0.0f) atomic_max_nonneg(a.g_absmax + cur_t, cur_max);
-                cur_t = t;
-                cur_max = 0.0f;
-            }
-            cur_max = fmaxf(cur_max, m);
+            if (col_ok) amax.add(t, f4_absmax(acc));
         }
     }
+    amax.flush(a.ws.absmax_slots, T);
+}
 
-    // flush the running maxima: one atomic per wave when the wave saw one table
-    const int tt = wave_max_int(cur_t);
-    if (__all(cur_t < 0 || cur_t == tt)) {
-        const float m = wave_max(cur_max);
-        if ((threadIdx.x & (kWave - 1)) == 0 && tt >= 0 && m > 0.0f) atomic_max_nonneg(a.g_absmax + tt, m);
-    } else if (cur_t >= 0 && cur_max > 0.0f) {
-        atomic_max_nonneg(a.g_absmax + cur_t, cur_max);
+// One lane group per segment; only segments of more than one chunk have work.
+template <int G>
+__global__ __launch_bounds__(kSegThreads) void combine_kernel(SegArgs a)
+{
+    __shared__ int s_tuo[DQRM_MAX_TABLES + 1];
+    __shared__ int s_base[DQRM_MAX_TABLES];
+    __shared__ unsigned s_max[DQRM_MAX_TABLES];
+    const int T = a.T, D = a.D;
+    BlockAbsmax amax;
+    amax.init(s_max, T);
+    for (int k = threadIdx.x; k <= T; k += kSegThreads) {
+        s_tuo[k] = a.tuo[k];
+        if (k < T) s_base[k] = a.ws.table_base[k];
     }
+    __syncthreads();
+    const int lg = threadIdx.x & (G - 1);
+    constexpr int kGroups = kSegThreads / G;
+    const int col = lg * 4;
+    const bool col_ok = col < D;
+    const int U = s_tuo[T];
+
+    for (int j = (int)blockIdx.x * kGroups + threadIdx.x / G; j < U; j += (int)gridDim.x * kGroups) {
+        const int t = table_of(s_tuo, T, j);
+        const int seg = j - s_tuo[t];
+        const int base = s_base[t];
+        const int sb = base + t;
+        const int s0 = a.ws.seg_start[sb + seg];
+        const int s1 = a.ws.seg_start[sb + seg + 1];
+        const int nchunks = (s1 - s0 + DQRM_SEG_CHUNK - 1) / DQRM_SEG_CHUNK;
+        if (nchunks <= 1) continue;
+        const int gpos = base + s0;
+        // the k-th full chunk of the segment starts at sorted position gpos + 32 k
+        const float *p_last = a.ws.partial_last + (int64_t)(gpos / DQRM_SEG_CHUNK) * D + col;
+        float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
+        if (col_ok) {
+            constexpr int kCb = 8; // partials requested before the first is added
+            for (int k0 = 0; k0 < nchunks; k0 += kCb) {
+                float4 pv[kCb];
+#pragma unroll
+                for (int q = 0; q < kCb; ++q) {
+                    const int k = k0 + q;
+                    if (k < nchunks) {
+                        const float *pf =
+                            a.ws.partial_full + (int64_t)((gpos + k * DQRM_SEG_CHUNK) / DQRM_SEG_CHUNK) * D + col;
+                        pv[q] = *reinterpret_cast<const float4 *>(k == nchunks - 1 ? p_last : pf);
+                    }
+                }
+#pragma unroll
+                for (int q = 0; q < kCb; ++q) {
+                    const int k = k0 + q;
+                    if (k < nchunks) acc = (k == 0) ? pv[q] : f4_add(acc, pv[q]);
+                }
+            }
+            *reinterpret_cast<float4 *>(a.values + (int64_t)j * D + col) = acc;
+        }
+        if (lg == 0) {
+            a.uniq_rows[j] = (int64_t)a.ws.seg_row[sb + seg];
+            a.seg_offsets[j] = gpos;
+        }
+        if (col_ok) amax.add(t, f4_absmax(acc));
+    }
+    amax.flush(a.ws.absmax_slots, T);
+}
+
+// g_absmax[t] = max over the table's slots
+__global__ void absmax_finalize_kernel(const float *__restrict__ slots, int T, float *__restrict__ g_absmax)
+{
+    const int t = blockIdx.x * blockDim.x + threadIdx.x;
+    if (t >= T) return;
+    float m = 0.0f;
+#pragma unroll
+    for (int k = 0; k < kAbsmaxSlots; ++k) m = fmaxf(m, slots[((int64_t)t * kAbsmaxSlots + k) * kAbsmaxStride]);
+    g_absmax[t] = m;
 }
 
 } // namespace dqrm

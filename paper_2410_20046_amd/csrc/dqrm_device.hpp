@@ -61,25 +61,43 @@ __device__ __forceinline__ unsigned pack4(float q0, float q1, float q2, float q3
 // ---- wave / block primitives ---------------------------------------------------
 __device__ __forceinline__ int lane_id() { return __builtin_amdgcn_mbcnt_hi(~0u, __builtin_amdgcn_mbcnt_lo(~0u, 0u)); }
 
-__device__ __forceinline__ int wave_incl_scan_add(int v, int lane)
+// DPP moves: lanes whose source lies outside the row (or whose row is masked
+// off) receive `identity`.
+template <int kCtrl, int kRowMask>
+__device__ __forceinline__ int dpp_or(int identity, int v)
 {
-#pragma unroll
-    for (int d = 1; d < kWave; d <<= 1) {
-        int o = __shfl_up(v, d, kWave);
-        if (lane >= d) v += o;
-    }
+    return __builtin_amdgcn_update_dpp(identity, v, kCtrl, kRowMask, 0xF, false);
+}
+
+constexpr int kDppRowShr1 = 0x111, kDppRowShr2 = 0x112, kDppRowShr4 = 0x114, kDppRowShr8 = 0x118;
+constexpr int kDppRowBcast15 = 0x142, kDppRowBcast31 = 0x143;
+
+// inclusive scans over the 64 lanes of a wave: four shifts inside each row of
+// 16 lanes, then the row totals are passed on to the following rows
+__device__ __forceinline__ int wave_incl_scan_add(int v, int /*lane*/)
+{
+    v += dpp_or<kDppRowShr1, 0xF>(0, v);
+    v += dpp_or<kDppRowShr2, 0xF>(0, v);
+    v += dpp_or<kDppRowShr4, 0xF>(0, v);
+    v += dpp_or<kDppRowShr8, 0xF>(0, v);
+    v += dpp_or<kDppRowBcast15, 0xA>(0, v);
+    v += dpp_or<kDppRowBcast31, 0xC>(0, v);
     return v;
 }
 
-__device__ __forceinline__ int wave_incl_scan_max(int v, int lane)
+// values must be >= -1 (the identity used for lanes without a source)
+__device__ __forceinline__ int wave_incl_scan_max(int v, int /*lane*/)
 {
-#pragma unroll
-    for (int d = 1; d < kWave; d <<= 1) {
-        int o = __shfl_up(v, d, kWave);
-        if (lane >= d) v = max(v, o);
-    }
+    v = max(v, dpp_or<kDppRowShr1, 0xF>(-1, v));
+    v = max(v, dpp_or<kDppRowShr2, 0xF>(-1, v));
+    v = max(v, dpp_or<kDppRowShr4, 0xF>(-1, v));
+    v = max(v, dpp_or<kDppRowShr8, 0xF>(-1, v));
+    v = max(v, dpp_or<kDppRowBcast15, 0xA>(-1, v));
+    v = max(v, dpp_or<kDppRowBcast31, 0xC>(-1, v));
     return v;
 }
+
+__device__ __forceinline__ int wave_last(int v) { return __builtin_amdgcn_readlane(v, kWave - 1); }
 
 __device__ __forceinline__ float wave_max(float v)
 {

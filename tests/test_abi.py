@@ -101,8 +101,6 @@ def test_validation_errors_before_any_launch():
     assert bwd(nu=None) == dq.ERR_INVALID_ARG
     assert bwd(values=FAKE + 4) == dq.ERR_INVALID_ARG
     assert bwd(tb=_tables(D=20)) == dq.ERR_UNSUPPORTED
-    assert L.dqrm_workspace_init(None, 1 << 20, S) == dq.ERR_INVALID_ARG
-    assert L.dqrm_workspace_init(FAKE, 16, S) == dq.ERR_INVALID_ARG
     # quantise / update
     gq = lambda T=2, D=16, cap=8, v=FAKE, tuo=FAKE, am=FAKE, q=FAKE, gs=FAKE: L.dqrm_grad_quant_int8(
         T, D, cap, v, tuo, am, q, gs, S)

@@ -62,6 +62,10 @@ def main():
     ap.add_argument("--pool", type=int, default=64, help="distinct index batches cycled")
     ap.add_argument("--grad-pool", type=int, default=8, help="distinct grad_out buffers cycled")
     ap.add_argument("--lr", type=float, default=0.1)
+    ap.add_argument("--overlap", default="pipeline", choices=["none", "fwd", "pipeline"],
+                    help="where dqrm_dedupe (needs only the indices) runs: none = in line on the one stream; "
+                         "fwd = on a second stream beside the same step's forward; pipeline = on a second stream, "
+                         "one step ahead (double-buffered workspace)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=12.0)
     args = ap.parse_args()
@@ -104,9 +108,45 @@ def main():
     dq.dqrm_pack_int4(tables)
     torch.cuda.synchronize()
 
+    main = torch.cuda.current_stream()
+    side = torch.cuda.Stream()  # default priority
+    nbuf = 2 if args.overlap == "pipeline" else 1
+    wss = [bufs.workspace] + [torch.empty_like(bufs.workspace) for _ in range(nbuf - 1)]
+    dup = lambda x: [x] + [torch.empty_like(x) for _ in range(nbuf - 1)]
+    sps, urs, sos = dup(bufs.sorted_pos), dup(bufs.uniq_rows), dup(bufs.seg_offsets)
+    tuos, nus = dup(bufs.table_uniq_offsets), dup(bufs.num_unique)
+    ev_dedupe = [torch.cuda.Event() for _ in range(nbuf)]   # dedupe into buffer i finished
+    ev_segsum = [torch.cuda.Event() for _ in range(nbuf)]   # last reader (the update) of buffer i finished
+    batch_of = lambda k: (idx_d[k % args.pool], off_d[k % args.pool])
+
+    def dedupe_on_side(k):
+        i = k % nbuf
+        side.wait_event(ev_segsum[i])  # the buffer's previous reader (no-op before the first record)
+        ix, of = batch_of(k)
+        dq.dqrm_dedupe(tables, ix, of, B, sps[i], urs[i], sos[i], tuos[i], nus[i], wss[i], stream=side)
+        ev_dedupe[i].record(side)
+
+    primed = [False]
+
     def step(k):
-        dq.dqrm_fwd_bwd_step(tables, bufs, idx_d[k % args.pool], off_d[k % args.pool], grad_d[k % args.grad_pool],
-                             args.lr, mode)
+        ix, of = batch_of(k)
+        if args.overlap == "none":
+            dq.dqrm_fwd_bwd_step(tables, bufs, ix, of, grad_d[k % args.grad_pool], args.lr, mode)
+            return
+        i = k % nbuf
+        if args.overlap == "fwd" or not primed[0]:
+            if not primed[0]:
+                side.wait_stream(main)  # first use: everything enqueued so far (uploads, packing) is done
+                primed[0] = True
+            dedupe_on_side(k)
+        dq.dqrm_embbag_fwd(tables, ix, of, B, mode, bufs.out, None)
+        if args.overlap == "pipeline":
+            dedupe_on_side(k + 1)  # the next batch's indices are already here
+        main.wait_event(ev_dedupe[i])
+        dq.dqrm_segment_sum(tables, B, N, grad_d[k % args.grad_pool], bufs.values, bufs.g_absmax, wss[i])
+        dq.dqrm_grad_quant_int8(T, D, bufs.cap, bufs.values, tuos[i], bufs.g_absmax, bufs.gq, bufs.g_scale)
+        dq.dqrm_sparse_update(tables, bufs.cap, urs[i], tuos[i], bufs.gq, bufs.g_scale, args.lr)
+        ev_segsum[i].record(main)  # the last reader of this dedupe result is done
 
     # ---- warm-up, then the timed region: exactly K steps, one stream, no host sync inside ----
     for k in range(args.warmup):
@@ -229,8 +269,8 @@ def main():
         "data": "synthetic",
         "config": {"workload": f"{args.workload}-shaped embedding layer: {T} tables, {wl.R} rows, dim {D}, batch {B}, "
                                f"1 Zipf index per table per sample, {args.mode}-mode forward, INT8 sparse grads, "
-                               f"SGD lr {args.lr}",
-                   "lookups_per_step": N, "unique_rows_per_step": round(U, 1), "fwd_mode": args.mode},
+                               f"SGD lr {args.lr}, dedupe overlap: {args.overlap}",
+                   "lookups_per_step": N, "unique_rows_per_step": round(U, 1), "fwd_mode": args.mode, "overlap": args.overlap},
         "roofline": roofline,
         "cpu_baseline": cpu,
         "step_algorithmic_bytes": int(ab["step"]),

@@ -128,12 +128,29 @@ size_t dqrm_embbag_bwd_workspace_bytes(int32_t num_tables, int32_t dim, int32_t 
  *   num_unique [1] int32               U (stays on the device: the following calls read it there)
  *   values [num_indices][D] fp32       first U rows: the summed row gradients (order: DQRM_SEG_CHUNK)
  *   g_absmax [T] fp32                  max |values| over the table's segments, 0 if none
- * Entries past U (U+1) of the capacity-sized outputs are left untouched. */
+ * Entries past U (U+1) of the capacity-sized outputs are left untouched.
+ * Equivalent to dqrm_dedupe followed by dqrm_segment_sum on the same stream. */
 int32_t dqrm_embbag_bwd(const dqrm_tables_t *tables, const int64_t *indices, const int64_t *offsets,
                         int32_t batch, int64_t num_indices, const float *grad_out, int32_t *sorted_pos,
                         int64_t *uniq_rows, int32_t *seg_offsets, int32_t *table_uniq_offsets,
                         int32_t *num_unique, float *values, float *g_absmax, void *workspace,
                         size_t workspace_bytes, void *stream);
+
+/* The two halves of dqrm_embbag_bwd, for callers that overlap them with other
+ * work.  dqrm_dedupe (the sparse-tensor coalescing of Sec. 4.3: sort the lookups
+ * by table, row, position and find the distinct rows) needs only the batch's
+ * indices, so it can run on a second stream beside the forward pass, or one
+ * step ahead; it writes every index-only output (sorted_pos, uniq_rows,
+ * seg_offsets, table_uniq_offsets, num_unique) and leaves the work list of the
+ * segment sums in `workspace`.  dqrm_segment_sum then needs that workspace (the
+ * caller orders the two, e.g. with an event) and grad_out, and writes `values`
+ * and `g_absmax`; it may be repeated on the same dedupe result. */
+int32_t dqrm_dedupe(const dqrm_tables_t *tables, const int64_t *indices, const int64_t *offsets, int32_t batch,
+                    int64_t num_indices, int32_t *sorted_pos, int64_t *uniq_rows, int32_t *seg_offsets,
+                    int32_t *table_uniq_offsets, int32_t *num_unique, void *workspace, size_t workspace_bytes,
+                    void *stream);
+int32_t dqrm_segment_sum(const dqrm_tables_t *tables, int32_t batch, int64_t num_indices, const float *grad_out,
+                         float *values, float *g_absmax, void *workspace, size_t workspace_bytes, void *stream);
 
 /* Distributed-training appendix (only the values of the sparse gradient are
  * quantised; the indices are left alone): one scale per table per step,

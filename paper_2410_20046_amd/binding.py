@@ -33,7 +33,7 @@ SEG_CHUNK = 32
 MAX_TABLE_LOOKUPS = 16384
 
 EXPORTS = ("dqrm_find_scale", "dqrm_pack_int4", "dqrm_embbag_fwd", "dqrm_embbag_bwd_workspace_bytes",
-           "dqrm_embbag_bwd", "dqrm_grad_quant_int8", "dqrm_sparse_update",
+           "dqrm_embbag_bwd", "dqrm_dedupe", "dqrm_segment_sum", "dqrm_grad_quant_int8", "dqrm_sparse_update",
            "dqrm_check_status", "dqrm_last_hip_error", "dqrm_version")
 
 
@@ -68,10 +68,12 @@ def lib() -> C.CDLL:
         L.dqrm_embbag_bwd_workspace_bytes.argtypes = [i32, i32, i32, i64]
         L.dqrm_embbag_bwd_workspace_bytes.restype = sz
         L.dqrm_embbag_bwd.argtypes = [tp, vp, vp, i32, i64, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+        L.dqrm_dedupe.argtypes = [tp, vp, vp, i32, i64, vp, vp, vp, vp, vp, vp, sz, vp]
+        L.dqrm_segment_sum.argtypes = [tp, i32, i64, vp, vp, vp, vp, sz, vp]
         L.dqrm_grad_quant_int8.argtypes = [i32, i32, i64, vp, vp, vp, vp, vp, vp]
         L.dqrm_sparse_update.argtypes = [tp, i64, vp, vp, vp, vp, C.c_float, vp]
         L.dqrm_check_status.argtypes = [vp, C.POINTER(i32), C.POINTER(i64)]
-        for n in ("dqrm_find_scale", "dqrm_pack_int4", "dqrm_embbag_fwd", "dqrm_embbag_bwd",
+        for n in ("dqrm_find_scale", "dqrm_pack_int4", "dqrm_embbag_fwd", "dqrm_embbag_bwd", "dqrm_dedupe", "dqrm_segment_sum",
                   "dqrm_grad_quant_int8", "dqrm_sparse_update", "dqrm_check_status"):
             getattr(L, n).restype = i32
         L.dqrm_last_hip_error.restype = C.c_char_p
@@ -154,6 +156,22 @@ def dqrm_embbag_bwd(tables: Tables, indices: torch.Tensor, offsets: torch.Tensor
                                  _ptr(sorted_pos), _ptr(uniq_rows), _ptr(seg_offsets), _ptr(table_uniq_offsets),
                                  _ptr(num_unique), _ptr(values), _ptr(g_absmax), _ptr(workspace),
                                  workspace.numel() * workspace.element_size(), _stream(stream)), "dqrm_embbag_bwd")
+
+
+def dqrm_dedupe(tables: Tables, indices: torch.Tensor, offsets: torch.Tensor, batch: int, sorted_pos: torch.Tensor,
+                uniq_rows: torch.Tensor, seg_offsets: torch.Tensor, table_uniq_offsets: torch.Tensor,
+                num_unique: torch.Tensor, workspace: torch.Tensor, stream=None) -> None:
+    _check(lib().dqrm_dedupe(tables.ref, _ptr(indices), _ptr(offsets), batch, indices.numel(), _ptr(sorted_pos),
+                             _ptr(uniq_rows), _ptr(seg_offsets), _ptr(table_uniq_offsets), _ptr(num_unique),
+                             _ptr(workspace), workspace.numel() * workspace.element_size(), _stream(stream)),
+           "dqrm_dedupe")
+
+
+def dqrm_segment_sum(tables: Tables, batch: int, num_indices: int, grad_out: torch.Tensor, values: torch.Tensor,
+                     g_absmax: torch.Tensor, workspace: torch.Tensor, stream=None) -> None:
+    _check(lib().dqrm_segment_sum(tables.ref, batch, num_indices, _ptr(grad_out), _ptr(values), _ptr(g_absmax),
+                                  _ptr(workspace), workspace.numel() * workspace.element_size(), _stream(stream)),
+           "dqrm_segment_sum")
 
 
 def dqrm_grad_quant_int8(num_tables: int, dim: int, capacity: int, values: torch.Tensor,

@@ -70,8 +70,8 @@ int32_t check_batch(const dqrm_tables_t *tb, const int64_t *indices, const int64
 
 // ---- workspace layout of dqrm_embbag_bwd -------------------------------------
 struct WsLayout {
-    size_t off_table_base, off_table_nuniq, off_table_nchunk, off_tco, off_bag_of_pos, off_sorted_bag, off_seg_row,
-        off_seg_start, off_chunk_start, off_chunk_seg, off_partial_full, off_partial_last, off_absmax_slots, total;
+    size_t off_table_base, off_table_nuniq, off_table_nchunk, off_totals, off_bag_of_pos, off_sorted_bag,
+        off_chunk_local, off_chunk_desc, off_partial_full, off_partial_last, off_absmax_slots, total;
 };
 
 size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
@@ -89,13 +89,11 @@ WsLayout ws_layout(int32_t T, int32_t D, int64_t N)
     L.off_table_base = take(t * sizeof(int));
     L.off_table_nuniq = take(t * sizeof(int));
     L.off_table_nchunk = take(t * sizeof(int));
-    L.off_tco = take((t + 1) * sizeof(int));
+    L.off_totals = take(2 * sizeof(int));
     L.off_bag_of_pos = take(n * sizeof(int));
     L.off_sorted_bag = take(n * sizeof(int));
-    L.off_seg_row = take((n + t + 1) * sizeof(unsigned));
-    L.off_seg_start = take((n + t + 1) * sizeof(int));
-    L.off_chunk_start = take(n * sizeof(int));
-    L.off_chunk_seg = take(n * sizeof(int));
+    L.off_chunk_local = take(n * 16);
+    L.off_chunk_desc = take(n * 16);
     L.off_partial_full = take(slots * (size_t)D * sizeof(float));
     L.off_partial_last = take(slots * (size_t)D * sizeof(float));
     L.off_absmax_slots = take(t * dqrm::kAbsmaxSlots * dqrm::kAbsmaxStride * sizeof(float));
@@ -110,13 +108,11 @@ dqrm::BwdWs ws_views(void *workspace, const WsLayout &L)
     w.table_base = reinterpret_cast<int *>(b + L.off_table_base);
     w.table_nuniq = reinterpret_cast<int *>(b + L.off_table_nuniq);
     w.table_nchunk = reinterpret_cast<int *>(b + L.off_table_nchunk);
-    w.table_chunk_offsets = reinterpret_cast<int *>(b + L.off_tco);
+    w.totals = reinterpret_cast<int *>(b + L.off_totals);
     w.bag_of_pos = reinterpret_cast<int *>(b + L.off_bag_of_pos);
     w.sorted_bag = reinterpret_cast<int *>(b + L.off_sorted_bag);
-    w.seg_row = reinterpret_cast<unsigned *>(b + L.off_seg_row);
-    w.seg_start = reinterpret_cast<int *>(b + L.off_seg_start);
-    w.chunk_start = reinterpret_cast<int *>(b + L.off_chunk_start);
-    w.chunk_seg = reinterpret_cast<int *>(b + L.off_chunk_seg);
+    w.chunk_local = reinterpret_cast<int4 *>(b + L.off_chunk_local);
+    w.chunk_desc = reinterpret_cast<int4 *>(b + L.off_chunk_desc);
     w.partial_full = reinterpret_cast<float *>(b + L.off_partial_full);
     w.partial_last = reinterpret_cast<float *>(b + L.off_partial_last);
     w.absmax_slots = reinterpret_cast<float *>(b + L.off_absmax_slots);
@@ -253,9 +249,7 @@ int32_t dqrm_embbag_fwd(const dqrm_tables_t *tables, const int64_t *indices, con
     a.num_bags = (int64_t)a.T * a.B;
 
     const int G = pow2ceil(a.D / 4);
-    const int64_t groups = (a.num_bags + dqrm::kBagsPerGroup - 1) / dqrm::kBagsPerGroup;
-    const int64_t threads = groups * G;
-    const int64_t blocks = (threads + dqrm::kFwdThreads - 1) / dqrm::kFwdThreads;
+    const int64_t blocks = (a.num_bags + dqrm::kFwdTile - 1) / dqrm::kFwdTile;
     hipStream_t st = static_cast<hipStream_t>(stream);
     if (mode == DQRM_FWD_PACKED)
         launch_fwd<true>(G, dim3((unsigned)blocks), st, a);
@@ -273,51 +267,87 @@ size_t dqrm_embbag_bwd_workspace_bytes(int32_t num_tables, int32_t dim, int32_t 
     return ws_layout(num_tables, dim, num_indices).total;
 }
 
-int32_t dqrm_embbag_bwd(const dqrm_tables_t *tables, const int64_t *indices, const int64_t *offsets, int32_t batch,
-                        int64_t num_indices, const float *grad_out, int32_t *sorted_pos, int64_t *uniq_rows,
-                        int32_t *seg_offsets, int32_t *table_uniq_offsets, int32_t *num_unique, float *values,
-                        float *g_absmax, void *workspace, size_t workspace_bytes, void *stream)
+int32_t dqrm_dedupe(const dqrm_tables_t *tables, const int64_t *indices, const int64_t *offsets, int32_t batch,
+                    int64_t num_indices, int32_t *sorted_pos, int64_t *uniq_rows, int32_t *seg_offsets,
+                    int32_t *table_uniq_offsets, int32_t *num_unique, void *workspace, size_t workspace_bytes,
+                    void *stream)
 {
     int64_t R = 0;
     int32_t rc = check_tables(tables, false, &R);
     if (rc != DQRM_OK) return rc;
     rc = check_batch(tables, indices, offsets, batch, num_indices);
     if (rc != DQRM_OK) return rc;
-    if (!grad_out || !sorted_pos || !uniq_rows || !seg_offsets || !table_uniq_offsets || !num_unique || !values ||
-        !g_absmax || !workspace)
+    if (!sorted_pos || !uniq_rows || !seg_offsets || !table_uniq_offsets || !num_unique || !workspace ||
+        !aligned(workspace, 256))
         return DQRM_ERR_INVALID_ARG;
+    const int T = tables->num_tables, D = tables->dim;
+    const WsLayout L = ws_layout(T, D, num_indices);
+    if (workspace_bytes < L.total) return DQRM_ERR_WORKSPACE_TOO_SMALL;
+
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    dqrm::FinishArgs fa;
+    fa.ws = ws_views(workspace, L);
+    fa.tuo = table_uniq_offsets;
+    fa.num_unique = num_unique;
+    fa.uniq_rows = uniq_rows;
+    fa.seg_offsets = seg_offsets;
+    fa.N = num_indices;
+    fa.T = T;
+    hipLaunchKernelGGL(dqrm::dedupe_kernel, dim3(T), dim3(dqrm::kDdThreads), 0, st, indices, offsets,
+                       tables->row_offsets_dev, T, (int)batch, num_indices, fa.ws, sorted_pos);
+    hipLaunchKernelGGL(dqrm::dedupe_finish_kernel, dim3(grid_for(num_indices, dqrm::kSegThreads, 2)),
+                       dim3(dqrm::kSegThreads), 0, st, fa);
+    DQRM_HIP_CHECK(hipGetLastError());
+    return DQRM_OK;
+}
+
+int32_t dqrm_segment_sum(const dqrm_tables_t *tables, int32_t batch, int64_t num_indices, const float *grad_out,
+                         float *values, float *g_absmax, void *workspace, size_t workspace_bytes, void *stream)
+{
+    int64_t R = 0;
+    int32_t rc = check_tables(tables, false, &R);
+    if (rc != DQRM_OK) return rc;
+    if (batch < 1 || num_indices < 0) return DQRM_ERR_INVALID_ARG;
+    if (num_indices > kMaxIndices || (int64_t)batch * tables->num_tables > kMaxIndices) return DQRM_ERR_UNSUPPORTED;
+    if (!grad_out || !values || !g_absmax || !workspace) return DQRM_ERR_INVALID_ARG;
     if (!aligned(grad_out, 16) || !aligned(values, 16) || !aligned(workspace, 256)) return DQRM_ERR_INVALID_ARG;
     const int T = tables->num_tables, D = tables->dim;
     const WsLayout L = ws_layout(T, D, num_indices);
     if (workspace_bytes < L.total) return DQRM_ERR_WORKSPACE_TOO_SMALL;
 
     hipStream_t st = static_cast<hipStream_t>(stream);
-    dqrm::BwdWs ws = ws_views(workspace, L);
-    hipLaunchKernelGGL(dqrm::dedupe_kernel, dim3(T), dim3(dqrm::kDdThreads), 0, st, indices, offsets,
-                       tables->row_offsets_dev, T, (int)batch, num_indices, ws, sorted_pos);
-
     dqrm::SegArgs sa;
     sa.grad_out = grad_out;
-    sa.ws = ws;
-    sa.tuo = table_uniq_offsets;
-    sa.num_unique = num_unique;
+    sa.ws = ws_views(workspace, L);
     sa.N = num_indices;
-    sa.uniq_rows = uniq_rows;
-    sa.seg_offsets = seg_offsets;
     sa.values = values;
     sa.g_absmax = g_absmax;
     sa.T = T;
     sa.B = batch;
     sa.D = D;
     const int G = pow2ceil(D / 4);
-    // at most one lane group per possible chunk / segment, at least one block
-    const int grid_sum = grid_for(num_indices * G, dqrm::kSegThreads, 8);
+    // at most one lane group per possible chunk, at least one block
+    const int grid_sum = grid_for(num_indices * G, dqrm::kSegThreads, dqrm::kSegBlocksPerCu);
     const int grid_comb = grid_for(num_indices * G, dqrm::kSegThreads, 4);
     launch_segsum(G, dim3(grid_sum), dim3(grid_comb), st, sa);
-    hipLaunchKernelGGL(dqrm::absmax_finalize_kernel, dim3((T + 255) / 256), dim3(256), 0, st, ws.absmax_slots, T,
+    hipLaunchKernelGGL(dqrm::absmax_finalize_kernel, dim3((T + 255) / 256), dim3(256), 0, st, sa.ws.absmax_slots, T,
                        g_absmax);
     DQRM_HIP_CHECK(hipGetLastError());
     return DQRM_OK;
+}
+
+int32_t dqrm_embbag_bwd(const dqrm_tables_t *tables, const int64_t *indices, const int64_t *offsets, int32_t batch,
+                        int64_t num_indices, const float *grad_out, int32_t *sorted_pos, int64_t *uniq_rows,
+                        int32_t *seg_offsets, int32_t *table_uniq_offsets, int32_t *num_unique, float *values,
+                        float *g_absmax, void *workspace, size_t workspace_bytes, void *stream)
+{
+    // validate everything before the first launch
+    if (!grad_out || !values || !g_absmax) return DQRM_ERR_INVALID_ARG;
+    if (!aligned(grad_out, 16) || !aligned(values, 16)) return DQRM_ERR_INVALID_ARG;
+    int32_t rc = dqrm_dedupe(tables, indices, offsets, batch, num_indices, sorted_pos, uniq_rows, seg_offsets,
+                             table_uniq_offsets, num_unique, workspace, workspace_bytes, stream);
+    if (rc != DQRM_OK) return rc;
+    return dqrm_segment_sum(tables, batch, num_indices, grad_out, values, g_absmax, workspace, workspace_bytes, stream);
 }
 
 int32_t dqrm_grad_quant_int8(int32_t num_tables, int32_t dim, int64_t capacity, const float *values,

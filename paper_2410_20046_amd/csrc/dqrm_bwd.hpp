@@ -6,13 +6,18 @@
 //   registers between passes; ranks come from per-wave digit counters and a
 //   wave-wide match of equal digits), marks segment heads and chunk heads,
 //   and writes table-local segment / chunk lists plus the table's counts.
-// Kernel 2 (chunk_sum_kernel): every workgroup first turns the per-table counts
-//   into offsets (T is small), then one lane group per chunk (<= DQRM_SEG_CHUNK
+// Kernel 2 (dedupe_finish_kernel): turns the per-table counts into offsets (T is
+//   small, every workgroup repeats the scan), writes the index-only outputs
+//   (unique rows, segment offsets, table offsets, count) and one dense list of
+//   16-byte chunk descriptors over all tables.
+// Kernels 1-2 need only the batch's indices; they form dqrm_dedupe.
+// Kernel 3 (chunk_sum_kernel): one lane group per chunk (<= DQRM_SEG_CHUNK
 //   consecutive contributions of one segment) adds its gradient rows left to
 //   right.  A segment of one chunk is final; chunks of longer segments store
 //   their partial sums.
-// Kernel 3 (combine_kernel): one lane group per long segment adds the chunk
-//   partials in chunk order.
+// Kernel 4 (combine_kernel): the last chunk of every long segment adds the
+//   segment's partials in chunk order.
+// Kernel 5 (absmax_finalize_kernel): folds the per-table maxima.
 // Kernel boundaries are the only synchronisation between workgroups, so the
 // result never depends on scheduling.
 #pragma once
@@ -26,19 +31,25 @@ constexpr int kDdWaves = kDdThreads / kWave;                      // 16
 constexpr int kDdMaxRounds = DQRM_MAX_TABLE_LOOKUPS / kDdThreads; // 16 items per thread at most
 constexpr int kDdCap = DQRM_MAX_TABLE_LOOKUPS;
 constexpr int kSegThreads = 256;
+#ifndef DQRM_SEG_BATCH
+#define DQRM_SEG_BATCH 16
+#endif
+#ifndef DQRM_SEG_BPC
+#define DQRM_SEG_BPC 8
+#endif
+constexpr int kSegBatch = DQRM_SEG_BATCH;      // gradient rows requested before the first is added
+constexpr int kSegBlocksPerCu = DQRM_SEG_BPC; // grid of the chunk-sum kernel, in workgroups per CU
 
 // Views into the caller's workspace (all device pointers).
 struct BwdWs {
     int *table_base;          // [T]   first lookup position of the table
     int *table_nuniq;         // [T]
     int *table_nchunk;        // [T]
-    int *table_chunk_offsets; // [T+1]
     int *bag_of_pos;          // [N]   bag (within its table) of every lookup position
     int *sorted_bag;          // [N]   bag of every sorted lookup
-    unsigned *seg_row;        // [N+T+1] table-local: row of segment
-    int *seg_start;           // [N+T+1] table-local: first sorted index of segment (+ end sentinel)
-    int *chunk_start;         // [N]   table-local: first sorted index of chunk
-    int *chunk_seg;           // [N]   table-local: segment of chunk
+    int4 *chunk_local;        // [N]   table-local chunk lists (table t's start at its first lookup position)
+    int4 *chunk_desc;         // [N]   dense chunk list over all tables, as the summing kernels read it
+    int *totals;              // [2]   chunks, segments
     float *partial_full;      // [(N/32 + 2) * D] partial of a full chunk of a long segment
     float *partial_last;      // [(N/32 + 2) * D] partial of the last chunk of a long segment
     float *absmax_slots;      // [T][kAbsmaxSlots] running maxima, one 128-byte line per entry
@@ -54,6 +65,22 @@ __device__ __forceinline__ float *absmax_slot(float *slots, int t, int k)
 {
     return slots + ((int64_t)t * kAbsmaxSlots + k) * kAbsmaxStride;
 }
+
+// A chunk = up to DQRM_SEG_CHUNK consecutive sorted lookups of one segment.  Its
+// descriptor is one 16-byte record, so that the summing kernels need a single
+// load to know their work:
+//   x  global sorted position of the chunk's first lookup
+//   y  len (bits 0..7) | index of the chunk inside its segment (bits 8..19) |
+//      chunks in the segment (bits 20..31)
+//   z  table-local index of the segment
+//   w  table-local row of the segment
+__device__ __forceinline__ int4 make_chunk_desc(int gstart, int len, int kchunk, int nchunks, int seg, unsigned row)
+{
+    return make_int4(gstart, len | (kchunk << 8) | (nchunks << 20), seg, (int)row);
+}
+__device__ __forceinline__ int desc_len(const int4 &d) { return d.y & 0xFF; }
+__device__ __forceinline__ int desc_kchunk(const int4 &d) { return (d.y >> 8) & 0xFFF; }
+__device__ __forceinline__ int desc_nchunks(const int4 &d) { return (int)((unsigned)d.y >> 20); }
 
 // Optional per-phase clock stamps of one workgroup of the dedupe kernel (developer
 // builds only: -DDQRM_PHASE_TIMING=<table>; the stamps are 100 MHz ticks).
@@ -96,6 +123,7 @@ __global__ __launch_bounds__(kDdThreads) void dedupe_kernel(const int64_t *__res
     __shared__ unsigned skey[kDdCap];        // 64 KB
     __shared__ unsigned short spos[kDdCap];  // 32 KB
     __shared__ unsigned cnt[kDdWaves * 256]; // 16 KB, cnt[wave * 256 + digit]
+    __shared__ unsigned short shead[kDdCap + 2]; // 32 KB, sorted index of each segment's head (+ end sentinel)
     __shared__ int s_w[kDdWaves];
     __shared__ int s_w2[kDdWaves];
 
@@ -305,6 +333,7 @@ __global__ __launch_bounds__(kDdThreads) void dedupe_kernel(const int64_t *__res
             seg_of[r] = seg_of[r] + heads_before - 1;
             start_of[r] = max(start_of[r], start_before);
             const bool valid = flags[r] & 1;
+            if (flags[r] & 2) shead[seg_of[r]] = (unsigned short)i;
             const bool chead = valid && (((i - start_of[r]) % DQRM_SEG_CHUNK) == 0);
             const int c = wave_incl_scan_add(chead ? 1 : 0, lane) + carry_chunks;
             carry_chunks = wave_last(c);
@@ -312,6 +341,7 @@ __global__ __launch_bounds__(kDdThreads) void dedupe_kernel(const int64_t *__res
             if (chead) flags[r] |= 4;
         }
     }
+    if (tid == 0) shead[n_uniq] = (unsigned short)n_valid; // end sentinel (n_valid <= 16384 fits)
     __syncthreads();
     if (lane == 0) s_w[wave] = carry_chunks;
     __syncthreads();
@@ -324,7 +354,6 @@ __global__ __launch_bounds__(kDdThreads) void dedupe_kernel(const int64_t *__res
 
     // ---- phase 4: write the table-local lists -------------------------------
     DQRM_TICK(5);
-    const int sb = base + t; // the table's slice of seg_row / seg_start has n + 1 slots
     int bag_of_item[kDdMaxRounds];
 #pragma unroll
     for (int r = 0; r < kDdMaxRounds; ++r) { // all gathers first, so that they overlap
@@ -346,19 +375,17 @@ __global__ __launch_bounds__(kDdThreads) void dedupe_kernel(const int64_t *__res
                 b = b < 0 ? 0 : (b >= B ? B - 1 : b);
                 ws.sorted_bag[base + i] = b;
             }
-            if (flags[r] & 2) {
-                ws.seg_row[sb + seg_of[r]] = skey[i];
-                ws.seg_start[sb + seg_of[r]] = i;
-            }
             if (flags[r] & 4) {
                 const int c = chunk_of[r] + chunks_before - 1;
-                ws.chunk_start[base + c] = i;
-                ws.chunk_seg[base + c] = seg_of[r];
+                const int s0 = start_of[r], s1 = shead[seg_of[r] + 1];
+                const int len = min(DQRM_SEG_CHUNK, s1 - i);
+                ws.chunk_local[base + c] =
+                    make_chunk_desc(base + i, len, (i - s0) / DQRM_SEG_CHUNK,
+                                    (s1 - s0 + DQRM_SEG_CHUNK - 1) / DQRM_SEG_CHUNK, seg_of[r], skey[i]);
             }
         }
     }
     if (tid == 0) {
-        ws.seg_start[sb + n_uniq] = n_valid; // end sentinel
         ws.table_base[t] = base;
         ws.table_nuniq[t] = n_uniq;
         ws.table_nchunk[t] = n_chunk;
@@ -368,14 +395,127 @@ __global__ __launch_bounds__(kDdThreads) void dedupe_kernel(const int64_t *__res
 }
 
 // ---------------------------------------------------------------------------
+// Kernel 2 of dqrm_dedupe: table-local lists -> one dense, global chunk list and
+// the index-only outputs (unique rows, segment offsets, table offsets, count).
 
-struct SegArgs {
-    const float *grad_out;
+struct FinishArgs {
     BwdWs ws;
     int32_t *tuo;
     int32_t *num_unique;
     int64_t *uniq_rows;
     int32_t *seg_offsets;
+    int64_t N;
+    int T;
+};
+
+// Turns the per-table counts into offsets in LDS (every block does this; T is
+// small).  s_tuo / s_tco receive T+1 entries, s_base T.
+__device__ __forceinline__ void table_offsets_to_lds(const BwdWs &ws, int T, int *s_tuo, int *s_tco, int *s_base,
+                                                     int *s_w)
+{
+    const int tid = threadIdx.x, lane = tid & (kWave - 1), wave = tid / kWave;
+    if (T <= kWave) {
+        // the usual case: one wave scans the counts, no block-wide scan needed
+        if (wave == 0) {
+            int u = 0, c = 0;
+            if (lane < T) {
+                u = ws.table_nuniq[lane];
+                c = ws.table_nchunk[lane];
+                s_base[lane] = ws.table_base[lane];
+            }
+            const int iu = wave_incl_scan_add(u, lane), ic = wave_incl_scan_add(c, lane);
+            if (lane < T) {
+                s_tuo[lane] = iu - u;
+                s_tco[lane] = ic - c;
+            }
+            if (lane == T - 1) {
+                s_tuo[T] = iu;
+                s_tco[T] = ic;
+            }
+        }
+        __syncthreads();
+        return;
+    }
+    // kSegThreads threads, each owns a run of consecutive tables
+    constexpr int kPer = (DQRM_MAX_TABLES + kSegThreads - 1) / kSegThreads; // 4
+    int u[kPer], c[kPer], su = 0, sc = 0;
+#pragma unroll
+    for (int q = 0; q < kPer; ++q) {
+        const int t = tid * kPer + q;
+        u[q] = c[q] = 0;
+        if (t < T) {
+            u[q] = ws.table_nuniq[t];
+            c[q] = ws.table_nchunk[t];
+            s_base[t] = ws.table_base[t];
+        }
+        su += u[q];
+        sc += c[q];
+    }
+    int tot_u, tot_c;
+    int eu = block_excl_scan_add<kSegThreads / kWave>(su, lane, wave, s_w, &tot_u);
+    int ec = block_excl_scan_add<kSegThreads / kWave>(sc, lane, wave, s_w, &tot_c);
+#pragma unroll
+    for (int q = 0; q < kPer; ++q) {
+        const int t = tid * kPer + q;
+        if (t < T) {
+            s_tuo[t] = eu;
+            s_tco[t] = ec;
+        }
+        eu += u[q];
+        ec += c[q];
+    }
+    if (tid == 0) {
+        s_tuo[T] = tot_u;
+        s_tco[T] = tot_c;
+    }
+    __syncthreads();
+}
+
+// Dense chunk descriptor, as the summing kernels read it:
+//   x  a segment of exactly one lookup: that lookup's bag;
+//      otherwise the global sorted position of the chunk's first lookup
+//   y  len | index of the chunk inside its segment | chunks in the segment (as above)
+//   z  global index of the segment (row of `values`)
+//   w  table
+__global__ __launch_bounds__(kSegThreads) void dedupe_finish_kernel(FinishArgs a)
+{
+    __shared__ int s_tco[DQRM_MAX_TABLES + 1];
+    __shared__ int s_tuo[DQRM_MAX_TABLES + 1];
+    __shared__ int s_base[DQRM_MAX_TABLES];
+    __shared__ int s_w[kSegThreads / kWave];
+    const int T = a.T;
+    table_offsets_to_lds(a.ws, T, s_tuo, s_tco, s_base, s_w);
+    const int C = s_tco[T], U = s_tuo[T];
+    if (blockIdx.x == 0) {
+        for (int k = threadIdx.x; k <= T; k += kSegThreads) a.tuo[k] = s_tuo[k];
+        if (threadIdx.x == 0) {
+            *a.num_unique = U;
+            a.seg_offsets[U] = (int32_t)a.N;
+            a.ws.totals[0] = C;
+            a.ws.totals[1] = U;
+        }
+    }
+    for (int c = (int)(blockIdx.x * kSegThreads + threadIdx.x); c < C; c += (int)(gridDim.x * kSegThreads)) {
+        const int t = table_of(s_tco, T, c);
+        const int4 d = a.ws.chunk_local[s_base[t] + (c - s_tco[t])];
+        const int j = s_tuo[t] + d.z;
+        const int len = desc_len(d), kchunk = desc_kchunk(d), nchunks = desc_nchunks(d);
+        int x = d.x;
+        if (kchunk == 0) { // first chunk of its segment: d.x is the segment's head
+            a.uniq_rows[j] = (int64_t)(unsigned)d.w;
+            a.seg_offsets[j] = d.x;
+            if (len == 1 && nchunks == 1) x = a.ws.sorted_bag[d.x];
+        }
+        a.ws.chunk_desc[c] = make_int4(x, d.y, j, t);
+    }
+}
+
+// ---------------------------------------------------------------------------
+// dqrm_segment_sum: chunk sums, then the combine of long segments, then absmax.
+
+struct SegArgs {
+    const float *grad_out;
+    BwdWs ws;
     float *values;
     float *g_absmax;
     int64_t N;
@@ -419,126 +559,77 @@ struct BlockAbsmax {
     }
 };
 
-// Turns the per-table counts into offsets in LDS (every block does this; T is
-// small).  s_tuo / s_tco receive T+1 entries, s_base T.
-__device__ __forceinline__ void table_offsets_to_lds(const BwdWs &ws, int T, int *s_tuo, int *s_tco, int *s_base,
-                                                     int *s_w)
-{
-    // kSegThreads threads, each owns a run of consecutive tables
-    constexpr int kPer = (DQRM_MAX_TABLES + kSegThreads - 1) / kSegThreads; // 4
-    const int tid = threadIdx.x, lane = tid & (kWave - 1), wave = tid / kWave;
-    int u[kPer], c[kPer], su = 0, sc = 0;
-#pragma unroll
-    for (int q = 0; q < kPer; ++q) {
-        const int t = tid * kPer + q;
-        u[q] = c[q] = 0;
-        if (t < T) {
-            u[q] = ws.table_nuniq[t];
-            c[q] = ws.table_nchunk[t];
-            s_base[t] = ws.table_base[t];
-        }
-        su += u[q];
-        sc += c[q];
-    }
-    int tot_u, tot_c;
-    int eu = block_excl_scan_add<kSegThreads / kWave>(su, lane, wave, s_w, &tot_u);
-    int ec = block_excl_scan_add<kSegThreads / kWave>(sc, lane, wave, s_w, &tot_c);
-#pragma unroll
-    for (int q = 0; q < kPer; ++q) {
-        const int t = tid * kPer + q;
-        if (t < T) {
-            s_tuo[t] = eu;
-            s_tco[t] = ec;
-        }
-        eu += u[q];
-        ec += c[q];
-    }
-    if (tid == 0) {
-        s_tuo[T] = tot_u;
-        s_tco[T] = tot_c;
-    }
-    __syncthreads();
-}
-
 template <int G>
 __global__ __launch_bounds__(kSegThreads) void chunk_sum_kernel(SegArgs a)
 {
-    __shared__ int s_tco[DQRM_MAX_TABLES + 1];
-    __shared__ int s_tuo[DQRM_MAX_TABLES + 1];
-    __shared__ int s_base[DQRM_MAX_TABLES];
-    __shared__ int s_w[kSegThreads / kWave];
     __shared__ unsigned s_max[DQRM_MAX_TABLES];
     const int T = a.T, D = a.D;
     BlockAbsmax amax;
     amax.init(s_max, T);
-    table_offsets_to_lds(a.ws, T, s_tuo, s_tco, s_base, s_w);
-    if (blockIdx.x == 0) { // publish the offsets: outputs of the call, and inputs of the next kernels
-        for (int k = threadIdx.x; k <= T; k += kSegThreads) {
-            a.tuo[k] = s_tuo[k];
-            a.ws.table_chunk_offsets[k] = s_tco[k];
-        }
-        if (threadIdx.x == 0) {
-            *a.num_unique = s_tuo[T];
-            a.seg_offsets[s_tuo[T]] = (int32_t)a.N;
-        }
-    }
 
     const int lg = threadIdx.x & (G - 1);
     const int grp = threadIdx.x / G;
     constexpr int kGroups = kSegThreads / G;
     const int col = lg * 4;
     const bool col_ok = col < D;
-    const int C = s_tco[T];
-    const int per_block = (C + (int)gridDim.x - 1) / (int)gridDim.x;
-    const int c_begin = (int)blockIdx.x * per_block;
-    const int c_end = min(C, c_begin + per_block);
     const int leader = (threadIdx.x & (kWave - 1)) & ~(G - 1);
     const int64_t tD = (int64_t)T * D;
+    const int stride = (int)gridDim.x * kGroups;
+    const int cap = (int)a.N; // the chunk list has N slots, so a descriptor may be requested before C is known
 
-    for (int c = c_begin + grp; c < c_end; c += kGroups) {
-        const int t = table_of(s_tco, T, c);
-        const int base = s_base[t];
-        const int sb = base + t;
-        const int lc = c - s_tco[t];
-        const int start = a.ws.chunk_start[base + lc];
-        const int seg = a.ws.chunk_seg[base + lc];
-        const int s0 = a.ws.seg_start[sb + seg];
-        const int s1 = a.ws.seg_start[sb + seg + 1];
-        int len = s1 - start;
+    // tiles of kGroups consecutive chunks are dealt round-robin to the workgroups, so the
+    // long chunks of hot rows spread over the whole grid; the next tile's descriptor is
+    // requested before the current tile is worked on
+    int c = (int)blockIdx.x * kGroups + grp;
+    int4 d = make_int4(0, 0, 0, 0);
+    if (c < cap) d = a.ws.chunk_desc[c];
+    const int C = min(a.ws.totals[0], cap);
+    __syncthreads(); // s_max is cleared
+    while (c < C) {
+        const int c_next = c + stride;
+        int4 d_next = make_int4(0, 0, 0, 0);
+        if (c_next < C) d_next = a.ws.chunk_desc[c_next];
+
+        int len = desc_len(d);
         len = len > DQRM_SEG_CHUNK ? DQRM_SEG_CHUNK : len;
-        const int nchunks = (s1 - s0 + DQRM_SEG_CHUNK - 1) / DQRM_SEG_CHUNK;
-        const int kchunk = (start - s0) / DQRM_SEG_CHUNK;
-        const int *bags = a.ws.sorted_bag + base + start;
+        const int nchunks = desc_nchunks(d), kchunk = desc_kchunk(d);
+        const int t = d.w;
         const float *g0 = a.grad_out + (int64_t)t * D + col;
-
-        // bag of every contribution: each lane fetches its share of the chunk's
-        // bag list once, the group then passes them round with shuffles
-        constexpr int kIdsPerLane = (DQRM_SEG_CHUNK + G - 1) / G;
-        int my_bags[kIdsPerLane];
-#pragma unroll
-        for (int q = 0; q < kIdsPerLane; ++q) {
-            const int i = q * G + lg;
-            my_bags[q] = (i < len) ? bags[i] : 0;
-        }
         float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
-        constexpr int kBatch = 8; // rows requested before the first is added
+
+        if (len == 1 && nchunks == 1) {
+            // a row looked up once: the descriptor already names the bag
+            if (col_ok) acc = *reinterpret_cast<const float4 *>(g0 + (int64_t)d.x * tD);
+        } else {
+            // bag of every contribution: each lane fetches its share of the chunk's
+            // bag list once, the group then passes them round with shuffles
+            const int *bags = a.ws.sorted_bag + d.x;
+            constexpr int kIdsPerLane = (DQRM_SEG_CHUNK + G - 1) / G;
+            int my_bags[kIdsPerLane];
 #pragma unroll
-        for (int i0 = 0; i0 < DQRM_SEG_CHUNK; i0 += kBatch) {
-            if (i0 < len) {
-                float4 g[kBatch];
+            for (int q = 0; q < kIdsPerLane; ++q) {
+                const int i = q * G + lg;
+                my_bags[q] = (i < len) ? bags[i] : 0;
+            }
+            constexpr int kBatch = kSegBatch;
 #pragma unroll
-                for (int q = 0; q < kBatch; ++q) {
-                    const int i = i0 + q;
-                    g[q] = make_float4(0.f, 0.f, 0.f, 0.f);
-                    if (i < len) {
-                        const int b = __shfl(my_bags[i / G], leader + (i % G), kWave);
-                        if (col_ok) g[q] = *reinterpret_cast<const float4 *>(g0 + (int64_t)b * tD);
+            for (int i0 = 0; i0 < DQRM_SEG_CHUNK; i0 += kBatch) {
+                if (i0 < len) {
+                    float4 g[kBatch];
+#pragma unroll
+                    for (int q = 0; q < kBatch; ++q) {
+                        const int i = i0 + q;
+                        g[q] = make_float4(0.f, 0.f, 0.f, 0.f);
+                        if (i < len) {
+                            const int b = __shfl(my_bags[i / G], leader + (i % G), kWave);
+                            if (col_ok) g[q] = *reinterpret_cast<const float4 *>(g0 + (int64_t)b * tD);
+                        }
                     }
-                }
 #pragma unroll
-                for (int q = 0; q < kBatch; ++q) {
-                    const int i = i0 + q;
-                    if (i < len) acc = (i == 0) ? g[q] : f4_add(acc, g[q]);
+                    for (int q = 0; q < kBatch; ++q) {
+                        const int i = i0 + q;
+                        if (i < len) acc = (i == 0) ? g[q] : f4_add(acc, g[q]);
+                    }
                 }
             }
         }
@@ -548,60 +639,47 @@ __global__ __launch_bounds__(kSegThreads) void chunk_sum_kernel(SegArgs a)
             // Full chunks are disjoint runs of DQRM_SEG_CHUNK sorted positions, so
             // (position / DQRM_SEG_CHUNK) names them uniquely; the last chunk of a
             // segment is filed under the slot of the segment's first chunk.
-            const int gpos = base + s0;
-            float *pslot = (kchunk == nchunks - 1)
-                               ? a.ws.partial_last + (int64_t)(gpos / DQRM_SEG_CHUNK) * D
-                               : a.ws.partial_full + (int64_t)((base + start) / DQRM_SEG_CHUNK) * D;
+            const int gpos = d.x - kchunk * DQRM_SEG_CHUNK; // global sorted position of the segment's head
+            float *pslot = (kchunk == nchunks - 1) ? a.ws.partial_last + (int64_t)(gpos / DQRM_SEG_CHUNK) * D
+                                                   : a.ws.partial_full + (int64_t)(d.x / DQRM_SEG_CHUNK) * D;
             if (col_ok) *reinterpret_cast<float4 *>(pslot + col) = acc;
-        } else {
-            const int j = s_tuo[t] + seg; // global segment
-            if (col_ok) *reinterpret_cast<float4 *>(a.values + (int64_t)j * D + col) = acc;
-            if (lg == 0) {
-                a.uniq_rows[j] = (int64_t)a.ws.seg_row[sb + seg];
-                a.seg_offsets[j] = base + s0;
-            }
-            if (col_ok) amax.add(t, f4_absmax(acc));
+        } else if (col_ok) {
+            *reinterpret_cast<float4 *>(a.values + (int64_t)d.z * D + col) = acc;
+            amax.add(t, f4_absmax(acc));
         }
+        c = c_next;
+        d = d_next;
     }
     amax.flush(a.ws.absmax_slots, T);
 }
 
-// One lane group per segment; only segments of more than one chunk have work.
+// One lane group per chunk descriptor; only the LAST chunk of a segment of more
+// than one chunk has work: it adds the segment's partial sums in chunk order.
 template <int G>
 __global__ __launch_bounds__(kSegThreads) void combine_kernel(SegArgs a)
 {
-    __shared__ int s_tuo[DQRM_MAX_TABLES + 1];
-    __shared__ int s_base[DQRM_MAX_TABLES];
     __shared__ unsigned s_max[DQRM_MAX_TABLES];
     const int T = a.T, D = a.D;
     BlockAbsmax amax;
     amax.init(s_max, T);
-    for (int k = threadIdx.x; k <= T; k += kSegThreads) {
-        s_tuo[k] = a.tuo[k];
-        if (k < T) s_base[k] = a.ws.table_base[k];
-    }
-    __syncthreads();
     const int lg = threadIdx.x & (G - 1);
     constexpr int kGroups = kSegThreads / G;
     const int col = lg * 4;
     const bool col_ok = col < D;
-    const int U = s_tuo[T];
+    const int cap = (int)a.N;
+    const int C = min(a.ws.totals[0], cap);
+    __syncthreads(); // s_max is cleared
 
-    for (int j = (int)blockIdx.x * kGroups + threadIdx.x / G; j < U; j += (int)gridDim.x * kGroups) {
-        const int t = table_of(s_tuo, T, j);
-        const int seg = j - s_tuo[t];
-        const int base = s_base[t];
-        const int sb = base + t;
-        const int s0 = a.ws.seg_start[sb + seg];
-        const int s1 = a.ws.seg_start[sb + seg + 1];
-        const int nchunks = (s1 - s0 + DQRM_SEG_CHUNK - 1) / DQRM_SEG_CHUNK;
-        if (nchunks <= 1) continue;
-        const int gpos = base + s0;
+    for (int c = (int)blockIdx.x * kGroups + threadIdx.x / G; c < C; c += (int)gridDim.x * kGroups) {
+        const int4 d = a.ws.chunk_desc[c];
+        const int nchunks = desc_nchunks(d), kchunk = desc_kchunk(d);
+        if (nchunks <= 1 || kchunk != nchunks - 1) continue;
+        const int gpos = d.x - kchunk * DQRM_SEG_CHUNK;
         // the k-th full chunk of the segment starts at sorted position gpos + 32 k
         const float *p_last = a.ws.partial_last + (int64_t)(gpos / DQRM_SEG_CHUNK) * D + col;
-        float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
         if (col_ok) {
-            constexpr int kCb = 8; // partials requested before the first is added
+            float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
+            constexpr int kCb = 16; // partials requested before the first is added
             for (int k0 = 0; k0 < nchunks; k0 += kCb) {
                 float4 pv[kCb];
 #pragma unroll
@@ -619,25 +697,28 @@ __global__ __launch_bounds__(kSegThreads) void combine_kernel(SegArgs a)
                     if (k < nchunks) acc = (k == 0) ? pv[q] : f4_add(acc, pv[q]);
                 }
             }
-            *reinterpret_cast<float4 *>(a.values + (int64_t)j * D + col) = acc;
+            *reinterpret_cast<float4 *>(a.values + (int64_t)d.z * D + col) = acc;
+            amax.add(d.w, f4_absmax(acc));
         }
-        if (lg == 0) {
-            a.uniq_rows[j] = (int64_t)a.ws.seg_row[sb + seg];
-            a.seg_offsets[j] = gpos;
-        }
-        if (col_ok) amax.add(t, f4_absmax(acc));
     }
     amax.flush(a.ws.absmax_slots, T);
 }
 
 // g_absmax[t] = max over the table's slots
-__global__ void absmax_finalize_kernel(const float *__restrict__ slots, int T, float *__restrict__ g_absmax)
+// (and clears them, so that the segment sums may be repeated on the same dedupe)
+__global__ void absmax_finalize_kernel(float *__restrict__ slots, int T, float *__restrict__ g_absmax)
 {
     const int t = blockIdx.x * blockDim.x + threadIdx.x;
     if (t >= T) return;
+    float v[kAbsmaxSlots];
+#pragma unroll
+    for (int k = 0; k < kAbsmaxSlots; ++k) v[k] = *absmax_slot(slots, t, k);
     float m = 0.0f;
 #pragma unroll
-    for (int k = 0; k < kAbsmaxSlots; ++k) m = fmaxf(m, slots[((int64_t)t * kAbsmaxSlots + k) * kAbsmaxStride]);
+    for (int k = 0; k < kAbsmaxSlots; ++k) {
+        m = fmaxf(m, v[k]);
+        *absmax_slot(slots, t, k) = 0.0f;
+    }
     g_absmax[t] = m;
 }
 

@@ -172,6 +172,45 @@ def test_determinism(oracle):
     assert run.status()[0] == 0
 
 
+def test_split_backward_on_two_streams(oracle):
+    """dqrm_dedupe on a side stream (it needs only the indices), dqrm_segment_sum on the main stream
+    after an event, twice on the same dedupe result with different gradients: same outputs as the
+    one-call backward / the oracle."""
+    import torch
+    import paper_2410_20046_amd as dq
+
+    cards = np.array([5, 2000, 300000, 64], np.int64)
+    wl = Workload(name="split", T=4, D=64, B=4096, alpha=1.1, seed=31, cards=cards)
+    idx, off = wl.batch(0)
+    W = np.zeros((wl.R, wl.D), np.float32)
+    run = GpuRun(wl.row_offsets, wl.D, W, wl.B, len(idx), with_packed=False, want_codes=False)
+    _say("split backward")
+    b = run.bufs
+    side = torch.cuda.Stream()
+    main = torch.cuda.current_stream()
+    run.upload_batch(idx, off, wl.grad_normal(0))
+    side.wait_stream(main)
+    dq.dqrm_dedupe(run.tables, run.idx, run.off, wl.B, b.sorted_pos, b.uniq_rows, b.seg_offsets,
+                   b.table_uniq_offsets, b.num_unique, b.workspace, stream=side)
+    ev = torch.cuda.Event()
+    ev.record(side)
+    main.wait_event(ev)
+    for k in (0, 1):
+        g = wl.grad_normal(k)
+        gd = torch.from_numpy(g).to(run.dev)
+        dq.dqrm_segment_sum(run.tables, wl.B, len(idx), gd, b.values, b.g_absmax, b.workspace)
+        U = int(b.num_unique.cpu().item())
+        got = dict(U=U, sorted_pos=b.sorted_pos.cpu().numpy(), uniq_rows=b.uniq_rows.cpu().numpy()[:U],
+                   seg_offsets=b.seg_offsets.cpu().numpy()[:U + 1],
+                   table_uniq_offsets=b.table_uniq_offsets.cpu().numpy(), values=b.values.cpu().numpy()[:U],
+                   g_absmax=b.g_absmax.cpu().numpy())
+        o = oracle.embbag_bwd(wl.T, wl.D, wl.B, idx, off, g)
+        compare_bwd(got, o, f"split/{k}")
+        assert_exact(got["values"].view(np.uint32), o["values"].view(np.uint32), f"split/{k} values bits")
+        assert_exact(got["g_absmax"].view(np.uint32), o["g_absmax"].view(np.uint32), f"split/{k} g_absmax bits")
+    assert run.status()[0] == 0
+
+
 # --------------------------------------------------------------------------
 # data-dependent errors: reported, never acted upon
 # --------------------------------------------------------------------------

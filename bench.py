@@ -55,17 +55,25 @@ def read_traffic(kernel):
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=2000)
+    ap.add_argument("--steps", type=int, default=1920)
     ap.add_argument("--warmup", type=int, default=100)
     ap.add_argument("--workload", default="terabyte", choices=["terabyte", "kaggle", "single", "tiny"])
     ap.add_argument("--mode", default="packed", choices=["packed", "master"])
     ap.add_argument("--pool", type=int, default=64, help="distinct index batches cycled")
     ap.add_argument("--grad-pool", type=int, default=8, help="distinct grad_out buffers cycled")
     ap.add_argument("--lr", type=float, default=0.1)
-    ap.add_argument("--overlap", default="pipeline", choices=["none", "fwd", "pipeline"],
+    ap.add_argument("--overlap", default="pipeline", choices=["none", "fwd", "pipeline", "ahead"],
                     help="where dqrm_dedupe (needs only the indices) runs: none = in line on the one stream; "
                          "fwd = on a second stream beside the same step's forward; pipeline = on a second stream, "
-                         "one step ahead (double-buffered workspace)")
+                         "one step ahead (double-buffered workspace); ahead = in line on the one stream, but for the "
+                         "next --ahead batches in one dqrm_dedupe_multi launch (a table's sort fills one CU, so several "
+                         "batches fill the chip; the data loader has their indices already)")
+    ap.add_argument("--ahead", type=int, default=8, help="batches per dqrm_dedupe_multi launch with --overlap ahead")
+    ap.add_argument("--two-call-update", dest="fused", action="store_false",
+                    help="dqrm_grad_quant_int8 + dqrm_sparse_update (and the absmax fold inside dqrm_segment_sum) "
+                         "instead of the one-pass dqrm_quant_update")
+    ap.add_argument("--no-graph", dest="graph", action="store_false",
+                    help="launch every kernel from the host instead of replaying a captured HIP graph of `pool` steps")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=12.0)
     args = ap.parse_args()
@@ -108,63 +116,104 @@ def main():
     dq.dqrm_pack_int4(tables)
     torch.cuda.synchronize()
 
-    main = torch.cuda.current_stream()
     side = torch.cuda.Stream()  # default priority
-    nbuf = 2 if args.overlap == "pipeline" else 1
-    wss = [bufs.workspace] + [torch.empty_like(bufs.workspace) for _ in range(nbuf - 1)]
+    nbuf = {"pipeline": 2, "ahead": args.ahead}.get(args.overlap, 1)
     dup = lambda x: [x] + [torch.empty_like(x) for _ in range(nbuf - 1)]
-    sps, urs, sos = dup(bufs.sorted_pos), dup(bufs.uniq_rows), dup(bufs.seg_offsets)
+    wss, sps, urs, sos = dup(bufs.workspace), dup(bufs.sorted_pos), dup(bufs.uniq_rows), dup(bufs.seg_offsets)
     tuos, nus = dup(bufs.table_uniq_offsets), dup(bufs.num_unique)
     ev_dedupe = [torch.cuda.Event() for _ in range(nbuf)]   # dedupe into buffer i finished
-    ev_segsum = [torch.cuda.Event() for _ in range(nbuf)]   # last reader (the update) of buffer i finished
+    ev_update = [torch.cuda.Event() for _ in range(nbuf)]   # last reader (the update) of buffer i finished
     batch_of = lambda k: (idx_d[k % args.pool], off_d[k % args.pool])
 
     def dedupe_on_side(k):
         i = k % nbuf
-        side.wait_event(ev_segsum[i])  # the buffer's previous reader (no-op before the first record)
+        side.wait_event(ev_update[i])  # the buffer's previous reader (no-op before the first record)
         ix, of = batch_of(k)
         dq.dqrm_dedupe(tables, ix, of, B, sps[i], urs[i], sos[i], tuos[i], nus[i], wss[i], stream=side)
         ev_dedupe[i].record(side)
 
-    primed = [False]
+    def rest_of_step(k, i):
+        """B3-B5 on the current stream, from the dedupe result in buffer i."""
+        g = grad_d[k % args.grad_pool]
+        if args.fused:
+            dq.dqrm_segment_sum(tables, B, N, g, bufs.values, None, wss[i])
+            dq.dqrm_quant_update(tables, bufs.cap, N, bufs.values, urs[i], tuos[i], bufs.g_absmax, bufs.gq,
+                                 bufs.g_scale, args.lr, wss[i])
+        else:
+            dq.dqrm_segment_sum(tables, B, N, g, bufs.values, bufs.g_absmax, wss[i])
+            dq.dqrm_grad_quant_int8(T, D, bufs.cap, bufs.values, tuos[i], bufs.g_absmax, bufs.gq, bufs.g_scale)
+            dq.dqrm_sparse_update(tables, bufs.cap, urs[i], tuos[i], bufs.gq, bufs.g_scale, args.lr)
 
-    def step(k):
-        ix, of = batch_of(k)
-        if args.overlap == "none":
-            dq.dqrm_fwd_bwd_step(tables, bufs, ix, of, grad_d[k % args.grad_pool], args.lr, mode)
+    def run_steps(k0, n):
+        """n consecutive steps starting with batch k0, all launches on the current stream (+ the side
+        stream for dqrm_dedupe when overlapping).  Self-contained: the side stream is joined at the end."""
+        main = torch.cuda.current_stream()
+        if args.overlap == "ahead":
+            for k in range(k0, k0 + n):
+                if (k - k0) % nbuf == 0:  # dedupe of this and the next nbuf-1 batches, in one launch pair
+                    group = range(k, min(k + nbuf, k0 + n))
+                    dq.dqrm_dedupe_multi(tables, B, [batch_of(j) + (sps[j % nbuf], urs[j % nbuf], sos[j % nbuf],
+                                                                    tuos[j % nbuf], nus[j % nbuf], wss[j % nbuf])
+                                                     for j in group])
+                ix, of = batch_of(k)
+                dq.dqrm_embbag_fwd(tables, ix, of, B, mode, bufs.out, None)
+                rest_of_step(k, k % nbuf)
             return
-        i = k % nbuf
-        if args.overlap == "fwd" or not primed[0]:
-            if not primed[0]:
-                side.wait_stream(main)  # first use: everything enqueued so far (uploads, packing) is done
-                primed[0] = True
-            dedupe_on_side(k)
-        dq.dqrm_embbag_fwd(tables, ix, of, B, mode, bufs.out, None)
+        if args.overlap == "none":
+            for k in range(k0, k0 + n):
+                ix, of = batch_of(k)
+                dq.dqrm_embbag_fwd(tables, ix, of, B, mode, bufs.out, None)
+                dq.dqrm_dedupe(tables, ix, of, B, sps[0], urs[0], sos[0], tuos[0], nus[0], wss[0])
+                rest_of_step(k, 0)
+            return
+        side.wait_stream(main)  # everything enqueued so far is visible to the side stream
         if args.overlap == "pipeline":
-            dedupe_on_side(k + 1)  # the next batch's indices are already here
-        main.wait_event(ev_dedupe[i])
-        dq.dqrm_segment_sum(tables, B, N, grad_d[k % args.grad_pool], bufs.values, bufs.g_absmax, wss[i])
-        dq.dqrm_grad_quant_int8(T, D, bufs.cap, bufs.values, tuos[i], bufs.g_absmax, bufs.gq, bufs.g_scale)
-        dq.dqrm_sparse_update(tables, bufs.cap, urs[i], tuos[i], bufs.gq, bufs.g_scale, args.lr)
-        ev_segsum[i].record(main)  # the last reader of this dedupe result is done
+            dedupe_on_side(k0)
+        for k in range(k0, k0 + n):
+            ix, of = batch_of(k)
+            i = k % nbuf
+            if args.overlap == "fwd":
+                dedupe_on_side(k)  # beside this step's forward
+            dq.dqrm_embbag_fwd(tables, ix, of, B, mode, bufs.out, None)
+            if args.overlap == "pipeline" and k + 1 < k0 + n:
+                dedupe_on_side(k + 1)  # one step ahead: the next batch's indices are already here
+            main.wait_event(ev_dedupe[i])
+            rest_of_step(k, i)
+            ev_update[i].record(main)
 
-    # ---- warm-up, then the timed region: exactly K steps, one stream, no host sync inside ----
-    for k in range(args.warmup):
-        step(k)
+    # ---- warm-up (eager), optional capture of `graph_steps` steps into one HIP graph ----
+    run_steps(0, args.warmup)
     torch.cuda.synchronize()
+    graph, gs = None, 0
+    if args.graph:
+        gs = min(args.pool, args.steps)
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph):
+            run_steps(args.warmup, gs)
+        graph.replay()  # one untimed replay
+        torch.cuda.synchronize()
+
+    # ---- the timed region: exactly K steps, no host synchronisation inside ----
     e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
     t_start = time.perf_counter()
     e0.record()
-    for k in range(args.steps):
-        step(args.warmup + k)
+    if graph is not None:
+        for _ in range(args.steps // gs):
+            graph.replay()
+        if args.steps % gs:
+            run_steps(args.warmup, args.steps % gs)
+    else:
+        run_steps(args.warmup, args.steps)
     e1.record()
+    t_issued = time.perf_counter() - t_start
     torch.cuda.synchronize()
     wall = time.perf_counter() - t_start
     ev_ms = e0.elapsed_time(e1)
     ms_per_step = wall * 1e3 / args.steps
     code, tb, val = dq.dqrm_check_status()
     assert code == 0, f"device status {code} (table {tb}, value {val})"
-    log(f"[bench] timed {args.steps} steps: wall {wall * 1e3:.2f} ms, events {ev_ms:.2f} ms, {ms_per_step * 1e3:.1f} us/step")
+    log(f"[bench] timed {args.steps} steps: wall {wall * 1e3:.2f} ms, events {ev_ms:.2f} ms, {ms_per_step * 1e3:.1f} us/step "
+        f"(host issued them in {t_issued * 1e3:.2f} ms = {t_issued * 1e6 / args.steps:.1f} us/step)")
 
     # ---- unique rows per batch (for the algorithmic byte counts) ----
     us = []
@@ -273,7 +322,9 @@ def main():
         "config": {"workload": f"{args.workload}-shaped embedding layer: {T} tables, {wl.R} rows, dim {D}, batch {B}, "
                                f"1 Zipf index per table per sample, {args.mode}-mode forward, INT8 sparse grads, "
                                f"SGD lr {args.lr}, dedupe overlap: {args.overlap}",
-                   "lookups_per_step": N, "unique_rows_per_step": round(U, 1), "fwd_mode": args.mode, "overlap": args.overlap},
+                   "lookups_per_step": N, "unique_rows_per_step": round(U, 1), "fwd_mode": args.mode, "overlap": args.overlap,
+                   "update": ("dqrm_quant_update (one pass)" if args.fused else "dqrm_grad_quant_int8 + dqrm_sparse_update"),
+                   "launch": (f"HIP graph of {gs} steps replayed" if graph is not None else "eager launches")},
         "roofline": roofline,
         "cpu_baseline": cpu,
         "step_algorithmic_bytes": int(ab["step"]),

@@ -58,6 +58,7 @@ extern "C" {
 #define DQRM_MAX_TABLES 1024
 #define DQRM_MAX_TABLE_ROWS 2147483646LL /* rows of one table */
 #define DQRM_MAX_TABLE_LOOKUPS 16384 /* lookups one table may receive in one batch (dedupe sorts them in LDS) */
+#define DQRM_MAX_DEDUPE_BATCHES 8    /* batches one dqrm_dedupe_multi call may take */
 
 /* Order of a segment's floating-point sum (the paper does not fix one; results
  * must be reproducible bit for bit, because the INT8 scale and codes depend on
@@ -144,13 +145,35 @@ int32_t dqrm_embbag_bwd(const dqrm_tables_t *tables, const int64_t *indices, con
  * seg_offsets, table_uniq_offsets, num_unique) and leaves the work list of the
  * segment sums in `workspace`.  dqrm_segment_sum then needs that workspace (the
  * caller orders the two, e.g. with an event) and grad_out, and writes `values`
- * and `g_absmax`; it may be repeated on the same dedupe result. */
+ * and `g_absmax`; it may be repeated on the same dedupe result.  g_absmax may be
+ * NULL if dqrm_quant_update follows (see there). */
 int32_t dqrm_dedupe(const dqrm_tables_t *tables, const int64_t *indices, const int64_t *offsets, int32_t batch,
                     int64_t num_indices, int32_t *sorted_pos, int64_t *uniq_rows, int32_t *seg_offsets,
                     int32_t *table_uniq_offsets, int32_t *num_unique, void *workspace, size_t workspace_bytes,
                     void *stream);
 int32_t dqrm_segment_sum(const dqrm_tables_t *tables, int32_t batch, int64_t num_indices, const float *grad_out,
                          float *values, float *g_absmax, void *workspace, size_t workspace_bytes, void *stream);
+
+/* dqrm_dedupe for up to DQRM_MAX_DEDUPE_BATCHES batches in one launch pair.  A
+ * table's sort occupies one CU, so one batch keeps only T CUs busy; the batches
+ * of the next few steps (a data loader has their indices long before the model
+ * needs them) fill the chip instead.  `batches` is a HOST array; each element
+ * holds the arguments dqrm_dedupe takes for one batch (its own outputs and its
+ * own workspace of at least `workspace_bytes` bytes, sized for the largest
+ * num_indices).  All batches have `batch` bags per table. */
+typedef struct {
+    const int64_t *indices;
+    const int64_t *offsets;
+    int64_t num_indices;
+    int32_t *sorted_pos;
+    int64_t *uniq_rows;
+    int32_t *seg_offsets;
+    int32_t *table_uniq_offsets;
+    int32_t *num_unique;
+    void *workspace;
+} dqrm_dedupe_batch_t;
+int32_t dqrm_dedupe_multi(const dqrm_tables_t *tables, int32_t batch, int32_t num_batches,
+                          const dqrm_dedupe_batch_t *batches, size_t workspace_bytes, void *stream);
 
 /* Distributed-training appendix (only the values of the sparse gradient are
  * quantised; the indices are left alone): one scale per table per step,
@@ -167,6 +190,17 @@ int32_t dqrm_grad_quant_int8(int32_t num_tables, int32_t dim, int64_t capacity, 
 int32_t dqrm_sparse_update(const dqrm_tables_t *tables, int64_t capacity, const int64_t *uniq_rows,
                            const int32_t *table_uniq_offsets, const int8_t *gq, const float *g_scale,
                            float lr, void *stream);
+
+/* B4 and B5 in one pass, for callers that do not exchange anything between the
+ * two (one GPU): same outputs as dqrm_grad_quant_int8 followed by
+ * dqrm_sparse_update -- gq, g_scale, the updated master rows and packed nibbles
+ * -- and it also writes g_absmax.  It is called after a dqrm_segment_sum that
+ * was given g_absmax = NULL (which then skips its last small kernel and leaves
+ * the per-table maxima in `workspace`; in that mode dqrm_segment_sum may run
+ * only once per dqrm_dedupe).  `workspace` / `num_indices` as for dqrm_dedupe. */
+int32_t dqrm_quant_update(const dqrm_tables_t *tables, int64_t capacity, int64_t num_indices, const float *values,
+                          const int64_t *uniq_rows, const int32_t *table_uniq_offsets, float *g_absmax, int8_t *gq,
+                          float *g_scale, float lr, void *workspace, size_t workspace_bytes, void *stream);
 
 /* Synchronises `stream`, returns the first data-dependent problem recorded on
  * the current device since the last call (DQRM_OK if none) and clears it.

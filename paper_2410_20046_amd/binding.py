@@ -33,7 +33,8 @@ SEG_CHUNK = 32
 MAX_TABLE_LOOKUPS = 16384
 
 EXPORTS = ("dqrm_find_scale", "dqrm_pack_int4", "dqrm_embbag_fwd", "dqrm_embbag_bwd_workspace_bytes",
-           "dqrm_embbag_bwd", "dqrm_dedupe", "dqrm_segment_sum", "dqrm_grad_quant_int8", "dqrm_sparse_update",
+           "dqrm_embbag_bwd", "dqrm_dedupe", "dqrm_dedupe_multi", "dqrm_segment_sum", "dqrm_grad_quant_int8",
+           "dqrm_sparse_update", "dqrm_quant_update",
            "dqrm_check_status", "dqrm_last_hip_error", "dqrm_version")
 
 
@@ -48,6 +49,14 @@ class dqrm_tables_t(C.Structure):
                 ("row_offsets_dev", C.c_void_p), ("master", C.c_void_p), ("packed", C.c_void_p),
                 ("w_scale", C.c_void_p)]
 
+
+class dqrm_dedupe_batch_t(C.Structure):
+    _fields_ = [("indices", C.c_void_p), ("offsets", C.c_void_p), ("num_indices", C.c_int64),
+                ("sorted_pos", C.c_void_p), ("uniq_rows", C.c_void_p), ("seg_offsets", C.c_void_p),
+                ("table_uniq_offsets", C.c_void_p), ("num_unique", C.c_void_p), ("workspace", C.c_void_p)]
+
+
+MAX_DEDUPE_BATCHES = 8
 
 _lib: Optional[C.CDLL] = None
 
@@ -69,12 +78,15 @@ def lib() -> C.CDLL:
         L.dqrm_embbag_bwd_workspace_bytes.restype = sz
         L.dqrm_embbag_bwd.argtypes = [tp, vp, vp, i32, i64, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
         L.dqrm_dedupe.argtypes = [tp, vp, vp, i32, i64, vp, vp, vp, vp, vp, vp, sz, vp]
+        L.dqrm_dedupe_multi.argtypes = [tp, i32, i32, C.POINTER(dqrm_dedupe_batch_t), sz, vp]
+        L.dqrm_dedupe_multi.restype = i32
         L.dqrm_segment_sum.argtypes = [tp, i32, i64, vp, vp, vp, vp, sz, vp]
+        L.dqrm_quant_update.argtypes = [tp, i64, i64, vp, vp, vp, vp, vp, vp, C.c_float, vp, sz, vp]
         L.dqrm_grad_quant_int8.argtypes = [i32, i32, i64, vp, vp, vp, vp, vp, vp]
         L.dqrm_sparse_update.argtypes = [tp, i64, vp, vp, vp, vp, C.c_float, vp]
         L.dqrm_check_status.argtypes = [vp, C.POINTER(i32), C.POINTER(i64)]
         for n in ("dqrm_find_scale", "dqrm_pack_int4", "dqrm_embbag_fwd", "dqrm_embbag_bwd", "dqrm_dedupe", "dqrm_segment_sum",
-                  "dqrm_grad_quant_int8", "dqrm_sparse_update", "dqrm_check_status"):
+                  "dqrm_quant_update", "dqrm_grad_quant_int8", "dqrm_sparse_update", "dqrm_check_status"):
             getattr(L, n).restype = i32
         L.dqrm_last_hip_error.restype = C.c_char_p
         L.dqrm_version.restype = C.c_char_p
@@ -167,6 +179,20 @@ def dqrm_dedupe(tables: Tables, indices: torch.Tensor, offsets: torch.Tensor, ba
            "dqrm_dedupe")
 
 
+def dqrm_dedupe_multi(tables: Tables, batch: int, batches, stream=None) -> None:
+    """``batches``: sequence of tuples (indices, offsets, sorted_pos, uniq_rows, seg_offsets, table_uniq_offsets,
+    num_unique, workspace) of device tensors, one per batch (at most MAX_DEDUPE_BATCHES)."""
+    arr = (dqrm_dedupe_batch_t * len(batches))()
+    ws_bytes = None
+    for i, (ix, of, sp, ur, so, tuo, nu, ws) in enumerate(batches):
+        arr[i] = dqrm_dedupe_batch_t(_ptr(ix), _ptr(of), ix.numel(), _ptr(sp), _ptr(ur), _ptr(so), _ptr(tuo), _ptr(nu),
+                                     _ptr(ws))
+        nb = ws.numel() * ws.element_size()
+        ws_bytes = nb if ws_bytes is None else min(ws_bytes, nb)
+    _check(lib().dqrm_dedupe_multi(tables.ref, batch, len(batches), arr, ws_bytes or 0, _stream(stream)),
+           "dqrm_dedupe_multi")
+
+
 def dqrm_segment_sum(tables: Tables, batch: int, num_indices: int, grad_out: torch.Tensor, values: torch.Tensor,
                      g_absmax: torch.Tensor, workspace: torch.Tensor, stream=None) -> None:
     _check(lib().dqrm_segment_sum(tables.ref, batch, num_indices, _ptr(grad_out), _ptr(values), _ptr(g_absmax),
@@ -186,6 +212,15 @@ def dqrm_sparse_update(tables: Tables, capacity: int, uniq_rows: torch.Tensor, t
                        gq: torch.Tensor, g_scale: torch.Tensor, lr: float, stream=None) -> None:
     _check(lib().dqrm_sparse_update(tables.ref, capacity, _ptr(uniq_rows), _ptr(table_uniq_offsets), _ptr(gq),
                                     _ptr(g_scale), lr, _stream(stream)), "dqrm_sparse_update")
+
+
+def dqrm_quant_update(tables: Tables, capacity: int, num_indices: int, values: torch.Tensor, uniq_rows: torch.Tensor,
+                      table_uniq_offsets: torch.Tensor, g_absmax: torch.Tensor, gq: torch.Tensor,
+                      g_scale: torch.Tensor, lr: float, workspace: torch.Tensor, stream=None) -> None:
+    _check(lib().dqrm_quant_update(tables.ref, capacity, num_indices, _ptr(values), _ptr(uniq_rows),
+                                   _ptr(table_uniq_offsets), _ptr(g_absmax), _ptr(gq), _ptr(g_scale), lr,
+                                   _ptr(workspace), workspace.numel() * workspace.element_size(), _stream(stream)),
+           "dqrm_quant_update")
 
 
 def dqrm_check_status(stream=None) -> Tuple[int, int, int]:

@@ -267,38 +267,68 @@ size_t dqrm_embbag_bwd_workspace_bytes(int32_t num_tables, int32_t dim, int32_t 
     return ws_layout(num_tables, dim, num_indices).total;
 }
 
+int32_t dqrm_dedupe_multi(const dqrm_tables_t *tables, int32_t batch, int32_t num_batches,
+                          const dqrm_dedupe_batch_t *batches, size_t workspace_bytes, void *stream)
+{
+    int64_t R = 0;
+    int32_t rc = check_tables(tables, false, &R);
+    if (rc != DQRM_OK) return rc;
+    if (!batches || num_batches < 1) return DQRM_ERR_INVALID_ARG;
+    if (num_batches > DQRM_MAX_DEDUPE_BATCHES) return DQRM_ERR_UNSUPPORTED;
+    const int T = tables->num_tables, D = tables->dim;
+    int64_t max_n = 0;
+    for (int i = 0; i < num_batches; ++i) {
+        const dqrm_dedupe_batch_t &b = batches[i];
+        rc = check_batch(tables, b.indices, b.offsets, batch, b.num_indices);
+        if (rc != DQRM_OK) return rc;
+        if (!b.sorted_pos || !b.uniq_rows || !b.seg_offsets || !b.table_uniq_offsets || !b.num_unique || !b.workspace ||
+            !aligned(b.workspace, 256))
+            return DQRM_ERR_INVALID_ARG;
+        if (workspace_bytes < ws_layout(T, D, b.num_indices).total) return DQRM_ERR_WORKSPACE_TOO_SMALL;
+        if (b.num_indices > max_n) max_n = b.num_indices;
+    }
+    dqrm::DedupeArgs da;
+    std::memset(&da, 0, sizeof(da));
+    for (int i = 0; i < num_batches; ++i) {
+        const dqrm_dedupe_batch_t &b = batches[i];
+        dqrm::DedupeBatch &o = da.b[i];
+        o.indices = b.indices;
+        o.offsets = b.offsets;
+        o.N = b.num_indices;
+        o.ws = ws_views(b.workspace, ws_layout(T, D, b.num_indices));
+        o.sorted_pos = b.sorted_pos;
+        o.tuo = b.table_uniq_offsets;
+        o.num_unique = b.num_unique;
+        o.uniq_rows = b.uniq_rows;
+        o.seg_offsets = b.seg_offsets;
+    }
+    da.row_offsets = tables->row_offsets_dev;
+    da.T = T;
+    da.B = batch;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    hipLaunchKernelGGL(dqrm::dedupe_kernel, dim3(T, num_batches), dim3(dqrm::kDdThreads), 0, st, da);
+    hipLaunchKernelGGL(dqrm::dedupe_finish_kernel, dim3(grid_for(max_n, dqrm::kSegThreads, 2), num_batches),
+                       dim3(dqrm::kSegThreads), 0, st, da);
+    DQRM_HIP_CHECK(hipGetLastError());
+    return DQRM_OK;
+}
+
 int32_t dqrm_dedupe(const dqrm_tables_t *tables, const int64_t *indices, const int64_t *offsets, int32_t batch,
                     int64_t num_indices, int32_t *sorted_pos, int64_t *uniq_rows, int32_t *seg_offsets,
                     int32_t *table_uniq_offsets, int32_t *num_unique, void *workspace, size_t workspace_bytes,
                     void *stream)
 {
-    int64_t R = 0;
-    int32_t rc = check_tables(tables, false, &R);
-    if (rc != DQRM_OK) return rc;
-    rc = check_batch(tables, indices, offsets, batch, num_indices);
-    if (rc != DQRM_OK) return rc;
-    if (!sorted_pos || !uniq_rows || !seg_offsets || !table_uniq_offsets || !num_unique || !workspace ||
-        !aligned(workspace, 256))
-        return DQRM_ERR_INVALID_ARG;
-    const int T = tables->num_tables, D = tables->dim;
-    const WsLayout L = ws_layout(T, D, num_indices);
-    if (workspace_bytes < L.total) return DQRM_ERR_WORKSPACE_TOO_SMALL;
-
-    hipStream_t st = static_cast<hipStream_t>(stream);
-    dqrm::FinishArgs fa;
-    fa.ws = ws_views(workspace, L);
-    fa.tuo = table_uniq_offsets;
-    fa.num_unique = num_unique;
-    fa.uniq_rows = uniq_rows;
-    fa.seg_offsets = seg_offsets;
-    fa.N = num_indices;
-    fa.T = T;
-    hipLaunchKernelGGL(dqrm::dedupe_kernel, dim3(T), dim3(dqrm::kDdThreads), 0, st, indices, offsets,
-                       tables->row_offsets_dev, T, (int)batch, num_indices, fa.ws, sorted_pos);
-    hipLaunchKernelGGL(dqrm::dedupe_finish_kernel, dim3(grid_for(num_indices, dqrm::kSegThreads, 2)),
-                       dim3(dqrm::kSegThreads), 0, st, fa);
-    DQRM_HIP_CHECK(hipGetLastError());
-    return DQRM_OK;
+    dqrm_dedupe_batch_t b;
+    b.indices = indices;
+    b.offsets = offsets;
+    b.num_indices = num_indices;
+    b.sorted_pos = sorted_pos;
+    b.uniq_rows = uniq_rows;
+    b.seg_offsets = seg_offsets;
+    b.table_uniq_offsets = table_uniq_offsets;
+    b.num_unique = num_unique;
+    b.workspace = workspace;
+    return dqrm_dedupe_multi(tables, batch, 1, &b, workspace_bytes, stream);
 }
 
 int32_t dqrm_segment_sum(const dqrm_tables_t *tables, int32_t batch, int64_t num_indices, const float *grad_out,
@@ -309,7 +339,7 @@ int32_t dqrm_segment_sum(const dqrm_tables_t *tables, int32_t batch, int64_t num
     if (rc != DQRM_OK) return rc;
     if (batch < 1 || num_indices < 0) return DQRM_ERR_INVALID_ARG;
     if (num_indices > kMaxIndices || (int64_t)batch * tables->num_tables > kMaxIndices) return DQRM_ERR_UNSUPPORTED;
-    if (!grad_out || !values || !g_absmax || !workspace) return DQRM_ERR_INVALID_ARG;
+    if (!grad_out || !values || !workspace) return DQRM_ERR_INVALID_ARG;
     if (!aligned(grad_out, 16) || !aligned(values, 16) || !aligned(workspace, 256)) return DQRM_ERR_INVALID_ARG;
     const int T = tables->num_tables, D = tables->dim;
     const WsLayout L = ws_layout(T, D, num_indices);
@@ -330,8 +360,9 @@ int32_t dqrm_segment_sum(const dqrm_tables_t *tables, int32_t batch, int64_t num
     const int grid_sum = grid_for(num_indices * G, dqrm::kSegThreads, dqrm::kSegBlocksPerCu);
     const int grid_comb = grid_for(num_indices * G, dqrm::kSegThreads, 4);
     launch_segsum(G, dim3(grid_sum), dim3(grid_comb), st, sa);
-    hipLaunchKernelGGL(dqrm::absmax_finalize_kernel, dim3((T + 255) / 256), dim3(256), 0, st, sa.ws.absmax_slots, T,
-                       g_absmax);
+    if (g_absmax)
+        hipLaunchKernelGGL(dqrm::absmax_finalize_kernel, dim3((T + 255) / 256), dim3(256), 0, st, sa.ws.absmax_slots,
+                           T, g_absmax);
     DQRM_HIP_CHECK(hipGetLastError());
     return DQRM_OK;
 }
@@ -400,6 +431,45 @@ int32_t dqrm_sparse_update(const dqrm_tables_t *tables, int64_t capacity, const 
     a.D = tables->dim;
     hipStream_t st = static_cast<hipStream_t>(stream);
     hipLaunchKernelGGL(dqrm::sparse_update_kernel, dim3(grid_for(capacity * (a.D / 4), dqrm::kEwThreads, 8)),
+                       dim3(dqrm::kEwThreads), 0, st, a);
+    DQRM_HIP_CHECK(hipGetLastError());
+    return DQRM_OK;
+}
+
+int32_t dqrm_quant_update(const dqrm_tables_t *tables, int64_t capacity, int64_t num_indices, const float *values,
+                          const int64_t *uniq_rows, const int32_t *table_uniq_offsets, float *g_absmax, int8_t *gq,
+                          float *g_scale, float lr, void *workspace, size_t workspace_bytes, void *stream)
+{
+    int64_t R = 0;
+    int32_t rc = check_tables(tables, false, &R);
+    if (rc != DQRM_OK) return rc;
+    if (capacity < 0 || num_indices < 0 || !values || !uniq_rows || !table_uniq_offsets || !g_absmax || !gq ||
+        !g_scale || !workspace)
+        return DQRM_ERR_INVALID_ARG;
+    if (capacity > kMaxIndices || num_indices > kMaxIndices) return DQRM_ERR_UNSUPPORTED;
+    if (!aligned(values, 16) || !aligned(gq, 4) || !aligned(workspace, 256)) return DQRM_ERR_INVALID_ARG;
+    const WsLayout L = ws_layout(tables->num_tables, tables->dim, num_indices);
+    if (workspace_bytes < L.total) return DQRM_ERR_WORKSPACE_TOO_SMALL;
+    dqrm::QuantUpdateArgs a;
+    a.u.master = tables->master;
+    a.u.packed = tables->packed;
+    a.u.w_scale = tables->w_scale;
+    a.u.row_offsets = tables->row_offsets_dev;
+    a.u.uniq_rows = uniq_rows;
+    a.u.tuo = table_uniq_offsets;
+    a.u.gq = nullptr;
+    a.u.g_scale = nullptr;
+    a.u.capacity = capacity;
+    a.u.lr = lr;
+    a.u.T = tables->num_tables;
+    a.u.D = tables->dim;
+    a.values = values;
+    a.absmax_slots = ws_views(workspace, L).absmax_slots;
+    a.g_absmax = g_absmax;
+    a.gq_out = gq;
+    a.g_scale_out = g_scale;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    hipLaunchKernelGGL(dqrm::quant_update_kernel, dim3(grid_for(capacity * (a.u.D / 4), dqrm::kEwThreads, 8)),
                        dim3(dqrm::kEwThreads), 0, st, a);
     DQRM_HIP_CHECK(hipGetLastError());
     return DQRM_OK;

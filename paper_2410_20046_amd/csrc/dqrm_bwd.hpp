@@ -55,17 +55,6 @@ struct BwdWs {
     float *absmax_slots;      // [T][kAbsmaxSlots] running maxima, one 128-byte line per entry
 };
 
-// Per-table maxima are first gathered in kAbsmaxSlots separate cache lines per
-// table (workgroups pick a slot by their index), so that atomics from thousands
-// of workgroups do not all queue on one line; a last small kernel folds them.
-constexpr int kAbsmaxSlots = 16;
-constexpr int kAbsmaxStride = 32; // floats between slots = 128 bytes
-
-__device__ __forceinline__ float *absmax_slot(float *slots, int t, int k)
-{
-    return slots + ((int64_t)t * kAbsmaxSlots + k) * kAbsmaxStride;
-}
-
 // A chunk = up to DQRM_SEG_CHUNK consecutive sorted lookups of one segment.  Its
 // descriptor is one 16-byte record, so that the summing kernels need a single
 // load to know their work:
@@ -115,11 +104,38 @@ __device__ __forceinline__ int block_excl_scan_add(int v, int lane, int wave, in
     return base + incl - v;
 }
 
-__global__ __launch_bounds__(kDdThreads) void dedupe_kernel(const int64_t *__restrict__ indices,
-                                                            const int64_t *__restrict__ offsets,
-                                                            const int64_t *__restrict__ row_offsets, int T, int B,
-                                                            int64_t N, BwdWs ws, int32_t *__restrict__ sorted_pos)
+// One launch can dedupe several batches (blockIdx.y picks the batch): the work
+// depends only on the indices, and a table's sort occupies a single CU, so the
+// batches of the next few steps fill the chip where one batch would use T CUs.
+struct DedupeBatch {
+    const int64_t *indices;
+    const int64_t *offsets;
+    int64_t N;
+    BwdWs ws;
+    int32_t *sorted_pos;
+    int32_t *tuo;
+    int32_t *num_unique;
+    int64_t *uniq_rows;
+    int32_t *seg_offsets;
+};
+struct DedupeArgs {
+    DedupeBatch b[DQRM_MAX_DEDUPE_BATCHES];
+    const int64_t *row_offsets;
+    int T, B;
+};
+
+__global__ __launch_bounds__(kDdThreads) void dedupe_kernel(DedupeArgs args)
 {
+    const DedupeBatch &bt = args.b[blockIdx.y];
+    const int64_t *__restrict__ indices = bt.indices;
+    const int64_t *__restrict__ offsets = bt.offsets;
+    const int64_t *__restrict__ row_offsets = args.row_offsets;
+    const int T = args.T, B = args.B;
+    const int64_t N = bt.N;
+    const BwdWs ws = bt.ws;
+    int32_t *__restrict__ sorted_pos = bt.sorted_pos;
+    (void)T;
+
     __shared__ unsigned skey[kDdCap];        // 64 KB
     __shared__ unsigned short spos[kDdCap];  // 32 KB
     __shared__ unsigned cnt[kDdWaves * 256]; // 16 KB, cnt[wave * 256 + digit]
@@ -398,16 +414,6 @@ __global__ __launch_bounds__(kDdThreads) void dedupe_kernel(const int64_t *__res
 // Kernel 2 of dqrm_dedupe: table-local lists -> one dense, global chunk list and
 // the index-only outputs (unique rows, segment offsets, table offsets, count).
 
-struct FinishArgs {
-    BwdWs ws;
-    int32_t *tuo;
-    int32_t *num_unique;
-    int64_t *uniq_rows;
-    int32_t *seg_offsets;
-    int64_t N;
-    int T;
-};
-
 // Turns the per-table counts into offsets in LDS (every block does this; T is
 // small).  s_tuo / s_tco receive T+1 entries, s_base T.
 __device__ __forceinline__ void table_offsets_to_lds(const BwdWs &ws, int T, int *s_tuo, int *s_tco, int *s_base,
@@ -477,8 +483,19 @@ __device__ __forceinline__ void table_offsets_to_lds(const BwdWs &ws, int T, int
 //   y  len | index of the chunk inside its segment | chunks in the segment (as above)
 //   z  global index of the segment (row of `values`)
 //   w  table
-__global__ __launch_bounds__(kSegThreads) void dedupe_finish_kernel(FinishArgs a)
+__global__ __launch_bounds__(kSegThreads) void dedupe_finish_kernel(DedupeArgs args)
 {
+    struct {
+        BwdWs ws;
+        int32_t *tuo;
+        int32_t *num_unique;
+        int64_t *uniq_rows;
+        int32_t *seg_offsets;
+        int64_t N;
+        int T;
+    } a = {args.b[blockIdx.y].ws,        args.b[blockIdx.y].tuo,         args.b[blockIdx.y].num_unique,
+           args.b[blockIdx.y].uniq_rows, args.b[blockIdx.y].seg_offsets, args.b[blockIdx.y].N,
+           args.T};
     __shared__ int s_tco[DQRM_MAX_TABLES + 1];
     __shared__ int s_tuo[DQRM_MAX_TABLES + 1];
     __shared__ int s_base[DQRM_MAX_TABLES];

@@ -149,4 +149,15 @@ __device__ __forceinline__ void atomic_max_nonneg(float *addr, float v)
     atomicMax(reinterpret_cast<unsigned *>(addr), __float_as_uint(v));
 }
 
+// Per-table maxima are first gathered in kAbsmaxSlots separate cache lines per
+// table (workgroups pick a slot by their index), so that atomics from thousands
+// of workgroups do not all queue on one line; a last small kernel folds them.
+constexpr int kAbsmaxSlots = 16;
+constexpr int kAbsmaxStride = 32; // floats between slots = 128 bytes
+
+__device__ __forceinline__ float *absmax_slot(float *slots, int t, int k)
+{
+    return slots + ((int64_t)t * kAbsmaxSlots + k) * kAbsmaxStride;
+}
+
 } // namespace dqrm

@@ -103,6 +103,113 @@ __global__ __launch_bounds__(kEwThreads) void sparse_update_kernel(UpdateArgs a)
     }
 }
 
+// ---- B4 + B5 in one pass ---------------------------------------------------------
+// Same results as grad_quant_kernel followed by sparse_update_kernel (and as the
+// fold of the per-table maxima that ends the segment sums): every block folds
+// the maxima itself, then each thread quantises four gradient values, stores
+// their INT8 codes, and applies the dequantised step to its four master weights.
+struct QuantUpdateArgs {
+    UpdateArgs u;             // u.gq / u.g_scale are written here, not read
+    const float *values;
+    float *absmax_slots;       // [T][kAbsmaxSlots], see absmax_slot()
+    float *g_absmax;           // [T] out
+    int8_t *gq_out;
+    float *g_scale_out;
+};
+
+constexpr int kQuPerThread = 4; // float4 elements a thread has in flight
+
+__global__ __launch_bounds__(kEwThreads) void quant_update_kernel(QuantUpdateArgs a)
+{
+    __shared__ int s_tuo[DQRM_MAX_TABLES + 1];
+    __shared__ float s_gs[DQRM_MAX_TABLES];
+    const int T = a.u.T;
+    for (int k = threadIdx.x; k <= T; k += kEwThreads) {
+        s_tuo[k] = a.u.tuo[k];
+        if (k < T) {
+            float v[kAbsmaxSlots];
+#pragma unroll
+            for (int q = 0; q < kAbsmaxSlots; ++q) v[q] = *absmax_slot(a.absmax_slots, k, q);
+            float m = 0.0f;
+#pragma unroll
+            for (int q = 0; q < kAbsmaxSlots; ++q) m = fmaxf(m, v[q]);
+            const float gs = scale_from_absmax(m, 127.0f);
+            s_gs[k] = gs;
+            if (blockIdx.x == 0) {
+                a.g_absmax[k] = m;
+                a.g_scale_out[k] = gs;
+            }
+        }
+    }
+    __syncthreads();
+    int64_t U = s_tuo[T];
+    U = U < 0 ? 0 : (U > a.u.capacity ? a.u.capacity : U);
+    const int D = a.u.D, q4 = D >> 2;
+    const int64_t total = U * q4;
+    const int64_t nthreads = (int64_t)gridDim.x * kEwThreads;
+    for (int64_t e0 = (int64_t)blockIdx.x * kEwThreads + threadIdx.x; e0 < total; e0 += nthreads * kQuPerThread) {
+        // 1. gradient values and row ids of all elements of the batch
+        float4 v[kQuPerThread];
+        int64_t row[kQuPerThread];
+        int tab[kQuPerThread], c4[kQuPerThread];
+#pragma unroll
+        for (int k = 0; k < kQuPerThread; ++k) {
+            const int64_t e = e0 + k * nthreads;
+            row[k] = -1;
+            tab[k] = 0;
+            c4[k] = 0;
+            v[k] = make_float4(0.f, 0.f, 0.f, 0.f);
+            if (e < total) {
+                const int64_t u = e / q4;
+                c4[k] = (int)(e - u * q4);
+                tab[k] = table_of(s_tuo, T, (int)u);
+                v[k] = reinterpret_cast<const float4 *>(a.values)[e];
+                row[k] = a.u.uniq_rows[u];
+            }
+        }
+        // 2. their master weights
+        float4 w[kQuPerThread];
+#pragma unroll
+        for (int k = 0; k < kQuPerThread; ++k) {
+            const int64_t e = e0 + k * nthreads;
+            w[k] = make_float4(0.f, 0.f, 0.f, 0.f);
+            if (e < total) {
+                const int64_t r0 = a.u.row_offsets[tab[k]], r1 = a.u.row_offsets[tab[k] + 1];
+                if (row[k] < 0 || row[k] >= r1 - r0) {
+                    if (c4[k] == 0) report(DQRM_ERR_INDEX_OUT_OF_RANGE, tab[k], row[k]);
+                    row[k] = -1;
+                } else {
+                    row[k] += r0;
+                    w[k] = reinterpret_cast<const float4 *>(a.u.master + row[k] * D)[c4[k]];
+                }
+            }
+        }
+        // 3. quantise, store the codes, step, re-encode
+#pragma unroll
+        for (int k = 0; k < kQuPerThread; ++k) {
+            const int64_t e = e0 + k * nthreads;
+            if (e >= total) continue;
+            const float gs = s_gs[tab[k]];
+            const char4 c = make_char4((signed char)(int)int8_code(v[k].x, gs), (signed char)(int)int8_code(v[k].y, gs),
+                                       (signed char)(int)int8_code(v[k].z, gs), (signed char)(int)int8_code(v[k].w, gs));
+            reinterpret_cast<char4 *>(a.gq_out)[e] = c;
+            if (row[k] < 0) continue;
+            // g = g_scale * code; w <- w - lr * g, each operation rounded on its own
+            float4 x = w[k];
+            x.x = x.x - a.u.lr * (gs * (float)c.x);
+            x.y = x.y - a.u.lr * (gs * (float)c.y);
+            x.z = x.z - a.u.lr * (gs * (float)c.z);
+            x.w = x.w - a.u.lr * (gs * (float)c.w);
+            reinterpret_cast<float4 *>(a.u.master + row[k] * D)[c4[k]] = x;
+            if (a.u.packed) {
+                const float ws = a.u.w_scale[tab[k]];
+                const unsigned p = pack4(int4_code(x.x, ws), int4_code(x.y, ws), int4_code(x.z, ws), int4_code(x.w, ws));
+                *reinterpret_cast<unsigned short *>(a.u.packed + row[k] * (D >> 1) + c4[k] * 2) = (unsigned short)p;
+            }
+        }
+    }
+}
+
 // ---- S0: per-table absmax of the master table ----------------------------------
 __global__ void fill_u32_kernel(unsigned *p, unsigned v, int n)
 {

@@ -211,6 +211,79 @@ def test_split_backward_on_two_streams(oracle):
     assert run.status()[0] == 0
 
 
+def test_dedupe_multi_equals_single(oracle):
+    """three batches deduped by one dqrm_dedupe_multi launch == the oracle's dedupe of each batch, and the
+    segment sums that follow use each batch's own workspace."""
+    import torch
+    import paper_2410_20046_amd as dq
+
+    cards = np.array([11, 5000, 250000], np.int64)
+    wl = Workload(name="multi", T=3, D=16, B=2048, alpha=1.05, seed=51, cards=cards)
+    W = np.zeros((wl.R, wl.D), np.float32)
+    _say("multi-batch dedupe")
+    runs, batches = [], []
+    host = [wl.batch(k, pooling="ragged" if k == 1 else "one", max_len=3) for k in range(3)]
+    cap = max(len(i) for i, _ in host)  # every batch gets buffers and a workspace sized for the largest
+    for k in range(3):
+        idx, off = host[k]
+        r = GpuRun(wl.row_offsets, wl.D, W, wl.B, cap, with_packed=False, want_codes=False)
+        r.upload_batch(idx, off, wl.grad_normal(k))
+        runs.append((r, idx, off))
+        b = r.bufs
+        batches.append((r.idx, r.off, b.sorted_pos, b.uniq_rows, b.seg_offsets, b.table_uniq_offsets, b.num_unique,
+                        b.workspace))
+    dq.dqrm_dedupe_multi(runs[0][0].tables, wl.B, batches)
+    for k, (r, idx, off) in enumerate(runs):
+        b = r.bufs
+        dq.dqrm_segment_sum(r.tables, wl.B, len(idx), r.grad, b.values, b.g_absmax, b.workspace)
+        U = int(b.num_unique.cpu().item())
+        got = dict(U=U, sorted_pos=b.sorted_pos.cpu().numpy()[:len(idx)], uniq_rows=b.uniq_rows.cpu().numpy()[:U],
+                   seg_offsets=b.seg_offsets.cpu().numpy()[:U + 1],
+                   table_uniq_offsets=b.table_uniq_offsets.cpu().numpy(), values=b.values.cpu().numpy()[:U],
+                   g_absmax=b.g_absmax.cpu().numpy())
+        o = oracle.embbag_bwd(wl.T, wl.D, wl.B, idx, off, wl.grad_normal(k))
+        compare_bwd(got, o, f"multi/{k}")
+        assert_exact(got["values"].view(np.uint32), o["values"].view(np.uint32), f"multi/{k} values bits")
+    assert runs[0][0].status()[0] == 0
+
+
+def test_fused_quant_update_matches_two_call_path(oracle):
+    """dqrm_segment_sum(g_absmax=NULL) + dqrm_quant_update == segment_sum + grad_quant_int8 + sparse_update
+    == the oracle, bit for bit (codes, scales, absmax, master, packed)."""
+    import torch
+    import paper_2410_20046_amd as dq
+
+    cards = np.array([9, 700, 120000, 33], np.int64)
+    wl = Workload(name="fused", T=4, D=64, B=4096, alpha=1.1, seed=41, cards=cards)
+    idx, off = wl.batch(0)
+    g = wl.grad_normal(0)
+    W = wl.tables(threads=1)
+    _say("fused quant+update")
+    run = GpuRun(wl.row_offsets, wl.D, W, wl.B, len(idx), want_codes=False)
+    run.upload_batch(idx, off, g)
+    s = run.find_scale()
+    run.pack()
+    b = run.bufs
+    dq.dqrm_dedupe(run.tables, run.idx, run.off, wl.B, b.sorted_pos, b.uniq_rows, b.seg_offsets,
+                   b.table_uniq_offsets, b.num_unique, b.workspace)
+    dq.dqrm_segment_sum(run.tables, wl.B, len(idx), run.grad, b.values, None, b.workspace)
+    dq.dqrm_quant_update(run.tables, b.cap, len(idx), b.values, b.uniq_rows, b.table_uniq_offsets, b.g_absmax, b.gq,
+                         b.g_scale, 0.1, b.workspace)
+    U = int(b.num_unique.cpu().item())
+    Wo = W.copy()
+    po = oracle.pack_int4(Wo, wl.row_offsets, s)
+    o = oracle.embbag_bwd(wl.T, wl.D, wl.B, idx, off, g)
+    gq_o, gs_o = oracle.grad_quant_int8(wl.T, wl.D, o["values"], o["table_uniq_offsets"], o["g_absmax"])
+    oracle.sparse_update(Wo, po, wl.row_offsets, s, o["uniq_rows"], o["table_uniq_offsets"], gq_o, gs_o, 0.1)
+    assert U == o["U"]
+    assert_exact(b.g_absmax.cpu().numpy().view(np.uint32), o["g_absmax"].view(np.uint32), "fused g_absmax bits")
+    assert_exact(b.g_scale.cpu().numpy().view(np.uint32), gs_o.view(np.uint32), "fused g_scale bits")
+    assert_exact(b.gq.cpu().numpy()[:U], gq_o, "fused INT8 codes")
+    assert_exact(run.master_np().view(np.uint32), Wo.view(np.uint32), "fused master bits")
+    assert_exact(run.packed_np(), po, "fused packed bytes")
+    assert run.status()[0] == 0
+
+
 # --------------------------------------------------------------------------
 # data-dependent errors: reported, never acted upon
 # --------------------------------------------------------------------------

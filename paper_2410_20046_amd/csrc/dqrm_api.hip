@@ -70,8 +70,8 @@ int32_t check_batch(const dqrm_tables_t *tb, const int64_t *indices, const int64
 
 // ---- workspace layout of dqrm_embbag_bwd -------------------------------------
 struct WsLayout {
-    size_t off_table_base, off_table_nuniq, off_table_nchunk, off_totals, off_bag_of_pos, off_sorted_bag,
-        off_chunk_local, off_chunk_desc, off_partial_full, off_partial_last, off_absmax_slots, total;
+    size_t off_table_base, off_table_nuniq, off_table_nchunk, off_table_nsingle, off_totals, off_bag_of_pos, off_sorted_bag,
+        off_chunk_local, off_single_local, off_chunk_desc, off_single_desc, off_partial_full, off_partial_last, off_absmax_slots, total;
 };
 
 size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
@@ -89,11 +89,14 @@ WsLayout ws_layout(int32_t T, int32_t D, int64_t N)
     L.off_table_base = take(t * sizeof(int));
     L.off_table_nuniq = take(t * sizeof(int));
     L.off_table_nchunk = take(t * sizeof(int));
-    L.off_totals = take(2 * sizeof(int));
+    L.off_table_nsingle = take(t * sizeof(int));
+    L.off_totals = take(4 * sizeof(int));
     L.off_bag_of_pos = take(n * sizeof(int));
     L.off_sorted_bag = take(n * sizeof(int));
     L.off_chunk_local = take(n * 16);
+    L.off_single_local = take(n * 16);
     L.off_chunk_desc = take(n * 16);
+    L.off_single_desc = take(n * 16);
     L.off_partial_full = take(slots * (size_t)D * sizeof(float));
     L.off_partial_last = take(slots * (size_t)D * sizeof(float));
     L.off_absmax_slots = take(t * dqrm::kAbsmaxSlots * dqrm::kAbsmaxStride * sizeof(float));
@@ -108,11 +111,14 @@ dqrm::BwdWs ws_views(void *workspace, const WsLayout &L)
     w.table_base = reinterpret_cast<int *>(b + L.off_table_base);
     w.table_nuniq = reinterpret_cast<int *>(b + L.off_table_nuniq);
     w.table_nchunk = reinterpret_cast<int *>(b + L.off_table_nchunk);
+    w.table_nsingle = reinterpret_cast<int *>(b + L.off_table_nsingle);
     w.totals = reinterpret_cast<int *>(b + L.off_totals);
     w.bag_of_pos = reinterpret_cast<int *>(b + L.off_bag_of_pos);
     w.sorted_bag = reinterpret_cast<int *>(b + L.off_sorted_bag);
     w.chunk_local = reinterpret_cast<int4 *>(b + L.off_chunk_local);
+    w.single_local = reinterpret_cast<int4 *>(b + L.off_single_local);
     w.chunk_desc = reinterpret_cast<int4 *>(b + L.off_chunk_desc);
+    w.single_desc = reinterpret_cast<int4 *>(b + L.off_single_desc);
     w.partial_full = reinterpret_cast<float *>(b + L.off_partial_full);
     w.partial_last = reinterpret_cast<float *>(b + L.off_partial_last);
     w.absmax_slots = reinterpret_cast<float *>(b + L.off_absmax_slots);

@@ -44,12 +44,15 @@ constexpr int kSegBlocksPerCu = DQRM_SEG_BPC; // grid of the chunk-sum kernel, i
 struct BwdWs {
     int *table_base;          // [T]   first lookup position of the table
     int *table_nuniq;         // [T]
-    int *table_nchunk;        // [T]
+    int *table_nchunk;        // [T]   chunks other than singles
+    int *table_nsingle;       // [T]   rows looked up exactly once
     int *bag_of_pos;          // [N]   bag (within its table) of every lookup position
     int *sorted_bag;          // [N]   bag of every sorted lookup
     int4 *chunk_local;        // [N]   table-local chunk lists (table t's start at its first lookup position)
+    int4 *single_local;       // [N]   table-local lists of singles: {sorted position, bag, segment, row}
     int4 *chunk_desc;         // [N]   dense chunk list over all tables, as the summing kernels read it
-    int *totals;              // [2]   chunks, segments
+    int4 *single_desc;        // [N]   dense list of singles: {bag, global segment, table, -}
+    int *totals;              // [3]   chunks, segments, singles
     float *partial_full;      // [(N/32 + 2) * D] partial of a full chunk of a long segment
     float *partial_last;      // [(N/32 + 2) * D] partial of the last chunk of a long segment
     float *absmax_slots;      // [T][kAbsmaxSlots] running maxima, one 128-byte line per entry
@@ -237,15 +240,15 @@ __global__ __launch_bounds__(kDdThreads) void dedupe_kernel(DedupeArgs args)
         DQRM_TICK(8 + p);
         for (int k = tid; k < kDdWaves * 256; k += kDdThreads) cnt[k] = 0;
         __syncthreads();
-        unsigned lrank[kDdMaxRounds];
+        // (the rank inside the wave's digit group rides in the upper half of pos[]:
+        //  both are below 16384)
 #pragma unroll
         for (int r = 0; r < kDdMaxRounds; ++r) {
-            lrank[r] = 0;
             if (r < rounds) {
                 const unsigned d = (key[r] >> shift) & 255u;
                 const unsigned long long peers = match_any8(d);
                 const unsigned prev = cnt[wave * 256 + d];
-                lrank[r] = prev + (unsigned)__popcll(peers & lt_mask);
+                pos[r] |= (prev + (unsigned)__popcll(peers & lt_mask)) << 16;
                 if ((peers & lt_mask) == 0ull) cnt[wave * 256 + d] = prev + (unsigned)__popcll(peers);
             }
         }
@@ -268,7 +271,7 @@ __global__ __launch_bounds__(kDdThreads) void dedupe_kernel(DedupeArgs args)
         for (int r = 0; r < kDdMaxRounds; ++r) {
             if (r < rounds) {
                 const unsigned d = (key[r] >> shift) & 255u;
-                const unsigned rank = cnt[wave * 256 + d] + lrank[r];
+                const unsigned rank = cnt[wave * 256 + d] + (pos[r] >> 16);
                 skey[rank] = key[r];
                 spos[rank] = (unsigned short)pos[r];
             }
@@ -291,28 +294,32 @@ __global__ __launch_bounds__(kDdThreads) void dedupe_kernel(DedupeArgs args)
     // ---- phase 3: segment heads and chunk heads ---------------------------
     // (skey / spos now hold the table's rounds*1024 items in sorted order;
     //  entries that are padding or had a bad index carry the sentinel key.)
-    int seg_of[kDdMaxRounds];   // inclusive head count up to the item, minus one
-    int start_of[kDdMaxRounds]; // sorted index of the head of the item's segment
-    unsigned char flags[kDdMaxRounds];
+    // Per item, packed into one word to keep the register count down:
+    //   bits 0..14  segment index + 1      bits 15..29  sorted index of the segment's head + 1
+    //   bit  30     valid                  bit  31      head of its segment
+    unsigned info[kDdMaxRounds];
+    auto info_seg = [](unsigned w) { return (int)(w & 0x7FFFu) - 1; };
+    auto info_start = [](unsigned w) { return (int)((w >> 15) & 0x7FFFu) - 1; };
+    auto info_valid = [](unsigned w) { return (w >> 30) & 1u; };
+    auto info_head = [](unsigned w) { return w >> 31; };
     int carry_heads = 0, carry_start = -1, carry_valid = 0;
 #pragma unroll
     for (int r = 0; r < kDdMaxRounds; ++r) {
-        seg_of[r] = 0;
-        start_of[r] = 0;
-        flags[r] = 0;
+        info[r] = 0;
+    }
+#pragma unroll
+    for (int r = 0; r < kDdMaxRounds; ++r) {
         if (r < rounds) {
             const int i = wave * per_wave + r * kWave + lane;
             const unsigned k = skey[i];
             const bool valid = k < rows_t;
             const bool head = valid && (i == 0 || skey[i - 1] != k);
-            const int h = wave_incl_scan_add(head ? 1 : 0, lane) + carry_heads;
+            const int h = wave_incl_scan_add(head ? 1 : 0, lane) + carry_heads; // heads up to here, this wave
             const int st = max(wave_incl_scan_max(head ? i : -1, lane), carry_start);
             carry_heads = wave_last(h);
             carry_start = wave_last(st);
             carry_valid += __popcll(__ballot(valid));
-            seg_of[r] = h;
-            start_of[r] = st;
-            flags[r] = (unsigned char)((valid ? 1 : 0) | (head ? 2 : 0));
+            info[r] = (unsigned)h | ((unsigned)(st + 1) << 15) | (valid ? 1u << 30 : 0u) | (head ? 1u << 31 : 0u);
         }
     }
     // across waves: exclusive head count, running maximum of head positions
@@ -338,47 +345,71 @@ __global__ __launch_bounds__(kDdThreads) void dedupe_kernel(DedupeArgs args)
 #pragma unroll
     for (int w = 0; w < kDdWaves; ++w) n_valid += s_w[w];
 
-    // chunk heads: every DQRM_SEG_CHUNK-th item of a segment, counted from its head
-    int chunk_of[kDdMaxRounds];
+    // segment heads leave their sorted index in LDS, so that every item can find
+    // the end of its segment
+#pragma unroll
+    for (int r = 0; r < kDdMaxRounds; ++r) {
+        if (r < rounds) {
+            const int i = wave * per_wave + r * kWave + lane;
+            const int seg = (int)(info[r] & 0x7FFFu) + heads_before - 1;     // -1 .. 16383
+            const int start = max(info_start(info[r]), start_before);        // -1 .. 16383
+            info[r] = (unsigned)(seg + 1) | ((unsigned)(start + 1) << 15) | (info[r] & 0xC0000000u);
+            if (info_head(info[r])) shead[seg] = (unsigned short)i;
+        }
+    }
+    if (tid == 0) shead[n_uniq] = (unsigned short)n_valid; // end sentinel (n_valid <= 16384 fits)
+    __syncthreads();
+
+    // chunk heads: every DQRM_SEG_CHUNK-th item of a segment, counted from its
+    // head.  Two classes, listed separately: "single" = a row looked up exactly
+    // once (the common case, no summation needed), and all other chunks.  One
+    // scan counts both (bits 0..14: singles, bits 16..30: the others; each <= 16384);
+    // bits 15 / 31 of the stored word then mark what the item itself is.
+    unsigned chunk_of[kDdMaxRounds];
     int carry_chunks = 0;
 #pragma unroll
     for (int r = 0; r < kDdMaxRounds; ++r) {
         chunk_of[r] = 0;
         if (r < rounds) {
             const int i = wave * per_wave + r * kWave + lane;
-            seg_of[r] = seg_of[r] + heads_before - 1;
-            start_of[r] = max(start_of[r], start_before);
-            const bool valid = flags[r] & 1;
-            if (flags[r] & 2) shead[seg_of[r]] = (unsigned short)i;
-            const bool chead = valid && (((i - start_of[r]) % DQRM_SEG_CHUNK) == 0);
-            const int c = wave_incl_scan_add(chead ? 1 : 0, lane) + carry_chunks;
+            const bool chead = info_valid(info[r]) && (((i - info_start(info[r])) % DQRM_SEG_CHUNK) == 0);
+            const bool single = chead && info_head(info[r]) && ((int)shead[info_seg(info[r]) + 1] == i + 1);
+            const int c = wave_incl_scan_add(chead ? (single ? 1 : 0x10000) : 0, lane) + carry_chunks;
             carry_chunks = wave_last(c);
-            chunk_of[r] = c;
-            if (chead) flags[r] |= 4;
+            chunk_of[r] = (unsigned)c | (chead ? (single ? 1u << 15 : 1u << 31) : 0u);
         }
     }
-    if (tid == 0) shead[n_uniq] = (unsigned short)n_valid; // end sentinel (n_valid <= 16384 fits)
     __syncthreads();
     if (lane == 0) s_w[wave] = carry_chunks;
     __syncthreads();
-    int chunks_before = 0, n_chunk = 0;
+    int singles_before = 0, chunks_before = 0, n_single = 0, n_chunk = 0;
 #pragma unroll
     for (int w = 0; w < kDdWaves; ++w) {
-        if (w < wave) chunks_before += s_w[w];
-        n_chunk += s_w[w];
+        const int x = s_w[w];
+        if (w < wave) {
+            singles_before += x & 0x7FFF;
+            chunks_before += x >> 16;
+        }
+        n_single += x & 0x7FFF;
+        n_chunk += x >> 16;
     }
 
     // ---- phase 4: write the table-local lists -------------------------------
     DQRM_TICK(5);
-    int bag_of_item[kDdMaxRounds];
+    if (!one_each) {
+        // bag of every sorted lookup: gathered first, all at once, so that the loads overlap
 #pragma unroll
-    for (int r = 0; r < kDdMaxRounds; ++r) { // all gathers first, so that they overlap
-        bag_of_item[r] = 0;
-        if (r < rounds) {
-            const int i = wave * per_wave + r * kWave + lane;
-            const int p = spos[i];
-            if (flags[r] & 1) bag_of_item[r] = one_each ? p : ws.bag_of_pos[base + p];
+        for (int r = 0; r < kDdMaxRounds; ++r) {
+            if (r < rounds) {
+                const int i = wave * per_wave + r * kWave + lane;
+                if (info_valid(info[r])) {
+                    int b = ws.bag_of_pos[base + spos[i]];
+                    b = b < 0 ? 0 : (b >= B ? B - 1 : b);
+                    ws.sorted_bag[base + i] = b;
+                }
+            }
         }
+        __syncthreads(); // the singles below read their own entry back
     }
 #pragma unroll
     for (int r = 0; r < kDdMaxRounds; ++r) {
@@ -386,18 +417,20 @@ __global__ __launch_bounds__(kDdThreads) void dedupe_kernel(DedupeArgs args)
             const int i = wave * per_wave + r * kWave + lane;
             const int p = spos[i];
             if (i < n) sorted_pos[base + i] = base + p;
-            if (flags[r] & 1) {
-                int b = bag_of_item[r];
-                b = b < 0 ? 0 : (b >= B ? B - 1 : b);
-                ws.sorted_bag[base + i] = b;
-            }
-            if (flags[r] & 4) {
-                const int c = chunk_of[r] + chunks_before - 1;
-                const int s0 = start_of[r], s1 = shead[seg_of[r] + 1];
+            if (one_each && info_valid(info[r])) ws.sorted_bag[base + i] = p < B ? p : B - 1;
+            const int seg = info_seg(info[r]);
+            if (chunk_of[r] & (1u << 31)) { // head of a chunk that is not a single
+                const int c = (int)((chunk_of[r] >> 16) & 0x7FFFu) + chunks_before - 1;
+                const int s0 = info_start(info[r]), s1 = shead[seg + 1];
                 const int len = min(DQRM_SEG_CHUNK, s1 - i);
                 ws.chunk_local[base + c] =
                     make_chunk_desc(base + i, len, (i - s0) / DQRM_SEG_CHUNK,
-                                    (s1 - s0 + DQRM_SEG_CHUNK - 1) / DQRM_SEG_CHUNK, seg_of[r], skey[i]);
+                                    (s1 - s0 + DQRM_SEG_CHUNK - 1) / DQRM_SEG_CHUNK, seg, skey[i]);
+            }
+            if (chunk_of[r] & (1u << 15)) { // a row looked up exactly once
+                const int c = (int)(chunk_of[r] & 0x7FFFu) + singles_before - 1;
+                const int b = one_each ? (p < B ? p : B - 1) : ws.sorted_bag[base + i];
+                ws.single_local[base + c] = make_int4(base + i, b, seg, (int)skey[i]);
             }
         }
     }
@@ -405,6 +438,7 @@ __global__ __launch_bounds__(kDdThreads) void dedupe_kernel(DedupeArgs args)
         ws.table_base[t] = base;
         ws.table_nuniq[t] = n_uniq;
         ws.table_nchunk[t] = n_chunk;
+        ws.table_nsingle[t] = n_single;
     }
     if (tid < kAbsmaxSlots) *absmax_slot(ws.absmax_slots, t, tid) = 0.0f;
     DQRM_TICK(6);
@@ -415,28 +449,33 @@ __global__ __launch_bounds__(kDdThreads) void dedupe_kernel(DedupeArgs args)
 // the index-only outputs (unique rows, segment offsets, table offsets, count).
 
 // Turns the per-table counts into offsets in LDS (every block does this; T is
-// small).  s_tuo / s_tco receive T+1 entries, s_base T.
-__device__ __forceinline__ void table_offsets_to_lds(const BwdWs &ws, int T, int *s_tuo, int *s_tco, int *s_base,
-                                                     int *s_w)
+// small).  s_tuo / s_tco / s_tso receive T+1 entries (segments, chunks, singles),
+// s_base T.
+__device__ __forceinline__ void table_offsets_to_lds(const BwdWs &ws, int T, int *s_tuo, int *s_tco, int *s_tso,
+                                                     int *s_base, int *s_w)
 {
     const int tid = threadIdx.x, lane = tid & (kWave - 1), wave = tid / kWave;
     if (T <= kWave) {
         // the usual case: one wave scans the counts, no block-wide scan needed
         if (wave == 0) {
-            int u = 0, c = 0;
+            int u = 0, c = 0, g = 0;
             if (lane < T) {
                 u = ws.table_nuniq[lane];
                 c = ws.table_nchunk[lane];
+                g = ws.table_nsingle[lane];
                 s_base[lane] = ws.table_base[lane];
             }
-            const int iu = wave_incl_scan_add(u, lane), ic = wave_incl_scan_add(c, lane);
+            const int iu = wave_incl_scan_add(u, lane), ic = wave_incl_scan_add(c, lane),
+                      ig = wave_incl_scan_add(g, lane);
             if (lane < T) {
                 s_tuo[lane] = iu - u;
                 s_tco[lane] = ic - c;
+                s_tso[lane] = ig - g;
             }
             if (lane == T - 1) {
                 s_tuo[T] = iu;
                 s_tco[T] = ic;
+                s_tso[T] = ig;
             }
         }
         __syncthreads();
@@ -444,45 +483,51 @@ __device__ __forceinline__ void table_offsets_to_lds(const BwdWs &ws, int T, int
     }
     // kSegThreads threads, each owns a run of consecutive tables
     constexpr int kPer = (DQRM_MAX_TABLES + kSegThreads - 1) / kSegThreads; // 4
-    int u[kPer], c[kPer], su = 0, sc = 0;
+    int u[kPer], c[kPer], g[kPer], su = 0, sc = 0, sg = 0;
 #pragma unroll
     for (int q = 0; q < kPer; ++q) {
         const int t = tid * kPer + q;
-        u[q] = c[q] = 0;
+        u[q] = c[q] = g[q] = 0;
         if (t < T) {
             u[q] = ws.table_nuniq[t];
             c[q] = ws.table_nchunk[t];
+            g[q] = ws.table_nsingle[t];
             s_base[t] = ws.table_base[t];
         }
         su += u[q];
         sc += c[q];
+        sg += g[q];
     }
-    int tot_u, tot_c;
+    int tot_u, tot_c, tot_g;
     int eu = block_excl_scan_add<kSegThreads / kWave>(su, lane, wave, s_w, &tot_u);
     int ec = block_excl_scan_add<kSegThreads / kWave>(sc, lane, wave, s_w, &tot_c);
+    int eg = block_excl_scan_add<kSegThreads / kWave>(sg, lane, wave, s_w, &tot_g);
 #pragma unroll
     for (int q = 0; q < kPer; ++q) {
         const int t = tid * kPer + q;
         if (t < T) {
             s_tuo[t] = eu;
             s_tco[t] = ec;
+            s_tso[t] = eg;
         }
         eu += u[q];
         ec += c[q];
+        eg += g[q];
     }
     if (tid == 0) {
         s_tuo[T] = tot_u;
         s_tco[T] = tot_c;
+        s_tso[T] = tot_g;
     }
     __syncthreads();
 }
 
 // Dense chunk descriptor, as the summing kernels read it:
-//   x  a segment of exactly one lookup: that lookup's bag;
-//      otherwise the global sorted position of the chunk's first lookup
+//   x  global sorted position of the chunk's first lookup
 //   y  len | index of the chunk inside its segment | chunks in the segment (as above)
 //   z  global index of the segment (row of `values`)
 //   w  table
+// Dense single descriptor: x bag, y global index of the segment, z table.
 __global__ __launch_bounds__(kSegThreads) void dedupe_finish_kernel(DedupeArgs args)
 {
     struct {
@@ -497,12 +542,13 @@ __global__ __launch_bounds__(kSegThreads) void dedupe_finish_kernel(DedupeArgs a
            args.b[blockIdx.y].uniq_rows, args.b[blockIdx.y].seg_offsets, args.b[blockIdx.y].N,
            args.T};
     __shared__ int s_tco[DQRM_MAX_TABLES + 1];
+    __shared__ int s_tso[DQRM_MAX_TABLES + 1];
     __shared__ int s_tuo[DQRM_MAX_TABLES + 1];
     __shared__ int s_base[DQRM_MAX_TABLES];
     __shared__ int s_w[kSegThreads / kWave];
     const int T = a.T;
-    table_offsets_to_lds(a.ws, T, s_tuo, s_tco, s_base, s_w);
-    const int C = s_tco[T], U = s_tuo[T];
+    table_offsets_to_lds(a.ws, T, s_tuo, s_tco, s_tso, s_base, s_w);
+    const int C = s_tco[T], U = s_tuo[T], S = s_tso[T];
     if (blockIdx.x == 0) {
         for (int k = threadIdx.x; k <= T; k += kSegThreads) a.tuo[k] = s_tuo[k];
         if (threadIdx.x == 0) {
@@ -510,20 +556,27 @@ __global__ __launch_bounds__(kSegThreads) void dedupe_finish_kernel(DedupeArgs a
             a.seg_offsets[U] = (int32_t)a.N;
             a.ws.totals[0] = C;
             a.ws.totals[1] = U;
+            a.ws.totals[2] = S;
         }
     }
-    for (int c = (int)(blockIdx.x * kSegThreads + threadIdx.x); c < C; c += (int)(gridDim.x * kSegThreads)) {
+    const int first = (int)(blockIdx.x * kSegThreads + threadIdx.x), step = (int)(gridDim.x * kSegThreads);
+    for (int c = first; c < C; c += step) {
         const int t = table_of(s_tco, T, c);
         const int4 d = a.ws.chunk_local[s_base[t] + (c - s_tco[t])];
         const int j = s_tuo[t] + d.z;
-        const int len = desc_len(d), kchunk = desc_kchunk(d), nchunks = desc_nchunks(d);
-        int x = d.x;
-        if (kchunk == 0) { // first chunk of its segment: d.x is the segment's head
+        if (desc_kchunk(d) == 0) { // first chunk of its segment: d.x is the segment's head
             a.uniq_rows[j] = (int64_t)(unsigned)d.w;
             a.seg_offsets[j] = d.x;
-            if (len == 1 && nchunks == 1) x = a.ws.sorted_bag[d.x];
         }
-        a.ws.chunk_desc[c] = make_int4(x, d.y, j, t);
+        a.ws.chunk_desc[c] = make_int4(d.x, d.y, j, t);
+    }
+    for (int c = first; c < S; c += step) {
+        const int t = table_of(s_tso, T, c);
+        const int4 d = a.ws.single_local[s_base[t] + (c - s_tso[t])]; // {sorted position, bag, segment, row}
+        const int j = s_tuo[t] + d.z;
+        a.uniq_rows[j] = (int64_t)(unsigned)d.w;
+        a.seg_offsets[j] = d.x;
+        a.ws.single_desc[c] = make_int4(d.y, j, t, 0);
     }
 }
 
@@ -576,6 +629,51 @@ struct BlockAbsmax {
     }
 };
 
+// Sum of one chunk: its gradient rows, left to right.
+template <int G>
+__device__ __forceinline__ float4 sum_chunk(const SegArgs &a, int gstart, int len, int lg, int leader, bool col_ok,
+                                            const float *g0, int64_t tD)
+{
+    // bag of every contribution: each lane fetches its share of the chunk's bag
+    // list once, the group then passes them round with shuffles
+    const int *bags = a.ws.sorted_bag + gstart;
+    constexpr int kIdsPerLane = (DQRM_SEG_CHUNK + G - 1) / G;
+    int my_bags[kIdsPerLane];
+#pragma unroll
+    for (int q = 0; q < kIdsPerLane; ++q) {
+        const int i = q * G + lg;
+        my_bags[q] = (i < len) ? bags[i] : 0;
+    }
+    float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
+    constexpr int kBatch = kSegBatch;
+#pragma unroll
+    for (int i0 = 0; i0 < DQRM_SEG_CHUNK; i0 += kBatch) {
+        if (i0 < len) {
+            float4 g[kBatch];
+#pragma unroll
+            for (int q = 0; q < kBatch; ++q) {
+                const int i = i0 + q;
+                g[q] = make_float4(0.f, 0.f, 0.f, 0.f);
+                if (i < len) {
+                    const int b = __shfl(my_bags[i / G], leader + (i % G), kWave);
+                    if (col_ok) g[q] = *reinterpret_cast<const float4 *>(g0 + (int64_t)b * tD);
+                }
+            }
+#pragma unroll
+            for (int q = 0; q < kBatch; ++q) {
+                const int i = i0 + q;
+                if (i < len) acc = (i == 0) ? g[q] : f4_add(acc, g[q]);
+            }
+        }
+    }
+    return acc;
+}
+
+// Lane groups take the chunks one each, in order, and the singles (rows looked up
+// once: a plain copy of one gradient row) kSinglesPerGroup at a time, dealt from
+// the other end of the grid so that groups without a chunk do the copying.
+constexpr int kSinglesPerGroup = 4;
+
 template <int G>
 __global__ __launch_bounds__(kSegThreads) void chunk_sum_kernel(SegArgs a)
 {
@@ -585,78 +683,72 @@ __global__ __launch_bounds__(kSegThreads) void chunk_sum_kernel(SegArgs a)
     amax.init(s_max, T);
 
     const int lg = threadIdx.x & (G - 1);
-    const int grp = threadIdx.x / G;
     constexpr int kGroups = kSegThreads / G;
     const int col = lg * 4;
     const bool col_ok = col < D;
     const int leader = (threadIdx.x & (kWave - 1)) & ~(G - 1);
     const int64_t tD = (int64_t)T * D;
-    const int stride = (int)gridDim.x * kGroups;
-    const int cap = (int)a.N; // the chunk list has N slots, so a descriptor may be requested before C is known
+    const int cap = (int)a.N; // both lists have N slots, so descriptors may be requested before the counts are known
+    const int ngroups = (int)gridDim.x * kGroups;
+    const int gi = (int)blockIdx.x * kGroups + (int)threadIdx.x / G;
 
-    // tiles of kGroups consecutive chunks are dealt round-robin to the workgroups, so the
-    // long chunks of hot rows spread over the whole grid; the next tile's descriptor is
-    // requested before the current tile is worked on
-    int c = (int)blockIdx.x * kGroups + grp;
+    int c = gi;
+    int s0 = (ngroups - 1 - gi) * kSinglesPerGroup;
     int4 d = make_int4(0, 0, 0, 0);
+    int4 sd[kSinglesPerGroup];
     if (c < cap) d = a.ws.chunk_desc[c];
-    const int C = min(a.ws.totals[0], cap);
+#pragma unroll
+    for (int k = 0; k < kSinglesPerGroup; ++k) {
+        sd[k] = make_int4(0, 0, 0, 0);
+        if (s0 + k < cap) sd[k] = a.ws.single_desc[s0 + k];
+    }
+    const int C = min(a.ws.totals[0], cap), S = min(a.ws.totals[2], cap);
     __syncthreads(); // s_max is cleared
+
+    // ---- singles: all rows of the batch are requested before any is stored
+#if defined(DQRM_EXP_SKIP_SINGLES)
+    s0 = S;
+#endif
+#if defined(DQRM_EXP_SKIP_CHUNKS)
+    c = C;
+#endif
+    while (s0 < S) {
+        float4 r[kSinglesPerGroup];
+#pragma unroll
+        for (int k = 0; k < kSinglesPerGroup; ++k) {
+            r[k] = make_float4(0.f, 0.f, 0.f, 0.f);
+            if (s0 + k < S && col_ok)
+                r[k] = *reinterpret_cast<const float4 *>(a.grad_out + (int64_t)sd[k].z * D + col + (int64_t)sd[k].x * tD);
+        }
+#pragma unroll
+        for (int k = 0; k < kSinglesPerGroup; ++k) {
+            if (s0 + k < S && col_ok) {
+                *reinterpret_cast<float4 *>(a.values + (int64_t)sd[k].y * D + col) = r[k];
+                amax.add(sd[k].z, f4_absmax(r[k]));
+            }
+        }
+        s0 += ngroups * kSinglesPerGroup;
+#pragma unroll
+        for (int k = 0; k < kSinglesPerGroup; ++k)
+            if (s0 + k < S) sd[k] = a.ws.single_desc[s0 + k];
+    }
+
+    // ---- chunks
     while (c < C) {
-        const int c_next = c + stride;
+        const int c_next = c + ngroups;
         int4 d_next = make_int4(0, 0, 0, 0);
         if (c_next < C) d_next = a.ws.chunk_desc[c_next];
-
         int len = desc_len(d);
         len = len > DQRM_SEG_CHUNK ? DQRM_SEG_CHUNK : len;
         const int nchunks = desc_nchunks(d), kchunk = desc_kchunk(d);
         const int t = d.w;
-        const float *g0 = a.grad_out + (int64_t)t * D + col;
-        float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
-
-        if (len == 1 && nchunks == 1) {
-            // a row looked up once: the descriptor already names the bag
-            if (col_ok) acc = *reinterpret_cast<const float4 *>(g0 + (int64_t)d.x * tD);
-        } else {
-            // bag of every contribution: each lane fetches its share of the chunk's
-            // bag list once, the group then passes them round with shuffles
-            const int *bags = a.ws.sorted_bag + d.x;
-            constexpr int kIdsPerLane = (DQRM_SEG_CHUNK + G - 1) / G;
-            int my_bags[kIdsPerLane];
-#pragma unroll
-            for (int q = 0; q < kIdsPerLane; ++q) {
-                const int i = q * G + lg;
-                my_bags[q] = (i < len) ? bags[i] : 0;
-            }
-            constexpr int kBatch = kSegBatch;
-#pragma unroll
-            for (int i0 = 0; i0 < DQRM_SEG_CHUNK; i0 += kBatch) {
-                if (i0 < len) {
-                    float4 g[kBatch];
-#pragma unroll
-                    for (int q = 0; q < kBatch; ++q) {
-                        const int i = i0 + q;
-                        g[q] = make_float4(0.f, 0.f, 0.f, 0.f);
-                        if (i < len) {
-                            const int b = __shfl(my_bags[i / G], leader + (i % G), kWave);
-                            if (col_ok) g[q] = *reinterpret_cast<const float4 *>(g0 + (int64_t)b * tD);
-                        }
-                    }
-#pragma unroll
-                    for (int q = 0; q < kBatch; ++q) {
-                        const int i = i0 + q;
-                        if (i < len) acc = (i == 0) ? g[q] : f4_add(acc, g[q]);
-                    }
-                }
-            }
-        }
-
+        const float4 acc = sum_chunk<G>(a, d.x, len, lg, leader, col_ok, a.grad_out + (int64_t)t * D + col, tD);
         if (nchunks > 1) {
             // chunk of a long segment: store the partial sum for the combine kernel.
             // Full chunks are disjoint runs of DQRM_SEG_CHUNK sorted positions, so
             // (position / DQRM_SEG_CHUNK) names them uniquely; the last chunk of a
             // segment is filed under the slot of the segment's first chunk.
-            const int gpos = d.x - kchunk * DQRM_SEG_CHUNK; // global sorted position of the segment's head
+            const int gpos = d.x - kchunk * DQRM_SEG_CHUNK; // sorted position of the segment's head
             float *pslot = (kchunk == nchunks - 1) ? a.ws.partial_last + (int64_t)(gpos / DQRM_SEG_CHUNK) * D
                                                    : a.ws.partial_full + (int64_t)(d.x / DQRM_SEG_CHUNK) * D;
             if (col_ok) *reinterpret_cast<float4 *>(pslot + col) = acc;

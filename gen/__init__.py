@@ -14,4 +14,7 @@ from .workloads import (  # noqa: F401
     index_batch,
     grad_dyadic,
     grad_normal,
+    DENSE_CONFIGS,
+    make_dense_model,
+    dense_batch,
 )

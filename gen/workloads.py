@@ -230,3 +230,46 @@ def grad_normal(B: int, T: int, D: int, seed: int, k: int) -> np.ndarray:
     g = rng.standard_normal(size=(B, T, D), dtype=np.float32)
     g *= np.float32(1e-4)
     return g
+
+
+# ---- the dense part of the model (BASELINE "full train step" configuration) ---------------
+DENSE_CONFIGS = {
+    # Kaggle shape: 13 dense features, bottom MLP 13-512-256-64-16, top MLP 367-512-256-1
+    "kaggle": dict(num_dense=13, bot=[13, 512, 256, 64, 16], top_hidden=[512, 256, 1]),
+    # a small shape with the same structure and awkward (non-multiple-of-tile) widths
+    "small": dict(num_dense=5, bot=[5, 40, 16], top_hidden=[70, 33, 1]),
+    "small8": dict(num_dense=5, bot=[5, 24, 8], top_hidden=[19, 7, 1]),
+}
+
+_STREAM_DENSE = 6
+
+
+def make_dense_model(name: str, T: int, D: int, seed: int):
+    """Seeded parameters of the MLPs: W_l ~ N(0, 2/(in+out)) and b_l ~ N(0, 1/out) in fp32 (the usual DLRM
+    initialisation; the paper gives only the layer widths).  Returns (bot_dims, bot_w, bot_b, top_dims, top_w,
+    top_b) with W_l of shape [out][in]."""
+    cfg = DENSE_CONFIGS[name]
+    bot_dims = list(cfg["bot"])
+    assert bot_dims[-1] == D
+    V = T + 1
+    top_dims = [D + V * (V - 1) // 2] + list(cfg["top_hidden"])
+    rng = _rng(seed, _STREAM_DENSE, 0)
+
+    def layers(dims):
+        ws, bs = [], []
+        for i, o in zip(dims[:-1], dims[1:]):
+            ws.append((rng.standard_normal((o, i)) * math.sqrt(2.0 / (i + o))).astype(np.float32))
+            bs.append((rng.standard_normal(o) * math.sqrt(1.0 / o)).astype(np.float32))
+        return ws, bs
+
+    bw, bb = layers(bot_dims)
+    tw, tb = layers(top_dims)
+    return bot_dims, bw, bb, top_dims, tw, tb
+
+
+def dense_batch(B: int, num_dense: int, seed: int, k: int):
+    """Dense features exp(N(0,1)) [B][num_dense] fp32 and labels Bernoulli(0.25) [B] fp32."""
+    rng = _rng(seed, _STREAM_DENSE, 1, k)
+    x = np.exp(rng.standard_normal((B, num_dense))).astype(np.float32)
+    y = (rng.random(B) < 0.25).astype(np.float32)
+    return x, y

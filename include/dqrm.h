@@ -11,6 +11,8 @@
  *   dqrm_embbag_bwd      every step      dedupe -> segment-sum = sparse gradient (Sec. 4.3, "specified sparsity")
  *   dqrm_grad_quant_int8 every step      INT8 codes of the gradient values       (Appendix, gradient quantisation)
  *   dqrm_sparse_update   every step      dequantise + SGD on touched rows        (same appendix)
+ * and, between the forward and the backward of the tables, the dense part of the model:
+ *   dqrm_dense_step      every step      MLPs, interaction, loss, their backward, dense SGD
  *
  * Conventions common to every entry point
  *   - Returns 0 (DQRM_OK) or a negative DQRM_ERR_* code.  Never throws, never aborts.
@@ -201,6 +203,42 @@ int32_t dqrm_sparse_update(const dqrm_tables_t *tables, int64_t capacity, const 
 int32_t dqrm_quant_update(const dqrm_tables_t *tables, int64_t capacity, int64_t num_indices, const float *values,
                           const int64_t *uniq_rows, const int32_t *table_uniq_offsets, float *g_absmax, int8_t *gq,
                           float *g_scale, float lr, void *workspace, size_t workspace_bytes, void *stream);
+
+/* The dense part of the DLRM train step (model-architecture table; Fig. 1(a)):
+ * bottom MLP over the dense features (ReLU after every layer), pairwise-dot
+ * interaction of its output with the T pooled embeddings, top MLP (ReLU after
+ * every layer but the last), sigmoid, mean binary cross-entropy against the
+ * labels; then the backward of all of it and a plain SGD step on the MLP weights
+ * and biases, in FP32 (the paper's "MLP in FP32" variant).  The matrix products
+ * run on the matrix cores.
+ *   Interaction: vectors Z = [bottom output, table 0 .. T-1] (V = T+1, width dim);
+ *   R[b] = [Z[0] (dim values), dot(Z[i], Z[j]) for i = 1..V-1, j = 0..i-1, row-major],
+ *   so the top MLP's input width is dim + V(V-1)/2 (367 for 26 tables of dim 16).
+ *   Loss: -mean(y log max(p,1e-12) + (1-y) log max(1-p,1e-12)), p = sigmoid(logit).
+ * The descriptor and its arrays are HOST memory; W_l is a device matrix
+ * [dims[l+1]][dims[l]] row-major, b_l a device vector [dims[l+1]]; both are
+ * updated in place.  Limits: T + 1 <= 64, (T+1)*dim <= 4096, at most 16 layers
+ * per MLP.
+ *   dense_x [batch][num_dense], emb_out [batch][T][dim] (= `out` of
+ *   dqrm_embbag_fwd), labels [batch] (0 or 1, as floats)  -> loss [1] (device),
+ *   grad_emb [batch][T][dim] (= `grad_out` of dqrm_embbag_bwd). */
+typedef struct {
+    int32_t num_dense;         /* dense features per sample (13) */
+    int32_t num_tables;        /* T */
+    int32_t dim;               /* embedding width = bottom MLP output width */
+    int32_t bot_layers;        /* number of linear layers of the bottom MLP */
+    const int32_t *bot_dims;   /* HOST [bot_layers+1], bot_dims[0] = num_dense, last = dim */
+    float *const *bot_w;       /* HOST array of device pointers */
+    float *const *bot_b;
+    int32_t top_layers;
+    const int32_t *top_dims;   /* HOST [top_layers+1], top_dims[0] = dim + V(V-1)/2, last = 1 */
+    float *const *top_w;
+    float *const *top_b;
+} dqrm_dense_model_t;
+size_t dqrm_dense_workspace_bytes(const dqrm_dense_model_t *model, int32_t batch);
+int32_t dqrm_dense_step(const dqrm_dense_model_t *model, int32_t batch, const float *dense_x, const float *emb_out,
+                        const float *labels, float lr, float *loss, float *grad_emb, void *workspace,
+                        size_t workspace_bytes, void *stream);
 
 /* Synchronises `stream`, returns the first data-dependent problem recorded on
  * the current device since the last call (DQRM_OK if none) and clears it.

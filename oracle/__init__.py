@@ -15,15 +15,17 @@ import numpy as np
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _SRC = os.path.join(_HERE, "dqrm_oracle.c")
+_SRC_DENSE = os.path.join(_HERE, "dqrm_dense_oracle.c")
 _LIB = os.path.join(_HERE, "libdqrm_oracle.so")
 _lib: Optional[C.CDLL] = None
 
 
 def build(force: bool = False) -> str:
     """Compile the oracle with gcc (one rounding per operation: no contraction)."""
-    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+    newest = max(os.path.getmtime(_SRC), os.path.getmtime(_SRC_DENSE))
+    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < newest:
         cmd = ["gcc", "-O2", "-ffp-contract=off", "-fno-fast-math", "-std=c11", "-shared", "-fPIC",
-               "-o", _LIB, _SRC, "-lm"]
+               "-o", _LIB, _SRC, _SRC_DENSE, "-lm"]
         subprocess.run(cmd, check=True)
     return _LIB
 
@@ -45,6 +47,7 @@ def lib() -> C.CDLL:
         _lib.oracle_scale_from_absmax.argtypes = [C.c_float, C.c_int]
         _lib.oracle_seg_chunk.restype = C.c_int
         _lib.oracle_embbag_bwd.restype = C.c_int64
+        _lib.oracle_dense_step.restype = C.c_double
     return _lib
 
 
@@ -140,3 +143,24 @@ def sparse_update(W: np.ndarray, packed: Optional[np.ndarray], row_offsets: np.n
                                _p(w_scale, C.c_float), C.c_int(T), C.c_int(D), _p(uniq_rows, C.c_int64),
                                _p(table_uniq_offsets, C.c_int32), _p(gq, C.c_int8), _p(g_scale, C.c_float),
                                C.c_float(lr))
+
+
+def dense_step(bot_dims, bot_w, bot_b, top_dims, top_w, top_b, dense_x, emb, labels, lr):
+    """The dense part of one train step in float64.  bot_w / bot_b / top_w / top_b: lists of float64 arrays
+    (updated IN PLACE by the SGD step).  dense_x [B][num_dense], emb [B][T][D], labels [B] (any float dtype).
+    Returns (loss, grad_emb [B][T][D] float64)."""
+    B, T, D = emb.shape
+    f64 = lambda a: np.ascontiguousarray(a, dtype=np.float64)
+    x, e, y = f64(dense_x), f64(emb), f64(labels)
+    for a in list(bot_w) + list(bot_b) + list(top_w) + list(top_b):
+        assert a.dtype == np.float64 and a.flags["C_CONTIGUOUS"]
+    bd = np.ascontiguousarray(bot_dims, dtype=np.int32)
+    td = np.ascontiguousarray(top_dims, dtype=np.int32)
+    PP = C.POINTER(C.c_double)
+    arr = lambda lst: (PP * len(lst))(*[a.ctypes.data_as(PP) for a in lst])
+    grad = np.empty((B, T, D), np.float64)
+    loss = lib().oracle_dense_step(C.c_int(B), C.c_int(x.shape[1]), C.c_int(T), C.c_int(D), C.c_int(len(bot_w)),
+                                   _p(bd, C.c_int32), arr(bot_w), arr(bot_b), C.c_int(len(top_w)), _p(td, C.c_int32),
+                                   arr(top_w), arr(top_b), _p(x, C.c_double), _p(e, C.c_double), _p(y, C.c_double),
+                                   C.c_double(lr), _p(grad, C.c_double))
+    return float(loss), grad

@@ -34,7 +34,7 @@ MAX_TABLE_LOOKUPS = 16384
 
 EXPORTS = ("dqrm_find_scale", "dqrm_pack_int4", "dqrm_embbag_fwd", "dqrm_embbag_bwd_workspace_bytes",
            "dqrm_embbag_bwd", "dqrm_dedupe", "dqrm_dedupe_multi", "dqrm_segment_sum", "dqrm_grad_quant_int8",
-           "dqrm_sparse_update", "dqrm_quant_update",
+           "dqrm_sparse_update", "dqrm_quant_update", "dqrm_dense_workspace_bytes", "dqrm_dense_step",
            "dqrm_check_status", "dqrm_last_hip_error", "dqrm_version")
 
 
@@ -57,6 +57,12 @@ class dqrm_dedupe_batch_t(C.Structure):
 
 
 MAX_DEDUPE_BATCHES = 8
+
+
+class dqrm_dense_model_t(C.Structure):
+    _fields_ = [("num_dense", C.c_int32), ("num_tables", C.c_int32), ("dim", C.c_int32), ("bot_layers", C.c_int32),
+                ("bot_dims", C.c_void_p), ("bot_w", C.c_void_p), ("bot_b", C.c_void_p), ("top_layers", C.c_int32),
+                ("top_dims", C.c_void_p), ("top_w", C.c_void_p), ("top_b", C.c_void_p)]
 
 _lib: Optional[C.CDLL] = None
 
@@ -84,6 +90,11 @@ def lib() -> C.CDLL:
         L.dqrm_quant_update.argtypes = [tp, i64, i64, vp, vp, vp, vp, vp, vp, C.c_float, vp, sz, vp]
         L.dqrm_grad_quant_int8.argtypes = [i32, i32, i64, vp, vp, vp, vp, vp, vp]
         L.dqrm_sparse_update.argtypes = [tp, i64, vp, vp, vp, vp, C.c_float, vp]
+        dp = C.POINTER(dqrm_dense_model_t)
+        L.dqrm_dense_workspace_bytes.argtypes = [dp, i32]
+        L.dqrm_dense_workspace_bytes.restype = sz
+        L.dqrm_dense_step.argtypes = [dp, i32, vp, vp, vp, C.c_float, vp, vp, vp, sz, vp]
+        L.dqrm_dense_step.restype = i32
         L.dqrm_check_status.argtypes = [vp, C.POINTER(i32), C.POINTER(i64)]
         for n in ("dqrm_find_scale", "dqrm_pack_int4", "dqrm_embbag_fwd", "dqrm_embbag_bwd", "dqrm_dedupe", "dqrm_segment_sum",
                   "dqrm_quant_update", "dqrm_grad_quant_int8", "dqrm_sparse_update", "dqrm_check_status"):
@@ -221,6 +232,39 @@ def dqrm_quant_update(tables: Tables, capacity: int, num_indices: int, values: t
                                    _ptr(table_uniq_offsets), _ptr(g_absmax), _ptr(gq), _ptr(g_scale), lr,
                                    _ptr(workspace), workspace.numel() * workspace.element_size(), _stream(stream)),
            "dqrm_quant_update")
+
+
+class DenseModel:
+    """Device copies of the MLP parameters and the C descriptor of the dense part of the model."""
+
+    def __init__(self, num_tables: int, dim: int, bot_dims, bot_w, bot_b, top_dims, top_w, top_b, device):
+        to_dev = lambda lst: [torch.from_numpy(np.ascontiguousarray(a, np.float32)).to(device) for a in lst]
+        self.bot_w, self.bot_b, self.top_w, self.top_b = to_dev(bot_w), to_dev(bot_b), to_dev(top_w), to_dev(top_b)
+        self.bot_dims = np.ascontiguousarray(bot_dims, np.int32)
+        self.top_dims = np.ascontiguousarray(top_dims, np.int32)
+        ptrs = lambda lst: (C.c_void_p * len(lst))(*[t.data_ptr() for t in lst])
+        self._pw = [ptrs(self.bot_w), ptrs(self.bot_b), ptrs(self.top_w), ptrs(self.top_b)]
+        addr = lambda a: C.cast(a, C.c_void_p).value
+        self.c = dqrm_dense_model_t(int(self.bot_dims[0]), num_tables, dim, len(self.bot_w),
+                                    self.bot_dims.ctypes.data, addr(self._pw[0]), addr(self._pw[1]),
+                                    len(self.top_w), self.top_dims.ctypes.data, addr(self._pw[2]), addr(self._pw[3]))
+        self.num_tables, self.dim = num_tables, dim
+
+    @property
+    def ref(self):
+        return C.byref(self.c)
+
+
+def dqrm_dense_workspace_bytes(model: DenseModel, batch: int) -> int:
+    return int(lib().dqrm_dense_workspace_bytes(model.ref, batch))
+
+
+def dqrm_dense_step(model: DenseModel, batch: int, dense_x: torch.Tensor, emb_out: torch.Tensor,
+                    labels: torch.Tensor, lr: float, loss: torch.Tensor, grad_emb: torch.Tensor,
+                    workspace: torch.Tensor, stream=None) -> None:
+    _check(lib().dqrm_dense_step(model.ref, batch, _ptr(dense_x), _ptr(emb_out), _ptr(labels), lr, _ptr(loss),
+                                 _ptr(grad_emb), _ptr(workspace), workspace.numel() * workspace.element_size(),
+                                 _stream(stream)), "dqrm_dense_step")
 
 
 def dqrm_check_status(stream=None) -> Tuple[int, int, int]:

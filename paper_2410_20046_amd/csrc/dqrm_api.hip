@@ -10,6 +10,7 @@
 #include "dqrm_fwd.hpp"
 #include "dqrm_bwd.hpp"
 #include "dqrm_update.hpp"
+#include "dqrm_dense.hpp"
 
 namespace {
 
@@ -477,6 +478,189 @@ int32_t dqrm_quant_update(const dqrm_tables_t *tables, int64_t capacity, int64_t
     hipStream_t st = static_cast<hipStream_t>(stream);
     hipLaunchKernelGGL(dqrm::quant_update_kernel, dim3(grid_for(capacity * (a.u.D / 4), dqrm::kEwThreads, 8)),
                        dim3(dqrm::kEwThreads), 0, st, a);
+    DQRM_HIP_CHECK(hipGetLastError());
+    return DQRM_OK;
+}
+
+// ---- the dense part of the train step ---------------------------------------------
+namespace {
+
+constexpr int kMaxMlpLayers = 16;
+
+struct DenseLayout {
+    // activations: bot_act[l] = output of bottom layer l, R = interaction output,
+    // top_act[l] = output of top layer l (the last one is the logit), dz, two gradient buffers
+    size_t bot_act[kMaxMlpLayers], top_act[kMaxMlpLayers], R, dz, gA, gB, total;
+};
+
+int32_t check_dense_model(const dqrm_dense_model_t *m, int32_t batch)
+{
+    if (!m || batch < 1) return DQRM_ERR_INVALID_ARG;
+    if (m->num_dense < 1 || m->num_tables < 1 || m->dim < 1 || m->bot_layers < 1 || m->top_layers < 1)
+        return DQRM_ERR_INVALID_ARG;
+    if (!m->bot_dims || !m->bot_w || !m->bot_b || !m->top_dims || !m->top_w || !m->top_b) return DQRM_ERR_INVALID_ARG;
+    if (m->bot_layers > kMaxMlpLayers || m->top_layers > kMaxMlpLayers) return DQRM_ERR_UNSUPPORTED;
+    const int V = m->num_tables + 1;
+    if (V > 64 || (int64_t)V * m->dim > dqrm::kInterMaxZ) return DQRM_ERR_UNSUPPORTED;
+    if (m->bot_dims[0] != m->num_dense || m->bot_dims[m->bot_layers] != m->dim) return DQRM_ERR_INVALID_ARG;
+    if (m->top_dims[0] != m->dim + V * (V - 1) / 2 || m->top_dims[m->top_layers] != 1) return DQRM_ERR_INVALID_ARG;
+    for (int l = 0; l <= m->bot_layers; ++l)
+        if (m->bot_dims[l] < 1 || m->bot_dims[l] > 65536) return DQRM_ERR_UNSUPPORTED;
+    for (int l = 0; l <= m->top_layers; ++l)
+        if (m->top_dims[l] < 1 || m->top_dims[l] > 65536) return DQRM_ERR_UNSUPPORTED;
+    for (int l = 0; l < m->bot_layers; ++l)
+        if (!m->bot_w[l] || !m->bot_b[l]) return DQRM_ERR_INVALID_ARG;
+    for (int l = 0; l < m->top_layers; ++l)
+        if (!m->top_w[l] || !m->top_b[l]) return DQRM_ERR_INVALID_ARG;
+    if ((int64_t)batch * 65536 > kMaxIndices) return DQRM_ERR_UNSUPPORTED;
+    return DQRM_OK;
+}
+
+DenseLayout dense_layout(const dqrm_dense_model_t *m, int32_t batch)
+{
+    DenseLayout L{};
+    size_t o = 0;
+    size_t widest = 1;
+    auto take = [&](size_t floats) {
+        size_t at = o;
+        o = align_up(o + floats * sizeof(float), 256);
+        return at;
+    };
+    for (int l = 0; l < m->bot_layers; ++l) {
+        L.bot_act[l] = take((size_t)batch * m->bot_dims[l + 1]);
+        if ((size_t)m->bot_dims[l + 1] > widest) widest = m->bot_dims[l + 1];
+    }
+    L.R = take((size_t)batch * m->top_dims[0]);
+    if ((size_t)m->top_dims[0] > widest) widest = m->top_dims[0];
+    for (int l = 0; l < m->top_layers; ++l) {
+        L.top_act[l] = take((size_t)batch * m->top_dims[l + 1]);
+        if ((size_t)m->top_dims[l + 1] > widest) widest = m->top_dims[l + 1];
+    }
+    L.dz = take((size_t)batch);
+    L.gA = take((size_t)batch * widest);
+    L.gB = take((size_t)batch * widest);
+    L.total = o;
+    return L;
+}
+
+void launch_gemm(hipStream_t st, const dqrm::GemmArgs &g)
+{
+    dim3 grid((g.N + dqrm::kGemmBN - 1) / dqrm::kGemmBN, (g.M + dqrm::kGemmBM - 1) / dqrm::kGemmBM);
+    hipLaunchKernelGGL(dqrm::gemm_mfma_kernel, grid, dim3(dqrm::kGemmThreads), 0, st, g);
+}
+
+// Y[B][out] = act(X[B][in] * W[out][in]^T + b)
+void linear_fwd(hipStream_t st, const float *X, const float *W, const float *b, float *Y, int B, int in, int out,
+                bool relu)
+{
+    dqrm::GemmArgs g{};
+    g.A = X, g.a_si = in, g.a_sr = 1, g.a_i_contig = 0;
+    g.B = W, g.b_sr = 1, g.b_sj = in, g.b_j_contig = 0;
+    g.C = Y, g.c_si = out, g.c_sj = 1;
+    g.M = B, g.N = out, g.K = in;
+    g.bias = b, g.mask = nullptr, g.relu = relu ? 1 : 0, g.update = 0, g.alpha = 0.0f;
+    launch_gemm(st, g);
+}
+
+// dX[B][in] = (dZ[B][out] * W[out][in]) masked by (mask[B][in] > 0)
+void linear_bwd_input(hipStream_t st, const float *dZ, const float *W, const float *mask, float *dX, int B, int in,
+                      int out)
+{
+    dqrm::GemmArgs g{};
+    g.A = dZ, g.a_si = out, g.a_sr = 1, g.a_i_contig = 0;
+    g.B = W, g.b_sr = in, g.b_sj = 1, g.b_j_contig = 1;
+    g.C = dX, g.c_si = in, g.c_sj = 1;
+    g.M = B, g.N = in, g.K = out;
+    g.bias = nullptr, g.mask = mask, g.relu = 0, g.update = 0, g.alpha = 0.0f;
+    launch_gemm(st, g);
+}
+
+// W[out][in] -= lr * dZ[B][out]^T * X[B][in];  b[out] -= lr * colsum(dZ)
+void linear_bwd_params(hipStream_t st, const float *dZ, const float *X, float *W, float *b, int B, int in, int out,
+                       float lr)
+{
+    dqrm::GemmArgs g{};
+    g.A = dZ, g.a_si = 1, g.a_sr = out, g.a_i_contig = 1;
+    g.B = X, g.b_sr = in, g.b_sj = 1, g.b_j_contig = 1;
+    g.C = W, g.c_si = in, g.c_sj = 1;
+    g.M = out, g.N = in, g.K = B;
+    g.bias = nullptr, g.mask = nullptr, g.relu = 0, g.update = 1, g.alpha = -lr;
+    launch_gemm(st, g);
+    hipLaunchKernelGGL(dqrm::bias_update_kernel, dim3((out + 63) / 64), dim3(256), 0, st, dZ, B, out, -lr, b);
+}
+
+} // namespace
+
+size_t dqrm_dense_workspace_bytes(const dqrm_dense_model_t *model, int32_t batch)
+{
+    if (check_dense_model(model, batch) != DQRM_OK) return 0;
+    return dense_layout(model, batch).total;
+}
+
+int32_t dqrm_dense_step(const dqrm_dense_model_t *m, int32_t batch, const float *dense_x, const float *emb_out,
+                        const float *labels, float lr, float *loss, float *grad_emb, void *workspace,
+                        size_t workspace_bytes, void *stream)
+{
+    int32_t rc = check_dense_model(m, batch);
+    if (rc != DQRM_OK) return rc;
+    if (!dense_x || !emb_out || !labels || !loss || !grad_emb || !workspace || !aligned(workspace, 256))
+        return DQRM_ERR_INVALID_ARG;
+    const DenseLayout L = dense_layout(m, batch);
+    if (workspace_bytes < L.total) return DQRM_ERR_WORKSPACE_TOO_SMALL;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    char *ws = static_cast<char *>(workspace);
+    auto F = [&](size_t off) { return reinterpret_cast<float *>(ws + off); };
+    const int B = batch, T = m->num_tables, D = m->dim;
+
+    // ---- forward
+    const float *x = dense_x;
+    for (int l = 0; l < m->bot_layers; ++l) {
+        linear_fwd(st, x, m->bot_w[l], m->bot_b[l], F(L.bot_act[l]), B, m->bot_dims[l], m->bot_dims[l + 1], true);
+        x = F(L.bot_act[l]);
+    }
+    dqrm::InteractArgs ia{};
+    ia.bot = x, ia.emb = emb_out, ia.R = F(L.R), ia.B = B, ia.T = T, ia.D = D;
+    hipLaunchKernelGGL(dqrm::interact_fwd_kernel, dim3(B), dim3(dqrm::kInterThreads), 0, st, ia);
+    x = F(L.R);
+    for (int l = 0; l < m->top_layers; ++l) {
+        linear_fwd(st, x, m->top_w[l], m->top_b[l], F(L.top_act[l]), B, m->top_dims[l], m->top_dims[l + 1],
+                   l + 1 < m->top_layers);
+        x = F(L.top_act[l]);
+    }
+    hipLaunchKernelGGL(dqrm::bce_kernel, dim3(1), dim3(256), 0, st, x, labels, B, F(L.dz), loss);
+
+    // ---- backward (dZ = gradient w.r.t. a layer's pre-activation) + SGD
+    const float *dZ = F(L.dz);
+    float *bufs[2] = {F(L.gA), F(L.gB)};
+    int cur = 0;
+    for (int l = m->top_layers - 1; l >= 0; --l) {
+        const float *in_act = l > 0 ? F(L.top_act[l - 1]) : F(L.R);
+        float *dX = bufs[cur];
+        // the input of top layer l > 0 is a ReLU output: mask; the interaction output is not
+        linear_bwd_input(st, dZ, m->top_w[l], l > 0 ? in_act : nullptr, dX, B, m->top_dims[l], m->top_dims[l + 1]);
+        linear_bwd_params(st, dZ, in_act, m->top_w[l], m->top_b[l], B, m->top_dims[l], m->top_dims[l + 1], lr);
+        dZ = dX;
+        cur ^= 1;
+    }
+    // dZ is now the gradient w.r.t. the interaction output
+    float *dbot = bufs[cur];
+    const float *bot_out = F(L.bot_act[m->bot_layers - 1]);
+    ia.dR = dZ, ia.dbot = dbot, ia.demb = grad_emb, ia.bot_mask = bot_out;
+    hipLaunchKernelGGL(dqrm::interact_bwd_kernel, dim3(B), dim3(dqrm::kInterThreads), 0, st, ia);
+    dZ = dbot;
+    cur ^= 1;
+    for (int l = m->bot_layers - 1; l >= 0; --l) {
+        const float *in_act = l > 0 ? F(L.bot_act[l - 1]) : dense_x;
+        if (l > 0) {
+            float *dX = bufs[cur];
+            linear_bwd_input(st, dZ, m->bot_w[l], in_act, dX, B, m->bot_dims[l], m->bot_dims[l + 1]);
+            linear_bwd_params(st, dZ, in_act, m->bot_w[l], m->bot_b[l], B, m->bot_dims[l], m->bot_dims[l + 1], lr);
+            dZ = dX;
+            cur ^= 1;
+        } else {
+            linear_bwd_params(st, dZ, in_act, m->bot_w[l], m->bot_b[l], B, m->bot_dims[l], m->bot_dims[l + 1], lr);
+        }
+    }
     DQRM_HIP_CHECK(hipGetLastError());
     return DQRM_OK;
 }

@@ -62,6 +62,10 @@ def main():
     ap.add_argument("--pool", type=int, default=64, help="distinct index batches cycled")
     ap.add_argument("--grad-pool", type=int, default=8, help="distinct grad_out buffers cycled")
     ap.add_argument("--lr", type=float, default=0.1)
+    ap.add_argument("--dense", action="store_true",
+                    help="full DQRM train step (use with --workload kaggle): dqrm_dense_step (MLPs 13-512-256-64-16 / "
+                         "367-512-256-1, interaction, BCE, backward, SGD) runs between the tables' forward and "
+                         "backward and produces grad_out")
     ap.add_argument("--overlap", default="pipeline", choices=["none", "fwd", "pipeline", "ahead"],
                     help="where dqrm_dedupe (needs only the indices) runs: none = in line on the one stream; "
                          "fwd = on a second stream beside the same step's forward; pipeline = on a second stream, "
@@ -132,9 +136,27 @@ def main():
         dq.dqrm_dedupe(tables, ix, of, B, sps[i], urs[i], sos[i], tuos[i], nus[i], wss[i], stream=side)
         ev_dedupe[i].record(side)
 
+    dense = None
+    if args.dense:
+        from gen import make_dense_model, dense_batch
+        bd, bw, bb, td, tw, tb = make_dense_model("kaggle", T, D, wl.seed)
+        dense = dq.DenseModel(T, D, bd, bw, bb, td, tw, tb, dev)
+        dense_ws = torch.empty(dq.dqrm_dense_workspace_bytes(dense, B), dtype=torch.uint8, device=dev)
+        dense_in = [dense_batch(B, bd[0], wl.seed, k) for k in range(args.grad_pool)]
+        dense_x = [torch.from_numpy(x).to(dev) for x, _ in dense_in]
+        dense_y = [torch.from_numpy(y).to(dev) for _, y in dense_in]
+        loss_d = torch.zeros(1, dtype=torch.float32, device=dev)
+        grad_live = torch.empty((B, T, D), dtype=torch.float32, device=dev)
+
+    def forward(k, ix, of):
+        dq.dqrm_embbag_fwd(tables, ix, of, B, mode, bufs.out, None)
+        if dense is not None:
+            j = k % args.grad_pool
+            dq.dqrm_dense_step(dense, B, dense_x[j], bufs.out, dense_y[j], args.lr, loss_d, grad_live, dense_ws)
+
     def rest_of_step(k, i):
         """B3-B5 on the current stream, from the dedupe result in buffer i."""
-        g = grad_d[k % args.grad_pool]
+        g = grad_live if dense is not None else grad_d[k % args.grad_pool]
         if args.fused:
             dq.dqrm_segment_sum(tables, B, N, g, bufs.values, None, wss[i])
             dq.dqrm_quant_update(tables, bufs.cap, N, bufs.values, urs[i], tuos[i], bufs.g_absmax, bufs.gq,
@@ -156,13 +178,13 @@ def main():
                                                                     tuos[j % nbuf], nus[j % nbuf], wss[j % nbuf])
                                                      for j in group])
                 ix, of = batch_of(k)
-                dq.dqrm_embbag_fwd(tables, ix, of, B, mode, bufs.out, None)
+                forward(k, ix, of)
                 rest_of_step(k, k % nbuf)
             return
         if args.overlap == "none":
             for k in range(k0, k0 + n):
                 ix, of = batch_of(k)
-                dq.dqrm_embbag_fwd(tables, ix, of, B, mode, bufs.out, None)
+                forward(k, ix, of)
                 dq.dqrm_dedupe(tables, ix, of, B, sps[0], urs[0], sos[0], tuos[0], nus[0], wss[0])
                 rest_of_step(k, 0)
             return
@@ -174,7 +196,7 @@ def main():
             i = k % nbuf
             if args.overlap == "fwd":
                 dedupe_on_side(k)  # beside this step's forward
-            dq.dqrm_embbag_fwd(tables, ix, of, B, mode, bufs.out, None)
+            forward(k, ix, of)
             if args.overlap == "pipeline" and k + 1 < k0 + n:
                 dedupe_on_side(k + 1)  # one step ahead: the next batch's indices are already here
             main.wait_event(ev_dedupe[i])
@@ -322,7 +344,7 @@ def main():
         "config": {"workload": f"{args.workload}-shaped embedding layer: {T} tables, {wl.R} rows, dim {D}, batch {B}, "
                                f"1 Zipf index per table per sample, {args.mode}-mode forward, INT8 sparse grads, "
                                f"SGD lr {args.lr}, dedupe overlap: {args.overlap}",
-                   "lookups_per_step": N, "unique_rows_per_step": round(U, 1), "fwd_mode": args.mode, "overlap": args.overlap,
+                   "lookups_per_step": N, "unique_rows_per_step": round(U, 1), "fwd_mode": args.mode, "overlap": args.overlap, "dense_part": bool(args.dense),
                    "update": ("dqrm_quant_update (one pass)" if args.fused else "dqrm_grad_quant_int8 + dqrm_sparse_update"),
                    "launch": (f"HIP graph of {gs} steps replayed" if graph is not None else "eager launches")},
         "roofline": roofline,

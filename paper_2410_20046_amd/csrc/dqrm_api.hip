@@ -3,6 +3,7 @@
 #include <hip/hip_runtime.h>
 
 #include <cstdio>
+#include <algorithm>
 #include <cstring>
 
 #include "dqrm.h"
@@ -482,15 +483,18 @@ int32_t dqrm_quant_update(const dqrm_tables_t *tables, int64_t capacity, int64_t
     return DQRM_OK;
 }
 
+} // extern "C"
+
 // ---- the dense part of the train step ---------------------------------------------
 namespace {
 
 constexpr int kMaxMlpLayers = 16;
+constexpr int kDenseMaxSplits = 16; // slices of the batch dimension in the weight-gradient products
 
 struct DenseLayout {
     // activations: bot_act[l] = output of bottom layer l, R = interaction output,
     // top_act[l] = output of top layer l (the last one is the logit), dz, two gradient buffers
-    size_t bot_act[kMaxMlpLayers], top_act[kMaxMlpLayers], R, dz, gA, gB, total;
+    size_t bot_act[kMaxMlpLayers], top_act[kMaxMlpLayers], R, dz, gA, gB, partials, total;
 };
 
 int32_t check_dense_model(const dqrm_dense_model_t *m, int32_t batch)
@@ -539,14 +543,22 @@ DenseLayout dense_layout(const dqrm_dense_model_t *m, int32_t batch)
     L.dz = take((size_t)batch);
     L.gA = take((size_t)batch * widest);
     L.gB = take((size_t)batch * widest);
+    size_t max_params = 1; // largest out * (in + 1) over the layers, for the split weight-gradient products
+    for (int l = 0; l < m->bot_layers; ++l)
+        max_params = std::max(max_params, (size_t)m->bot_dims[l + 1] * (m->bot_dims[l] + 1));
+    for (int l = 0; l < m->top_layers; ++l)
+        max_params = std::max(max_params, (size_t)m->top_dims[l + 1] * (m->top_dims[l] + 1));
+    L.partials = take((size_t)kDenseMaxSplits * max_params);
     L.total = o;
     return L;
 }
 
-void launch_gemm(hipStream_t st, const dqrm::GemmArgs &g)
+// A_I / B_J: whether A's row index i / B's column index j is the contiguous one in memory
+template <bool A_I, bool B_J>
+void launch_gemm(hipStream_t st, const dqrm::GemmArgs &g, int splits)
 {
-    dim3 grid((g.N + dqrm::kGemmBN - 1) / dqrm::kGemmBN, (g.M + dqrm::kGemmBM - 1) / dqrm::kGemmBM);
-    hipLaunchKernelGGL(dqrm::gemm_mfma_kernel, grid, dim3(dqrm::kGemmThreads), 0, st, g);
+    dim3 grid((g.N + dqrm::kGemmBN - 1) / dqrm::kGemmBN, (g.M + dqrm::kGemmBM - 1) / dqrm::kGemmBM, splits);
+    hipLaunchKernelGGL((dqrm::gemm_mfma_kernel<A_I, B_J>), grid, dim3(dqrm::kGemmThreads), 0, st, g);
 }
 
 // Y[B][out] = act(X[B][in] * W[out][in]^T + b)
@@ -554,12 +566,12 @@ void linear_fwd(hipStream_t st, const float *X, const float *W, const float *b, 
                 bool relu)
 {
     dqrm::GemmArgs g{};
-    g.A = X, g.a_si = in, g.a_sr = 1, g.a_i_contig = 0;
-    g.B = W, g.b_sr = 1, g.b_sj = in, g.b_j_contig = 0;
+    g.A = X, g.a_si = in, g.a_sr = 1;
+    g.B = W, g.b_sr = 1, g.b_sj = in;
     g.C = Y, g.c_si = out, g.c_sj = 1;
     g.M = B, g.N = out, g.K = in;
-    g.bias = b, g.mask = nullptr, g.relu = relu ? 1 : 0, g.update = 0, g.alpha = 0.0f;
-    launch_gemm(st, g);
+    g.bias = b, g.relu = relu ? 1 : 0, g.k_per_split = in;
+    launch_gemm<false, false>(st, g, 1);
 }
 
 // dX[B][in] = (dZ[B][out] * W[out][in]) masked by (mask[B][in] > 0)
@@ -567,29 +579,39 @@ void linear_bwd_input(hipStream_t st, const float *dZ, const float *W, const flo
                       int out)
 {
     dqrm::GemmArgs g{};
-    g.A = dZ, g.a_si = out, g.a_sr = 1, g.a_i_contig = 0;
-    g.B = W, g.b_sr = in, g.b_sj = 1, g.b_j_contig = 1;
+    g.A = dZ, g.a_si = out, g.a_sr = 1;
+    g.B = W, g.b_sr = in, g.b_sj = 1;
     g.C = dX, g.c_si = in, g.c_sj = 1;
     g.M = B, g.N = in, g.K = out;
-    g.bias = nullptr, g.mask = mask, g.relu = 0, g.update = 0, g.alpha = 0.0f;
-    launch_gemm(st, g);
+    g.mask = mask, g.k_per_split = out;
+    launch_gemm<false, true>(st, g, 1);
 }
 
-// W[out][in] -= lr * dZ[B][out]^T * X[B][in];  b[out] -= lr * colsum(dZ)
-void linear_bwd_params(hipStream_t st, const float *dZ, const float *X, float *W, float *b, int B, int in, int out,
-                       float lr)
+// W[out][in] -= lr * dZ[B][out]^T * X[B][in];  b[out] -= lr * colsum(dZ).  The product is taken with X
+// extended by a column of ones (its last column is the bias gradient) and the batch dimension cut into
+// slices, one workgroup layer per slice; sgd_from_partials_kernel adds the slices in order.
+void linear_bwd_params(hipStream_t st, const float *dZ, const float *X, float *W, float *b, float *partials, int B,
+                       int in, int out, float lr)
 {
+    int splits = (B + 4 * dqrm::kGemmBK - 1) / (4 * dqrm::kGemmBK); // about four slabs per slice
+    if (splits > kDenseMaxSplits) splits = kDenseMaxSplits;
+    if (splits < 2) splits = 2; // the kernel writes partial tiles only when the reduction is split
+    int per = (B + splits - 1) / splits;
+    per = (per + dqrm::kGemmBK - 1) / dqrm::kGemmBK * dqrm::kGemmBK;
     dqrm::GemmArgs g{};
-    g.A = dZ, g.a_si = 1, g.a_sr = out, g.a_i_contig = 1;
-    g.B = X, g.b_sr = in, g.b_sj = 1, g.b_j_contig = 1;
-    g.C = W, g.c_si = in, g.c_sj = 1;
-    g.M = out, g.N = in, g.K = B;
-    g.bias = nullptr, g.mask = nullptr, g.relu = 0, g.update = 1, g.alpha = -lr;
-    launch_gemm(st, g);
-    hipLaunchKernelGGL(dqrm::bias_update_kernel, dim3((out + 63) / 64), dim3(256), 0, st, dZ, B, out, -lr, b);
+    g.A = dZ, g.a_si = 1, g.a_sr = out;
+    g.B = X, g.b_sr = in, g.b_sj = 1, g.b_ones_last = 1;
+    g.M = out, g.N = in + 1, g.K = B;
+    g.k_per_split = per, g.P = partials;
+    launch_gemm<true, true>(st, g, splits);
+    const long long total = (long long)out * (in + 1);
+    hipLaunchKernelGGL(dqrm::sgd_from_partials_kernel, dim3((unsigned)std::min<long long>((total + 255) / 256, 2048)),
+                       dim3(256), 0, st, partials, splits, out, in, lr, W, b);
 }
 
 } // namespace
+
+extern "C" {
 
 size_t dqrm_dense_workspace_bytes(const dqrm_dense_model_t *model, int32_t batch)
 {
@@ -638,7 +660,8 @@ int32_t dqrm_dense_step(const dqrm_dense_model_t *m, int32_t batch, const float 
         float *dX = bufs[cur];
         // the input of top layer l > 0 is a ReLU output: mask; the interaction output is not
         linear_bwd_input(st, dZ, m->top_w[l], l > 0 ? in_act : nullptr, dX, B, m->top_dims[l], m->top_dims[l + 1]);
-        linear_bwd_params(st, dZ, in_act, m->top_w[l], m->top_b[l], B, m->top_dims[l], m->top_dims[l + 1], lr);
+        linear_bwd_params(st, dZ, in_act, m->top_w[l], m->top_b[l], F(L.partials), B, m->top_dims[l],
+                          m->top_dims[l + 1], lr);
         dZ = dX;
         cur ^= 1;
     }
@@ -654,11 +677,13 @@ int32_t dqrm_dense_step(const dqrm_dense_model_t *m, int32_t batch, const float 
         if (l > 0) {
             float *dX = bufs[cur];
             linear_bwd_input(st, dZ, m->bot_w[l], in_act, dX, B, m->bot_dims[l], m->bot_dims[l + 1]);
-            linear_bwd_params(st, dZ, in_act, m->bot_w[l], m->bot_b[l], B, m->bot_dims[l], m->bot_dims[l + 1], lr);
+            linear_bwd_params(st, dZ, in_act, m->bot_w[l], m->bot_b[l], F(L.partials), B, m->bot_dims[l],
+                              m->bot_dims[l + 1], lr);
             dZ = dX;
             cur ^= 1;
         } else {
-            linear_bwd_params(st, dZ, in_act, m->bot_w[l], m->bot_b[l], B, m->bot_dims[l], m->bot_dims[l + 1], lr);
+            linear_bwd_params(st, dZ, in_act, m->bot_w[l], m->bot_b[l], F(L.partials), B, m->bot_dims[l],
+                              m->bot_dims[l + 1], lr);
         }
     }
     DQRM_HIP_CHECK(hipGetLastError());

@@ -13,6 +13,14 @@ typedef float floatx16 __attribute__((ext_vector_type(16)));
 
 // C(i,j) = epilogue( sum_r A(i,r) * B(r,j) ), all operands addressed with
 // explicit strides so that one kernel serves X*W^T, dY*W and dY^T*X.
+//
+// Workgroup = 4 waves, each owns a 32x32 block of a 64x64 tile of C and feeds
+// v_mfma_f32_32x32x2_f32 from LDS.  The reduction runs in slabs of 64: while the
+// matrix cores work on one slab, the next one is already on its way from HBM
+// into registers (these products are small -- a few hundred workgroups -- so
+// latency, not bandwidth, is what has to be hidden).  With gridDim.z > 1 the
+// reduction is split: slice z covers r in [z*k_per_split, ...) and stores its raw
+// partial tile to P[z][M][N]; a second kernel adds the slices in order.
 struct GemmArgs {
     const float *A;
     long long a_si, a_sr;
@@ -24,16 +32,32 @@ struct GemmArgs {
     const float *bias; // [N] added per column j, or null
     const float *mask; // same addressing as C: result multiplied by (mask > 0), or null
     int relu;          // max(x, 0) after the bias
-    int update;        // 0: C = acc';  1: C = C + alpha * acc' (in place, e.g. W -= lr * dW)
-    float alpha;
-    int a_i_contig;    // which index of A is contiguous in memory (only steers the load pattern)
-    int b_j_contig;
+    int b_ones_last;   // B's last column (j = N-1) is all ones and is not read from memory
+    int k_per_split;   // reduction length per z slice (multiple of kGemmBK), K if not split
+    float *P;          // [gridDim.z][M][N] partial tiles when split
 };
 
 constexpr int kGemmThreads = 256;
-constexpr int kGemmBM = 64, kGemmBN = 64, kGemmBK = 16;
-constexpr int kGemmLd = kGemmBM + 4; // LDS row pitch (floats)
+constexpr int kGemmBM = 64, kGemmBN = 64, kGemmBK = 32;
+constexpr int kGemmLd = kGemmBM + 1;                             // LDS row pitch (floats)
+constexpr int kGemmPerThread = kGemmBM * kGemmBK / kGemmThreads; // 8 elements of each operand per slab
 
+// A thread's q-th element (q = 0..7) of a 64 (i or j) x 32 (r) operand slab.  CONTIG
+// says whether the 64-wide index is the one that is contiguous in memory; either
+// way consecutive threads walk along the contiguous direction, four elements each.
+template <bool WIDE_CONTIG>
+__device__ __forceinline__ void gemm_slot(int tid, int q, int *wide, int *r)
+{
+    if (WIDE_CONTIG) {
+        *wide = (tid & 15) * 4 + (q & 3);
+        *r = (tid >> 4) + 16 * (q >> 2);
+    } else {
+        *r = (tid & 7) * 4 + (q & 3);
+        *wide = (tid >> 3) + 32 * (q >> 2);
+    }
+}
+
+template <bool A_I_CONTIG, bool B_J_CONTIG>
 __global__ __launch_bounds__(kGemmThreads) void gemm_mfma_kernel(GemmArgs g)
 {
     __shared__ float As[kGemmBK][kGemmLd]; // As[r][i]
@@ -42,38 +66,58 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_mfma_kernel(GemmArgs g)
     const int lane = tid & 63, wave = tid >> 6;
     const int wm = wave >> 1, wn = wave & 1;
     const int i0 = blockIdx.y * kGemmBM, j0 = blockIdx.x * kGemmBN;
+    const int r_begin = blockIdx.z * g.k_per_split;
+    const int r_end = min(g.K, r_begin + g.k_per_split);
+
+    // per-thread element offsets of the first slab (the host checks that every matrix has < 2^31 elements)
+    int off_a[kGemmPerThread], off_b[kGemmPerThread];
+    unsigned ok_a = 0, ok_b = 0, ones_b = 0;
+#pragma unroll
+    for (int q = 0; q < kGemmPerThread; ++q) {
+        int ai, ar, bj, br;
+        gemm_slot<A_I_CONTIG>(tid, q, &ai, &ar);
+        gemm_slot<B_J_CONTIG>(tid, q, &bj, &br);
+        off_a[q] = (int)((long long)(i0 + ai) * g.a_si + (long long)(r_begin + ar) * g.a_sr);
+        off_b[q] = (int)((long long)(r_begin + br) * g.b_sr + (long long)(j0 + bj) * g.b_sj);
+        if (i0 + ai < g.M) ok_a |= 1u << q;
+        if (j0 + bj < g.N) ok_b |= 1u << q;
+        if (g.b_ones_last && j0 + bj == g.N - 1) ones_b |= 1u << q;
+    }
+    const int step_a = (int)(kGemmBK * g.a_sr), step_b = (int)(kGemmBK * g.b_sr);
 
     floatx16 acc;
 #pragma unroll
     for (int v = 0; v < 16; ++v) acc[v] = 0.0f;
 
-    for (int r0 = 0; r0 < g.K; r0 += kGemmBK) {
-        // global -> LDS, 4 elements of each operand per thread, zero-filled outside the matrices
+    float av[kGemmPerThread], bv[kGemmPerThread];
+    auto load_slab = [&](int r0) {
 #pragma unroll
-        for (int q = 0; q < 4; ++q) {
-            const int e = tid + q * kGemmThreads; // 0..1023
+        for (int q = 0; q < kGemmPerThread; ++q) {
             int ai, ar, bj, br;
-            if (g.a_i_contig) {
-                ai = e & 63;
-                ar = e >> 6;
-            } else {
-                ar = e & 15;
-                ai = e >> 4;
-            }
-            if (g.b_j_contig) {
-                bj = e & 63;
-                br = e >> 6;
-            } else {
-                br = e & 15;
-                bj = e >> 4;
-            }
-            float av = 0.0f, bv = 0.0f;
-            if (i0 + ai < g.M && r0 + ar < g.K) av = g.A[(long long)(i0 + ai) * g.a_si + (long long)(r0 + ar) * g.a_sr];
-            if (j0 + bj < g.N && r0 + br < g.K) bv = g.B[(long long)(r0 + br) * g.b_sr + (long long)(j0 + bj) * g.b_sj];
-            As[ar][ai] = av;
-            Bs[br][bj] = bv;
+            gemm_slot<A_I_CONTIG>(tid, q, &ai, &ar);
+            gemm_slot<B_J_CONTIG>(tid, q, &bj, &br);
+            const bool in_a = ((ok_a >> q) & 1u) && (r0 + ar < r_end);
+            const bool in_b = ((ok_b >> q) & 1u) && (r0 + br < r_end);
+            av[q] = in_a ? g.A[off_a[q]] : 0.0f;
+            bv[q] = in_b ? (((ones_b >> q) & 1u) ? 1.0f : g.B[off_b[q]]) : 0.0f;
+            off_a[q] += step_a;
+            off_b[q] += step_b;
+        }
+    };
+    if (r_begin < r_end) load_slab(r_begin);
+    for (int r0 = r_begin; r0 < r_end; r0 += kGemmBK) {
+        // registers -> LDS
+#pragma unroll
+        for (int q = 0; q < kGemmPerThread; ++q) {
+            int ai, ar, bj, br;
+            gemm_slot<A_I_CONTIG>(tid, q, &ai, &ar);
+            gemm_slot<B_J_CONTIG>(tid, q, &bj, &br);
+            As[ar][ai] = av[q];
+            Bs[br][bj] = bv[q];
         }
         __syncthreads();
+        // next slab: on its way while the matrix cores run
+        if (r0 + kGemmBK < r_end) load_slab(r0 + kGemmBK);
         // one 32x32x2 product per step: lane l feeds A(i = l % 32, r = l / 32) and B(r = l / 32, j = l % 32)
 #pragma unroll
         for (int rr = 0; rr < kGemmBK; rr += 2) {
@@ -87,6 +131,15 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_mfma_kernel(GemmArgs g)
     // accumulator layout: lane l holds column j = l % 32 and rows 8*(v/4) + 4*(l/32) + v%4, v = 0..15
     const int j = j0 + wn * 32 + (lane & 31);
     if (j >= g.N) return;
+    if (gridDim.z > 1) {
+        float *p = g.P + (long long)blockIdx.z * g.M * g.N;
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+            const int i = i0 + wm * 32 + 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3);
+            if (i < g.M) p[(long long)i * g.N + j] = acc[v];
+        }
+        return;
+    }
     const float bj = g.bias ? g.bias[j] : 0.0f;
 #pragma unroll
     for (int v = 0; v < 16; ++v) {
@@ -96,26 +149,25 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_mfma_kernel(GemmArgs g)
         if (g.relu) x = fmaxf(x, 0.0f);
         const long long off = (long long)i * g.c_si + (long long)j * g.c_sj;
         if (g.mask) x = g.mask[off] > 0.0f ? x : 0.0f;
-        if (g.update)
-            g.C[off] = g.C[off] + g.alpha * x;
-        else
-            g.C[off] = x;
+        g.C[off] = x;
     }
 }
 
-// b[n] += alpha * sum_m dZ[m][n]   (bias gradient + SGD step); one block per 64 columns
-__global__ __launch_bounds__(256) void bias_update_kernel(const float *__restrict__ dZ, int M, int N, float alpha,
-                                                          float *__restrict__ b)
+// SGD step from the split products of [dZ^T * X | dZ^T * 1]: P is [S][out][in + 1];
+// W[o][i] -= lr * sum_s P[s][o][i],  b[o] -= lr * sum_s P[s][o][in]  (slices added in order)
+__global__ __launch_bounds__(256) void sgd_from_partials_kernel(const float *__restrict__ P, int S, int out, int in,
+                                                                float lr, float *__restrict__ W, float *__restrict__ b)
 {
-    __shared__ float part[4][64];
-    const int c = threadIdx.x & 63, q = threadIdx.x >> 6;
-    const int n = blockIdx.x * 64 + c;
-    float s = 0.0f;
-    if (n < N)
-        for (int m = q; m < M; m += 4) s += dZ[(long long)m * N + n];
-    part[q][c] = s;
-    __syncthreads();
-    if (q == 0 && n < N) b[n] = b[n] + alpha * (((part[0][c] + part[1][c]) + part[2][c]) + part[3][c]);
+    const long long total = (long long)out * (in + 1);
+    for (long long e = (long long)blockIdx.x * 256 + threadIdx.x; e < total; e += (long long)gridDim.x * 256) {
+        float s = 0.0f;
+        for (int z = 0; z < S; ++z) s += P[(long long)z * total + e];
+        const int o = (int)(e / (in + 1)), i = (int)(e - (long long)o * (in + 1));
+        if (i < in)
+            W[(long long)o * in + i] = W[(long long)o * in + i] - lr * s;
+        else
+            b[o] = b[o] - lr * s;
+    }
 }
 
 // ---- pairwise-dot interaction ---------------------------------------------------

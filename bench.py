@@ -206,12 +206,12 @@ def main():
     # ---- warm-up (eager), optional capture of `graph_steps` steps into one HIP graph ----
     run_steps(0, args.warmup)
     torch.cuda.synchronize()
-    graph, gs = None, 0
+    graph, graph_steps = None, 0
     if args.graph:
-        gs = min(args.pool, args.steps)
+        graph_steps = min(args.pool, args.steps)
         graph = torch.cuda.CUDAGraph()
         with torch.cuda.graph(graph):
-            run_steps(args.warmup, gs)
+            run_steps(args.warmup, graph_steps)
         graph.replay()  # one untimed replay
         torch.cuda.synchronize()
 
@@ -220,10 +220,10 @@ def main():
     t_start = time.perf_counter()
     e0.record()
     if graph is not None:
-        for _ in range(args.steps // gs):
+        for _ in range(args.steps // graph_steps):
             graph.replay()
-        if args.steps % gs:
-            run_steps(args.warmup, args.steps % gs)
+        if args.steps % graph_steps:
+            run_steps(args.warmup, args.steps % graph_steps)
     else:
         run_steps(args.warmup, args.steps)
     e1.record()
@@ -248,7 +248,7 @@ def main():
     ab = algorithmic_bytes(T, D, B, N, U, packed_fwd=(mode == dq.FWD_PACKED), packed_mirror=True)
 
     # ---- per-call HIP-event timing, one stream, events on the launch stream ----
-    stages = ["fwd", "dedupe", "segment_sum", "quant", "update"]
+    stages = ["fwd", "dedupe", "segment_sum", "quant", "update", "quant_update"]
     calls = {
         "fwd": lambda k: dq.dqrm_embbag_fwd(tables, idx_d[k % args.pool], off_d[k % args.pool], B, mode, bufs.out, None),
         "dedupe": lambda k: dq.dqrm_dedupe(tables, idx_d[k % args.pool], off_d[k % args.pool], B, bufs.sorted_pos,
@@ -260,20 +260,30 @@ def main():
                                                    bufs.g_absmax, bufs.gq, bufs.g_scale),
         "update": lambda k: dq.dqrm_sparse_update(tables, bufs.cap, bufs.uniq_rows, bufs.table_uniq_offsets, bufs.gq,
                                                   bufs.g_scale, args.lr),
+        "quant_update": lambda k: dq.dqrm_quant_update(tables, bufs.cap, N, bufs.values, bufs.uniq_rows,
+                                                       bufs.table_uniq_offsets, bufs.g_absmax, bufs.gq, bufs.g_scale,
+                                                       args.lr, bufs.workspace),
     }
-    n_ev = min(args.steps, 500)
-    evs = [[torch.cuda.Event(enable_timing=True) for _ in range(len(stages) + 1)] for _ in range(n_ev)]
-    for k in range(n_ev):
-        evs[k][0].record()
-        for s, name in enumerate(stages):
+    # Each call is timed on its own: `reps` back-to-back launches of the same call (cycling through the
+    # batches) between two events, so that the cost of recording an event is not charged to a 5-20 us kernel.
+    # The calls are launched in path order first, so every call finds valid inputs.
+    for name in stages:
+        calls[name](args.warmup)
+    reps = max(10, min(args.steps, 200))
+    stage_us = {}
+    for name in stages:
+        for k in range(3):
             calls[name](args.warmup + k)
-            evs[k][s + 1].record()
-    torch.cuda.synchronize()
-    stage_us = {name: 1e3 * float(np.mean([evs[k][s].elapsed_time(evs[k][s + 1]) for k in range(n_ev)]))
-                for s, name in enumerate(stages)}
+        ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        ev0.record()
+        for k in range(reps):
+            calls[name](args.warmup + k)
+        ev1.record()
+        torch.cuda.synchronize()
+        stage_us[name] = 1e3 * ev0.elapsed_time(ev1) / reps
     log("[bench] per-call HIP-event time (us): " + ", ".join(f"{k}={v:.1f}" for k, v in stage_us.items()))
     stage_bytes = {"fwd": ab["fwd"], "dedupe": ab["dedupe"], "segment_sum": ab["segsum"], "quant": ab["quant"],
-                   "update": ab["update"]}
+                   "update": ab["update"], "quant_update": ab["quant"] + ab["update"] - D * U}
     stage_gbs = {k: stage_bytes[k] / (stage_us[k] * 1e-6) / 1e9 for k in stages}
 
     # The dominant kernel of the step's critical path: dqrm_embbag_fwd is exactly one kernel launch
@@ -346,7 +356,7 @@ def main():
                                f"SGD lr {args.lr}, dedupe overlap: {args.overlap}",
                    "lookups_per_step": N, "unique_rows_per_step": round(U, 1), "fwd_mode": args.mode, "overlap": args.overlap, "dense_part": bool(args.dense),
                    "update": ("dqrm_quant_update (one pass)" if args.fused else "dqrm_grad_quant_int8 + dqrm_sparse_update"),
-                   "launch": (f"HIP graph of {gs} steps replayed" if graph is not None else "eager launches")},
+                   "launch": (f"HIP graph of {graph_steps} steps replayed" if graph is not None else "eager launches")},
         "roofline": roofline,
         "cpu_baseline": cpu,
         "step_algorithmic_bytes": int(ab["step"]),

@@ -62,6 +62,10 @@ def main():
     ap.add_argument("--pool", type=int, default=64, help="distinct index batches cycled")
     ap.add_argument("--grad-pool", type=int, default=8, help="distinct grad_out buffers cycled")
     ap.add_argument("--lr", type=float, default=0.1)
+    ap.add_argument("--refresh-period", type=int, default=0,
+                    help="P > 0: every P steps the per-table weight scale is recomputed from the whole master table "
+                         "(dqrm_find_scale) and the packed mirror re-encoded (dqrm_pack_int4), in line, inside the timed "
+                         "region -- the paper's periodic scale update; 0 = never (the scale stays cached)")
     ap.add_argument("--dense", action="store_true",
                     help="full DQRM train step (use with --workload kaggle): dqrm_dense_step (MLPs 13-512-256-64-16 / "
                          "367-512-256-1, interaction, BCE, backward, SGD) runs between the tables' forward and "
@@ -148,7 +152,16 @@ def main():
         loss_d = torch.zeros(1, dtype=torch.float32, device=dev)
         grad_live = torch.empty((B, T, D), dtype=torch.float32, device=dev)
 
+    def refresh_scale():
+        """Sec. 3.2: recompute the per-table scale from the whole master table, re-encode the packed mirror."""
+        dq.dqrm_find_scale(tables)
+        dq.dqrm_pack_int4(tables)
+
+    refresh_in_steps = [args.refresh_period > 0]  # False while a graph handles the refresh between replays
+
     def forward(k, ix, of):
+        if refresh_in_steps[0] and (k - args.warmup) % args.refresh_period == 0:
+            refresh_scale()
         dq.dqrm_embbag_fwd(tables, ix, of, B, mode, bufs.out, None)
         if dense is not None:
             j = k % args.grad_pool
@@ -209,6 +222,12 @@ def main():
     graph, graph_steps = None, 0
     if args.graph:
         graph_steps = min(args.pool, args.steps)
+        P = args.refresh_period
+        if P > graph_steps:
+            assert P % graph_steps == 0, "--refresh-period must be a multiple (or a divisor) of the graph's steps"
+            refresh_in_steps[0] = False  # refreshed eagerly before every (P / graph_steps)-th replay
+        elif P > 0:
+            assert graph_steps % P == 0, "--refresh-period must be a multiple (or a divisor) of the graph's steps"
         graph = torch.cuda.CUDAGraph()
         with torch.cuda.graph(graph):
             run_steps(args.warmup, graph_steps)
@@ -220,7 +239,9 @@ def main():
     t_start = time.perf_counter()
     e0.record()
     if graph is not None:
-        for _ in range(args.steps // graph_steps):
+        for rep in range(args.steps // graph_steps):
+            if args.refresh_period > graph_steps and (rep * graph_steps) % args.refresh_period == 0:
+                refresh_scale()
             graph.replay()
         if args.steps % graph_steps:
             run_steps(args.warmup, args.steps % graph_steps)
@@ -354,7 +375,7 @@ def main():
         "config": {"workload": f"{args.workload}-shaped embedding layer: {T} tables, {wl.R} rows, dim {D}, batch {B}, "
                                f"1 Zipf index per table per sample, {args.mode}-mode forward, INT8 sparse grads, "
                                f"SGD lr {args.lr}, dedupe overlap: {args.overlap}",
-                   "lookups_per_step": N, "unique_rows_per_step": round(U, 1), "fwd_mode": args.mode, "overlap": args.overlap, "dense_part": bool(args.dense),
+                   "lookups_per_step": N, "unique_rows_per_step": round(U, 1), "fwd_mode": args.mode, "overlap": args.overlap, "scale_refresh_period": args.refresh_period, "dense_part": bool(args.dense),
                    "update": ("dqrm_quant_update (one pass)" if args.fused else "dqrm_grad_quant_int8 + dqrm_sparse_update"),
                    "launch": (f"HIP graph of {graph_steps} steps replayed" if graph is not None else "eager launches")},
         "roofline": roofline,

@@ -255,6 +255,7 @@ int32_t dqrm_embbag_fwd(const dqrm_tables_t *tables, const int64_t *indices, con
     a.B = batch;
     a.D = tables->dim;
     a.num_bags = (int64_t)a.T * a.B;
+    a.no_rows = tables->row_offsets_host[a.T] <= 0;
 
     const int G = pow2ceil(a.D / 4);
     const int64_t blocks = (a.num_bags + dqrm::kFwdTile - 1) / dqrm::kFwdTile;

@@ -41,30 +41,10 @@ struct FwdArgs {
     int64_t num_indices;
     int64_t num_bags; // T * B
     int T, B, D;
+    int no_rows; // the tables hold no row at all: nothing may be read from them
 };
 
 typedef float f32x4 __attribute__((ext_vector_type(4)));
-
-// codes of 4 consecutive elements of one row, as floats
-template <bool PACKED>
-__device__ __forceinline__ float4 load_codes(const FwdArgs &a, int64_t row, int col, float s)
-{
-    float4 q;
-    if (PACKED) {
-        unsigned v = *reinterpret_cast<const unsigned short *>(a.packed + row * (a.D >> 1) + (col >> 1));
-        q.x = (float)nibble_code(v);
-        q.y = (float)nibble_code(v >> 4);
-        q.z = (float)nibble_code(v >> 8);
-        q.w = (float)nibble_code(v >> 12);
-    } else {
-        float4 w = *reinterpret_cast<const float4 *>(a.master + row * a.D + col);
-        q.x = int4_code(w.x, s);
-        q.y = int4_code(w.y, s);
-        q.z = int4_code(w.z, s);
-        q.w = int4_code(w.w, s);
-    }
-    return q;
-}
 
 __device__ __forceinline__ void store_codes(int8_t *codes, int64_t i, int D, int col, float4 q)
 {
@@ -72,24 +52,81 @@ __device__ __forceinline__ void store_codes(int8_t *codes, int64_t i, int D, int
     *reinterpret_cast<char4 *>(codes + i * D + col) = c;
 }
 
+// The raw bytes of 4 consecutive elements of one row as they come from memory:
+// two packed bytes, or four fp32 values.
+template <bool PACKED> struct RowPiece;
+template <> struct RowPiece<true> {
+    unsigned v;
+    __device__ __forceinline__ void load(const char *p) { v = *reinterpret_cast<const unsigned short *>(p); }
+    __device__ __forceinline__ float4 codes(float) const
+    {
+        // the builtin's result is typed unsigned although the extract sign-extends
+        return make_float4((float)(int)__builtin_amdgcn_sbfe((int)v, 0, 4), (float)(int)__builtin_amdgcn_sbfe((int)v, 4, 4),
+                           (float)(int)__builtin_amdgcn_sbfe((int)v, 8, 4), (float)(int)__builtin_amdgcn_sbfe((int)v, 12, 4));
+    }
+};
+template <> struct RowPiece<false> {
+    float4 w;
+    __device__ __forceinline__ void load(const char *p) { w = *reinterpret_cast<const float4 *>(p); }
+    __device__ __forceinline__ float4 codes(float s) const
+    {
+        return make_float4(int4_code(w.x, s), int4_code(w.y, s), int4_code(w.z, s), int4_code(w.w, s));
+    }
+};
+
+// The tile when no bag has more than one lookup (the usual batch): out = 0 + s * q, nothing else to add.
+// A slot without a valid lookup reads row 0 and multiplies by 0; the addition turns a -0 product into the
+// +0 of an empty sum.  WHOLE: all kFwdTile slots exist; otherwise only the first `live` do.
+template <int G, bool PACKED, bool WHOLE>
+__device__ __forceinline__ void fwd_single_lookup_tile(const char *tab, const int64_t *s_off, const float *s_scale,
+                                                       const float *s_mul, int grp, float *outp, size_t out_step,
+                                                       int live)
+{
+    constexpr int kGroups = kFwdThreads / G;
+    constexpr int kIters = kFwdTile / kGroups;
+    constexpr int kBatch = kIters < kFwdBatch ? kIters : kFwdBatch;
+    for (int k0 = 0; k0 < kIters; k0 += kBatch) {
+        RowPiece<PACKED> piece[kBatch];
+#pragma unroll
+        for (int k = 0; k < kBatch; ++k) piece[k].load(tab + s_off[(k0 + k) * kGroups + grp]);
+#pragma unroll
+        for (int k = 0; k < kBatch; ++k) {
+            const int i = (k0 + k) * kGroups + grp;
+            const float m = s_mul[i];
+            const float4 q = piece[k].codes(s_scale[i]);
+            const f32x4 v = {0.f + m * q.x, 0.f + m * q.y, 0.f + m * q.z, 0.f + m * q.w};
+            // `out` is written once and not read again by this library: stream it past the caches
+            if (WHOLE || i < live)
+                __builtin_nontemporal_store(v, reinterpret_cast<f32x4 *>(outp + (size_t)(k0 + k) * out_step));
+        }
+    }
+}
+
 template <int G, bool PACKED>
 __global__ __launch_bounds__(kFwdThreads) void embbag_fwd_kernel(FwdArgs a)
 {
-    __shared__ int64_t s_row[kFwdTile]; // absolute row of the bag's first lookup, -1 if none / invalid
+    __shared__ int64_t s_off[kFwdTile]; // byte offset of the first lookup's row in the table (0 if none / invalid)
     __shared__ int64_t s_beg[kFwdTile]; // position of the bag's first lookup
     __shared__ int s_len[kFwdTile];     // lookups in the bag
     __shared__ int s_tab[kFwdTile];
-    __shared__ float s_scale[kFwdTile];
+    __shared__ float s_scale[kFwdTile]; // table scale
+    __shared__ float s_mul[kFwdTile];   // table scale, or 0 when the first lookup is absent or invalid
+    __shared__ unsigned char s_ok[kFwdTile]; // the first lookup exists and is in range
+    __shared__ int s_general;           // some bag of the tile has more than one lookup
 
     const int tid = threadIdx.x;
     const int64_t slot0 = (int64_t)blockIdx.x * kFwdTile;
+    const int row_bytes = PACKED ? (a.D >> 1) : a.D * 4;
+    if (tid == 0) s_general = 0;
+    __syncthreads();
 
     // ---- phase A: one slot per thread ------------------------------------------
     {
         const int64_t o = slot0 + tid;
-        int64_t row = -1, beg = 0;
+        int64_t off = 0, beg = 0;
         int len = 0, t = 0;
-        float sc = 1.0f;
+        float sc = 1.0f, mul = 0.0f;
+        bool ok = false;
         if (o < a.num_bags) {
             const unsigned b = (unsigned)o / (unsigned)a.T; // num_bags < 2^31 (checked on the host)
             t = (int)((unsigned)o - b * (unsigned)a.T);
@@ -106,17 +143,23 @@ __global__ __launch_bounds__(kFwdThreads) void embbag_fwd_kernel(FwdArgs a)
             if (len > 0) {
                 const int64_t idx = a.indices[s];
                 const int64_t r0 = a.row_offsets[t], r1 = a.row_offsets[t + 1];
-                if (idx >= 0 && idx < r1 - r0)
-                    row = r0 + idx;
-                else
+                if (idx >= 0 && idx < r1 - r0) {
+                    off = (r0 + idx) * row_bytes;
+                    mul = sc;
+                    ok = true;
+                } else {
                     report(DQRM_ERR_INDEX_OUT_OF_RANGE, t, idx);
+                }
+                if (len > 1) s_general = 1;
             }
         }
-        s_row[tid] = row;
+        s_off[tid] = off;
         s_beg[tid] = beg;
         s_len[tid] = len;
         s_tab[tid] = t;
         s_scale[tid] = sc;
+        s_mul[tid] = mul;
+        s_ok[tid] = ok;
     }
     __syncthreads();
 
@@ -127,58 +170,61 @@ __global__ __launch_bounds__(kFwdThreads) void embbag_fwd_kernel(FwdArgs a)
     const int lg = tid & (G - 1);
     const int grp = tid / G;
     const int col = lg * 4;
-    const bool col_ok = col < a.D;
+    if (col >= a.D) return; // lanes beyond the row (D / 4 not a power of two) have nothing to do from here on
+    const char *tab = PACKED ? reinterpret_cast<const char *>(a.packed) + (col >> 1)
+                             : reinterpret_cast<const char *>(a.master + col);
+    float *outp = a.out + (slot0 + grp) * a.D + col; // slot i = k * kGroups + grp lies k * kGroups rows further
+    const size_t out_step = (size_t)kGroups * a.D;
+    const bool general = s_general != 0 || a.codes != nullptr || a.no_rows != 0;
 
-    for (int k0 = 0; k0 < kIters; k0 += kBatch) {
-        float4 q[kBatch];
-#pragma unroll
-        for (int k = 0; k < kBatch; ++k) { // B: request the first rows of the whole batch
-            const int i = (k0 + k) * kGroups + grp;
-            const int64_t row = s_row[i];
-            q[k] = make_float4(0.f, 0.f, 0.f, 0.f);
-            if (row >= 0 && col_ok) q[k] = load_codes<PACKED>(a, row, col, s_scale[i]);
+    if (!general) {
+        if (slot0 + kFwdTile <= a.num_bags)
+            fwd_single_lookup_tile<G, PACKED, true>(tab, s_off, s_scale, s_mul, grp, outp, out_step, 0);
+        else
+            fwd_single_lookup_tile<G, PACKED, false>(tab, s_off, s_scale, s_mul, grp, outp, out_step,
+                                                     (int)(a.num_bags - slot0));
+        return;
+    }
+
+    // general bags: the remaining lookups are added in order; codes are written out when asked for
+    for (int k = 0; k < kIters; ++k) {
+        const int i = k * kGroups + grp;
+        if (slot0 + i >= a.num_bags) break;
+        const float s = s_scale[i];
+        const int len = s_len[i];
+        const int64_t beg = s_beg[i];
+        float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
+        if (s_ok[i]) {
+            RowPiece<PACKED> piece;
+            piece.load(tab + s_off[i]);
+            const float4 q = piece.codes(s);
+            acc.x = acc.x + s * q.x;
+            acc.y = acc.y + s * q.y;
+            acc.z = acc.z + s * q.z;
+            acc.w = acc.w + s * q.w;
+            if (a.codes) store_codes(a.codes, beg, a.D, col, q);
         }
-#pragma unroll
-        for (int k = 0; k < kBatch; ++k) { // C: pool and store
-            const int i = (k0 + k) * kGroups + grp;
-            const int64_t o = slot0 + i;
-            if (o >= a.num_bags) continue;
-            const float s = s_scale[i];
-            const int len = s_len[i];
-            float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
-            if (s_row[i] >= 0) {
-                acc.x = acc.x + s * q[k].x;
-                acc.y = acc.y + s * q[k].y;
-                acc.z = acc.z + s * q[k].z;
-                acc.w = acc.w + s * q[k].w;
-                if (a.codes && col_ok) store_codes(a.codes, s_beg[i], a.D, col, q[k]);
-            }
-            if (len > 1) {
-                const int t = s_tab[i];
-                const int64_t r0 = a.row_offsets[t], r1 = a.row_offsets[t + 1];
-                const int64_t beg = s_beg[i];
-                for (int64_t p = beg + 1; p < beg + len; ++p) {
-                    const int64_t idx = a.indices[p];
-                    if (idx < 0 || idx >= r1 - r0) {
-                        if (lg == 0) report(DQRM_ERR_INDEX_OUT_OF_RANGE, t, idx);
-                        continue;
-                    }
-                    if (col_ok) {
-                        const float4 qq = load_codes<PACKED>(a, r0 + idx, col, s);
-                        acc.x = acc.x + s * qq.x;
-                        acc.y = acc.y + s * qq.y;
-                        acc.z = acc.z + s * qq.z;
-                        acc.w = acc.w + s * qq.w;
-                        if (a.codes) store_codes(a.codes, p, a.D, col, qq);
-                    }
+        if (len > 1) {
+            const int t = s_tab[i];
+            const int64_t r0 = a.row_offsets[t], r1 = a.row_offsets[t + 1];
+            for (int64_t p = beg + 1; p < beg + len; ++p) {
+                const int64_t idx = a.indices[p];
+                if (idx < 0 || idx >= r1 - r0) {
+                    if (lg == 0) report(DQRM_ERR_INDEX_OUT_OF_RANGE, t, idx);
+                    continue;
                 }
-            }
-            if (col_ok) {
-                // `out` is written once and not read again by this library: stream it past the caches
-                f32x4 v = {acc.x, acc.y, acc.z, acc.w};
-                __builtin_nontemporal_store(v, reinterpret_cast<f32x4 *>(a.out + o * a.D + col));
+                RowPiece<PACKED> piece;
+                piece.load(tab + (r0 + idx) * row_bytes);
+                const float4 q = piece.codes(s);
+                acc.x = acc.x + s * q.x;
+                acc.y = acc.y + s * q.y;
+                acc.z = acc.z + s * q.z;
+                acc.w = acc.w + s * q.w;
+                if (a.codes) store_codes(a.codes, p, a.D, col, q);
             }
         }
+        const f32x4 v = {acc.x, acc.y, acc.z, acc.w};
+        __builtin_nontemporal_store(v, reinterpret_cast<f32x4 *>(outp + (size_t)k * out_step));
     }
 }
 

@@ -70,13 +70,17 @@ def main():
                     help="full DQRM train step (use with --workload kaggle): dqrm_dense_step (MLPs 13-512-256-64-16 / "
                          "367-512-256-1, interaction, BCE, backward, SGD) runs between the tables' forward and "
                          "backward and produces grad_out")
-    ap.add_argument("--overlap", default="pipeline", choices=["none", "fwd", "pipeline", "ahead"],
+    ap.add_argument("--overlap", default="pipeline", choices=["none", "fwd", "pipeline", "ahead", "group"],
                     help="where dqrm_dedupe (needs only the indices) runs: none = in line on the one stream; "
                          "fwd = on a second stream beside the same step's forward; pipeline = on a second stream, "
                          "one step ahead (double-buffered workspace); ahead = in line on the one stream, but for the "
                          "next --ahead batches in one dqrm_dedupe_multi launch (a table's sort fills one CU, so several "
-                         "batches fill the chip; the data loader has their indices already)")
-    ap.add_argument("--ahead", type=int, default=8, help="batches per dqrm_dedupe_multi launch with --overlap ahead")
+                         "batches fill the chip; the data loader has their indices already); group = that launch on the "
+                         "second stream, one group of --ahead batches ahead, so the streams meet once per group")
+    ap.add_argument("--ahead", type=int, default=8, help="batches per dqrm_dedupe_multi launch with --overlap ahead / group")
+    ap.add_argument("--side-multi", action="store_true",
+                    help="with --overlap group: the side stream uses one dqrm_dedupe_multi launch per group instead "
+                         "of one dqrm_dedupe per batch")
     ap.add_argument("--two-call-update", dest="fused", action="store_false",
                     help="dqrm_grad_quant_int8 + dqrm_sparse_update (and the absmax fold inside dqrm_segment_sum) "
                          "instead of the one-pass dqrm_quant_update")
@@ -125,7 +129,7 @@ def main():
     torch.cuda.synchronize()
 
     side = torch.cuda.Stream()  # default priority
-    nbuf = {"pipeline": 2, "ahead": args.ahead}.get(args.overlap, 1)
+    nbuf = {"pipeline": 2, "ahead": args.ahead, "group": 2 * args.ahead}.get(args.overlap, 1)
     dup = lambda x: [x] + [torch.empty_like(x) for _ in range(nbuf - 1)]
     wss, sps, urs, sos = dup(bufs.workspace), dup(bufs.sorted_pos), dup(bufs.uniq_rows), dup(bufs.seg_offsets)
     tuos, nus = dup(bufs.table_uniq_offsets), dup(bufs.num_unique)
@@ -193,6 +197,41 @@ def main():
                 ix, of = batch_of(k)
                 forward(k, ix, of)
                 rest_of_step(k, k % nbuf)
+            return
+        if args.overlap == "group":
+            # dqrm_dedupe_multi of the NEXT group of --ahead batches runs on the side stream while the main
+            # stream works through the current group: the two streams meet once per group, not once per step
+            A = args.ahead
+            groups = [range(s, min(s + A, k0 + n)) for s in range(k0, k0 + n, A)]
+            slot = lambda gi, k: (gi % 2) * A + (k - groups[gi][0])
+            def dedupe_group(gi, stream):
+                if stream is side and not args.side_multi:
+                    # one batch at a time: 26 workgroups take 26 CUs from the main stream's kernels, 208 would
+                    # take most of the chip
+                    for k in groups[gi]:
+                        j = slot(gi, k)
+                        dq.dqrm_dedupe(tables, *batch_of(k), B, sps[j], urs[j], sos[j], tuos[j], nus[j], wss[j],
+                                       stream=side)
+                    return
+                dq.dqrm_dedupe_multi(tables, B, [batch_of(k) + (sps[slot(gi, k)], urs[slot(gi, k)], sos[slot(gi, k)],
+                                                                tuos[slot(gi, k)], nus[slot(gi, k)], wss[slot(gi, k)])
+                                                 for k in groups[gi]], stream=stream)
+            side.wait_stream(main)
+            dedupe_group(0, main)  # the first group in line
+            for gi, grp in enumerate(groups):
+                if gi + 1 < len(groups):
+                    if gi >= 1:
+                        side.wait_event(ev_update[(gi - 1) % 2])  # readers of that half of the buffers are done
+                    dedupe_group(gi + 1, side)
+                    ev_dedupe[(gi + 1) % 2].record(side)
+                if gi >= 1:
+                    main.wait_event(ev_dedupe[gi % 2])
+                for k in grp:
+                    ix, of = batch_of(k)
+                    forward(k, ix, of)
+                    rest_of_step(k, slot(gi, k))
+                ev_update[gi % 2].record(main)
+            main.wait_stream(side)
             return
         if args.overlap == "none":
             for k in range(k0, k0 + n):

@@ -59,6 +59,8 @@ int32_t check_tables(const dqrm_tables_t *tb, bool need_packed, int64_t *total_r
 }
 
 constexpr int64_t kMaxIndices = 2147483647LL - 2 * DQRM_MAX_TABLES - 64;
+// the element-wise kernels index quarter-rows (float4) of the sparse gradient with 32-bit numbers
+constexpr int64_t kMaxRowQuarters = 2147483647LL - 4LL * 2048 * 256;
 
 int32_t check_batch(const dqrm_tables_t *tb, const int64_t *indices, const int64_t *offsets, int32_t batch,
                     int64_t num_indices)
@@ -399,6 +401,7 @@ int32_t dqrm_grad_quant_int8(int32_t num_tables, int32_t dim, int64_t capacity, 
     if (num_tables > DQRM_MAX_TABLES || dim % 8 != 0 || dim > DQRM_MAX_DIM) return DQRM_ERR_UNSUPPORTED;
     if (capacity > kMaxIndices) return DQRM_ERR_UNSUPPORTED;
     if (!aligned(values, 16) || !aligned(gq, 4)) return DQRM_ERR_INVALID_ARG;
+    if (capacity * (dim / 4) > kMaxRowQuarters) return DQRM_ERR_UNSUPPORTED;
     dqrm::QuantArgs a;
     a.values = values;
     a.tuo = table_uniq_offsets;
@@ -408,9 +411,10 @@ int32_t dqrm_grad_quant_int8(int32_t num_tables, int32_t dim, int64_t capacity, 
     a.capacity = capacity;
     a.T = num_tables;
     a.D = dim;
+    a.by_q4 = dqrm::FastDiv::make((unsigned)(dim / 4));
     hipStream_t st = static_cast<hipStream_t>(stream);
     hipLaunchKernelGGL(dqrm::grad_quant_kernel, dim3(grid_for(capacity * (dim / 4), dqrm::kEwThreads, 8)),
-                       dim3(dqrm::kEwThreads), 0, st, a);
+                       dim3(dqrm::kEwThreads), dqrm::TableLds::bytes(num_tables), st, a);
     DQRM_HIP_CHECK(hipGetLastError());
     return DQRM_OK;
 }
@@ -425,6 +429,7 @@ int32_t dqrm_sparse_update(const dqrm_tables_t *tables, int64_t capacity, const 
     if (capacity < 0 || !uniq_rows || !table_uniq_offsets || !gq || !g_scale) return DQRM_ERR_INVALID_ARG;
     if (capacity > kMaxIndices) return DQRM_ERR_UNSUPPORTED;
     if (!aligned(gq, 4)) return DQRM_ERR_INVALID_ARG;
+    if (capacity * (tables->dim / 4) > kMaxRowQuarters) return DQRM_ERR_UNSUPPORTED;
     dqrm::UpdateArgs a;
     a.master = tables->master;
     a.packed = tables->packed;
@@ -438,9 +443,10 @@ int32_t dqrm_sparse_update(const dqrm_tables_t *tables, int64_t capacity, const 
     a.lr = lr;
     a.T = tables->num_tables;
     a.D = tables->dim;
+    a.by_q4 = dqrm::FastDiv::make((unsigned)(a.D / 4));
     hipStream_t st = static_cast<hipStream_t>(stream);
     hipLaunchKernelGGL(dqrm::sparse_update_kernel, dim3(grid_for(capacity * (a.D / 4), dqrm::kEwThreads, 8)),
-                       dim3(dqrm::kEwThreads), 0, st, a);
+                       dim3(dqrm::kEwThreads), dqrm::TableLds::bytes(a.T), st, a);
     DQRM_HIP_CHECK(hipGetLastError());
     return DQRM_OK;
 }
@@ -457,6 +463,7 @@ int32_t dqrm_quant_update(const dqrm_tables_t *tables, int64_t capacity, int64_t
         return DQRM_ERR_INVALID_ARG;
     if (capacity > kMaxIndices || num_indices > kMaxIndices) return DQRM_ERR_UNSUPPORTED;
     if (!aligned(values, 16) || !aligned(gq, 4) || !aligned(workspace, 256)) return DQRM_ERR_INVALID_ARG;
+    if (capacity * (tables->dim / 4) > kMaxRowQuarters) return DQRM_ERR_UNSUPPORTED;
     const WsLayout L = ws_layout(tables->num_tables, tables->dim, num_indices);
     if (workspace_bytes < L.total) return DQRM_ERR_WORKSPACE_TOO_SMALL;
     dqrm::QuantUpdateArgs a;
@@ -472,6 +479,7 @@ int32_t dqrm_quant_update(const dqrm_tables_t *tables, int64_t capacity, int64_t
     a.u.lr = lr;
     a.u.T = tables->num_tables;
     a.u.D = tables->dim;
+    a.u.by_q4 = dqrm::FastDiv::make((unsigned)(a.u.D / 4));
     a.values = values;
     a.absmax_slots = ws_views(workspace, L).absmax_slots;
     a.g_absmax = g_absmax;
@@ -479,7 +487,7 @@ int32_t dqrm_quant_update(const dqrm_tables_t *tables, int64_t capacity, int64_t
     a.g_scale_out = g_scale;
     hipStream_t st = static_cast<hipStream_t>(stream);
     hipLaunchKernelGGL(dqrm::quant_update_kernel, dim3(grid_for(capacity * (a.u.D / 4), dqrm::kEwThreads, 8)),
-                       dim3(dqrm::kEwThreads), 0, st, a);
+                       dim3(dqrm::kEwThreads), dqrm::TableLds::bytes(a.u.T), st, a);
     DQRM_HIP_CHECK(hipGetLastError());
     return DQRM_OK;
 }

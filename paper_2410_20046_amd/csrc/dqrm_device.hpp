@@ -32,30 +32,87 @@ __device__ __forceinline__ void report(int code, int table, long long value)
 }
 
 // ---- the quantiser -----------------------------------------------------------
-// scale = max(absmax / qmax, 1e-8); code = clamp(rint(x / scale), lo, hi).
-// IEEE division (hipcc rounds fp32 division correctly unless told otherwise),
-// round-half-even (v_rndne_f32), one rounding per operation.
+// scale = max(absmax / qmax, 1e-8); code = clamp(rint(x / scale), lo, hi) with
+// the IEEE quotient, round-half-even (v_rndne_f32), one rounding per operation.
 __device__ __forceinline__ float scale_from_absmax(float absmax, float qmax)
 {
     return fmaxf(absmax / qmax, 1e-8f);
 }
 
-__device__ __forceinline__ float code_f(float x, float scale, float lo, float hi)
+// One scale and its correctly rounded reciprocal (one IEEE division per table,
+// not one per element).
+struct Scale {
+    float s, y;
+    Scale() = default;
+    __device__ __forceinline__ explicit Scale(float scale) : s(scale), y(1.0f / scale) {}
+    __device__ __forceinline__ Scale(float scale, float recip) : s(scale), y(recip) {}
+};
+
+// x / s rounded to nearest, as the division instruction sequence would give it,
+// from y = RN(1 / s).  q0 = x * y is within two units in the last place of the
+// quotient; the remainder x - s * q is exact in one fused operation, and adding
+// remainder * y first gives a faithful quotient and then the correctly rounded
+// one (Markstein's correction step, twice).  Needs no overflow and an exactly
+// representable remainder: scales are >= 1e-8, so a quotient that can reach 0.5
+// has a normal x, and smaller quotients round to code 0 whatever their last bits
+// are.  GUARD: quotients beyond 1e6 in magnitude (possible only with a scale the
+// data has outgrown) are left as x * y, far out in the clamped range, so that the
+// correction never sees an infinity.
+template <bool GUARD>
+__device__ __forceinline__ float quotient(float x, Scale sc)
 {
-    return fminf(fmaxf(rintf(x / scale), lo), hi);
+    const float q0 = x * sc.y;
+    float q = __builtin_fmaf(__builtin_fmaf(-sc.s, q0, x), sc.y, q0);
+    q = __builtin_fmaf(__builtin_fmaf(-sc.s, q, x), sc.y, q);
+    if (GUARD) q = __builtin_fabsf(q0) < 1e6f ? q : q0;
+    return q;
 }
 
-__device__ __forceinline__ float int4_code(float w, float s) { return code_f(w, s, -8.0f, 7.0f); }
-__device__ __forceinline__ float int8_code(float g, float s) { return code_f(g, s, -128.0f, 127.0f); }
+// the code as an integer in [lo, hi]
+template <bool GUARD>
+__device__ __forceinline__ int code_i(float x, Scale sc, float lo, float hi)
+{
+    return (int)__builtin_amdgcn_fmed3f(__builtin_rintf(quotient<GUARD>(x, sc)), lo, hi);
+}
+
+// INT4 code of a weight: the scale may be stale (Sec. 3.2), so the quotient is guarded and the clamp is live
+__device__ __forceinline__ int int4_code(float w, Scale sc) { return code_i<true>(w, sc, -8.0f, 7.0f); }
+// INT8 code of a gradient value under a scale the caller supplied
+__device__ __forceinline__ int int8_code(float g, Scale sc) { return code_i<true>(g, sc, -128.0f, 127.0f); }
+// ... under a scale derived from the maximum of the very values being quantised: |g / s| <= 127 (1 + 2^-23)
+__device__ __forceinline__ int int8_code_fresh(float g, Scale sc) { return code_i<false>(g, sc, -128.0f, 127.0f); }
+
+// four codes -> four bytes, element 0 in the low byte
+__device__ __forceinline__ unsigned pack_bytes(int q0, int q1, int q2, int q3)
+{
+    return ((unsigned)q0 & 0xFFu) | (((unsigned)q1 & 0xFFu) << 8) | (((unsigned)q2 & 0xFFu) << 16) | ((unsigned)q3 << 24);
+}
+
+// unsigned division of numbers below 2^31 by a fixed divisor (host-side set-up)
+struct FastDiv {
+    unsigned magic, shift, d;
+    __host__ static FastDiv make(unsigned divisor)
+    {
+        FastDiv f;
+        unsigned l = 0;
+        while ((1u << l) < divisor) ++l;
+        // ceil(2^(31 + l) / d) < 2^32 for d >= 2; exact quotients for every dividend below 2^31
+        const unsigned long long p = 1ull << (31 + l);
+        f.magic = divisor > 1 ? (unsigned)((p + divisor - 1) / divisor) : 0u;
+        f.shift = l > 0 ? l - 1 : 0;
+        f.d = divisor;
+        return f;
+    }
+    __device__ __forceinline__ unsigned div(unsigned x) const { return d > 1 ? __umulhi(x, magic) >> shift : x; }
+};
 
 // sign-extend the low 4 bits of v
 __device__ __forceinline__ int nibble_code(unsigned v) { return (int)((v & 0xFu) ^ 8u) - 8; }
 
 // four codes -> two bytes, element 0 in the low nibble of byte 0
-__device__ __forceinline__ unsigned pack4(float q0, float q1, float q2, float q3)
+__device__ __forceinline__ unsigned pack4(int q0, int q1, int q2, int q3)
 {
-    return ((unsigned)(int)q0 & 0xFu) | (((unsigned)(int)q1 & 0xFu) << 4) | (((unsigned)(int)q2 & 0xFu) << 8) |
-           (((unsigned)(int)q3 & 0xFu) << 12);
+    return ((unsigned)q0 & 0xFu) | (((unsigned)q1 & 0xFu) << 4) | (((unsigned)q2 & 0xFu) << 8) | (((unsigned)q3 & 0xFu) << 12);
 }
 
 // ---- wave / block primitives ---------------------------------------------------

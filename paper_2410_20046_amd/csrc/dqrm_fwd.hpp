@@ -58,7 +58,7 @@ template <bool PACKED> struct RowPiece;
 template <> struct RowPiece<true> {
     unsigned v;
     __device__ __forceinline__ void load(const char *p) { v = *reinterpret_cast<const unsigned short *>(p); }
-    __device__ __forceinline__ float4 codes(float) const
+    __device__ __forceinline__ float4 codes(Scale) const
     {
         // the builtin's result is typed unsigned although the extract sign-extends
         return make_float4((float)(int)__builtin_amdgcn_sbfe((int)v, 0, 4), (float)(int)__builtin_amdgcn_sbfe((int)v, 4, 4),
@@ -68,9 +68,10 @@ template <> struct RowPiece<true> {
 template <> struct RowPiece<false> {
     float4 w;
     __device__ __forceinline__ void load(const char *p) { w = *reinterpret_cast<const float4 *>(p); }
-    __device__ __forceinline__ float4 codes(float s) const
+    __device__ __forceinline__ float4 codes(Scale s) const
     {
-        return make_float4(int4_code(w.x, s), int4_code(w.y, s), int4_code(w.z, s), int4_code(w.w, s));
+        return make_float4((float)int4_code(w.x, s), (float)int4_code(w.y, s), (float)int4_code(w.z, s),
+                           (float)int4_code(w.w, s));
     }
 };
 
@@ -78,7 +79,7 @@ template <> struct RowPiece<false> {
 // A slot without a valid lookup reads row 0 and multiplies by 0; the addition turns a -0 product into the
 // +0 of an empty sum.  WHOLE: all kFwdTile slots exist; otherwise only the first `live` do.
 template <int G, bool PACKED, bool WHOLE>
-__device__ __forceinline__ void fwd_single_lookup_tile(const char *tab, const int64_t *s_off, const float *s_scale,
+__device__ __forceinline__ void fwd_single_lookup_tile(const char *tab, const int64_t *s_off, const Scale *s_scale,
                                                        const float *s_mul, int grp, float *outp, size_t out_step,
                                                        int live)
 {
@@ -109,7 +110,7 @@ __global__ __launch_bounds__(kFwdThreads) void embbag_fwd_kernel(FwdArgs a)
     __shared__ int64_t s_beg[kFwdTile]; // position of the bag's first lookup
     __shared__ int s_len[kFwdTile];     // lookups in the bag
     __shared__ int s_tab[kFwdTile];
-    __shared__ float s_scale[kFwdTile]; // table scale
+    __shared__ Scale s_scale[kFwdTile]; // table scale (and its reciprocal)
     __shared__ float s_mul[kFwdTile];   // table scale, or 0 when the first lookup is absent or invalid
     __shared__ unsigned char s_ok[kFwdTile]; // the first lookup exists and is in range
     __shared__ int s_general;           // some bag of the tile has more than one lookup
@@ -157,7 +158,8 @@ __global__ __launch_bounds__(kFwdThreads) void embbag_fwd_kernel(FwdArgs a)
         s_beg[tid] = beg;
         s_len[tid] = len;
         s_tab[tid] = t;
-        s_scale[tid] = sc;
+        // the packed rows hold codes already: no quotient, no reciprocal
+        s_scale[tid] = PACKED ? Scale(sc, 0.0f) : Scale(sc);
         s_mul[tid] = mul;
         s_ok[tid] = ok;
     }
@@ -190,14 +192,15 @@ __global__ __launch_bounds__(kFwdThreads) void embbag_fwd_kernel(FwdArgs a)
     for (int k = 0; k < kIters; ++k) {
         const int i = k * kGroups + grp;
         if (slot0 + i >= a.num_bags) break;
-        const float s = s_scale[i];
+        const Scale sq = s_scale[i];
+        const float s = sq.s;
         const int len = s_len[i];
         const int64_t beg = s_beg[i];
         float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
         if (s_ok[i]) {
             RowPiece<PACKED> piece;
             piece.load(tab + s_off[i]);
-            const float4 q = piece.codes(s);
+            const float4 q = piece.codes(sq);
             acc.x = acc.x + s * q.x;
             acc.y = acc.y + s * q.y;
             acc.z = acc.z + s * q.z;
@@ -215,7 +218,7 @@ __global__ __launch_bounds__(kFwdThreads) void embbag_fwd_kernel(FwdArgs a)
                 }
                 RowPiece<PACKED> piece;
                 piece.load(tab + (r0 + idx) * row_bytes);
-                const float4 q = piece.codes(s);
+                const float4 q = piece.codes(sq);
                 acc.x = acc.x + s * q.x;
                 acc.y = acc.y + s * q.y;
                 acc.z = acc.z + s * q.z;

@@ -9,6 +9,45 @@ namespace dqrm {
 
 constexpr int kEwThreads = 256;
 
+// Per-table constants of the element-wise kernels, in dynamic LDS:
+// [T+1] int tuo | [T] Scale gradient | [T] Scale weight | [T+1] int64 row offsets
+struct TableLds {
+    int *tuo;
+    Scale *gs, *ws;
+    int64_t *r0;
+    __device__ __forceinline__ explicit TableLds(unsigned char *base, int T)
+    {
+        r0 = reinterpret_cast<int64_t *>(base);
+        gs = reinterpret_cast<Scale *>(r0 + (T + 1));
+        ws = gs + T;
+        tuo = reinterpret_cast<int *>(ws + T);
+    }
+    __host__ __device__ static size_t bytes(int T) { return (size_t)(T + 1) * 8 + (size_t)T * 16 + (size_t)(T + 1) * 4; }
+};
+
+// One float4 of one unique row: which row, which table, which quarter-row.
+struct RowElem {
+    unsigned e;  // float4 index into values / char4 index into gq
+    int u, t, c4;
+};
+
+// the element's position; e < total <= capacity * D / 4 < 2^31
+__device__ __forceinline__ RowElem row_elem(unsigned e, FastDiv by_q4, const TableLds &L, int T)
+{
+    RowElem r;
+    r.e = e;
+    r.u = (int)by_q4.div(e);
+    r.c4 = (int)(e - (unsigned)r.u * by_q4.d);
+    r.t = table_of(L.tuo, T, r.u);
+    return r;
+}
+
+__device__ __forceinline__ unsigned clamp_u(const int *tuo, int T, int64_t capacity)
+{
+    int64_t U = tuo[T];
+    return (unsigned)(U < 0 ? 0 : (U > capacity ? capacity : U));
+}
+
 // ---- B4: values -> INT8 codes, one scale per table ---------------------------
 struct QuantArgs {
     const float *values;
@@ -17,35 +56,32 @@ struct QuantArgs {
     int8_t *gq;
     float *g_scale;
     int64_t capacity;
+    FastDiv by_q4;
     int T, D;
 };
 
 __global__ __launch_bounds__(kEwThreads) void grad_quant_kernel(QuantArgs a)
 {
-    __shared__ int s_tuo[DQRM_MAX_TABLES + 1];
-    __shared__ float s_gs[DQRM_MAX_TABLES];
+    extern __shared__ __align__(16) unsigned char s_dyn[];
+    const TableLds L(s_dyn, a.T);
     const int T = a.T;
     for (int k = threadIdx.x; k <= T; k += kEwThreads) {
-        s_tuo[k] = a.tuo[k];
+        L.tuo[k] = a.tuo[k];
         if (k < T) {
             const float gs = scale_from_absmax(a.g_absmax[k], 127.0f);
-            s_gs[k] = gs;
+            L.gs[k] = Scale(gs);
             if (blockIdx.x == 0) a.g_scale[k] = gs;
         }
     }
     __syncthreads();
-    int64_t U = s_tuo[T];
-    U = U < 0 ? 0 : (U > a.capacity ? a.capacity : U);
-    const int q4 = a.D >> 2; // float4 per row
-    const int64_t total = U * q4;
-    for (int64_t e = (int64_t)blockIdx.x * kEwThreads + threadIdx.x; e < total; e += (int64_t)gridDim.x * kEwThreads) {
-        const int64_t u = e / q4;
-        const int t = table_of(s_tuo, T, (int)u);
-        const float gs = s_gs[t];
+    const unsigned total = clamp_u(L.tuo, T, a.capacity) * a.by_q4.d;
+    for (unsigned e = blockIdx.x * kEwThreads + threadIdx.x; e < total; e += gridDim.x * kEwThreads) {
+        const RowElem r = row_elem(e, a.by_q4, L, T);
+        const Scale gs = L.gs[r.t];
         const float4 v = reinterpret_cast<const float4 *>(a.values)[e];
-        char4 c = make_char4((signed char)(int)int8_code(v.x, gs), (signed char)(int)int8_code(v.y, gs),
-                             (signed char)(int)int8_code(v.z, gs), (signed char)(int)int8_code(v.w, gs));
-        reinterpret_cast<char4 *>(a.gq)[e] = c;
+        // the caller's g_absmax may be smaller than the values' (then codes clamp): guarded quotient
+        reinterpret_cast<unsigned *>(a.gq)[e] =
+            pack_bytes(int8_code(v.x, gs), int8_code(v.y, gs), int8_code(v.z, gs), int8_code(v.w, gs));
     }
 }
 
@@ -60,46 +96,57 @@ struct UpdateArgs {
     const int8_t *gq;
     const float *g_scale;
     int64_t capacity;
+    FastDiv by_q4;
     float lr;
     int T, D;
 };
 
+// w <- w - lr * (gs * code), each operation rounded on its own; returns the new weights
+__device__ __forceinline__ float4 sgd_step(float4 w, int c0, int c1, int c2, int c3, float gs, float lr)
+{
+    w.x = w.x - lr * (gs * (float)c0);
+    w.y = w.y - lr * (gs * (float)c1);
+    w.z = w.z - lr * (gs * (float)c2);
+    w.w = w.w - lr * (gs * (float)c3);
+    return w;
+}
+
+__device__ __forceinline__ unsigned short encode4(float4 w, Scale ws)
+{
+    return (unsigned short)pack4(int4_code(w.x, ws), int4_code(w.y, ws), int4_code(w.z, ws), int4_code(w.w, ws));
+}
+
 __global__ __launch_bounds__(kEwThreads) void sparse_update_kernel(UpdateArgs a)
 {
-    __shared__ int s_tuo[DQRM_MAX_TABLES + 1];
+    extern __shared__ __align__(16) unsigned char s_dyn[];
+    const TableLds L(s_dyn, a.T);
     const int T = a.T;
-    for (int k = threadIdx.x; k <= T; k += kEwThreads) s_tuo[k] = a.tuo[k];
+    for (int k = threadIdx.x; k <= T; k += kEwThreads) {
+        L.tuo[k] = a.tuo[k];
+        L.r0[k] = a.row_offsets[k];
+        if (k < T) {
+            L.gs[k].s = a.g_scale[k];
+            if (a.packed) L.ws[k] = Scale(a.w_scale[k]);
+        }
+    }
     __syncthreads();
-    int64_t U = s_tuo[T];
-    U = U < 0 ? 0 : (U > a.capacity ? a.capacity : U);
-    const int q4 = a.D >> 2;
-    const int64_t total = U * q4;
-    for (int64_t e = (int64_t)blockIdx.x * kEwThreads + threadIdx.x; e < total; e += (int64_t)gridDim.x * kEwThreads) {
-        const int64_t u = e / q4;
-        const int c4 = (int)(e - u * q4);
-        const int t = table_of(s_tuo, T, (int)u);
-        const int64_t r0 = a.row_offsets[t], r1 = a.row_offsets[t + 1];
-        const int64_t lr_row = a.uniq_rows[u];
+    const unsigned total = clamp_u(L.tuo, T, a.capacity) * a.by_q4.d;
+    const int q4 = (int)a.by_q4.d;
+    for (unsigned e = blockIdx.x * kEwThreads + threadIdx.x; e < total; e += gridDim.x * kEwThreads) {
+        const RowElem r = row_elem(e, a.by_q4, L, T);
+        const int64_t r0 = L.r0[r.t], r1 = L.r0[r.t + 1];
+        const int64_t lr_row = a.uniq_rows[r.u];
         if (lr_row < 0 || lr_row >= r1 - r0) {
-            if (c4 == 0) report(DQRM_ERR_INDEX_OUT_OF_RANGE, t, lr_row);
+            if (r.c4 == 0) report(DQRM_ERR_INDEX_OUT_OF_RANGE, r.t, lr_row);
             continue;
         }
         const int64_t row = r0 + lr_row;
-        const float gs = a.g_scale[t];
         const char4 c = reinterpret_cast<const char4 *>(a.gq)[e];
-        float4 *wp = reinterpret_cast<float4 *>(a.master + row * a.D) + c4;
-        float4 w = *wp;
-        // g = g_scale * code; w <- w - lr * g, each operation rounded on its own
-        w.x = w.x - a.lr * (gs * (float)c.x);
-        w.y = w.y - a.lr * (gs * (float)c.y);
-        w.z = w.z - a.lr * (gs * (float)c.z);
-        w.w = w.w - a.lr * (gs * (float)c.w);
+        float4 *wp = reinterpret_cast<float4 *>(a.master) + row * q4 + r.c4;
+        const float4 w = sgd_step(*wp, c.x, c.y, c.z, c.w, L.gs[r.t].s, a.lr);
         *wp = w;
-        if (a.packed) {
-            const float ws = a.w_scale[t];
-            const unsigned p = pack4(int4_code(w.x, ws), int4_code(w.y, ws), int4_code(w.z, ws), int4_code(w.w, ws));
-            *reinterpret_cast<unsigned short *>(a.packed + row * (a.D >> 1) + c4 * 2) = (unsigned short)p;
-        }
+        if (a.packed)
+            reinterpret_cast<unsigned short *>(a.packed)[row * q4 + r.c4] = encode4(w, L.ws[r.t]);
     }
 }
 
@@ -117,15 +164,19 @@ struct QuantUpdateArgs {
     float *g_scale_out;
 };
 
-constexpr int kQuPerThread = 4; // float4 elements a thread has in flight
+#ifndef DQRM_QU_PER_THREAD
+#define DQRM_QU_PER_THREAD 2
+#endif
+constexpr int kQuPerThread = DQRM_QU_PER_THREAD; // float4 elements a thread has in flight
 
 __global__ __launch_bounds__(kEwThreads) void quant_update_kernel(QuantUpdateArgs a)
 {
-    __shared__ int s_tuo[DQRM_MAX_TABLES + 1];
-    __shared__ float s_gs[DQRM_MAX_TABLES];
+    extern __shared__ __align__(16) unsigned char s_dyn[];
     const int T = a.u.T;
+    const TableLds L(s_dyn, T);
     for (int k = threadIdx.x; k <= T; k += kEwThreads) {
-        s_tuo[k] = a.u.tuo[k];
+        L.tuo[k] = a.u.tuo[k];
+        L.r0[k] = a.u.row_offsets[k];
         if (k < T) {
             float v[kAbsmaxSlots];
 #pragma unroll
@@ -134,7 +185,8 @@ __global__ __launch_bounds__(kEwThreads) void quant_update_kernel(QuantUpdateArg
 #pragma unroll
             for (int q = 0; q < kAbsmaxSlots; ++q) m = fmaxf(m, v[q]);
             const float gs = scale_from_absmax(m, 127.0f);
-            s_gs[k] = gs;
+            L.gs[k] = Scale(gs);
+            if (a.u.packed) L.ws[k] = Scale(a.u.w_scale[k]);
             if (blockIdx.x == 0) {
                 a.g_absmax[k] = m;
                 a.g_scale_out[k] = gs;
@@ -142,70 +194,57 @@ __global__ __launch_bounds__(kEwThreads) void quant_update_kernel(QuantUpdateArg
         }
     }
     __syncthreads();
-    int64_t U = s_tuo[T];
-    U = U < 0 ? 0 : (U > a.u.capacity ? a.u.capacity : U);
-    const int D = a.u.D, q4 = D >> 2;
-    const int64_t total = U * q4;
-    const int64_t nthreads = (int64_t)gridDim.x * kEwThreads;
-    for (int64_t e0 = (int64_t)blockIdx.x * kEwThreads + threadIdx.x; e0 < total; e0 += nthreads * kQuPerThread) {
+    const unsigned total = clamp_u(L.tuo, T, a.u.capacity) * a.u.by_q4.d;
+    const int q4 = (int)a.u.by_q4.d;
+    const unsigned nthreads = gridDim.x * kEwThreads;
+    // e0 + 3 * nthreads < 2^32: total < 2^31 and nthreads <= 2^19 (host)
+    for (unsigned e0 = blockIdx.x * kEwThreads + threadIdx.x; e0 < total; e0 += nthreads * kQuPerThread) {
         // 1. gradient values and row ids of all elements of the batch
+        RowElem r[kQuPerThread];
         float4 v[kQuPerThread];
         int64_t row[kQuPerThread];
-        int tab[kQuPerThread], c4[kQuPerThread];
 #pragma unroll
         for (int k = 0; k < kQuPerThread; ++k) {
-            const int64_t e = e0 + k * nthreads;
+            const unsigned e = e0 + k * nthreads;
             row[k] = -1;
-            tab[k] = 0;
-            c4[k] = 0;
             v[k] = make_float4(0.f, 0.f, 0.f, 0.f);
+            r[k] = row_elem(e < total ? e : 0u, a.u.by_q4, L, T);
             if (e < total) {
-                const int64_t u = e / q4;
-                c4[k] = (int)(e - u * q4);
-                tab[k] = table_of(s_tuo, T, (int)u);
                 v[k] = reinterpret_cast<const float4 *>(a.values)[e];
-                row[k] = a.u.uniq_rows[u];
+                row[k] = a.u.uniq_rows[r[k].u];
             }
         }
         // 2. their master weights
         float4 w[kQuPerThread];
 #pragma unroll
         for (int k = 0; k < kQuPerThread; ++k) {
-            const int64_t e = e0 + k * nthreads;
+            const unsigned e = e0 + k * nthreads;
             w[k] = make_float4(0.f, 0.f, 0.f, 0.f);
             if (e < total) {
-                const int64_t r0 = a.u.row_offsets[tab[k]], r1 = a.u.row_offsets[tab[k] + 1];
+                const int64_t r0 = L.r0[r[k].t], r1 = L.r0[r[k].t + 1];
                 if (row[k] < 0 || row[k] >= r1 - r0) {
-                    if (c4[k] == 0) report(DQRM_ERR_INDEX_OUT_OF_RANGE, tab[k], row[k]);
+                    if (r[k].c4 == 0) report(DQRM_ERR_INDEX_OUT_OF_RANGE, r[k].t, row[k]);
                     row[k] = -1;
                 } else {
-                    row[k] += r0;
-                    w[k] = reinterpret_cast<const float4 *>(a.u.master + row[k] * D)[c4[k]];
+                    row[k] = (r0 + row[k]) * q4 + r[k].c4; // float4 index into the master table
+                    w[k] = reinterpret_cast<const float4 *>(a.u.master)[row[k]];
                 }
             }
         }
         // 3. quantise, store the codes, step, re-encode
 #pragma unroll
         for (int k = 0; k < kQuPerThread; ++k) {
-            const int64_t e = e0 + k * nthreads;
+            const unsigned e = e0 + k * nthreads;
             if (e >= total) continue;
-            const float gs = s_gs[tab[k]];
-            const char4 c = make_char4((signed char)(int)int8_code(v[k].x, gs), (signed char)(int)int8_code(v[k].y, gs),
-                                       (signed char)(int)int8_code(v[k].z, gs), (signed char)(int)int8_code(v[k].w, gs));
-            reinterpret_cast<char4 *>(a.gq_out)[e] = c;
+            const Scale gs = L.gs[r[k].t];
+            // the scale comes from the maximum of these very values: no quotient beyond 127 (1 + 2^-23)
+            const int c0 = int8_code_fresh(v[k].x, gs), c1 = int8_code_fresh(v[k].y, gs);
+            const int c2 = int8_code_fresh(v[k].z, gs), c3 = int8_code_fresh(v[k].w, gs);
+            reinterpret_cast<unsigned *>(a.gq_out)[e] = pack_bytes(c0, c1, c2, c3);
             if (row[k] < 0) continue;
-            // g = g_scale * code; w <- w - lr * g, each operation rounded on its own
-            float4 x = w[k];
-            x.x = x.x - a.u.lr * (gs * (float)c.x);
-            x.y = x.y - a.u.lr * (gs * (float)c.y);
-            x.z = x.z - a.u.lr * (gs * (float)c.z);
-            x.w = x.w - a.u.lr * (gs * (float)c.w);
-            reinterpret_cast<float4 *>(a.u.master + row[k] * D)[c4[k]] = x;
-            if (a.u.packed) {
-                const float ws = a.u.w_scale[tab[k]];
-                const unsigned p = pack4(int4_code(x.x, ws), int4_code(x.y, ws), int4_code(x.z, ws), int4_code(x.w, ws));
-                *reinterpret_cast<unsigned short *>(a.u.packed + row[k] * (D >> 1) + c4[k] * 2) = (unsigned short)p;
-            }
+            const float4 x = sgd_step(w[k], c0, c1, c2, c3, gs.s, a.u.lr);
+            reinterpret_cast<float4 *>(a.u.master)[row[k]] = x;
+            if (a.u.packed) reinterpret_cast<unsigned short *>(a.u.packed)[row[k]] = encode4(x, L.ws[r[k].t]);
         }
     }
 }
@@ -265,17 +304,17 @@ __global__ __launch_bounds__(kEwThreads) void pack_int4_kernel(const float *__re
                                                                uint8_t *__restrict__ packed)
 {
     __shared__ int64_t s_ro[DQRM_MAX_TABLES + 1];
-    __shared__ float s_ws[DQRM_MAX_TABLES];
+    __shared__ Scale s_ws[DQRM_MAX_TABLES];
     for (int k = threadIdx.x; k <= T; k += kEwThreads) {
         s_ro[k] = row_offsets[k];
-        if (k < T) s_ws[k] = w_scale[k];
+        if (k < T) s_ws[k] = Scale(w_scale[k]);
     }
     __syncthreads();
     const int q8 = D >> 3; // groups of 8 elements per row -> 4 packed bytes each
     const int64_t total = s_ro[T] * q8;
     int cur_t = -1;
     int64_t cur_end = -1;
-    float ws = 1.0f;
+    Scale ws(1.0f);
     for (int64_t e = (int64_t)blockIdx.x * kEwThreads + threadIdx.x; e < total; e += (int64_t)gridDim.x * kEwThreads) {
         if (e >= cur_end) {
             cur_t = table_of(s_ro, T, e / q8);

@@ -75,7 +75,7 @@ int32_t check_batch(const dqrm_tables_t *tb, const int64_t *indices, const int64
 // ---- workspace layout of dqrm_embbag_bwd -------------------------------------
 struct WsLayout {
     size_t off_table_base, off_table_nuniq, off_table_nchunk, off_table_nsingle, off_totals, off_bag_of_pos, off_sorted_bag,
-        off_chunk_local, off_single_local, off_chunk_desc, off_single_desc, off_partial_full, off_partial_last, off_absmax_slots, total;
+        off_chunk_local, off_single_local, off_chunk_desc, off_chunk_bags, off_single_desc, off_partial_full, off_partial_last, off_absmax_slots, total;
 };
 
 size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
@@ -100,6 +100,7 @@ WsLayout ws_layout(int32_t T, int32_t D, int64_t N)
     L.off_chunk_local = take(n * 16);
     L.off_single_local = take(n * 16);
     L.off_chunk_desc = take(n * 16);
+    L.off_chunk_bags = take((n / 2 + 1) * DQRM_SEG_CHUNK * sizeof(int));
     L.off_single_desc = take(n * 16);
     L.off_partial_full = take(slots * (size_t)D * sizeof(float));
     L.off_partial_last = take(slots * (size_t)D * sizeof(float));
@@ -122,6 +123,7 @@ dqrm::BwdWs ws_views(void *workspace, const WsLayout &L)
     w.chunk_local = reinterpret_cast<int4 *>(b + L.off_chunk_local);
     w.single_local = reinterpret_cast<int4 *>(b + L.off_single_local);
     w.chunk_desc = reinterpret_cast<int4 *>(b + L.off_chunk_desc);
+    w.chunk_bags = reinterpret_cast<int *>(b + L.off_chunk_bags);
     w.single_desc = reinterpret_cast<int4 *>(b + L.off_single_desc);
     w.partial_full = reinterpret_cast<float *>(b + L.off_partial_full);
     w.partial_last = reinterpret_cast<float *>(b + L.off_partial_last);

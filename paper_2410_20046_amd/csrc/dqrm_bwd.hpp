@@ -51,6 +51,7 @@ struct BwdWs {
     int4 *chunk_local;        // [N]   table-local chunk lists (table t's start at its first lookup position)
     int4 *single_local;       // [N]   table-local lists of singles: {sorted position, bag, segment, row}
     int4 *chunk_desc;         // [N]   dense chunk list over all tables, as the summing kernels read it
+    int *chunk_bags;          // [N/2 + 1][32] bags of chunk c's lookups, so that they can be read before its descriptor
     int4 *single_desc;        // [N]   dense list of singles: {bag, global segment, table, -}
     int *totals;              // [3]   chunks, segments, singles
     float *partial_full;      // [(N/32 + 2) * D] partial of a full chunk of a long segment
@@ -570,6 +571,14 @@ __global__ __launch_bounds__(kSegThreads) void dedupe_finish_kernel(DedupeArgs a
         }
         a.ws.chunk_desc[c] = make_int4(d.x, d.y, j, t);
     }
+    // the bags of chunk c's lookups at a place that depends on c alone (a chunk has at least two lookups,
+    // so there are at most N / 2 chunks): DQRM_SEG_CHUNK consecutive threads per chunk
+    for (int64_t w = first; w < (int64_t)C * DQRM_SEG_CHUNK; w += step) {
+        const int c = (int)(w / DQRM_SEG_CHUNK), i = (int)(w % DQRM_SEG_CHUNK);
+        const int t = table_of(s_tco, T, c);
+        const int4 d = a.ws.chunk_local[s_base[t] + (c - s_tco[t])];
+        if (i < desc_len(d)) a.ws.chunk_bags[w] = a.ws.sorted_bag[d.x + i];
+    }
     for (int c = first; c < S; c += step) {
         const int t = table_of(s_tso, T, c);
         const int4 d = a.ws.single_local[s_base[t] + (c - s_tso[t])]; // {sorted position, bag, segment, row}
@@ -629,21 +638,28 @@ struct BlockAbsmax {
     }
 };
 
+// entries of a chunk's bag list that each lane of a group of g lanes holds
+constexpr int kChunkIdsPerLane(int g) { return (DQRM_SEG_CHUNK + g - 1) / g; }
+
+// The chunk's bag list: each lane fetches its share once (the whole 32-entry record, whatever the chunk's
+// length: the list sits at a place known from the chunk's index, so no descriptor is needed to ask for it).
+template <int G>
+__device__ __forceinline__ void load_chunk_bags(const SegArgs &a, int c, int lg, int (&my_bags)[kChunkIdsPerLane(G)])
+{
+    const int *bags = a.ws.chunk_bags + (int64_t)c * DQRM_SEG_CHUNK;
+#pragma unroll
+    for (int q = 0; q < kChunkIdsPerLane(G); ++q) {
+        const int i = q * G + lg;
+        my_bags[q] = i < DQRM_SEG_CHUNK ? bags[i] : 0;
+    }
+}
+
 // Sum of one chunk: its gradient rows, left to right.
 template <int G>
-__device__ __forceinline__ float4 sum_chunk(const SegArgs &a, int gstart, int len, int lg, int leader, bool col_ok,
-                                            const float *g0, int64_t tD)
+__device__ __forceinline__ float4 sum_chunk(const SegArgs &a, const int (&my_bags)[kChunkIdsPerLane(G)], int len, int lg,
+                                            int leader, bool col_ok, const float *g0, int64_t tD)
 {
-    // bag of every contribution: each lane fetches its share of the chunk's bag
-    // list once, the group then passes them round with shuffles
-    const int *bags = a.ws.sorted_bag + gstart;
-    constexpr int kIdsPerLane = (DQRM_SEG_CHUNK + G - 1) / G;
-    int my_bags[kIdsPerLane];
-#pragma unroll
-    for (int q = 0; q < kIdsPerLane; ++q) {
-        const int i = q * G + lg;
-        my_bags[q] = (i < len) ? bags[i] : 0;
-    }
+    // the group passes the bags round with shuffles
     float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
     constexpr int kBatch = kSegBatch;
 #pragma unroll
@@ -696,13 +712,18 @@ __global__ __launch_bounds__(kSegThreads) void chunk_sum_kernel(SegArgs a)
     int s0 = (ngroups - 1 - gi) * kSinglesPerGroup;
     int4 d = make_int4(0, 0, 0, 0);
     int4 sd[kSinglesPerGroup];
-    if (c < cap) d = a.ws.chunk_desc[c];
+    int my_bags[kChunkIdsPerLane(G)] = {};
+    const int cap_chunks = cap / 2; // a chunk has at least two lookups
+    if (c < cap_chunks) {
+        d = a.ws.chunk_desc[c];
+        load_chunk_bags<G>(a, c, lg, my_bags);
+    }
 #pragma unroll
     for (int k = 0; k < kSinglesPerGroup; ++k) {
         sd[k] = make_int4(0, 0, 0, 0);
         if (s0 + k < cap) sd[k] = a.ws.single_desc[s0 + k];
     }
-    const int C = min(a.ws.totals[0], cap), S = min(a.ws.totals[2], cap);
+    const int C = min(a.ws.totals[0], cap_chunks), S = min(a.ws.totals[2], cap);
     __syncthreads(); // s_max is cleared
 
     // ---- singles: all rows of the batch are requested before any is stored
@@ -737,12 +758,16 @@ __global__ __launch_bounds__(kSegThreads) void chunk_sum_kernel(SegArgs a)
     while (c < C) {
         const int c_next = c + ngroups;
         int4 d_next = make_int4(0, 0, 0, 0);
-        if (c_next < C) d_next = a.ws.chunk_desc[c_next];
+        int next_bags[kChunkIdsPerLane(G)] = {};
+        if (c_next < C) {
+            d_next = a.ws.chunk_desc[c_next];
+            load_chunk_bags<G>(a, c_next, lg, next_bags);
+        }
         int len = desc_len(d);
         len = len > DQRM_SEG_CHUNK ? DQRM_SEG_CHUNK : len;
         const int nchunks = desc_nchunks(d), kchunk = desc_kchunk(d);
         const int t = d.w;
-        const float4 acc = sum_chunk<G>(a, d.x, len, lg, leader, col_ok, a.grad_out + (int64_t)t * D + col, tD);
+        const float4 acc = sum_chunk<G>(a, my_bags, len, lg, leader, col_ok, a.grad_out + (int64_t)t * D + col, tD);
         if (nchunks > 1) {
             // chunk of a long segment: store the partial sum for the combine kernel.
             // Full chunks are disjoint runs of DQRM_SEG_CHUNK sorted positions, so
@@ -758,6 +783,8 @@ __global__ __launch_bounds__(kSegThreads) void chunk_sum_kernel(SegArgs a)
         }
         c = c_next;
         d = d_next;
+#pragma unroll
+        for (int q = 0; q < kChunkIdsPerLane(G); ++q) my_bags[q] = next_bags[q];
     }
     amax.flush(a.ws.absmax_slots, T);
 }

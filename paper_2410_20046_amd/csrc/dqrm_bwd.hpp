@@ -655,24 +655,36 @@ __device__ __forceinline__ void load_chunk_bags(const SegArgs &a, int c, int lg,
 }
 
 // Sum of one chunk: its gradient rows, left to right.
+//
+// Every load of a batch is issued before the first is used, and none sits under a
+// per-lane branch: a lane without a row at position i reads the row of bag 0
+// instead and leaves it out of the sum.  (With loads under divergent branches the
+// compiler cannot count the loads in flight and waits for all of them before each
+// next one.)  `wave_len` is the longest chunk among the wave's groups: batches
+// and quarters of batches beyond it are skipped by the whole wave.
 template <int G>
-__device__ __forceinline__ float4 sum_chunk(const SegArgs &a, const int (&my_bags)[kChunkIdsPerLane(G)], int len, int lg,
-                                            int leader, bool col_ok, const float *g0, int64_t tD)
+__device__ __forceinline__ float4 sum_chunk(const int (&my_bags)[kChunkIdsPerLane(G)], int len, int wave_len, int leader,
+                                            const float *g0, unsigned tD)
 {
-    // the group passes the bags round with shuffles
     float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
-    constexpr int kBatch = kSegBatch;
+    constexpr int kBatch = kSegBatch, kQuarter = kBatch / 4;
 #pragma unroll
     for (int i0 = 0; i0 < DQRM_SEG_CHUNK; i0 += kBatch) {
-        if (i0 < len) {
+        if (i0 < wave_len) {
             float4 g[kBatch];
 #pragma unroll
-            for (int q = 0; q < kBatch; ++q) {
-                const int i = i0 + q;
-                g[q] = make_float4(0.f, 0.f, 0.f, 0.f);
-                if (i < len) {
-                    const int b = __shfl(my_bags[i / G], leader + (i % G), kWave);
-                    if (col_ok) g[q] = *reinterpret_cast<const float4 *>(g0 + (int64_t)b * tD);
+            for (int q0 = 0; q0 < kBatch; q0 += kQuarter) {
+                if (q0 == 0 || i0 + q0 < wave_len) {
+#pragma unroll
+                    for (int q = q0; q < q0 + kQuarter; ++q) {
+                        const int i = i0 + q;
+                        int b = __shfl(my_bags[i / G], leader + (i % G), kWave); // the group passes the bags round
+                        b = i < len ? b : 0;
+                        g[q] = *reinterpret_cast<const float4 *>(g0 + (uint64_t)(unsigned)b * tD);
+                    }
+                } else {
+#pragma unroll
+                    for (int q = q0; q < q0 + kQuarter; ++q) g[q] = make_float4(0.f, 0.f, 0.f, 0.f);
                 }
             }
 #pragma unroll
@@ -688,6 +700,8 @@ __device__ __forceinline__ float4 sum_chunk(const SegArgs &a, const int (&my_bag
 // Lane groups take the chunks one each, in order, and the singles (rows looked up
 // once: a plain copy of one gradient row) kSinglesPerGroup at a time, dealt from
 // the other end of the grid so that groups without a chunk do the copying.
+// The loops run as long as any group of the wave has work; a group without work
+// goes through the motions on bag 0 of table 0 and stores nothing.
 constexpr int kSinglesPerGroup = 4;
 
 template <int G>
@@ -702,9 +716,12 @@ __global__ __launch_bounds__(kSegThreads) void chunk_sum_kernel(SegArgs a)
     constexpr int kGroups = kSegThreads / G;
     const int col = lg * 4;
     const bool col_ok = col < D;
-    const int leader = (threadIdx.x & (kWave - 1)) & ~(G - 1);
-    const int64_t tD = (int64_t)T * D;
+    const float *grad_col = a.grad_out + (col_ok ? col : 0); // lanes beyond the row read column 0 and store nothing
+    const int lane = threadIdx.x & (kWave - 1);
+    const int leader = lane & ~(G - 1);
+    const unsigned tD = (unsigned)T * (unsigned)D;
     const int cap = (int)a.N; // both lists have N slots, so descriptors may be requested before the counts are known
+    const int cap_chunks = cap / 2; // a chunk has at least two lookups
     const int ngroups = (int)gridDim.x * kGroups;
     const int gi = (int)blockIdx.x * kGroups + (int)threadIdx.x / G;
 
@@ -713,73 +730,74 @@ __global__ __launch_bounds__(kSegThreads) void chunk_sum_kernel(SegArgs a)
     int4 d = make_int4(0, 0, 0, 0);
     int4 sd[kSinglesPerGroup];
     int my_bags[kChunkIdsPerLane(G)] = {};
-    const int cap_chunks = cap / 2; // a chunk has at least two lookups
     if (c < cap_chunks) {
         d = a.ws.chunk_desc[c];
         load_chunk_bags<G>(a, c, lg, my_bags);
     }
 #pragma unroll
-    for (int k = 0; k < kSinglesPerGroup; ++k) {
-        sd[k] = make_int4(0, 0, 0, 0);
-        if (s0 + k < cap) sd[k] = a.ws.single_desc[s0 + k];
-    }
+    for (int k = 0; k < kSinglesPerGroup; ++k) sd[k] = a.ws.single_desc[min(s0 + k, cap - 1)];
     const int C = min(a.ws.totals[0], cap_chunks), S = min(a.ws.totals[2], cap);
     __syncthreads(); // s_max is cleared
 
-    // ---- singles: all rows of the batch are requested before any is stored
 #if defined(DQRM_EXP_SKIP_SINGLES)
     s0 = S;
 #endif
 #if defined(DQRM_EXP_SKIP_CHUNKS)
     c = C;
 #endif
-    while (s0 < S) {
+    // ---- singles: the wave's last group holds the lowest positions
+    while (__builtin_amdgcn_readlane(s0, kWave - 1) < S) {
         float4 r[kSinglesPerGroup];
+        int4 cur[kSinglesPerGroup];
 #pragma unroll
         for (int k = 0; k < kSinglesPerGroup; ++k) {
-            r[k] = make_float4(0.f, 0.f, 0.f, 0.f);
-            if (s0 + k < S && col_ok)
-                r[k] = *reinterpret_cast<const float4 *>(a.grad_out + (int64_t)sd[k].z * D + col + (int64_t)sd[k].x * tD);
+            cur[k] = s0 + k < S ? sd[k] : make_int4(0, 0, 0, 0);
+            r[k] = *reinterpret_cast<const float4 *>(grad_col + (uint64_t)(unsigned)cur[k].x * tD +
+                                                     (unsigned)cur[k].z * (unsigned)D);
         }
+        const int s_next = s0 + ngroups * kSinglesPerGroup;
+#pragma unroll
+        for (int k = 0; k < kSinglesPerGroup; ++k) sd[k] = a.ws.single_desc[min(s_next + k, cap - 1)];
 #pragma unroll
         for (int k = 0; k < kSinglesPerGroup; ++k) {
             if (s0 + k < S && col_ok) {
-                *reinterpret_cast<float4 *>(a.values + (int64_t)sd[k].y * D + col) = r[k];
-                amax.add(sd[k].z, f4_absmax(r[k]));
+                *reinterpret_cast<float4 *>(a.values + (int64_t)cur[k].y * D + col) = r[k];
+                amax.add(cur[k].z, f4_absmax(r[k]));
             }
         }
-        s0 += ngroups * kSinglesPerGroup;
-#pragma unroll
-        for (int k = 0; k < kSinglesPerGroup; ++k)
-            if (s0 + k < S) sd[k] = a.ws.single_desc[s0 + k];
+        s0 = s_next;
     }
 
-    // ---- chunks
-    while (c < C) {
+    // ---- chunks: the wave's first group holds the lowest index
+    while (__builtin_amdgcn_readfirstlane(c) < C) {
         const int c_next = c + ngroups;
         int4 d_next = make_int4(0, 0, 0, 0);
         int next_bags[kChunkIdsPerLane(G)] = {};
-        if (c_next < C) {
-            d_next = a.ws.chunk_desc[c_next];
-            load_chunk_bags<G>(a, c_next, lg, next_bags);
+        if (__builtin_amdgcn_readfirstlane(c_next) < C) { // whole wave or none; groups past C - 1 read slots that exist
+            d_next = a.ws.chunk_desc[min(c_next, cap_chunks - 1)];
+            load_chunk_bags<G>(a, min(c_next, cap_chunks - 1), lg, next_bags);
         }
-        int len = desc_len(d);
+        const bool live = c < C;
+        int len = live ? desc_len(d) : 0;
         len = len > DQRM_SEG_CHUNK ? DQRM_SEG_CHUNK : len;
+        const int wave_len = __builtin_amdgcn_readfirstlane(wave_max_int(len));
         const int nchunks = desc_nchunks(d), kchunk = desc_kchunk(d);
-        const int t = d.w;
-        const float4 acc = sum_chunk<G>(a, my_bags, len, lg, leader, col_ok, a.grad_out + (int64_t)t * D + col, tD);
-        if (nchunks > 1) {
-            // chunk of a long segment: store the partial sum for the combine kernel.
-            // Full chunks are disjoint runs of DQRM_SEG_CHUNK sorted positions, so
-            // (position / DQRM_SEG_CHUNK) names them uniquely; the last chunk of a
-            // segment is filed under the slot of the segment's first chunk.
-            const int gpos = d.x - kchunk * DQRM_SEG_CHUNK; // sorted position of the segment's head
-            float *pslot = (kchunk == nchunks - 1) ? a.ws.partial_last + (int64_t)(gpos / DQRM_SEG_CHUNK) * D
-                                                   : a.ws.partial_full + (int64_t)(d.x / DQRM_SEG_CHUNK) * D;
-            if (col_ok) *reinterpret_cast<float4 *>(pslot + col) = acc;
-        } else if (col_ok) {
-            *reinterpret_cast<float4 *>(a.values + (int64_t)d.z * D + col) = acc;
-            amax.add(t, f4_absmax(acc));
+        const int t = live ? d.w : 0;
+        const float4 acc = sum_chunk<G>(my_bags, len, wave_len, leader, grad_col + (unsigned)t * (unsigned)D, tD);
+        if (live && col_ok) {
+            if (nchunks > 1) {
+                // chunk of a long segment: store the partial sum for the combine kernel.
+                // Full chunks are disjoint runs of DQRM_SEG_CHUNK sorted positions, so
+                // (position / DQRM_SEG_CHUNK) names them uniquely; the last chunk of a
+                // segment is filed under the slot of the segment's first chunk.
+                const int gpos = d.x - kchunk * DQRM_SEG_CHUNK; // sorted position of the segment's head
+                float *pslot = (kchunk == nchunks - 1) ? a.ws.partial_last + (int64_t)(gpos / DQRM_SEG_CHUNK) * D
+                                                       : a.ws.partial_full + (int64_t)(d.x / DQRM_SEG_CHUNK) * D;
+                *reinterpret_cast<float4 *>(pslot + col) = acc;
+            } else {
+                *reinterpret_cast<float4 *>(a.values + (int64_t)d.z * D + col) = acc;
+                amax.add(t, f4_absmax(acc));
+            }
         }
         c = c_next;
         d = d_next;

@@ -70,10 +70,11 @@ def main():
                     help="full DQRM train step (use with --workload kaggle): dqrm_dense_step (MLPs 13-512-256-64-16 / "
                          "367-512-256-1, interaction, BCE, backward, SGD) runs between the tables' forward and "
                          "backward and produces grad_out")
-    ap.add_argument("--overlap", default="pipeline", choices=["none", "fwd", "pipeline", "ahead", "group"],
+    ap.add_argument("--overlap", default="ahead", choices=["none", "fwd", "pipeline", "pipeline2", "ahead", "group"],
                     help="where dqrm_dedupe (needs only the indices) runs: none = in line on the one stream; "
                          "fwd = on a second stream beside the same step's forward; pipeline = on a second stream, "
-                         "one step ahead (double-buffered workspace); ahead = in line on the one stream, but for the "
+                         "one step ahead (double-buffered workspace); pipeline2 = two steps ahead, alternating between two "
+                         "side streams; ahead = in line on the one stream, but for the "
                          "next --ahead batches in one dqrm_dedupe_multi launch (a table's sort fills one CU, so several "
                          "batches fill the chip; the data loader has their indices already); group = that launch on the "
                          "second stream, one group of --ahead batches ahead, so the streams meet once per group")
@@ -129,7 +130,7 @@ def main():
     torch.cuda.synchronize()
 
     side = torch.cuda.Stream()  # default priority
-    nbuf = {"pipeline": 2, "ahead": args.ahead, "group": 2 * args.ahead}.get(args.overlap, 1)
+    nbuf = {"pipeline": 2, "pipeline2": 4, "ahead": args.ahead, "group": 2 * args.ahead}.get(args.overlap, 1)
     dup = lambda x: [x] + [torch.empty_like(x) for _ in range(nbuf - 1)]
     wss, sps, urs, sos = dup(bufs.workspace), dup(bufs.sorted_pos), dup(bufs.uniq_rows), dup(bufs.seg_offsets)
     tuos, nus = dup(bufs.table_uniq_offsets), dup(bufs.num_unique)
@@ -137,12 +138,15 @@ def main():
     ev_update = [torch.cuda.Event() for _ in range(nbuf)]   # last reader (the update) of buffer i finished
     batch_of = lambda k: (idx_d[k % args.pool], off_d[k % args.pool])
 
-    def dedupe_on_side(k):
+    side2 = torch.cuda.Stream()  # default priority; pipeline2 alternates between the two side streams
+
+    def dedupe_on_side(k, stream=None):
+        stream = stream or side
         i = k % nbuf
-        side.wait_event(ev_update[i])  # the buffer's previous reader (no-op before the first record)
+        stream.wait_event(ev_update[i])  # the buffer's previous reader (no-op before the first record)
         ix, of = batch_of(k)
-        dq.dqrm_dedupe(tables, ix, of, B, sps[i], urs[i], sos[i], tuos[i], nus[i], wss[i], stream=side)
-        ev_dedupe[i].record(side)
+        dq.dqrm_dedupe(tables, ix, of, B, sps[i], urs[i], sos[i], tuos[i], nus[i], wss[i], stream=stream)
+        ev_dedupe[i].record(stream)
 
     dense = None
     if args.dense:
@@ -239,6 +243,26 @@ def main():
                 forward(k, ix, of)
                 dq.dqrm_dedupe(tables, ix, of, B, sps[0], urs[0], sos[0], tuos[0], nus[0], wss[0])
                 rest_of_step(k, 0)
+            return
+        if args.overlap == "pipeline2":
+            # two steps ahead, alternating between two side streams: a dedupe has two step times to finish
+            sides = [side, side2]
+            side.wait_stream(main)
+            side2.wait_stream(main)
+            dedupe_on_side(k0, sides[k0 % 2])
+            if n > 1:
+                dedupe_on_side(k0 + 1, sides[(k0 + 1) % 2])
+            for k in range(k0, k0 + n):
+                ix, of = batch_of(k)
+                i = k % nbuf
+                forward(k, ix, of)
+                if k + 2 < k0 + n:
+                    dedupe_on_side(k + 2, sides[k % 2])
+                main.wait_event(ev_dedupe[i])
+                rest_of_step(k, i)
+                ev_update[i].record(main)
+            main.wait_stream(side)
+            main.wait_stream(side2)
             return
         side.wait_stream(main)  # everything enqueued so far is visible to the side stream
         if args.overlap == "pipeline":

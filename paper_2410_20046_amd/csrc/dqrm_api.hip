@@ -258,16 +258,17 @@ int32_t dqrm_embbag_fwd(const dqrm_tables_t *tables, const int64_t *indices, con
     a.T = tables->num_tables;
     a.B = batch;
     a.D = tables->dim;
-    a.num_bags = (int64_t)a.T * a.B;
     a.no_rows = tables->row_offsets_host[a.T] <= 0;
+    a.tile_t = a.T < dqrm::kFwdTileT ? a.T : dqrm::kFwdTileT;
 
     const int G = pow2ceil(a.D / 4);
-    const int64_t blocks = (a.num_bags + dqrm::kFwdTile - 1) / dqrm::kFwdTile;
     hipStream_t st = static_cast<hipStream_t>(stream);
+    const dim3 grid((unsigned)((a.B + dqrm::kFwdTileB - 1) / dqrm::kFwdTileB),
+                    (unsigned)((a.T + a.tile_t - 1) / a.tile_t));
     if (mode == DQRM_FWD_PACKED)
-        launch_fwd<true>(G, dim3((unsigned)blocks), st, a);
+        launch_fwd<true>(G, grid, st, a);
     else
-        launch_fwd<false>(G, dim3((unsigned)blocks), st, a);
+        launch_fwd<false>(G, grid, st, a);
     DQRM_HIP_CHECK(hipGetLastError());
     return DQRM_OK;
 }

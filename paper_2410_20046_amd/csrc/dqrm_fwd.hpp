@@ -1,14 +1,18 @@
 // Forward: gather -> INT4 fake-quant -> sum-pool (Sec. 3.1 and Sec. 4.1 of the paper).
 //
-// A workgroup owns kFwdTile consecutive output slots (slot = b * T + t, i.e. a
-// contiguous piece of `out`).  It works in three phases, each one memory round
-// trip deep, so the dependent chain offsets -> index -> row is paid once per
-// workgroup and not once per bag:
-//   A  thread i reads the extent of slot i's bag and the bag's first index,
-//      checks them, and leaves the row address and the table scale in LDS;
-//   B  groups of G = pow2ceil(D/4) lanes walk the slots; lane l of a group owns
-//      columns 4l..4l+3 (one 16-byte access per row).  The first rows of a whole
-//      batch of slots are requested before any is used;
+// A workgroup owns a tile of kFwdTileB consecutive samples x up to kFwdTileT
+// consecutive tables.  The index arrays are table-major (bag = t * B + b), the
+// output is sample-major (slot = b * T + t): with 16 samples per tile every
+// 128-byte line of `offsets` / `indices` is read by one workgroup only, and with
+// all tables in the tile (T <= kFwdTileT) the workgroup's output is one
+// contiguous piece of `out`.  Three phases, each one memory round trip deep, so
+// the dependent chain offsets -> index -> row is paid once per workgroup:
+//   A  one thread per bag (sample fastest, so the reads coalesce) reads the
+//      bag's extent and first index, checks them, and leaves the row's byte
+//      offset, the table scale and the output slot in LDS, filed in output order;
+//   B  groups of G = pow2ceil(D/4) lanes walk the tile in output order; lane l
+//      of a group owns columns 4l..4l+3 (one 16-byte store per row).  The first
+//      rows of a whole batch of slots are requested before any is used;
 //   C  the bag's remaining lookups (none in the usual one-index-per-bag batch)
 //      are added in order, and the pooled row is stored.
 // The per-column sum is the plain left-to-right sum over the bag, so no
@@ -19,15 +23,23 @@
 
 namespace dqrm {
 
-#ifndef DQRM_FWD_TILE
-#define DQRM_FWD_TILE 128
+#ifndef DQRM_FWD_TILE_B
+#define DQRM_FWD_TILE_B 16
+#endif
+#ifndef DQRM_FWD_TILE_T
+#define DQRM_FWD_TILE_T 32
+#endif
+#ifndef DQRM_FWD_THREADS
+#define DQRM_FWD_THREADS 512
 #endif
 #ifndef DQRM_FWD_BATCH
 #define DQRM_FWD_BATCH 16
 #endif
-constexpr int kFwdTile = DQRM_FWD_TILE;   // output slots per workgroup
-constexpr int kFwdThreads = kFwdTile;     // phase A is one slot per thread
-constexpr int kFwdBatch = DQRM_FWD_BATCH; // first rows in flight per lane
+constexpr int kFwdTileB = DQRM_FWD_TILE_B;         // samples per tile
+constexpr int kFwdTileT = DQRM_FWD_TILE_T;         // tables per tile, at most
+constexpr int kFwdSlots = kFwdTileB * kFwdTileT;   // bags per tile, at most
+constexpr int kFwdThreads = DQRM_FWD_THREADS;
+constexpr int kFwdBatch = DQRM_FWD_BATCH;          // first rows in flight per lane
 
 struct FwdArgs {
     const float *master;
@@ -39,8 +51,8 @@ struct FwdArgs {
     float *out;
     int8_t *codes;
     int64_t num_indices;
-    int64_t num_bags; // T * B
     int T, B, D;
+    int tile_t;  // tables per tile: min(T, kFwdTileT); gridDim = (ceil(B / kFwdTileB), ceil(T / tile_t))
     int no_rows; // the tables hold no row at all: nothing may be read from them
 };
 
@@ -75,30 +87,35 @@ template <> struct RowPiece<false> {
     }
 };
 
-// The tile when no bag has more than one lookup (the usual batch): out = 0 + s * q, nothing else to add.
-// A slot without a valid lookup reads row 0 and multiplies by 0; the addition turns a -0 product into the
-// +0 of an empty sum.  WHOLE: all kFwdTile slots exist; otherwise only the first `live` do.
-template <int G, bool PACKED, bool WHOLE>
+// The slots of the tile in output order when no bag has more than one lookup (the usual batch):
+// out = 0 + s * q, nothing else to add.  A slot without a valid lookup reads row 0 and multiplies by 0;
+// the addition turns a -0 product into the +0 of an empty sum.  Slots from `live` on do not exist
+// (samples beyond the batch); their LDS entries read as "no lookup".
+template <int G, bool PACKED>
 __device__ __forceinline__ void fwd_single_lookup_tile(const char *tab, const int64_t *s_off, const Scale *s_scale,
-                                                       const float *s_mul, int grp, float *outp, size_t out_step,
-                                                       int live)
+                                                       const float *s_mul, const int *s_slot, int grp, float *out_col,
+                                                       int D, int live)
 {
     constexpr int kGroups = kFwdThreads / G;
-    constexpr int kIters = kFwdTile / kGroups;
+    constexpr int kIters = (kFwdSlots + kGroups - 1) / kGroups;
     constexpr int kBatch = kIters < kFwdBatch ? kIters : kFwdBatch;
-    for (int k0 = 0; k0 < kIters; k0 += kBatch) {
+    for (int k0 = 0; k0 * kGroups < live; k0 += kBatch) {
         RowPiece<PACKED> piece[kBatch];
 #pragma unroll
-        for (int k = 0; k < kBatch; ++k) piece[k].load(tab + s_off[(k0 + k) * kGroups + grp]);
+        for (int k = 0; k < kBatch; ++k) {
+            const int i = min((k0 + k) * kGroups + grp, kFwdSlots - 1);
+            piece[k].load(tab + s_off[i]);
+        }
 #pragma unroll
         for (int k = 0; k < kBatch; ++k) {
             const int i = (k0 + k) * kGroups + grp;
-            const float m = s_mul[i];
-            const float4 q = piece[k].codes(s_scale[i]);
-            const f32x4 v = {0.f + m * q.x, 0.f + m * q.y, 0.f + m * q.z, 0.f + m * q.w};
-            // `out` is written once and not read again by this library: stream it past the caches
-            if (WHOLE || i < live)
-                __builtin_nontemporal_store(v, reinterpret_cast<f32x4 *>(outp + (size_t)(k0 + k) * out_step));
+            if (i < live) {
+                const float m = s_mul[i];
+                const float4 q = piece[k].codes(s_scale[i]);
+                const f32x4 v = {0.f + m * q.x, 0.f + m * q.y, 0.f + m * q.z, 0.f + m * q.w};
+                // `out` is written once and not read again by this library: stream it past the caches
+                __builtin_nontemporal_store(v, reinterpret_cast<f32x4 *>(out_col + (size_t)(unsigned)s_slot[i] * D));
+            }
         }
     }
 }
@@ -106,43 +123,49 @@ __device__ __forceinline__ void fwd_single_lookup_tile(const char *tab, const in
 template <int G, bool PACKED>
 __global__ __launch_bounds__(kFwdThreads) void embbag_fwd_kernel(FwdArgs a)
 {
-    __shared__ int64_t s_off[kFwdTile]; // byte offset of the first lookup's row in the table (0 if none / invalid)
-    __shared__ int64_t s_beg[kFwdTile]; // position of the bag's first lookup
-    __shared__ int s_len[kFwdTile];     // lookups in the bag
-    __shared__ int s_tab[kFwdTile];
-    __shared__ Scale s_scale[kFwdTile]; // table scale (and its reciprocal)
-    __shared__ float s_mul[kFwdTile];   // table scale, or 0 when the first lookup is absent or invalid
-    __shared__ unsigned char s_ok[kFwdTile]; // the first lookup exists and is in range
-    __shared__ int s_general;           // some bag of the tile has more than one lookup
+    __shared__ int64_t s_off[kFwdSlots]; // byte offset of the first lookup's row in the table (0 if none / invalid)
+    __shared__ int64_t s_beg[kFwdSlots]; // position of the bag's first lookup
+    __shared__ int s_len[kFwdSlots];     // lookups in the bag
+    __shared__ int s_tab[kFwdSlots];
+    __shared__ int s_slot[kFwdSlots];    // output slot b * T + t (below 2^31: checked on the host)
+    __shared__ Scale s_scale[kFwdSlots]; // table scale (and its reciprocal)
+    __shared__ float s_mul[kFwdSlots];   // table scale, or 0 when the first lookup is absent or invalid
+    __shared__ unsigned char s_ok[kFwdSlots]; // the first lookup exists and is in range
+    __shared__ int s_general;            // some bag of the tile has more than one lookup
 
     const int tid = threadIdx.x;
-    const int64_t slot0 = (int64_t)blockIdx.x * kFwdTile;
+    const int b0 = (int)blockIdx.x * kFwdTileB, t0 = (int)blockIdx.y * a.tile_t;
+    const int nb = min(kFwdTileB, a.B - b0), nt = min(a.tile_t, a.T - t0); // samples / tables of this tile
+    const int live = nb * nt;                                              // its slots, a prefix in output order
     const int row_bytes = PACKED ? (a.D >> 1) : a.D * 4;
     if (tid == 0) s_general = 0;
     __syncthreads();
 
-    // ---- phase A: one slot per thread ------------------------------------------
-    {
-        const int64_t o = slot0 + tid;
+    // ---- phase A: one bag per thread, sample fastest ---------------------------
+    for (int s = tid; s < kFwdSlots; s += kFwdThreads) {
+        const int bl = s % kFwdTileB, tl = s / kFwdTileB;
+        const bool exists = bl < nb && tl < nt;
+        // output-order index inside the tile; the entries past `live` are filled with "no lookup"
+        int i = bl * nt + tl;
+        if (!exists) i = tl < nt ? live + (bl - nb) * nt + tl : s;
         int64_t off = 0, beg = 0;
-        int len = 0, t = 0;
+        int len = 0;
+        const int t = exists ? t0 + tl : 0, b = b0 + bl;
         float sc = 1.0f, mul = 0.0f;
         bool ok = false;
-        if (o < a.num_bags) {
-            const unsigned b = (unsigned)o / (unsigned)a.T; // num_bags < 2^31 (checked on the host)
-            t = (int)((unsigned)o - b * (unsigned)a.T);
+        if (exists) {
             const int64_t bag = (int64_t)t * a.B + b;
-            int64_t s = a.offsets[bag], e = a.offsets[bag + 1];
-            if (s < 0 || e > a.num_indices || s > e) {
+            int64_t lo = a.offsets[bag], hi = a.offsets[bag + 1];
+            if (lo < 0 || hi > a.num_indices || lo > hi) {
                 report(DQRM_ERR_BAD_OFFSETS, t, bag);
-                s = e = 0;
+                lo = hi = 0;
             }
-            if (e - s > 0x7fffffff) e = s + 0x7fffffff;
-            beg = s;
-            len = (int)(e - s);
+            if (hi - lo > 0x7fffffff) hi = lo + 0x7fffffff;
+            beg = lo;
+            len = (int)(hi - lo);
             sc = a.w_scale[t];
             if (len > 0) {
-                const int64_t idx = a.indices[s];
+                const int64_t idx = a.indices[lo];
                 const int64_t r0 = a.row_offsets[t], r1 = a.row_offsets[t + 1];
                 if (idx >= 0 && idx < r1 - r0) {
                     off = (r0 + idx) * row_bytes;
@@ -154,44 +177,36 @@ __global__ __launch_bounds__(kFwdThreads) void embbag_fwd_kernel(FwdArgs a)
                 if (len > 1) s_general = 1;
             }
         }
-        s_off[tid] = off;
-        s_beg[tid] = beg;
-        s_len[tid] = len;
-        s_tab[tid] = t;
+        s_off[i] = off;
+        s_beg[i] = beg;
+        s_len[i] = len;
+        s_tab[i] = t;
+        s_slot[i] = exists ? b * a.T + t : 0;
         // the packed rows hold codes already: no quotient, no reciprocal
-        s_scale[tid] = PACKED ? Scale(sc, 0.0f) : Scale(sc);
-        s_mul[tid] = mul;
-        s_ok[tid] = ok;
+        s_scale[i] = PACKED ? Scale(sc, 0.0f) : Scale(sc);
+        s_mul[i] = mul;
+        s_ok[i] = ok;
     }
     __syncthreads();
 
     // ---- phases B and C ------------------------------------------------------------
-    constexpr int kGroups = kFwdThreads / G;   // groups per workgroup
-    constexpr int kIters = kFwdTile / kGroups; // slots per group (= G)
-    constexpr int kBatch = kIters < kFwdBatch ? kIters : kFwdBatch;
+    constexpr int kGroups = kFwdThreads / G; // groups per workgroup
     const int lg = tid & (G - 1);
     const int grp = tid / G;
     const int col = lg * 4;
     if (col >= a.D) return; // lanes beyond the row (D / 4 not a power of two) have nothing to do from here on
     const char *tab = PACKED ? reinterpret_cast<const char *>(a.packed) + (col >> 1)
                              : reinterpret_cast<const char *>(a.master + col);
-    float *outp = a.out + (slot0 + grp) * a.D + col; // slot i = k * kGroups + grp lies k * kGroups rows further
-    const size_t out_step = (size_t)kGroups * a.D;
+    float *out_col = a.out + col;
     const bool general = s_general != 0 || a.codes != nullptr || a.no_rows != 0;
 
     if (!general) {
-        if (slot0 + kFwdTile <= a.num_bags)
-            fwd_single_lookup_tile<G, PACKED, true>(tab, s_off, s_scale, s_mul, grp, outp, out_step, 0);
-        else
-            fwd_single_lookup_tile<G, PACKED, false>(tab, s_off, s_scale, s_mul, grp, outp, out_step,
-                                                     (int)(a.num_bags - slot0));
+        fwd_single_lookup_tile<G, PACKED>(tab, s_off, s_scale, s_mul, s_slot, grp, out_col, a.D, live);
         return;
     }
 
     // general bags: the remaining lookups are added in order; codes are written out when asked for
-    for (int k = 0; k < kIters; ++k) {
-        const int i = k * kGroups + grp;
-        if (slot0 + i >= a.num_bags) break;
+    for (int i = grp; i < live; i += kGroups) {
         const Scale sq = s_scale[i];
         const float s = sq.s;
         const int len = s_len[i];
@@ -227,7 +242,7 @@ __global__ __launch_bounds__(kFwdThreads) void embbag_fwd_kernel(FwdArgs a)
             }
         }
         const f32x4 v = {acc.x, acc.y, acc.z, acc.w};
-        __builtin_nontemporal_store(v, reinterpret_cast<f32x4 *>(outp + (size_t)k * out_step));
+        __builtin_nontemporal_store(v, reinterpret_cast<f32x4 *>(out_col + (size_t)(unsigned)s_slot[i] * a.D));
     }
 }
 

@@ -504,10 +504,23 @@ constexpr int kMaxMlpLayers = 16;
 constexpr int kDenseMaxSplits = 16; // slices of the batch dimension in the weight-gradient products
 
 struct DenseLayout {
-    // activations: bot_act[l] = output of bottom layer l, R = interaction output,
-    // top_act[l] = output of top layer l (the last one is the logit), dz, two gradient buffers
-    size_t bot_act[kMaxMlpLayers], top_act[kMaxMlpLayers], R, dz, gA, gB, partials, total;
+    // activations: bot_act[l] = output of bottom layer l, R = interaction output, top_act[l] = output of top
+    // layer l (the last one is the logit); gradients w.r.t. the layers' pre-activations: bot_dz[l], top_dz[l]
+    // (the last top one is the loss gradient), dR w.r.t. the interaction output; per-layer slices of the split
+    // weight-gradient products: bot_part[l], top_part[l]
+    size_t bot_act[kMaxMlpLayers], top_act[kMaxMlpLayers], R;
+    size_t bot_dz[kMaxMlpLayers], top_dz[kMaxMlpLayers], dR;
+    size_t bot_part[kMaxMlpLayers], top_part[kMaxMlpLayers];
+    size_t total;
 };
+
+// slices of the batch dimension in a weight-gradient product: about eight reduction slabs per slice, at
+// least two (the kernel stores partial tiles only when the reduction is split; a slice may be empty)
+int dense_splits(int batch)
+{
+    int s = (batch + 8 * dqrm::kGemmBK - 1) / (8 * dqrm::kGemmBK);
+    return s < 2 ? 2 : (s > kDenseMaxSplits ? kDenseMaxSplits : s);
+}
 
 int32_t check_dense_model(const dqrm_dense_model_t *m, int32_t batch)
 {
@@ -536,89 +549,89 @@ DenseLayout dense_layout(const dqrm_dense_model_t *m, int32_t batch)
 {
     DenseLayout L{};
     size_t o = 0;
-    size_t widest = 1;
     auto take = [&](size_t floats) {
         size_t at = o;
         o = align_up(o + floats * sizeof(float), 256);
         return at;
     };
+    const size_t splits = (size_t)dense_splits(batch);
     for (int l = 0; l < m->bot_layers; ++l) {
         L.bot_act[l] = take((size_t)batch * m->bot_dims[l + 1]);
-        if ((size_t)m->bot_dims[l + 1] > widest) widest = m->bot_dims[l + 1];
+        L.bot_dz[l] = take((size_t)batch * m->bot_dims[l + 1]);
+        L.bot_part[l] = take(splits * (size_t)m->bot_dims[l + 1] * (m->bot_dims[l] + 1));
     }
     L.R = take((size_t)batch * m->top_dims[0]);
-    if ((size_t)m->top_dims[0] > widest) widest = m->top_dims[0];
+    L.dR = take((size_t)batch * m->top_dims[0]);
     for (int l = 0; l < m->top_layers; ++l) {
         L.top_act[l] = take((size_t)batch * m->top_dims[l + 1]);
-        if ((size_t)m->top_dims[l + 1] > widest) widest = m->top_dims[l + 1];
+        L.top_dz[l] = take((size_t)batch * m->top_dims[l + 1]);
+        L.top_part[l] = take(splits * (size_t)m->top_dims[l + 1] * (m->top_dims[l] + 1));
     }
-    L.dz = take((size_t)batch);
-    L.gA = take((size_t)batch * widest);
-    L.gB = take((size_t)batch * widest);
-    size_t max_params = 1; // largest out * (in + 1) over the layers, for the split weight-gradient products
-    for (int l = 0; l < m->bot_layers; ++l)
-        max_params = std::max(max_params, (size_t)m->bot_dims[l + 1] * (m->bot_dims[l] + 1));
-    for (int l = 0; l < m->top_layers; ++l)
-        max_params = std::max(max_params, (size_t)m->top_dims[l + 1] * (m->top_dims[l] + 1));
-    L.partials = take((size_t)kDenseMaxSplits * max_params);
     L.total = o;
     return L;
 }
 
-// A_I / B_J: whether A's row index i / B's column index j is the contiguous one in memory
-template <bool A_I, bool B_J>
-void launch_gemm(hipStream_t st, const dqrm::GemmArgs &g, int splits)
+// A_RC / B_RC: whether the reduction index is the unit-stride one of A / B in memory (otherwise the 32-wide
+// index i / j must be).  One launch for all problems of the group.
+template <bool A_RC, bool B_RC>
+hipError_t launch_gemm_group(hipStream_t st, dqrm::GemmGroup &grp)
 {
-    dim3 grid((g.N + dqrm::kGemmBN - 1) / dqrm::kGemmBN, (g.M + dqrm::kGemmBM - 1) / dqrm::kGemmBM, splits);
-    hipLaunchKernelGGL((dqrm::gemm_mfma_kernel<A_I, B_J>), grid, dim3(dqrm::kGemmThreads), 0, st, g);
+    int tiles = 0;
+    for (int q = 0; q < grp.count; ++q) {
+        dqrm::GemmArgs &g = grp.p[q];
+        g.tile_begin = tiles;
+        tiles += ((g.M + 31) / 32) * ((g.N + 31) / 32) * g.splits;
+    }
+    grp.total_tiles = tiles;
+    if (tiles == 0) return hipSuccess;
+    hipLaunchKernelGGL((dqrm::gemm_wave_kernel<A_RC, B_RC>), dim3((tiles + dqrm::kGemmWaves - 1) / dqrm::kGemmWaves),
+                       dim3(dqrm::kGemmThreads), 0, st, grp);
+    return hipGetLastError();
 }
 
 // Y[B][out] = act(X[B][in] * W[out][in]^T + b)
-void linear_fwd(hipStream_t st, const float *X, const float *W, const float *b, float *Y, int B, int in, int out,
+hipError_t linear_fwd(hipStream_t st, const float *X, const float *W, const float *b, float *Y, int B, int in, int out,
                 bool relu)
 {
-    dqrm::GemmArgs g{};
+    dqrm::GemmGroup grp{};
+    dqrm::GemmArgs &g = grp.p[0];
+    grp.count = 1;
     g.A = X, g.a_si = in, g.a_sr = 1;
     g.B = W, g.b_sr = 1, g.b_sj = in;
     g.C = Y, g.c_si = out, g.c_sj = 1;
     g.M = B, g.N = out, g.K = in;
-    g.bias = b, g.relu = relu ? 1 : 0, g.k_per_split = in;
-    launch_gemm<false, false>(st, g, 1);
+    g.bias = b, g.relu = relu ? 1 : 0, g.splits = 1, g.k_per_split = in;
+    return launch_gemm_group<true, true>(st, grp);
 }
 
 // dX[B][in] = (dZ[B][out] * W[out][in]) masked by (mask[B][in] > 0)
-void linear_bwd_input(hipStream_t st, const float *dZ, const float *W, const float *mask, float *dX, int B, int in,
+hipError_t linear_bwd_input(hipStream_t st, const float *dZ, const float *W, const float *mask, float *dX, int B, int in,
                       int out)
 {
-    dqrm::GemmArgs g{};
+    dqrm::GemmGroup grp{};
+    dqrm::GemmArgs &g = grp.p[0];
+    grp.count = 1;
     g.A = dZ, g.a_si = out, g.a_sr = 1;
     g.B = W, g.b_sr = in, g.b_sj = 1;
     g.C = dX, g.c_si = in, g.c_sj = 1;
     g.M = B, g.N = in, g.K = out;
-    g.mask = mask, g.k_per_split = out;
-    launch_gemm<false, true>(st, g, 1);
+    g.mask = mask, g.splits = 1, g.k_per_split = out;
+    return launch_gemm_group<true, false>(st, grp);
 }
 
-// W[out][in] -= lr * dZ[B][out]^T * X[B][in];  b[out] -= lr * colsum(dZ).  The product is taken with X
-// extended by a column of ones (its last column is the bias gradient) and the batch dimension cut into
-// slices, one workgroup layer per slice; sgd_from_partials_kernel adds the slices in order.
-void linear_bwd_params(hipStream_t st, const float *dZ, const float *X, float *W, float *b, float *partials, int B,
-                       int in, int out, float lr)
+// One layer's weight-gradient product  [dZ^T * X | dZ^T * 1]  ([out][in + 1], the last column is the bias
+// gradient) with the batch dimension cut into `splits` slices: partials[s][out][in + 1].
+dqrm::GemmArgs weight_grad_problem(const float *dZ, const float *X, float *partials, int B, int in, int out, int splits)
 {
-    int splits = (B + 4 * dqrm::kGemmBK - 1) / (4 * dqrm::kGemmBK); // about four slabs per slice
-    if (splits > kDenseMaxSplits) splits = kDenseMaxSplits;
-    if (splits < 2) splits = 2; // the kernel writes partial tiles only when the reduction is split
     int per = (B + splits - 1) / splits;
     per = (per + dqrm::kGemmBK - 1) / dqrm::kGemmBK * dqrm::kGemmBK;
     dqrm::GemmArgs g{};
     g.A = dZ, g.a_si = 1, g.a_sr = out;
     g.B = X, g.b_sr = in, g.b_sj = 1, g.b_ones_last = 1;
     g.M = out, g.N = in + 1, g.K = B;
+    g.splits = splits; // exactly the slices the workspace holds; slices past the batch come out as zeros
     g.k_per_split = per, g.P = partials;
-    launch_gemm<true, true>(st, g, splits);
-    const long long total = (long long)out * (in + 1);
-    hipLaunchKernelGGL(dqrm::sgd_from_partials_kernel, dim3((unsigned)std::min<long long>((total + 255) / 256, 2048)),
-                       dim3(256), 0, st, partials, splits, out, in, lr, W, b);
+    return g;
 }
 
 } // namespace
@@ -649,7 +662,7 @@ int32_t dqrm_dense_step(const dqrm_dense_model_t *m, int32_t batch, const float 
     // ---- forward
     const float *x = dense_x;
     for (int l = 0; l < m->bot_layers; ++l) {
-        linear_fwd(st, x, m->bot_w[l], m->bot_b[l], F(L.bot_act[l]), B, m->bot_dims[l], m->bot_dims[l + 1], true);
+        DQRM_HIP_CHECK(linear_fwd(st, x, m->bot_w[l], m->bot_b[l], F(L.bot_act[l]), B, m->bot_dims[l], m->bot_dims[l + 1], true));
         x = F(L.bot_act[l]);
     }
     dqrm::InteractArgs ia{};
@@ -657,47 +670,62 @@ int32_t dqrm_dense_step(const dqrm_dense_model_t *m, int32_t batch, const float 
     hipLaunchKernelGGL(dqrm::interact_fwd_kernel, dim3(B), dim3(dqrm::kInterThreads), 0, st, ia);
     x = F(L.R);
     for (int l = 0; l < m->top_layers; ++l) {
-        linear_fwd(st, x, m->top_w[l], m->top_b[l], F(L.top_act[l]), B, m->top_dims[l], m->top_dims[l + 1],
-                   l + 1 < m->top_layers);
+        DQRM_HIP_CHECK(linear_fwd(st, x, m->top_w[l], m->top_b[l], F(L.top_act[l]), B, m->top_dims[l], m->top_dims[l + 1],
+                                  l + 1 < m->top_layers));
         x = F(L.top_act[l]);
     }
-    hipLaunchKernelGGL(dqrm::bce_kernel, dim3(1), dim3(256), 0, st, x, labels, B, F(L.dz), loss);
+    hipLaunchKernelGGL(dqrm::bce_kernel, dim3(1), dim3(256), 0, st, x, labels, B, F(L.top_dz[m->top_layers - 1]), loss);
 
-    // ---- backward (dZ = gradient w.r.t. a layer's pre-activation) + SGD
-    const float *dZ = F(L.dz);
-    float *bufs[2] = {F(L.gA), F(L.gB)};
-    int cur = 0;
+    // ---- backward: the chain of input gradients first (dZ = gradient w.r.t. a layer's pre-activation) ...
     for (int l = m->top_layers - 1; l >= 0; --l) {
         const float *in_act = l > 0 ? F(L.top_act[l - 1]) : F(L.R);
-        float *dX = bufs[cur];
+        float *dX = l > 0 ? F(L.top_dz[l - 1]) : F(L.dR);
         // the input of top layer l > 0 is a ReLU output: mask; the interaction output is not
-        linear_bwd_input(st, dZ, m->top_w[l], l > 0 ? in_act : nullptr, dX, B, m->top_dims[l], m->top_dims[l + 1]);
-        linear_bwd_params(st, dZ, in_act, m->top_w[l], m->top_b[l], F(L.partials), B, m->top_dims[l],
-                          m->top_dims[l + 1], lr);
-        dZ = dX;
-        cur ^= 1;
+        DQRM_HIP_CHECK(linear_bwd_input(st, F(L.top_dz[l]), m->top_w[l], l > 0 ? in_act : nullptr, dX, B,
+                                        m->top_dims[l], m->top_dims[l + 1]));
     }
-    // dZ is now the gradient w.r.t. the interaction output
-    float *dbot = bufs[cur];
     const float *bot_out = F(L.bot_act[m->bot_layers - 1]);
-    ia.dR = dZ, ia.dbot = dbot, ia.demb = grad_emb, ia.bot_mask = bot_out;
+    ia.dR = F(L.dR), ia.dbot = F(L.bot_dz[m->bot_layers - 1]), ia.demb = grad_emb, ia.bot_mask = bot_out;
     hipLaunchKernelGGL(dqrm::interact_bwd_kernel, dim3(B), dim3(dqrm::kInterThreads), 0, st, ia);
-    dZ = dbot;
-    cur ^= 1;
-    for (int l = m->bot_layers - 1; l >= 0; --l) {
-        const float *in_act = l > 0 ? F(L.bot_act[l - 1]) : dense_x;
-        if (l > 0) {
-            float *dX = bufs[cur];
-            linear_bwd_input(st, dZ, m->bot_w[l], in_act, dX, B, m->bot_dims[l], m->bot_dims[l + 1]);
-            linear_bwd_params(st, dZ, in_act, m->bot_w[l], m->bot_b[l], F(L.partials), B, m->bot_dims[l],
-                              m->bot_dims[l + 1], lr);
-            dZ = dX;
-            cur ^= 1;
-        } else {
-            linear_bwd_params(st, dZ, in_act, m->bot_w[l], m->bot_b[l], F(L.partials), B, m->bot_dims[l],
-                              m->bot_dims[l + 1], lr);
-        }
-    }
+    for (int l = m->bot_layers - 1; l > 0; --l)
+        DQRM_HIP_CHECK(linear_bwd_input(st, F(L.bot_dz[l]), m->bot_w[l], F(L.bot_act[l - 1]), F(L.bot_dz[l - 1]), B,
+                                        m->bot_dims[l], m->bot_dims[l + 1]));
+
+    // ... then every layer's weight gradient in one launch and the SGD step in another (the input gradients
+    // above used the weights of before the step)
+    const int splits = dense_splits(B);
+    dqrm::GemmGroup wg{};
+    dqrm::SgdGroup sg{};
+    sg.lr = lr;
+    hipError_t launch_err = hipSuccess;
+    auto flush = [&]() {
+        if (wg.count == 0) return;
+        hipError_t e = launch_gemm_group<false, false>(st, wg);
+        if (e != hipSuccess && launch_err == hipSuccess) launch_err = e;
+        hipLaunchKernelGGL(dqrm::sgd_from_partials_kernel,
+                           dim3((unsigned)std::min<long long>((sg.total + 255) / 256, 2048)), dim3(256), 0, st, sg);
+        e = hipGetLastError();
+        if (e != hipSuccess && launch_err == hipSuccess) launch_err = e;
+        wg.count = 0;
+        sg.count = 0;
+        sg.total = 0;
+    };
+    auto add_layer = [&](const float *dZ, const float *X, float *W, float *b, float *part, int in, int out) {
+        if (wg.count == dqrm::kGemmMaxGroup) flush();
+        const dqrm::GemmArgs g = weight_grad_problem(dZ, X, part, B, in, out, splits);
+        wg.p[wg.count++] = g;
+        dqrm::SgdLayer &s = sg.l[sg.count++];
+        s.P = part, s.W = W, s.b = b, s.S = g.splits, s.out = out, s.in = in, s.elem_begin = sg.total;
+        sg.total += (long long)out * (in + 1);
+    };
+    for (int l = 0; l < m->top_layers; ++l)
+        add_layer(F(L.top_dz[l]), l > 0 ? F(L.top_act[l - 1]) : F(L.R), m->top_w[l], m->top_b[l], F(L.top_part[l]),
+                  m->top_dims[l], m->top_dims[l + 1]);
+    for (int l = 0; l < m->bot_layers; ++l)
+        add_layer(F(L.bot_dz[l]), l > 0 ? F(L.bot_act[l - 1]) : dense_x, m->bot_w[l], m->bot_b[l], F(L.bot_part[l]),
+                  m->bot_dims[l], m->bot_dims[l + 1]);
+    flush();
+    DQRM_HIP_CHECK(launch_err);
     DQRM_HIP_CHECK(hipGetLastError());
     return DQRM_OK;
 }

@@ -14,13 +14,29 @@ typedef float floatx16 __attribute__((ext_vector_type(16)));
 // C(i,j) = epilogue( sum_r A(i,r) * B(r,j) ), all operands addressed with
 // explicit strides so that one kernel serves X*W^T, dY*W and dY^T*X.
 //
-// Workgroup = 4 waves, each owns a 32x32 block of a 64x64 tile of C and feeds
-// v_mfma_f32_32x32x2_f32 from LDS.  The reduction runs in slabs of 64: while the
-// matrix cores work on one slab, the next one is already on its way from HBM
-// into registers (these products are small -- a few hundred workgroups -- so
-// latency, not bandwidth, is what has to be hidden).  With gridDim.z > 1 the
-// reduction is split: slice z covers r in [z*k_per_split, ...) and stores its raw
-// partial tile to P[z][M][N]; a second kernel adds the slices in order.
+// One wave owns a 32x32 tile of C and needs no other wave: it keeps the tile in
+// the 16 accumulator registers of v_mfma_f32_32x32x2_f32 and walks the
+// reduction in slabs of 32.  In a slab, lane l = (h, w) with w = l % 32, h = l / 32
+// holds A(i0 + w, r0 + 16 h + s) and B(r0 + 16 h + s, j0 + w) for s = 0..15 and
+// issues 16 products, the s-th pairing r0 + s (lanes h = 0) with r0 + 16 + s
+// (lanes h = 1): every r of the slab is used once, in an order that is the same
+// for both operands.  The next slab's loads are issued before the current
+// slab's products, so the matrix core works while they are in flight.
+//
+// How an operand's slab reaches that register layout depends on its memory layout:
+//   wide-contiguous (the 32-wide index i or j is the unit-stride one): 16 loads,
+//     each 32 lanes reading 128 consecutive bytes, straight into place;
+//   reduction-contiguous (r is the unit-stride index, as in a row-major X or W read
+//     along its rows): lanes run along r (32 lanes = 128 consecutive bytes of one
+//     row, two rows per load), and the 32x32 slab is turned through a per-wave
+//     piece of LDS.  Nothing assumes an alignment beyond 4 bytes.
+// No load sits under a branch: indices past the edge are clamped and the value is
+// replaced by 0 (or by 1 for the virtual all-ones last column of B).
+//
+// Several products can share one launch (the weight gradients of all layers):
+// the waves are dealt over the tiles of all problems.  With splits > 1 the
+// reduction is cut: slice z covers r in [z*k_per_split, ...) and stores its raw
+// partial tile to P[z][M][N]; sgd_from_partials_kernel adds the slices in order.
 struct GemmArgs {
     const float *A;
     long long a_si, a_sr;
@@ -33,117 +49,222 @@ struct GemmArgs {
     const float *mask; // same addressing as C: result multiplied by (mask > 0), or null
     int relu;          // max(x, 0) after the bias
     int b_ones_last;   // B's last column (j = N-1) is all ones and is not read from memory
-    int k_per_split;   // reduction length per z slice (multiple of kGemmBK), K if not split
-    float *P;          // [gridDim.z][M][N] partial tiles when split
+    int splits;        // slices of the reduction (1: the epilogue above; > 1: partial tiles to P)
+    int k_per_split;   // reduction length per slice (multiple of 32), K if not split
+    float *P;          // [splits][M][N] partial tiles when split
+    int tile_begin;    // first wave-tile of this problem in the launch (filled by the launcher)
+};
+
+constexpr int kGemmMaxGroup = 16;
+struct GemmGroup {
+    GemmArgs p[kGemmMaxGroup];
+    int count, total_tiles;
 };
 
 constexpr int kGemmThreads = 256;
-constexpr int kGemmBM = 64, kGemmBN = 64, kGemmBK = 32;
-constexpr int kGemmLd = kGemmBM + 1;                             // LDS row pitch (floats)
-constexpr int kGemmPerThread = kGemmBM * kGemmBK / kGemmThreads; // 8 elements of each operand per slab
+constexpr int kGemmWaves = kGemmThreads / kWave;
+constexpr int kGemmBK = 32;      // reduction slab
+constexpr int kGemmPitch = 36;   // LDS row pitch of a turned slab (floats): rows stay 16-byte aligned
 
-// A thread's q-th element (q = 0..7) of a 64 (i or j) x 32 (r) operand slab.  CONTIG
-// says whether the 64-wide index is the one that is contiguous in memory; either
-// way consecutive threads walk along the contiguous direction, four elements each.
-template <bool WIDE_CONTIG>
-__device__ __forceinline__ void gemm_slot(int tid, int q, int *wide, int *r)
+struct SlabRegs {
+    float v[16];
+};
+
+// Wide-contiguous operand: element (wide, r) at base[wide * sw + r * sr].  Lane (h, w) reads
+// r = r0 + 16 h + s, s = 0..15, of its own wide index.  SAFE: the wide index was clamped by the caller and r
+// is clamped / zeroed here (edge tiles, the last partial slab); otherwise everything is known to be inside.
+template <bool SAFE>
+__device__ __forceinline__ void slab_load_direct(SlabRegs &x, const float *base, long long sw, long long sr, int wide,
+                                                 int r0, int r_end, int h, bool ones)
 {
-    if (WIDE_CONTIG) {
-        *wide = (tid & 15) * 4 + (q & 3);
-        *r = (tid >> 4) + 16 * (q >> 2);
-    } else {
-        *r = (tid & 7) * 4 + (q & 3);
-        *wide = (tid >> 3) + 32 * (q >> 2);
+    if (!SAFE) {
+        const float *p = base + (long long)wide * sw + (long long)(r0 + 16 * h) * sr;
+#pragma unroll
+        for (int s = 0; s < 16; ++s) x.v[s] = p[(long long)s * sr];
+        return;
+    }
+#pragma unroll
+    for (int s = 0; s < 16; ++s) {
+        const int r = r0 + 16 * h + s;
+        const int rc = min(r, r_end - 1);
+        const float val = base[(long long)wide * sw + (long long)rc * sr];
+        x.v[s] = r < r_end ? (ones ? 1.0f : val) : 0.0f;
     }
 }
 
-template <bool A_I_CONTIG, bool B_J_CONTIG>
-__global__ __launch_bounds__(kGemmThreads) void gemm_mfma_kernel(GemmArgs g)
+// Reduction-contiguous operand: element (wide, r) at base[wide * sw + r].  Step 1: lane l reads
+// r = r0 + l % 32 of the tile's rows 2 it + l / 32, it = 0..15 (first_wide = the tile's first wide index,
+// n_wide = the operand's extent in that index).
+template <bool SAFE>
+__device__ __forceinline__ void slab_load_along_r(SlabRegs &x, const float *base, long long sw, int first_wide,
+                                                  int n_wide, int r0, int r_end, int lane)
 {
-    __shared__ float As[kGemmBK][kGemmLd]; // As[r][i]
-    __shared__ float Bs[kGemmBK][kGemmLd]; // Bs[r][j]
-    const int tid = threadIdx.x;
-    const int lane = tid & 63, wave = tid >> 6;
-    const int wm = wave >> 1, wn = wave & 1;
-    const int i0 = blockIdx.y * kGemmBM, j0 = blockIdx.x * kGemmBN;
-    const int r_begin = blockIdx.z * g.k_per_split;
-    const int r_end = min(g.K, r_begin + g.k_per_split);
-
-    // per-thread element offsets of the first slab (the host checks that every matrix has < 2^31 elements)
-    int off_a[kGemmPerThread], off_b[kGemmPerThread];
-    unsigned ok_a = 0, ok_b = 0, ones_b = 0;
+    if (!SAFE) {
+        const float *p = base + (long long)(first_wide + (lane >> 5)) * sw + (r0 + (lane & 31));
 #pragma unroll
-    for (int q = 0; q < kGemmPerThread; ++q) {
-        int ai, ar, bj, br;
-        gemm_slot<A_I_CONTIG>(tid, q, &ai, &ar);
-        gemm_slot<B_J_CONTIG>(tid, q, &bj, &br);
-        off_a[q] = (int)((long long)(i0 + ai) * g.a_si + (long long)(r_begin + ar) * g.a_sr);
-        off_b[q] = (int)((long long)(r_begin + br) * g.b_sr + (long long)(j0 + bj) * g.b_sj);
-        if (i0 + ai < g.M) ok_a |= 1u << q;
-        if (j0 + bj < g.N) ok_b |= 1u << q;
-        if (g.b_ones_last && j0 + bj == g.N - 1) ones_b |= 1u << q;
+        for (int it = 0; it < 16; ++it) x.v[it] = p[(long long)(2 * it) * sw];
+        return;
     }
-    const int step_a = (int)(kGemmBK * g.a_sr), step_b = (int)(kGemmBK * g.b_sr);
+    const int r = r0 + (lane & 31);
+    const int rc = min(r, r_end - 1);
+#pragma unroll
+    for (int it = 0; it < 16; ++it) {
+        const int wide = min(first_wide + 2 * it + (lane >> 5), n_wide - 1);
+        const float val = base[(long long)wide * sw + rc];
+        x.v[it] = r < r_end ? val : 0.0f;
+    }
+}
+
+// step 2: through the wave's LDS piece into the product layout
+__device__ __forceinline__ void slab_turn(SlabRegs &x, const SlabRegs &st, float *lds, int lane)
+{
+#pragma unroll
+    for (int it = 0; it < 16; ++it) lds[(2 * it + (lane >> 5)) * kGemmPitch + (lane & 31)] = st.v[it];
+    // (same wave: the LDS operations complete in order, no barrier needed)
+    const float4 *row = reinterpret_cast<const float4 *>(lds + (lane & 31) * kGemmPitch + 16 * (lane >> 5));
+#pragma unroll
+    for (int s4 = 0; s4 < 4; ++s4) {
+        const float4 q = row[s4];
+        x.v[4 * s4 + 0] = q.x, x.v[4 * s4 + 1] = q.y, x.v[4 * s4 + 2] = q.z, x.v[4 * s4 + 3] = q.w;
+    }
+}
+
+template <bool A_RC, bool B_RC>
+__global__ __launch_bounds__(kGemmThreads) void gemm_wave_kernel(GemmGroup grp)
+{
+    constexpr int kTurn = (A_RC || B_RC) ? 32 * kGemmPitch : 4; // only turned operands need the LDS pieces
+    __shared__ __align__(16) float turn[kGemmWaves][2][kTurn];
+    const int lane = threadIdx.x & (kWave - 1);
+    const int wave = __builtin_amdgcn_readfirstlane((int)threadIdx.x / kWave); // wave-uniform, and known to be
+    const int tile = (int)blockIdx.x * kGemmWaves + wave;
+    if (tile >= grp.total_tiles) return; // whole waves leave; no barrier below
+    int pi = 0;
+#pragma unroll 1
+    for (int q = 1; q < grp.count; ++q)
+        if (tile >= grp.p[q].tile_begin) pi = q;
+    const GemmArgs &g = grp.p[pi];
+    const int tiles_j = (g.N + 31) / 32, tiles_i = (g.M + 31) / 32;
+    int local = tile - g.tile_begin;
+    const int z = local / (tiles_i * tiles_j);
+    local -= z * tiles_i * tiles_j;
+    const int i0 = (local / tiles_j) * 32, j0 = (local % tiles_j) * 32;
+    const int r_begin = z * g.k_per_split;
+    const int r_end = min(g.K, r_begin + g.k_per_split);
+    const int w = lane & 31, h = lane >> 5;
+
+    // Edge tiles: rows of A past M and columns of B past N re-read the last one (their results are not
+    // stored); the all-ones last column of B is virtual (direct B only: host).
+    const int n_mem = g.b_ones_last ? g.N - 1 : g.N; // columns of B that exist in memory (>= 1: host)
+    const bool inner = i0 + 32 <= g.M && j0 + 32 <= n_mem; // the whole tile reads real rows and columns
+    const int ia = min(i0 + w, g.M - 1), jb = min(j0 + w, n_mem - 1);
+    const bool ones = g.b_ones_last && j0 + w == g.N - 1;
+    float *lds_a = turn[wave][0], *lds_b = turn[wave][1];
+    // (requested now, used in the epilogue)
+    const float bias_j = (g.bias && g.splits <= 1) ? g.bias[min(j0 + w, g.N - 1)] : 0.0f;
 
     floatx16 acc;
 #pragma unroll
     for (int v = 0; v < 16; ++v) acc[v] = 0.0f;
 
-    float av[kGemmPerThread], bv[kGemmPerThread];
-    auto load_slab = [&](int r0) {
-#pragma unroll
-        for (int q = 0; q < kGemmPerThread; ++q) {
-            int ai, ar, bj, br;
-            gemm_slot<A_I_CONTIG>(tid, q, &ai, &ar);
-            gemm_slot<B_J_CONTIG>(tid, q, &bj, &br);
-            const bool in_a = ((ok_a >> q) & 1u) && (r0 + ar < r_end);
-            const bool in_b = ((ok_b >> q) & 1u) && (r0 + br < r_end);
-            av[q] = in_a ? g.A[off_a[q]] : 0.0f;
-            bv[q] = in_b ? (((ones_b >> q) & 1u) ? 1.0f : g.B[off_b[q]]) : 0.0f;
-            off_a[q] += step_a;
-            off_b[q] += step_b;
-        }
+    // Two slabs are in flight while a third is multiplied: sa[q] / sb[q] receive slab n with n % 2 == q as it
+    // comes from memory (for a turned operand: along r), a / b hold the current slab in product layout.
+    SlabRegs a, b, sa[2], sb[2];
+    auto fetch_safe = [&](int q, int r0) {
+        if (A_RC)
+            slab_load_along_r<true>(sa[q], g.A, g.a_si, i0, g.M, r0, r_end, lane);
+        else
+            slab_load_direct<true>(sa[q], g.A, g.a_si, g.a_sr, ia, r0, r_end, h, false);
+        if (B_RC)
+            slab_load_along_r<true>(sb[q], g.B, g.b_sj, j0, n_mem, r0, r_end, lane);
+        else
+            slab_load_direct<true>(sb[q], g.B, g.b_sj, g.b_sr, jb, r0, r_end, h, ones);
     };
-    if (r_begin < r_end) load_slab(r_begin);
-    for (int r0 = r_begin; r0 < r_end; r0 += kGemmBK) {
-        // registers -> LDS
+    auto fetch_fast = [&](int q, int r0) { // inner tile, whole slab
+        if (A_RC)
+            slab_load_along_r<false>(sa[q], g.A, g.a_si, i0, g.M, r0, r_end, lane);
+        else
+            slab_load_direct<false>(sa[q], g.A, g.a_si, g.a_sr, ia, r0, r_end, h, false);
+        if (B_RC)
+            slab_load_along_r<false>(sb[q], g.B, g.b_sj, j0, n_mem, r0, r_end, lane);
+        else
+            slab_load_direct<false>(sb[q], g.B, g.b_sj, g.b_sr, jb, r0, r_end, h, false);
+    };
+    auto settle = [&](int q) { // staging registers -> product layout
+        if (A_RC)
+            slab_turn(a, sa[q], lds_a, lane);
+        else
+            a = sa[q];
+        if (B_RC)
+            slab_turn(b, sb[q], lds_b, lane);
+        else
+            b = sb[q];
+    };
+    auto products = [&]() {
 #pragma unroll
-        for (int q = 0; q < kGemmPerThread; ++q) {
-            int ai, ar, bj, br;
-            gemm_slot<A_I_CONTIG>(tid, q, &ai, &ar);
-            gemm_slot<B_J_CONTIG>(tid, q, &bj, &br);
-            As[ar][ai] = av[q];
-            Bs[br][bj] = bv[q];
+        for (int s = 0; s < 16; ++s) acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a.v[s], b.v[s], acc, 0, 0, 0);
+    };
+
+    // Pairs of whole slabs of an inner tile.  The loop bodies below have no branch and every fetch is
+    // unconditional, so that the loads in flight are the same, in number and order, on entry and on the way
+    // round: only then does the compiler wait for exactly the slab it needs.  (A fetch past the fast part
+    // re-reads its last pair of slabs: harmless.)
+    int r0 = r_begin;
+    const int r_pairs = inner ? r_begin + (r_end - r_begin) / (2 * kGemmBK) * (2 * kGemmBK) : r_begin;
+    if (r0 < r_pairs) {
+        const int r_last = r_pairs - 2 * kGemmBK;
+        fetch_fast(0, r0);
+        __builtin_amdgcn_sched_barrier(0);
+        fetch_fast(1, r0 + kGemmBK);
+        __builtin_amdgcn_sched_barrier(0);
+        for (; r0 < r_pairs; r0 += 2 * kGemmBK) {
+            const int rn = min(r0 + 2 * kGemmBK, r_last);
+            // (the scheduling barriers keep the compiler from moving loads across the phases, which would
+            //  change which loads are in flight at each wait)
+            settle(0);
+            __builtin_amdgcn_sched_barrier(0);
+            fetch_fast(0, rn);
+            __builtin_amdgcn_sched_barrier(0);
+            products();
+            __builtin_amdgcn_sched_barrier(0);
+            settle(1);
+            __builtin_amdgcn_sched_barrier(0);
+            fetch_fast(1, rn + kGemmBK);
+            __builtin_amdgcn_sched_barrier(0);
+            products();
+            __builtin_amdgcn_sched_barrier(0);
         }
-        __syncthreads();
-        // next slab: on its way while the matrix cores run
-        if (r0 + kGemmBK < r_end) load_slab(r0 + kGemmBK);
-        // one 32x32x2 product per step: lane l feeds A(i = l % 32, r = l / 32) and B(r = l / 32, j = l % 32)
-#pragma unroll
-        for (int rr = 0; rr < kGemmBK; rr += 2) {
-            const float a = As[rr + (lane >> 5)][wm * 32 + (lane & 31)];
-            const float b = Bs[rr + (lane >> 5)][wn * 32 + (lane & 31)];
-            acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a, b, acc, 0, 0, 0);
+    }
+    // what is left: at most one whole and one partial slab of an inner tile, or everything of an edge tile
+    // (past the end: clamped addresses, zeros, and a product that adds nothing)
+    if (r0 < r_end) {
+        fetch_safe(0, r0);
+        fetch_safe(1, r0 + kGemmBK);
+        for (; r0 < r_end; r0 += 2 * kGemmBK) {
+            settle(0);
+            fetch_safe(0, r0 + 2 * kGemmBK);
+            products();
+            settle(1);
+            fetch_safe(1, r0 + 3 * kGemmBK);
+            products();
         }
-        __syncthreads();
     }
 
     // accumulator layout: lane l holds column j = l % 32 and rows 8*(v/4) + 4*(l/32) + v%4, v = 0..15
-    const int j = j0 + wn * 32 + (lane & 31);
+    const int j = j0 + w;
     if (j >= g.N) return;
-    if (gridDim.z > 1) {
-        float *p = g.P + (long long)blockIdx.z * g.M * g.N;
+    if (g.splits > 1) {
+        float *p = g.P + (long long)z * g.M * g.N;
 #pragma unroll
         for (int v = 0; v < 16; ++v) {
-            const int i = i0 + wm * 32 + 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3);
+            const int i = i0 + 8 * (v >> 2) + 4 * h + (v & 3);
             if (i < g.M) p[(long long)i * g.N + j] = acc[v];
         }
         return;
     }
-    const float bj = g.bias ? g.bias[j] : 0.0f;
+    const float bj = bias_j;
 #pragma unroll
     for (int v = 0; v < 16; ++v) {
-        const int i = i0 + wm * 32 + 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3);
+        const int i = i0 + 8 * (v >> 2) + 4 * h + (v & 3);
         if (i >= g.M) continue;
         float x = acc[v] + bj;
         if (g.relu) x = fmaxf(x, 0.0f);
@@ -153,20 +274,38 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_mfma_kernel(GemmArgs g)
     }
 }
 
-// SGD step from the split products of [dZ^T * X | dZ^T * 1]: P is [S][out][in + 1];
-// W[o][i] -= lr * sum_s P[s][o][i],  b[o] -= lr * sum_s P[s][o][in]  (slices added in order)
-__global__ __launch_bounds__(256) void sgd_from_partials_kernel(const float *__restrict__ P, int S, int out, int in,
-                                                                float lr, float *__restrict__ W, float *__restrict__ b)
+// SGD step from the split products of [dZ^T * X | dZ^T * 1], all layers in one launch:
+// layer q's P is [S][out][in + 1];  W[o][i] -= lr * sum_s P[s][o][i],  b[o] -= lr * sum_s P[s][o][in]
+// (slices added in order).  elem_begin[q] = first element of layer q in the launch's flat index space.
+struct SgdLayer {
+    const float *P;
+    float *W, *b;
+    int S, out, in;
+    long long elem_begin;
+};
+struct SgdGroup {
+    SgdLayer l[kGemmMaxGroup];
+    int count;
+    long long total;
+    float lr;
+};
+
+__global__ __launch_bounds__(256) void sgd_from_partials_kernel(SgdGroup grp)
 {
-    const long long total = (long long)out * (in + 1);
-    for (long long e = (long long)blockIdx.x * 256 + threadIdx.x; e < total; e += (long long)gridDim.x * 256) {
+    for (long long e = (long long)blockIdx.x * 256 + threadIdx.x; e < grp.total; e += (long long)gridDim.x * 256) {
+        int q = 0;
+#pragma unroll 1
+        for (int k = 1; k < grp.count; ++k)
+            if (e >= grp.l[k].elem_begin) q = k;
+        const SgdLayer &L = grp.l[q];
+        const long long le = e - L.elem_begin, per = (long long)L.out * (L.in + 1);
         float s = 0.0f;
-        for (int z = 0; z < S; ++z) s += P[(long long)z * total + e];
-        const int o = (int)(e / (in + 1)), i = (int)(e - (long long)o * (in + 1));
-        if (i < in)
-            W[(long long)o * in + i] = W[(long long)o * in + i] - lr * s;
+        for (int z = 0; z < L.S; ++z) s += L.P[(long long)z * per + le];
+        const int o = (int)(le / (L.in + 1)), i = (int)(le - (long long)o * (L.in + 1));
+        if (i < L.in)
+            L.W[(long long)o * L.in + i] = L.W[(long long)o * L.in + i] - grp.lr * s;
         else
-            b[o] = b[o] - lr * s;
+            L.b[o] = L.b[o] - grp.lr * s;
     }
 }
 

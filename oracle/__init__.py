@@ -48,6 +48,8 @@ def lib() -> C.CDLL:
         _lib.oracle_seg_chunk.restype = C.c_int
         _lib.oracle_embbag_bwd.restype = C.c_int64
         _lib.oracle_dense_step.restype = C.c_double
+        _lib.oracle_dense_step_ex.restype = C.c_double
+        _lib.oracle_mlp_grad_quant_ec.restype = C.c_float
     return _lib
 
 
@@ -164,3 +166,53 @@ def dense_step(bot_dims, bot_w, bot_b, top_dims, top_w, top_b, dense_x, emb, lab
                                    arr(top_w), arr(top_b), _p(x, C.c_double), _p(e, C.c_double), _p(y, C.c_double),
                                    C.c_double(lr), _p(grad, C.c_double))
     return float(loss), grad
+
+
+def dense_step_ex(bot_dims, bot_w, bot_b, top_dims, top_w, top_b, dense_x, emb, labels, lr, bot_wf=None, top_wf=None,
+                  apply_sgd=True, want_grads=False):
+    """The general dense step in float64: ``bot_wf`` / ``top_wf`` (lists of float64 arrays or None) are the
+    weights the forward and the input gradients use; the master weights take the step iff ``apply_sgd``.
+    Returns (loss, grad_emb[, (bot_gw, bot_gb, top_gw, top_gb)])."""
+    B, T, D = emb.shape
+    f64 = lambda a: np.ascontiguousarray(a, dtype=np.float64)
+    x, e, y = f64(dense_x), f64(emb), f64(labels)
+    for a in list(bot_w) + list(bot_b) + list(top_w) + list(top_b) + list(bot_wf or []) + list(top_wf or []):
+        assert a.dtype == np.float64 and a.flags["C_CONTIGUOUS"]
+    bd = np.ascontiguousarray(bot_dims, dtype=np.int32)
+    td = np.ascontiguousarray(top_dims, dtype=np.int32)
+    PP = C.POINTER(C.c_double)
+    arr = lambda lst: (PP * len(lst))(*[a.ctypes.data_as(PP) for a in lst]) if lst is not None else None
+    grads = None
+    if want_grads:
+        grads = tuple([np.zeros_like(a) for a in lst] for lst in (bot_w, bot_b, top_w, top_b))
+    grad = np.empty((B, T, D), np.float64)
+    loss = lib().oracle_dense_step_ex(
+        C.c_int(B), C.c_int(x.shape[1]), C.c_int(T), C.c_int(D), C.c_int(len(bot_w)), _p(bd, C.c_int32), arr(bot_w),
+        arr(bot_b), C.c_int(len(top_w)), _p(td, C.c_int32), arr(top_w), arr(top_b), _p(x, C.c_double),
+        _p(e, C.c_double), _p(y, C.c_double), C.c_double(lr), _p(grad, C.c_double), arr(bot_wf), arr(top_wf),
+        C.c_int(1 if apply_sgd else 0), arr(grads[0]) if grads else None, arr(grads[1]) if grads else None,
+        arr(grads[2]) if grads else None, arr(grads[3]) if grads else None)
+    return (float(loss), grad, grads) if want_grads else (float(loss), grad)
+
+
+def mlp_fake_quant(W: np.ndarray, bits: int):
+    """Channel-wise fake quantisation of W [out][in] (float32).  Returns (Wq float32, row_scale float32, codes int8)."""
+    assert W.dtype == np.float32 and W.flags["C_CONTIGUOUS"] and W.ndim == 2
+    out, inn = W.shape
+    Wq = np.empty_like(W)
+    scale = np.empty(out, np.float32)
+    codes = np.empty((out, inn), np.int8)
+    lib().oracle_mlp_fake_quant(_p(W, C.c_float), C.c_int(out), C.c_int(inn), C.c_int(bits), _p(Wq, C.c_float),
+                                _p(scale, C.c_float), _p(codes, C.c_int8))
+    return Wq, scale, codes
+
+
+def mlp_grad_quant_ec(g: np.ndarray, err: Optional[np.ndarray], param: np.ndarray, lr: float):
+    """INT8 + error compensation on one tensor, IN PLACE on ``err`` (may be None) and ``param`` (float32, any
+    shape, contiguous).  Returns (scale, codes int8 of g's shape)."""
+    for a in (g, param) + ((err,) if err is not None else ()):
+        assert a.dtype == np.float32 and a.flags["C_CONTIGUOUS"]
+    codes = np.empty(g.shape, np.int8)
+    s = lib().oracle_mlp_grad_quant_ec(C.c_int64(g.size), _p(g, C.c_float), _p(err, C.c_float) if err is not None else None,
+                                       _p(param, C.c_float), C.c_float(lr), _p(codes, C.c_int8))
+    return float(np.float32(s)), codes

@@ -22,6 +22,24 @@
  * torch (float64 CPU tensors, autograd) -- loss, gradient w.r.t. the pooled
  * embeddings and the updated parameters agree to 1e-12.
  *
+ * The quantised variants of the dense part (distributed-training section and the
+ * model-quantisation appendix of the paper):
+ *   oracle_mlp_fake_quant     channel-wise (one scale per output row) INT4 / INT8
+ *                             fake quantisation of a linear layer's weights; the
+ *                             forward and the input gradients use the quantised
+ *                             weights, the step goes to the fp32 weights
+ *                             (straight-through), activations stay unquantised;
+ *   oracle_mlp_grad_quant_ec  per-tensor INT8 quantisation of an MLP gradient with
+ *                             error compensation.  The paper only cites the scheme
+ *                             (error feedback); the reading taken: the residual of
+ *                             the previous step is added before quantising,
+ *                             g' = g + e;  q = Q(g');  e <- g' - s*q;  the step uses s*q.
+ * Both decide integer codes, so they compute in binary32 (one rounding per
+ * operation), like the embedding oracle.  Pins: tests/test_oracle_mlp_quant_pins.py
+ * (the scalar quantiser and the table-wise routines of the embedding oracle on the
+ * same numbers, closed-form invariants, the telescoping sum of error feedback, hand
+ * examples under tests/golden/, torch autograd with a straight-through weight).
+ *
  * Build: gcc -O2 -ffp-contract=off -shared -fPIC
  */
 #include <math.h>
@@ -41,15 +59,16 @@ static void linear_fwd(const double *x, const double *W, const double *bias, dou
         }
 }
 
-/* given dz (gradient w.r.t. the layer's pre-activation): dx, then the SGD step on W and bias */
-static void linear_bwd(const double *dz, const double *x, double *W, double *bias, double *dx, int B, int in, int out,
-                       double lr)
+/* given dz (gradient w.r.t. the layer's pre-activation): dx through the weights Wf the forward used, the
+ * gradients gw / gb (stored if the pointers are given), and -- if asked -- the SGD step on W and bias */
+static void linear_bwd(const double *dz, const double *x, const double *Wf, double *W, double *bias, double *dx, int B,
+                       int in, int out, double lr, int apply_sgd, double *gw_out, double *gb_out)
 {
     if (dx)
         for (int b = 0; b < B; ++b)
             for (int i = 0; i < in; ++i) {
                 double s = 0.0;
-                for (int o = 0; o < out; ++o) s += dz[(size_t)b * out + o] * W[(size_t)o * in + i];
+                for (int o = 0; o < out; ++o) s += dz[(size_t)b * out + o] * Wf[(size_t)o * in + i];
                 dx[(size_t)b * in + i] = s;
             }
     for (int o = 0; o < out; ++o) {
@@ -58,9 +77,11 @@ static void linear_bwd(const double *dz, const double *x, double *W, double *bia
         for (int i = 0; i < in; ++i) {
             double gw = 0.0;
             for (int b = 0; b < B; ++b) gw += dz[(size_t)b * out + o] * x[(size_t)b * in + i];
-            W[(size_t)o * in + i] -= lr * gw;
+            if (gw_out) gw_out[(size_t)o * in + i] = gw;
+            if (apply_sgd) W[(size_t)o * in + i] -= lr * gw;
         }
-        bias[o] -= lr * gb;
+        if (gb_out) gb_out[o] = gb;
+        if (apply_sgd) bias[o] -= lr * gb;
     }
 }
 
@@ -68,11 +89,20 @@ static void linear_bwd(const double *dz, const double *x, double *W, double *bia
  * All matrices row-major.  bot_w / top_w: arrays of pointers to double matrices
  * [dims[l+1]][dims[l]] (updated in place); bot_b / top_b likewise.
  * Returns the loss; grad_emb [B][T][D] receives d loss / d emb.
+ *
+ * The general form.  bot_wf / top_wf: the weights the forward and the input gradients use (NULL: the
+ * master weights bot_w / top_w; otherwise e.g. their fake-quantised copies).  apply_sgd: whether the master
+ * weights and biases take the step.  bot_gw / bot_gb / top_gw / top_gb: arrays of pointers that receive the
+ * gradients (NULL: not wanted).
  */
-double oracle_dense_step(int B, int num_dense, int T, int D, int bot_layers, const int32_t *bot_dims, double **bot_w,
-                         double **bot_b, int top_layers, const int32_t *top_dims, double **top_w, double **top_b,
-                         const double *dense_x, const double *emb, const double *labels, double lr, double *grad_emb)
+double oracle_dense_step_ex(int B, int num_dense, int T, int D, int bot_layers, const int32_t *bot_dims,
+                            double **bot_w, double **bot_b, int top_layers, const int32_t *top_dims, double **top_w,
+                            double **top_b, const double *dense_x, const double *emb, const double *labels, double lr,
+                            double *grad_emb, double **bot_wf, double **top_wf, int apply_sgd, double **bot_gw,
+                            double **bot_gb, double **top_gw, double **top_gb)
 {
+    if (!bot_wf) bot_wf = bot_w;
+    if (!top_wf) top_wf = top_w;
     const int V = T + 1, P = V * (V - 1) / 2, RW = D + P;
     (void)num_dense;
     /* ---- forward */
@@ -81,7 +111,7 @@ double oracle_dense_step(int B, int num_dense, int T, int D, int bot_layers, con
     ba[0] = (double *)dense_x;
     for (int l = 0; l < bot_layers; ++l) {
         ba[l + 1] = (double *)malloc(sizeof(double) * (size_t)B * bot_dims[l + 1]);
-        linear_fwd(ba[l], bot_w[l], bot_b[l], ba[l + 1], B, bot_dims[l], bot_dims[l + 1], 1);
+        linear_fwd(ba[l], bot_wf[l], bot_b[l], ba[l + 1], B, bot_dims[l], bot_dims[l + 1], 1);
     }
     double *Z = (double *)malloc(sizeof(double) * (size_t)B * V * D); /* [B][V][D] */
     double *R = (double *)malloc(sizeof(double) * (size_t)B * RW);
@@ -103,7 +133,7 @@ double oracle_dense_step(int B, int num_dense, int T, int D, int bot_layers, con
     ta[0] = R;
     for (int l = 0; l < top_layers; ++l) {
         ta[l + 1] = (double *)malloc(sizeof(double) * (size_t)B * top_dims[l + 1]);
-        linear_fwd(ta[l], top_w[l], top_b[l], ta[l + 1], B, top_dims[l], top_dims[l + 1], l + 1 < top_layers);
+        linear_fwd(ta[l], top_wf[l], top_b[l], ta[l + 1], B, top_dims[l], top_dims[l + 1], l + 1 < top_layers);
     }
     /* ---- loss and its gradient w.r.t. the logit */
     double loss = 0.0;
@@ -120,7 +150,8 @@ double oracle_dense_step(int B, int num_dense, int T, int D, int bot_layers, con
     double *g = dz; /* gradient w.r.t. the pre-activation of the current layer */
     for (int l = top_layers - 1; l >= 0; --l) {
         double *dx = (double *)malloc(sizeof(double) * (size_t)B * top_dims[l]);
-        linear_bwd(g, ta[l], top_w[l], top_b[l], dx, B, top_dims[l], top_dims[l + 1], lr);
+        linear_bwd(g, ta[l], top_wf[l], top_w[l], top_b[l], dx, B, top_dims[l], top_dims[l + 1], lr, apply_sgd,
+                   top_gw ? top_gw[l] : NULL, top_gb ? top_gb[l] : NULL);
         if (l > 0) /* ta[l] is a ReLU output */
             for (size_t e = 0; e < (size_t)B * top_dims[l]; ++e)
                 if (!(ta[l][e] > 0.0)) dx[e] = 0.0;
@@ -154,7 +185,8 @@ double oracle_dense_step(int B, int num_dense, int T, int D, int bot_layers, con
     g = dbot;
     for (int l = bot_layers - 1; l >= 0; --l) {
         double *dx = l > 0 ? (double *)malloc(sizeof(double) * (size_t)B * bot_dims[l]) : NULL;
-        linear_bwd(g, ba[l], bot_w[l], bot_b[l], dx, B, bot_dims[l], bot_dims[l + 1], lr);
+        linear_bwd(g, ba[l], bot_wf[l], bot_w[l], bot_b[l], dx, B, bot_dims[l], bot_dims[l + 1], lr, apply_sgd,
+                   bot_gw ? bot_gw[l] : NULL, bot_gb ? bot_gb[l] : NULL);
         if (l > 0)
             for (size_t e = 0; e < (size_t)B * bot_dims[l]; ++e)
                 if (!(ba[l][e] > 0.0)) dx[e] = 0.0;
@@ -168,4 +200,68 @@ double oracle_dense_step(int B, int num_dense, int T, int D, int bot_layers, con
     free(Z);
     free(R);
     return loss;
+}
+
+/* the plain fp32-weight train step */
+double oracle_dense_step(int B, int num_dense, int T, int D, int bot_layers, const int32_t *bot_dims, double **bot_w,
+                         double **bot_b, int top_layers, const int32_t *top_dims, double **top_w, double **top_b,
+                         const double *dense_x, const double *emb, const double *labels, double lr, double *grad_emb)
+{
+    return oracle_dense_step_ex(B, num_dense, T, D, bot_layers, bot_dims, bot_w, bot_b, top_layers, top_dims, top_w,
+                                top_b, dense_x, emb, labels, lr, grad_emb, NULL, NULL, 1, NULL, NULL, NULL, NULL);
+}
+
+/* ---- channel-wise fake quantisation of a linear layer's weights (binary32) ----
+ * W [out][in] row-major.  Per output row o:  a = max_i |W[o][i]|,  s_o = max(a / qmax, 1e-8) with
+ * qmax = 2^(bits-1) - 1;  code = clamp(rint(W / s_o), -2^(bits-1), qmax);  Wq = s_o * code.
+ * row_scale [out] and codes [out][in] are optional outputs. */
+void oracle_mlp_fake_quant(const float *W, int out, int in, int bits, float *Wq, float *row_scale, int8_t *codes)
+{
+    const float qmax = (float)((1 << (bits - 1)) - 1), qmin = -(float)(1 << (bits - 1));
+    for (int o = 0; o < out; ++o) {
+        float a = 0.0f;
+        for (int i = 0; i < in; ++i) {
+            const float m = fabsf(W[(size_t)o * in + i]);
+            if (m > a) a = m;
+        }
+        float s = a / qmax;
+        if (s < 1e-8f) s = 1e-8f;
+        if (row_scale) row_scale[o] = s;
+        for (int i = 0; i < in; ++i) {
+            float q = rintf(W[(size_t)o * in + i] / s);
+            if (q < qmin) q = qmin;
+            if (q > qmax) q = qmax;
+            if (codes) codes[(size_t)o * in + i] = (int8_t)q;
+            Wq[(size_t)o * in + i] = s * q;
+        }
+    }
+}
+
+/* ---- INT8 quantisation of one parameter tensor's gradient with error compensation (binary32) ----
+ * g [n] the gradient, err [n] the residual carried from the previous step (NULL: none is kept),
+ * param [n] the parameter.  g' = g + err;  s = max(max|g'| / 127, 1e-8);  code = clamp(rint(g' / s), -128, 127);
+ * err <- g' - s * code;  param <- param - lr * (s * code).  Returns s. */
+float oracle_mlp_grad_quant_ec(int64_t n, const float *g, float *err, float *param, float lr, int8_t *codes)
+{
+    float a = 0.0f;
+    for (int64_t k = 0; k < n; ++k) {
+        const float gp = err ? g[k] + err[k] : g[k];
+        const float m = fabsf(gp);
+        if (m > a) a = m;
+    }
+    float s = a / 127.0f;
+    if (s < 1e-8f) s = 1e-8f;
+    for (int64_t k = 0; k < n; ++k) {
+        const float gp = err ? g[k] + err[k] : g[k];
+        float q = rintf(gp / s);
+        if (q < -128.0f) q = -128.0f;
+        if (q > 127.0f) q = 127.0f;
+        const int8_t c = (int8_t)q;
+        if (codes) codes[k] = c;
+        const float deq = s * (float)c;
+        if (err) err[k] = gp - deq;
+        const float step = lr * deq;
+        param[k] = param[k] - step;
+    }
+    return s;
 }

@@ -62,6 +62,10 @@ def main():
     ap.add_argument("--pool", type=int, default=64, help="distinct index batches cycled")
     ap.add_argument("--grad-pool", type=int, default=8, help="distinct grad_out buffers cycled")
     ap.add_argument("--lr", type=float, default=0.1)
+    ap.add_argument("--mlp-weight-bits", type=int, default=0, choices=[0, 4, 8],
+                    help="with --dense: channel-wise fake quantisation of the MLP weights (dqrm_dense_step_quant)")
+    ap.add_argument("--mlp-grad-bits", type=int, default=0, choices=[0, 8],
+                    help="with --dense: INT8 MLP gradients with error compensation (dqrm_dense_step_quant)")
     ap.add_argument("--refresh-period", type=int, default=0,
                     help="P > 0: every P steps the per-table weight scale is recomputed from the whole master table "
                          "(dqrm_find_scale) and the packed mirror re-encoded (dqrm_pack_int4), in line, inside the timed "
@@ -159,6 +163,14 @@ def main():
         dense_y = [torch.from_numpy(y).to(dev) for _, y in dense_in]
         loss_d = torch.zeros(1, dtype=torch.float32, device=dev)
         grad_live = torch.empty((B, T, D), dtype=torch.float32, device=dev)
+        dense_quant = None
+        if args.mlp_weight_bits or args.mlp_grad_bits:
+            P = dq.dqrm_dense_param_count(dense)
+            dense_quant = dq.DenseQuant(
+                weight_bits=args.mlp_weight_bits, grad_bits=args.mlp_grad_bits,
+                grad_error=torch.zeros(P, dtype=torch.float32, device=dev) if args.mlp_grad_bits else None,
+                grad_scale=torch.zeros(2 * (len(bw) + len(tw)), dtype=torch.float32, device=dev) if args.mlp_grad_bits else None,
+                grad_codes=torch.zeros(P, dtype=torch.int8, device=dev) if args.mlp_grad_bits else None)
 
     def refresh_scale():
         """Sec. 3.2: recompute the per-table scale from the whole master table, re-encode the packed mirror."""
@@ -173,7 +185,8 @@ def main():
         dq.dqrm_embbag_fwd(tables, ix, of, B, mode, bufs.out, None)
         if dense is not None:
             j = k % args.grad_pool
-            dq.dqrm_dense_step(dense, B, dense_x[j], bufs.out, dense_y[j], args.lr, loss_d, grad_live, dense_ws)
+            dq.dqrm_dense_step_quant(dense, dense_quant, B, dense_x[j], bufs.out, dense_y[j], args.lr, loss_d, grad_live,
+                                     dense_ws)
 
     def rest_of_step(k, i):
         """B3-B5 on the current stream, from the dedupe result in buffer i."""
@@ -438,7 +451,7 @@ def main():
         "config": {"workload": f"{args.workload}-shaped embedding layer: {T} tables, {wl.R} rows, dim {D}, batch {B}, "
                                f"1 Zipf index per table per sample, {args.mode}-mode forward, INT8 sparse grads, "
                                f"SGD lr {args.lr}, dedupe overlap: {args.overlap}",
-                   "lookups_per_step": N, "unique_rows_per_step": round(U, 1), "fwd_mode": args.mode, "overlap": args.overlap, "scale_refresh_period": args.refresh_period, "dense_part": bool(args.dense),
+                   "lookups_per_step": N, "unique_rows_per_step": round(U, 1), "fwd_mode": args.mode, "overlap": args.overlap, "scale_refresh_period": args.refresh_period, "dense_part": bool(args.dense), "mlp_weight_bits": args.mlp_weight_bits, "mlp_grad_bits": args.mlp_grad_bits,
                    "update": ("dqrm_quant_update (one pass)" if args.fused else "dqrm_grad_quant_int8 + dqrm_sparse_update"),
                    "launch": (f"HIP graph of {graph_steps} steps replayed" if graph is not None else "eager launches")},
         "roofline": roofline,

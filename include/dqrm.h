@@ -13,6 +13,7 @@
  *   dqrm_sparse_update   every step      dequantise + SGD on touched rows        (same appendix)
  * and, between the forward and the backward of the tables, the dense part of the model:
  *   dqrm_dense_step      every step      MLPs, interaction, loss, their backward, dense SGD
+ *   dqrm_dense_step_quant  the same with channel-wise INT4 weights and / or INT8 gradients + error compensation
  *
  * Conventions common to every entry point
  *   - Returns 0 (DQRM_OK) or a negative DQRM_ERR_* code.  Never throws, never aborts.
@@ -239,6 +240,41 @@ size_t dqrm_dense_workspace_bytes(const dqrm_dense_model_t *model, int32_t batch
 int32_t dqrm_dense_step(const dqrm_dense_model_t *model, int32_t batch, const float *dense_x, const float *emb_out,
                         const float *labels, float lr, float *loss, float *grad_emb, void *workspace,
                         size_t workspace_bytes, void *stream);
+
+/* The quantised variants of the dense part.
+ *   weight_bits = 4 (or 8): every linear layer's weights are fake-quantised channel-wise for the forward and
+ *     the input gradients -- one scale per output row, s_o = max(max_i |W[o][i]| / (2^(bits-1)-1), 1e-8),
+ *     Wq = s_o * clamp(rint(W / s_o)) -- while the step goes to the FP32 weights (straight-through);
+ *     biases and activations stay FP32 (model-quantisation appendix: "a scale for every row inside the
+ *     linear layer weights"; whole-model results section).  weight_bits = 0: FP32 weights.
+ *   grad_bits = 8: the gradient of every parameter tensor (each layer's weight matrix and each bias vector
+ *     on its own) is quantised to INT8 with one scale per tensor before the step, with error compensation
+ *     when grad_error is given (distributed-training section: INT8 gradients, compensation for the MLP
+ *     layers only; gradient-quantisation appendix).  The paper only cites the compensation scheme; the
+ *     reading taken is error feedback:  g' = g + e;  s = max(max|g'| / 127, 1e-8);
+ *     code = clamp(rint(g' / s), -128, 127);  e <- g' - s * code;  parameter <- parameter - lr * (s * code).
+ *     On one GPU the "unified" scale is the local one.  grad_bits = 0: FP32 gradients.
+ * Flat parameter order of grad_error / grad_codes / grads: the layers of the top MLP (0 .. top_layers-1), then
+ * those of the bottom MLP; layer l contributes out * (in + 1) values, row-major [out][in + 1], column `in`
+ * being the bias.  dqrm_dense_param_count returns the total P.  Tensor order of grad_scale: two per layer in
+ * the same layer order, weights then bias.  wq: the layers' quantised weights in the same layer order,
+ * [out][in] each (P - sum of out values in total).
+ * All pointers are DEVICE memory owned by the caller; the descriptor itself is HOST memory. */
+typedef struct {
+    int32_t weight_bits; /* 0, 4 or 8 */
+    int32_t grad_bits;   /* 0 or 8 */
+    float *grad_error;   /* [P] in/out: residuals carried from step to step (zero them before the first step);
+                            NULL: INT8 gradients without compensation */
+    float *grad_scale;   /* [2 * (top_layers + bot_layers)] out; required when grad_bits = 8 */
+    int8_t *grad_codes;  /* [P] out, or NULL: the INT8 codes (what a data-parallel run would exchange) */
+    float *grads;        /* [P] out, or NULL: this step's FP32 gradients before compensation */
+    float *wq;           /* out, or NULL: the fake-quantised weights this step used */
+} dqrm_dense_quant_t;
+int64_t dqrm_dense_param_count(const dqrm_dense_model_t *model); /* P, or -1 for an invalid descriptor */
+/* As dqrm_dense_step; `quant` may be NULL (then it IS dqrm_dense_step).  Same workspace. */
+int32_t dqrm_dense_step_quant(const dqrm_dense_model_t *model, const dqrm_dense_quant_t *quant, int32_t batch,
+                              const float *dense_x, const float *emb_out, const float *labels, float lr, float *loss,
+                              float *grad_emb, void *workspace, size_t workspace_bytes, void *stream);
 
 /* Synchronises `stream`, returns the first data-dependent problem recorded on
  * the current device since the last call (DQRM_OK if none) and clears it.

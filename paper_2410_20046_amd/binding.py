@@ -35,7 +35,7 @@ MAX_TABLE_LOOKUPS = 16384
 EXPORTS = ("dqrm_find_scale", "dqrm_pack_int4", "dqrm_embbag_fwd", "dqrm_embbag_bwd_workspace_bytes",
            "dqrm_embbag_bwd", "dqrm_dedupe", "dqrm_dedupe_multi", "dqrm_segment_sum", "dqrm_grad_quant_int8",
            "dqrm_sparse_update", "dqrm_quant_update", "dqrm_dense_workspace_bytes", "dqrm_dense_step",
-           "dqrm_check_status", "dqrm_last_hip_error", "dqrm_version")
+           "dqrm_dense_param_count", "dqrm_dense_step_quant", "dqrm_check_status", "dqrm_last_hip_error", "dqrm_version")
 
 
 class DqrmError(RuntimeError):
@@ -63,6 +63,12 @@ class dqrm_dense_model_t(C.Structure):
     _fields_ = [("num_dense", C.c_int32), ("num_tables", C.c_int32), ("dim", C.c_int32), ("bot_layers", C.c_int32),
                 ("bot_dims", C.c_void_p), ("bot_w", C.c_void_p), ("bot_b", C.c_void_p), ("top_layers", C.c_int32),
                 ("top_dims", C.c_void_p), ("top_w", C.c_void_p), ("top_b", C.c_void_p)]
+
+
+class dqrm_dense_quant_t(C.Structure):
+    _fields_ = [("weight_bits", C.c_int32), ("grad_bits", C.c_int32), ("grad_error", C.c_void_p),
+                ("grad_scale", C.c_void_p), ("grad_codes", C.c_void_p), ("grads", C.c_void_p), ("wq", C.c_void_p)]
+
 
 _lib: Optional[C.CDLL] = None
 
@@ -95,6 +101,11 @@ def lib() -> C.CDLL:
         L.dqrm_dense_workspace_bytes.restype = sz
         L.dqrm_dense_step.argtypes = [dp, i32, vp, vp, vp, C.c_float, vp, vp, vp, sz, vp]
         L.dqrm_dense_step.restype = i32
+        L.dqrm_dense_param_count.argtypes = [dp]
+        L.dqrm_dense_param_count.restype = i64
+        L.dqrm_dense_step_quant.argtypes = [dp, C.POINTER(dqrm_dense_quant_t), i32, vp, vp, vp, C.c_float, vp, vp, vp,
+                                            sz, vp]
+        L.dqrm_dense_step_quant.restype = i32
         L.dqrm_check_status.argtypes = [vp, C.POINTER(i32), C.POINTER(i64)]
         for n in ("dqrm_find_scale", "dqrm_pack_int4", "dqrm_embbag_fwd", "dqrm_embbag_bwd", "dqrm_dedupe", "dqrm_segment_sum",
                   "dqrm_quant_update", "dqrm_grad_quant_int8", "dqrm_sparse_update", "dqrm_check_status"):
@@ -265,6 +276,34 @@ def dqrm_dense_step(model: DenseModel, batch: int, dense_x: torch.Tensor, emb_ou
     _check(lib().dqrm_dense_step(model.ref, batch, _ptr(dense_x), _ptr(emb_out), _ptr(labels), lr, _ptr(loss),
                                  _ptr(grad_emb), _ptr(workspace), workspace.numel() * workspace.element_size(),
                                  _stream(stream)), "dqrm_dense_step")
+
+
+def dqrm_dense_param_count(model: DenseModel) -> int:
+    return int(lib().dqrm_dense_param_count(model.ref))
+
+
+class DenseQuant:
+    """Descriptor of the quantised variants of the dense step; the tensors (device) stay owned by the caller."""
+
+    def __init__(self, weight_bits: int = 0, grad_bits: int = 0, grad_error: Optional[torch.Tensor] = None,
+                 grad_scale: Optional[torch.Tensor] = None, grad_codes: Optional[torch.Tensor] = None,
+                 grads: Optional[torch.Tensor] = None, wq: Optional[torch.Tensor] = None):
+        self._keep = (grad_error, grad_scale, grad_codes, grads, wq)
+        p = lambda t: t.data_ptr() if t is not None else None
+        self.c = dqrm_dense_quant_t(weight_bits, grad_bits, p(grad_error), p(grad_scale), p(grad_codes), p(grads), p(wq))
+
+    @property
+    def ref(self):
+        return C.byref(self.c)
+
+
+def dqrm_dense_step_quant(model: DenseModel, quant: Optional[DenseQuant], batch: int, dense_x: torch.Tensor,
+                          emb_out: torch.Tensor, labels: torch.Tensor, lr: float, loss: torch.Tensor,
+                          grad_emb: torch.Tensor, workspace: torch.Tensor, stream=None) -> None:
+    _check(lib().dqrm_dense_step_quant(model.ref, quant.ref if quant is not None else None, batch, _ptr(dense_x),
+                                       _ptr(emb_out), _ptr(labels), lr, _ptr(loss), _ptr(grad_emb), _ptr(workspace),
+                                       workspace.numel() * workspace.element_size(), _stream(stream)),
+           "dqrm_dense_step_quant")
 
 
 def dqrm_check_status(stream=None) -> Tuple[int, int, int]:

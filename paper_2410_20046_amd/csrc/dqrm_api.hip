@@ -511,8 +511,19 @@ struct DenseLayout {
     size_t bot_act[kMaxMlpLayers], top_act[kMaxMlpLayers], R;
     size_t bot_dz[kMaxMlpLayers], top_dz[kMaxMlpLayers], dR;
     size_t bot_part[kMaxMlpLayers], top_part[kMaxMlpLayers];
+    // the quantised variants: fake-quantised weights (layers in flat order), flat FP32 gradients, per-tensor maxima
+    size_t wq, grads, gmax;
     size_t total;
 };
+
+// flat parameter order (see dqrm_dense_quant_t): top layers, then bottom layers
+int64_t dense_param_count(const dqrm_dense_model_t *m)
+{
+    int64_t p = 0;
+    for (int l = 0; l < m->top_layers; ++l) p += (int64_t)m->top_dims[l + 1] * (m->top_dims[l] + 1);
+    for (int l = 0; l < m->bot_layers; ++l) p += (int64_t)m->bot_dims[l + 1] * (m->bot_dims[l] + 1);
+    return p;
+}
 
 // slices of the batch dimension in a weight-gradient product: about eight reduction slabs per slice, at
 // least two (the kernel stores partial tiles only when the reduction is split; a slice may be empty)
@@ -567,6 +578,10 @@ DenseLayout dense_layout(const dqrm_dense_model_t *m, int32_t batch)
         L.top_dz[l] = take((size_t)batch * m->top_dims[l + 1]);
         L.top_part[l] = take(splits * (size_t)m->top_dims[l + 1] * (m->top_dims[l] + 1));
     }
+    const size_t P = (size_t)dense_param_count(m);
+    L.wq = take(P);
+    L.grads = take(P);
+    L.gmax = take(dqrm::kMaxGradTensors);
     L.total = o;
     return L;
 }
@@ -644,12 +659,29 @@ size_t dqrm_dense_workspace_bytes(const dqrm_dense_model_t *model, int32_t batch
     return dense_layout(model, batch).total;
 }
 
+int64_t dqrm_dense_param_count(const dqrm_dense_model_t *model)
+{
+    if (check_dense_model(model, 1) != DQRM_OK) return -1;
+    return dense_param_count(model);
+}
+
 int32_t dqrm_dense_step(const dqrm_dense_model_t *m, int32_t batch, const float *dense_x, const float *emb_out,
                         const float *labels, float lr, float *loss, float *grad_emb, void *workspace,
                         size_t workspace_bytes, void *stream)
 {
+    return dqrm_dense_step_quant(m, nullptr, batch, dense_x, emb_out, labels, lr, loss, grad_emb, workspace,
+                                 workspace_bytes, stream);
+}
+
+int32_t dqrm_dense_step_quant(const dqrm_dense_model_t *m, const dqrm_dense_quant_t *quant, int32_t batch,
+                              const float *dense_x, const float *emb_out, const float *labels, float lr, float *loss,
+                              float *grad_emb, void *workspace, size_t workspace_bytes, void *stream)
+{
     int32_t rc = check_dense_model(m, batch);
     if (rc != DQRM_OK) return rc;
+    const int wbits = quant ? quant->weight_bits : 0, gbits = quant ? quant->grad_bits : 0;
+    if ((wbits != 0 && wbits != 4 && wbits != 8) || (gbits != 0 && gbits != 8)) return DQRM_ERR_UNSUPPORTED;
+    if (gbits == 8 && !quant->grad_scale) return DQRM_ERR_INVALID_ARG;
     if (!dense_x || !emb_out || !labels || !loss || !grad_emb || !workspace || !aligned(workspace, 256))
         return DQRM_ERR_INVALID_ARG;
     const DenseLayout L = dense_layout(m, batch);
@@ -659,10 +691,44 @@ int32_t dqrm_dense_step(const dqrm_dense_model_t *m, int32_t batch, const float 
     auto F = [&](size_t off) { return reinterpret_cast<float *>(ws + off); };
     const int B = batch, T = m->num_tables, D = m->dim;
 
+    // ---- the weights the forward and the input gradients use: the model's, or their fake-quantised copies
+    const float *top_wf[kMaxMlpLayers], *bot_wf[kMaxMlpLayers];
+    for (int l = 0; l < m->top_layers; ++l) top_wf[l] = m->top_w[l];
+    for (int l = 0; l < m->bot_layers; ++l) bot_wf[l] = m->bot_w[l];
+    if (wbits) {
+        float *wq = quant->wq ? quant->wq : F(L.wq);
+        dqrm::FqGroup fq{};
+        fq.qmax = (float)((1 << (wbits - 1)) - 1);
+        int rows = 0;
+        auto flush_fq = [&]() -> hipError_t {
+            if (fq.count == 0) return hipSuccess;
+            fq.total_rows = rows;
+            hipLaunchKernelGGL(dqrm::mlp_fake_quant_kernel, dim3((rows + 3) / 4), dim3(256), 0, st, fq);
+            fq.count = 0;
+            rows = 0;
+            return hipGetLastError();
+        };
+        auto add_fq = [&](const float *W, const float **wf, int in, int out) -> hipError_t {
+            hipError_t e = hipSuccess;
+            if (fq.count == dqrm::kGemmMaxGroup) e = flush_fq();
+            dqrm::FqLayer &q = fq.l[fq.count++];
+            q.W = W, q.Wq = wq, q.out = out, q.in = in, q.row_begin = rows;
+            rows += out;
+            *wf = wq;
+            wq += (size_t)out * in;
+            return e;
+        };
+        for (int l = 0; l < m->top_layers; ++l)
+            DQRM_HIP_CHECK(add_fq(m->top_w[l], &top_wf[l], m->top_dims[l], m->top_dims[l + 1]));
+        for (int l = 0; l < m->bot_layers; ++l)
+            DQRM_HIP_CHECK(add_fq(m->bot_w[l], &bot_wf[l], m->bot_dims[l], m->bot_dims[l + 1]));
+        DQRM_HIP_CHECK(flush_fq());
+    }
+
     // ---- forward
     const float *x = dense_x;
     for (int l = 0; l < m->bot_layers; ++l) {
-        DQRM_HIP_CHECK(linear_fwd(st, x, m->bot_w[l], m->bot_b[l], F(L.bot_act[l]), B, m->bot_dims[l], m->bot_dims[l + 1], true));
+        DQRM_HIP_CHECK(linear_fwd(st, x, bot_wf[l], m->bot_b[l], F(L.bot_act[l]), B, m->bot_dims[l], m->bot_dims[l + 1], true));
         x = F(L.bot_act[l]);
     }
     dqrm::InteractArgs ia{};
@@ -670,25 +736,27 @@ int32_t dqrm_dense_step(const dqrm_dense_model_t *m, int32_t batch, const float 
     hipLaunchKernelGGL(dqrm::interact_fwd_kernel, dim3(B), dim3(dqrm::kInterThreads), 0, st, ia);
     x = F(L.R);
     for (int l = 0; l < m->top_layers; ++l) {
-        DQRM_HIP_CHECK(linear_fwd(st, x, m->top_w[l], m->top_b[l], F(L.top_act[l]), B, m->top_dims[l], m->top_dims[l + 1],
+        DQRM_HIP_CHECK(linear_fwd(st, x, top_wf[l], m->top_b[l], F(L.top_act[l]), B, m->top_dims[l], m->top_dims[l + 1],
                                   l + 1 < m->top_layers));
         x = F(L.top_act[l]);
     }
-    hipLaunchKernelGGL(dqrm::bce_kernel, dim3(1), dim3(256), 0, st, x, labels, B, F(L.top_dz[m->top_layers - 1]), loss);
+    unsigned *gmax = reinterpret_cast<unsigned *>(ws + L.gmax);
+    hipLaunchKernelGGL(dqrm::bce_kernel, dim3(1), dim3(256), 0, st, x, labels, B, F(L.top_dz[m->top_layers - 1]), loss,
+                       gmax, gbits ? dqrm::kMaxGradTensors : 0);
 
     // ---- backward: the chain of input gradients first (dZ = gradient w.r.t. a layer's pre-activation) ...
     for (int l = m->top_layers - 1; l >= 0; --l) {
         const float *in_act = l > 0 ? F(L.top_act[l - 1]) : F(L.R);
         float *dX = l > 0 ? F(L.top_dz[l - 1]) : F(L.dR);
         // the input of top layer l > 0 is a ReLU output: mask; the interaction output is not
-        DQRM_HIP_CHECK(linear_bwd_input(st, F(L.top_dz[l]), m->top_w[l], l > 0 ? in_act : nullptr, dX, B,
+        DQRM_HIP_CHECK(linear_bwd_input(st, F(L.top_dz[l]), top_wf[l], l > 0 ? in_act : nullptr, dX, B,
                                         m->top_dims[l], m->top_dims[l + 1]));
     }
     const float *bot_out = F(L.bot_act[m->bot_layers - 1]);
     ia.dR = F(L.dR), ia.dbot = F(L.bot_dz[m->bot_layers - 1]), ia.demb = grad_emb, ia.bot_mask = bot_out;
     hipLaunchKernelGGL(dqrm::interact_bwd_kernel, dim3(B), dim3(dqrm::kInterThreads), 0, st, ia);
     for (int l = m->bot_layers - 1; l > 0; --l)
-        DQRM_HIP_CHECK(linear_bwd_input(st, F(L.bot_dz[l]), m->bot_w[l], F(L.bot_act[l - 1]), F(L.bot_dz[l - 1]), B,
+        DQRM_HIP_CHECK(linear_bwd_input(st, F(L.bot_dz[l]), bot_wf[l], F(L.bot_act[l - 1]), F(L.bot_dz[l - 1]), B,
                                         m->bot_dims[l], m->bot_dims[l + 1]));
 
     // ... then every layer's weight gradient in one launch and the SGD step in another (the input gradients
@@ -697,13 +765,27 @@ int32_t dqrm_dense_step(const dqrm_dense_model_t *m, int32_t batch, const float 
     dqrm::GemmGroup wg{};
     dqrm::SgdGroup sg{};
     sg.lr = lr;
+    if (gbits) {
+        sg.grads = quant->grads ? quant->grads : F(L.grads);
+        sg.err = quant->grad_error;
+        sg.codes = quant->grad_codes;
+        sg.gmax_bits = gmax;
+        sg.grad_scale = quant->grad_scale;
+    }
+    long long flat = 0;
+    int tensor = 0;
     hipError_t launch_err = hipSuccess;
     auto flush = [&]() {
         if (wg.count == 0) return;
         hipError_t e = launch_gemm_group<false, false>(st, wg);
         if (e != hipSuccess && launch_err == hipSuccess) launch_err = e;
-        hipLaunchKernelGGL(dqrm::sgd_from_partials_kernel,
-                           dim3((unsigned)std::min<long long>((sg.total + 255) / 256, 2048)), dim3(256), 0, st, sg);
+        const dim3 sgd_grid((unsigned)std::min<long long>((sg.total + 255) / 256, 2048));
+        if (gbits) {
+            hipLaunchKernelGGL(dqrm::grad_sum_absmax_kernel, sgd_grid, dim3(256), 0, st, sg);
+            hipLaunchKernelGGL(dqrm::grad_quant_ec_kernel, sgd_grid, dim3(256), 0, st, sg);
+        } else {
+            hipLaunchKernelGGL(dqrm::sgd_from_partials_kernel, sgd_grid, dim3(256), 0, st, sg);
+        }
         e = hipGetLastError();
         if (e != hipSuccess && launch_err == hipSuccess) launch_err = e;
         wg.count = 0;
@@ -716,7 +798,10 @@ int32_t dqrm_dense_step(const dqrm_dense_model_t *m, int32_t batch, const float 
         wg.p[wg.count++] = g;
         dqrm::SgdLayer &s = sg.l[sg.count++];
         s.P = part, s.W = W, s.b = b, s.S = g.splits, s.out = out, s.in = in, s.elem_begin = sg.total;
+        s.flat_begin = flat, s.tensor0 = tensor;
         sg.total += (long long)out * (in + 1);
+        flat += (long long)out * (in + 1);
+        tensor += 2;
     };
     for (int l = 0; l < m->top_layers; ++l)
         add_layer(F(L.top_dz[l]), l > 0 ? F(L.top_act[l - 1]) : F(L.R), m->top_w[l], m->top_b[l], F(L.top_part[l]),

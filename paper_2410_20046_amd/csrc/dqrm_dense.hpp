@@ -281,31 +281,151 @@ struct SgdLayer {
     const float *P;
     float *W, *b;
     int S, out, in;
-    long long elem_begin;
+    long long elem_begin; // first element of the layer in this launch's index space
+    long long flat_begin; // ... in the model's flat parameter order (see dqrm_dense_quant_t)
+    int tensor0;          // index of the layer's weight tensor in that order (its bias is tensor0 + 1)
 };
 struct SgdGroup {
     SgdLayer l[kGemmMaxGroup];
     int count;
     long long total;
     float lr;
+    // INT8 gradients with error compensation (distributed-training section): flat arrays over the model
+    float *grads;        // [P] this step's FP32 gradients (before the residual is added)
+    float *err;          // [P] residuals carried between steps, or null
+    int8_t *codes;       // [P] INT8 codes out, or null
+    unsigned *gmax_bits; // [tensors] running max |g + e| per tensor, as bit patterns (zeroed before the step)
+    float *grad_scale;   // [tensors] out
 };
+
+// which layer of the group element e belongs to, and where inside it
+struct SgdElem {
+    int q, o, i; // layer, output row, input column (i == in: the bias)
+    long long le;
+};
+__device__ __forceinline__ SgdElem sgd_elem(const SgdGroup &grp, long long e)
+{
+    SgdElem r;
+    r.q = 0;
+#pragma unroll 1
+    for (int k = 1; k < grp.count; ++k)
+        if (e >= grp.l[k].elem_begin) r.q = k;
+    const SgdLayer &L = grp.l[r.q];
+    r.le = e - L.elem_begin;
+    r.o = (int)(r.le / (L.in + 1));
+    r.i = (int)(r.le - (long long)r.o * (L.in + 1));
+    return r;
+}
+
+__device__ __forceinline__ float sum_partials(const SgdLayer &L, long long le)
+{
+    const long long per = (long long)L.out * (L.in + 1);
+    float s = 0.0f;
+    for (int z = 0; z < L.S; ++z) s += L.P[(long long)z * per + le];
+    return s;
+}
 
 __global__ __launch_bounds__(256) void sgd_from_partials_kernel(SgdGroup grp)
 {
     for (long long e = (long long)blockIdx.x * 256 + threadIdx.x; e < grp.total; e += (long long)gridDim.x * 256) {
-        int q = 0;
-#pragma unroll 1
-        for (int k = 1; k < grp.count; ++k)
-            if (e >= grp.l[k].elem_begin) q = k;
-        const SgdLayer &L = grp.l[q];
-        const long long le = e - L.elem_begin, per = (long long)L.out * (L.in + 1);
-        float s = 0.0f;
-        for (int z = 0; z < L.S; ++z) s += L.P[(long long)z * per + le];
-        const int o = (int)(le / (L.in + 1)), i = (int)(le - (long long)o * (L.in + 1));
-        if (i < L.in)
-            L.W[(long long)o * L.in + i] = L.W[(long long)o * L.in + i] - grp.lr * s;
+        const SgdElem x = sgd_elem(grp, e);
+        const SgdLayer &L = grp.l[x.q];
+        const float s = sum_partials(L, x.le);
+        if (x.i < L.in)
+            L.W[(long long)x.o * L.in + x.i] = L.W[(long long)x.o * L.in + x.i] - grp.lr * s;
         else
-            L.b[o] = L.b[o] - grp.lr * s;
+            L.b[x.o] = L.b[x.o] - grp.lr * s;
+    }
+}
+
+// INT8 gradients, pass 1: the FP32 gradient of every parameter (slices added in order) goes to `grads`,
+// and the maximum of |gradient + residual| of every tensor to gmax_bits (per-block maxima in LDS first).
+constexpr int kMaxGradTensors = 2 * 2 * 16; // weights and bias of at most 16 + 16 layers
+__global__ __launch_bounds__(256) void grad_sum_absmax_kernel(SgdGroup grp)
+{
+    __shared__ unsigned s_max[kMaxGradTensors];
+    for (int k = threadIdx.x; k < kMaxGradTensors; k += 256) s_max[k] = 0u;
+    __syncthreads();
+    for (long long e = (long long)blockIdx.x * 256 + threadIdx.x; e < grp.total; e += (long long)gridDim.x * 256) {
+        const SgdElem x = sgd_elem(grp, e);
+        const SgdLayer &L = grp.l[x.q];
+        const float s = sum_partials(L, x.le);
+        const long long f = L.flat_begin + x.le;
+        grp.grads[f] = s;
+        const float gp = grp.err ? s + grp.err[f] : s;
+        const unsigned b = __float_as_uint(fabsf(gp));
+        const int t = L.tensor0 + (x.i < L.in ? 0 : 1);
+        if (b > s_max[t]) atomicMax(s_max + t, b);
+    }
+    __syncthreads();
+    for (int k = threadIdx.x; k < kMaxGradTensors; k += 256)
+        if (s_max[k] != 0u) atomicMax(grp.gmax_bits + k, s_max[k]);
+}
+
+// pass 2: g' = g + e;  s = max(max|g'| / 127, 1e-8);  code = clamp(rint(g' / s), -128, 127);
+// e <- g' - s * code;  parameter <- parameter - lr * (s * code)   (every operation rounded on its own)
+__global__ __launch_bounds__(256) void grad_quant_ec_kernel(SgdGroup grp)
+{
+    __shared__ Scale s_scale[kMaxGradTensors];
+    // the tensors of this launch's layers
+    for (int k = threadIdx.x; k < 2 * grp.count; k += 256) {
+        const int t = grp.l[k >> 1].tensor0 + (k & 1);
+        const float gs = scale_from_absmax(__uint_as_float(grp.gmax_bits[t]), 127.0f);
+        s_scale[t] = Scale(gs);
+        if (blockIdx.x == 0) grp.grad_scale[t] = gs;
+    }
+    __syncthreads();
+    for (long long e = (long long)blockIdx.x * 256 + threadIdx.x; e < grp.total; e += (long long)gridDim.x * 256) {
+        const SgdElem x = sgd_elem(grp, e);
+        const SgdLayer &L = grp.l[x.q];
+        const long long f = L.flat_begin + x.le;
+        const Scale sc = s_scale[L.tensor0 + (x.i < L.in ? 0 : 1)];
+        const float g = grp.grads[f];
+        const float gp = grp.err ? g + grp.err[f] : g;
+        const int c = int8_code_fresh(gp, sc); // the scale comes from the maximum of these very values
+        if (grp.codes) grp.codes[f] = (int8_t)c;
+        const float deq = sc.s * (float)c;
+        if (grp.err) grp.err[f] = gp - deq;
+        const float step = grp.lr * deq;
+        float *p = x.i < L.in ? L.W + (long long)x.o * L.in + x.i : L.b + x.o;
+        *p = *p - step;
+    }
+}
+
+// ---- channel-wise fake quantisation of the linear layers' weights (model-quantisation appendix) ------
+// One scale per output row: s_o = max(max_i |W[o][i]| / qmax, 1e-8), Wq[o][i] = s_o * clamp(rint(W[o][i] / s_o)).
+// One wave per row, all layers in one launch.
+struct FqLayer {
+    const float *W;
+    float *Wq;
+    int out, in, row_begin;
+};
+struct FqGroup {
+    FqLayer l[kGemmMaxGroup];
+    int count, total_rows;
+    float qmax; // 7 or 127; the lowest code is -qmax - 1
+};
+
+__global__ __launch_bounds__(256) void mlp_fake_quant_kernel(FqGroup grp)
+{
+    const int lane = threadIdx.x & (kWave - 1);
+    const int row = __builtin_amdgcn_readfirstlane((int)(blockIdx.x * (256 / kWave) + threadIdx.x / kWave));
+    if (row >= grp.total_rows) return;
+    int q = 0;
+#pragma unroll 1
+    for (int k = 1; k < grp.count; ++k)
+        if (row >= grp.l[k].row_begin) q = k;
+    const FqLayer &L = grp.l[q];
+    const float *w = L.W + (long long)(row - L.row_begin) * L.in;
+    float *wq = L.Wq + (long long)(row - L.row_begin) * L.in;
+    float m = 0.0f;
+    for (int i = lane; i < L.in; i += kWave) m = fmaxf(m, fabsf(w[i]));
+    m = wave_max(m);
+    const Scale sc(scale_from_absmax(m, grp.qmax));
+    for (int i = lane; i < L.in; i += kWave) {
+        // a fresh scale: no quotient beyond qmax (1 + 2^-23)
+        const int c = code_i<false>(w[i], sc, -grp.qmax - 1.0f, grp.qmax);
+        wq[i] = sc.s * (float)c;
     }
 }
 
@@ -384,10 +504,14 @@ __global__ __launch_bounds__(kInterThreads) void interact_bwd_kernel(InteractArg
 // ---- sigmoid + mean binary cross-entropy -------------------------------------------
 // p = 1 / (1 + exp(-z)); loss = -mean(y log max(p, 1e-12) + (1-y) log max(1-p, 1e-12));
 // dz = (p - y) / B.  One block; B is a few thousand.
+// (It also clears the `nzero` words at `zero`: the per-tensor gradient maxima of the INT8-gradient path,
+// which are accumulated later in the same step.)
 __global__ __launch_bounds__(256) void bce_kernel(const float *__restrict__ z, const float *__restrict__ y, int B,
-                                                  float *__restrict__ dz, float *__restrict__ loss)
+                                                  float *__restrict__ dz, float *__restrict__ loss,
+                                                  unsigned *__restrict__ zero, int nzero)
 {
     __shared__ float part[256];
+    for (int k = threadIdx.x; k < nzero; k += 256) zero[k] = 0u;
     float s = 0.0f;
     for (int b = threadIdx.x; b < B; b += 256) {
         const float p = 1.0f / (1.0f + expf(-z[b]));

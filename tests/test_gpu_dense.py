@@ -112,3 +112,143 @@ def test_full_train_step_kaggle_shape(oracle):
     assert_exact(run.master_np().view(np.uint32), Wo.view(np.uint32), "master bits after the step")
     assert_exact(run.packed_np(), po, "packed bytes after the step")
     assert run.status()[0] == 0
+
+
+# --------------------------------------------------------------------------------------------------
+# the quantised variants of the dense part: channel-wise INT4 weights, INT8 gradients + error compensation
+# --------------------------------------------------------------------------------------------------
+def _flat_layers(bot_dims, top_dims):
+    """(name, layer, in, out) in the flat parameter order of the C ABI: top layers, then bottom layers."""
+    order = [("top", l, top_dims[l], top_dims[l + 1]) for l in range(len(top_dims) - 1)]
+    return order + [("bot", l, bot_dims[l], bot_dims[l + 1]) for l in range(len(bot_dims) - 1)]
+
+
+def _split_flat(flat, bot_dims, top_dims):
+    """flat [P] in the C ABI's order -> {(name, l): (W-part [out][in], bias-part [out])}."""
+    out, o = {}, 0
+    for name, l, i_, o_ in _flat_layers(bot_dims, top_dims):
+        blk = flat[o:o + o_ * (i_ + 1)].reshape(o_, i_ + 1)
+        out[(name, l)] = (np.ascontiguousarray(blk[:, :i_]), np.ascontiguousarray(blk[:, i_]))
+        o += o_ * (i_ + 1)
+    assert o == flat.size
+    return out
+
+
+@pytest.mark.parametrize("bits", [4, 8])
+def test_dense_step_channelwise_weight_quant(oracle, bits):
+    """weight_bits = 4 / 8: the fake-quantised weights the GPU used equal the oracle's bit for bit; loss, the
+    gradient w.r.t. the embeddings and the stepped FP32 weights match the float64 oracle that runs forward and
+    input gradients through those quantised weights (straight-through)."""
+    import torch
+    import paper_2410_20046_amd as dq
+
+    T, D, B = 5, 8, 200
+    _say(f"dense step, channel-wise INT{bits} weights")
+    bot_dims, bw, bb, top_dims, tw, tb = make_dense_model("small8", T, D, seed=1005)
+    x, y = dense_batch(B, bot_dims[0], seed=1005, k=0)
+    emb = (np.random.default_rng(5).standard_normal((B, T, D)) * 0.25).astype(np.float32)
+    dev = torch.device("cuda:0")
+    m = dq.DenseModel(T, D, bot_dims, bw, bb, top_dims, tw, tb, dev)
+    n_w = sum(w.size for w in tw + bw)
+    wq_d = torch.zeros(n_w, dtype=torch.float32, device=dev)
+    q = dq.DenseQuant(weight_bits=bits, wq=wq_d)
+    ws = torch.empty(dq.dqrm_dense_workspace_bytes(m, B), dtype=torch.uint8, device=dev)
+    loss = torch.zeros(1, dtype=torch.float32, device=dev)
+    grad = torch.empty((B, T, D), dtype=torch.float32, device=dev)
+    xd, ed, yd = (torch.from_numpy(a).to(dev) for a in (x, emb, y))
+    dq.dqrm_dense_step_quant(m, q, B, xd, ed, yd, 0.1, loss, grad, ws)
+    torch.cuda.synchronize()
+    # the quantised weights, layer by layer (top first)
+    wq = wq_d.cpu().numpy()
+    o = 0
+    twq, bwq = [], []
+    for name, l, i_, o_ in _flat_layers(bot_dims, top_dims):
+        W = (tw if name == "top" else bw)[l]
+        exp, _, _ = oracle.mlp_fake_quant(np.ascontiguousarray(W, np.float32), bits)
+        got = wq[o:o + o_ * i_].reshape(o_, i_)
+        # value-exact (the sign of a zero weight is not compared: s * code with code 0 from a negative weight
+        # is -0 in the oracle's float arithmetic and +0 from the kernel's integer code)
+        assert_exact(got, exp, f"{name}[{l}] fake-quantised weights")
+        (twq if name == "top" else bwq).append(exp)
+        o += o_ * i_
+    assert any(not np.array_equal(a, b) for a, b in zip(twq + bwq, tw + bw))
+    f64 = lambda l: [np.ascontiguousarray(a, np.float64) for a in l]
+    BW, BB, TW, TB = f64(bw), f64(bb), f64(tw), f64(tb)
+    loss_o, grad_o = oracle.dense_step_ex(bot_dims, BW, BB, top_dims, TW, TB, x, emb, y, 0.1, bot_wf=f64(bwq),
+                                          top_wf=f64(twq))
+    loss_g = float(loss.cpu().item())
+    assert abs(loss_g - loss_o) <= 1e-6 + 1e-5 * abs(loss_o), (loss_g, loss_o)
+    assert_float_close(grad.cpu().numpy(), grad_o, "grad_emb")
+    for name, got, exp in (("bot_w", m.bot_w, BW), ("bot_b", m.bot_b, BB), ("top_w", m.top_w, TW), ("top_b", m.top_b, TB)):
+        for l, (g, e) in enumerate(zip(got, exp)):
+            assert_float_close(g.cpu().numpy(), e, f"{name}[{l}] after SGD")
+
+
+def test_dense_step_int8_gradients_with_error_compensation(oracle):
+    """grad_bits = 8 over three consecutive steps (so the residuals are live).  Every step: the FP32 gradients
+    match the float64 oracle; then, stage-isolated on the GPU's own gradient bytes, the oracle's INT8 + error
+    compensation gives the same codes, scales, residuals and stepped parameters bit for bit."""
+    import torch
+    import paper_2410_20046_amd as dq
+
+    T, D, B = 3, 16, 37
+    bot_dims, bw, bb, top_dims, tw, tb = make_dense_model("small", T, D, seed=1005)
+    dev = torch.device("cuda:0")
+    m = dq.DenseModel(T, D, bot_dims, bw, bb, top_dims, tw, tb, dev)
+    P = dq.dqrm_dense_param_count(m)
+    assert P == sum(w.size for w in tw + bw) + sum(b.size for b in tb + bb)
+    n_t = 2 * (len(tw) + len(bw))
+    err_d = torch.zeros(P, dtype=torch.float32, device=dev)
+    scale_d = torch.zeros(n_t, dtype=torch.float32, device=dev)
+    codes_d = torch.zeros(P, dtype=torch.int8, device=dev)
+    grads_d = torch.zeros(P, dtype=torch.float32, device=dev)
+    q = dq.DenseQuant(grad_bits=8, grad_error=err_d, grad_scale=scale_d, grad_codes=codes_d, grads=grads_d)
+    ws = torch.empty(dq.dqrm_dense_workspace_bytes(m, B), dtype=torch.uint8, device=dev)
+    loss = torch.zeros(1, dtype=torch.float32, device=dev)
+    grad = torch.empty((B, T, D), dtype=torch.float32, device=dev)
+    lr = 0.5
+    params = lambda: {("top", l): (m.top_w[l].cpu().numpy(), m.top_b[l].cpu().numpy()) for l in range(len(tw))} | \
+                     {("bot", l): (m.bot_w[l].cpu().numpy(), m.bot_b[l].cpu().numpy()) for l in range(len(bw))}
+    err_o = _split_flat(np.zeros(P, np.float32), bot_dims, top_dims)
+    nonzero_residual_used = False
+    for k in range(3):
+        _say(f"dense step, INT8 gradients + error compensation, step {k}")
+        x, y = dense_batch(B, bot_dims[0], seed=1005, k=k)
+        emb = (np.random.default_rng(50 + k).standard_normal((B, T, D)) * 0.25).astype(np.float32)
+        before = params()
+        xd, ed, yd = (torch.from_numpy(a).to(dev) for a in (x, emb, y))
+        dq.dqrm_dense_step_quant(m, q, B, xd, ed, yd, lr, loss, grad, ws)
+        torch.cuda.synchronize()
+        g_gpu = _split_flat(grads_d.cpu().numpy(), bot_dims, top_dims)
+        c_gpu = _split_flat(codes_d.cpu().numpy(), bot_dims, top_dims)
+        e_gpu = _split_flat(err_d.cpu().numpy(), bot_dims, top_dims)
+        s_gpu = scale_d.cpu().numpy()
+        after = params()
+        # 1. the FP32 gradients against the float64 oracle on the weights of before the step
+        f64 = lambda d, name, n: [np.ascontiguousarray(d[(name, l)][0], np.float64) for l in range(n)]
+        f64b = lambda d, name, n: [np.ascontiguousarray(d[(name, l)][1], np.float64) for l in range(n)]
+        BW, BB = f64(before, "bot", len(bw)), f64b(before, "bot", len(bw))
+        TW, TB = f64(before, "top", len(tw)), f64b(before, "top", len(tw))
+        loss_o, grad_o, (gbw, gbb, gtw, gtb) = oracle.dense_step_ex(bot_dims, BW, BB, top_dims, TW, TB, x, emb, y, lr,
+                                                                    apply_sgd=False, want_grads=True)
+        assert abs(float(loss.cpu().item()) - loss_o) <= 1e-6 + 1e-5 * abs(loss_o)
+        assert_float_close(grad.cpu().numpy(), grad_o, f"step {k} grad_emb")
+        for name, gw, gb in (("top", gtw, gtb), ("bot", gbw, gbb)):
+            for l in range(len(gw)):
+                assert_float_close(g_gpu[(name, l)][0], gw[l], f"step {k} {name}_w[{l}] gradient")
+                assert_float_close(g_gpu[(name, l)][1], gb[l], f"step {k} {name}_b[{l}] gradient")
+        # 2. stage-isolated: INT8 + error compensation on the GPU's own gradients
+        for t_idx, (name, l, i_, o_) in enumerate(_flat_layers(bot_dims, top_dims)):
+            for part, what in ((0, "weights"), (1, "bias")):
+                g = np.ascontiguousarray(g_gpu[(name, l)][part])
+                e = np.ascontiguousarray(err_o[(name, l)][part]).copy()
+                nonzero_residual_used |= bool(np.any(e != 0))
+                p = np.ascontiguousarray(before[(name, l)][part]).copy()
+                s, codes = oracle.mlp_grad_quant_ec(g, e, p, lr)
+                tag = f"step {k} {name}[{l}] {what}"
+                assert np.float32(s) == s_gpu[2 * t_idx + part], (tag, s, s_gpu[2 * t_idx + part])
+                assert_exact(c_gpu[(name, l)][part], codes, tag + " INT8 codes")
+                assert_exact(e_gpu[(name, l)][part].view(np.uint32), e.view(np.uint32), tag + " residual bits")
+                assert_exact(after[(name, l)][part].view(np.uint32), p.view(np.uint32), tag + " stepped parameter bits")
+                err_o[(name, l)] = tuple(e if j == part else err_o[(name, l)][j] for j in (0, 1))
+    assert nonzero_residual_used

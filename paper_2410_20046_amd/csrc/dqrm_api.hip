@@ -581,7 +581,7 @@ DenseLayout dense_layout(const dqrm_dense_model_t *m, int32_t batch)
     const size_t P = (size_t)dense_param_count(m);
     L.wq = take(P);
     L.grads = take(P);
-    L.gmax = take(dqrm::kMaxGradTensors);
+    L.gmax = take((size_t)dqrm::kMaxGradTensors * dqrm::kGradMaxStride);
     L.total = o;
     return L;
 }
@@ -742,7 +742,7 @@ int32_t dqrm_dense_step_quant(const dqrm_dense_model_t *m, const dqrm_dense_quan
     }
     unsigned *gmax = reinterpret_cast<unsigned *>(ws + L.gmax);
     hipLaunchKernelGGL(dqrm::bce_kernel, dim3(1), dim3(256), 0, st, x, labels, B, F(L.top_dz[m->top_layers - 1]), loss,
-                       gmax, gbits ? dqrm::kMaxGradTensors : 0);
+                       gmax, gbits ? dqrm::kMaxGradTensors * dqrm::kGradMaxStride : 0);
 
     // ---- backward: the chain of input gradients first (dZ = gradient w.r.t. a layer's pre-activation) ...
     for (int l = m->top_layers - 1; l >= 0; --l) {
@@ -781,7 +781,9 @@ int32_t dqrm_dense_step_quant(const dqrm_dense_model_t *m, const dqrm_dense_quan
         if (e != hipSuccess && launch_err == hipSuccess) launch_err = e;
         const dim3 sgd_grid((unsigned)std::min<long long>((sg.total + 255) / 256, 2048));
         if (gbits) {
-            hipLaunchKernelGGL(dqrm::grad_sum_absmax_kernel, sgd_grid, dim3(256), 0, st, sg);
+            // few workgroups: each one ends with a global atomic per tensor it met
+            const dim3 sum_grid((unsigned)std::min<long long>((sg.total + 255) / 256, 256));
+            hipLaunchKernelGGL(dqrm::grad_sum_absmax_kernel, sum_grid, dim3(256), 0, st, sg);
             hipLaunchKernelGGL(dqrm::grad_quant_ec_kernel, sgd_grid, dim3(256), 0, st, sg);
         } else {
             hipLaunchKernelGGL(dqrm::sgd_from_partials_kernel, sgd_grid, dim3(256), 0, st, sg);

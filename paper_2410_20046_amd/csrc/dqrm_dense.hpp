@@ -294,7 +294,8 @@ struct SgdGroup {
     float *grads;        // [P] this step's FP32 gradients (before the residual is added)
     float *err;          // [P] residuals carried between steps, or null
     int8_t *codes;       // [P] INT8 codes out, or null
-    unsigned *gmax_bits; // [tensors] running max |g + e| per tensor, as bit patterns (zeroed before the step)
+    unsigned *gmax_bits; // [tensors][kGradMaxStride] running max |g + e| per tensor (word 0 of each line), as bit
+                         // patterns, zeroed before the step
     float *grad_scale;   // [tensors] out
 };
 
@@ -341,11 +342,16 @@ __global__ __launch_bounds__(256) void sgd_from_partials_kernel(SgdGroup grp)
 // INT8 gradients, pass 1: the FP32 gradient of every parameter (slices added in order) goes to `grads`,
 // and the maximum of |gradient + residual| of every tensor to gmax_bits (per-block maxima in LDS first).
 constexpr int kMaxGradTensors = 2 * 2 * 16; // weights and bias of at most 16 + 16 layers
+constexpr int kGradMaxStride = 32;          // words between two tensors' maxima: one 128-byte line each (same-line
+                                            // atomics from many workgroups serialise at the memory side)
 __global__ __launch_bounds__(256) void grad_sum_absmax_kernel(SgdGroup grp)
 {
     __shared__ unsigned s_max[kMaxGradTensors];
     for (int k = threadIdx.x; k < kMaxGradTensors; k += 256) s_max[k] = 0u;
     __syncthreads();
+    // a thread keeps the running maximum of the tensor it is in and hands it over when the tensor changes
+    int cur_t = -1;
+    float cur_max = 0.0f;
     for (long long e = (long long)blockIdx.x * 256 + threadIdx.x; e < grp.total; e += (long long)gridDim.x * 256) {
         const SgdElem x = sgd_elem(grp, e);
         const SgdLayer &L = grp.l[x.q];
@@ -353,13 +359,25 @@ __global__ __launch_bounds__(256) void grad_sum_absmax_kernel(SgdGroup grp)
         const long long f = L.flat_begin + x.le;
         grp.grads[f] = s;
         const float gp = grp.err ? s + grp.err[f] : s;
-        const unsigned b = __float_as_uint(fabsf(gp));
         const int t = L.tensor0 + (x.i < L.in ? 0 : 1);
-        if (b > s_max[t]) atomicMax(s_max + t, b);
+        if (t != cur_t) {
+            if (cur_t >= 0 && cur_max > 0.0f) atomicMax(s_max + cur_t, __float_as_uint(cur_max));
+            cur_t = t;
+            cur_max = 0.0f;
+        }
+        cur_max = fmaxf(cur_max, fabsf(gp));
+    }
+    // usually the whole wave ends in one tensor: one LDS atomic per wave
+    const int tt = wave_max_int(cur_t);
+    if (__all(cur_t < 0 || cur_t == tt)) {
+        const float m = wave_max(cur_max);
+        if ((threadIdx.x & (kWave - 1)) == 0 && tt >= 0 && m > 0.0f) atomicMax(s_max + tt, __float_as_uint(m));
+    } else if (cur_t >= 0 && cur_max > 0.0f) {
+        atomicMax(s_max + cur_t, __float_as_uint(cur_max));
     }
     __syncthreads();
     for (int k = threadIdx.x; k < kMaxGradTensors; k += 256)
-        if (s_max[k] != 0u) atomicMax(grp.gmax_bits + k, s_max[k]);
+        if (s_max[k] != 0u) atomicMax(grp.gmax_bits + k * kGradMaxStride, s_max[k]);
 }
 
 // pass 2: g' = g + e;  s = max(max|g'| / 127, 1e-8);  code = clamp(rint(g' / s), -128, 127);
@@ -370,7 +388,7 @@ __global__ __launch_bounds__(256) void grad_quant_ec_kernel(SgdGroup grp)
     // the tensors of this launch's layers
     for (int k = threadIdx.x; k < 2 * grp.count; k += 256) {
         const int t = grp.l[k >> 1].tensor0 + (k & 1);
-        const float gs = scale_from_absmax(__uint_as_float(grp.gmax_bits[t]), 127.0f);
+        const float gs = scale_from_absmax(__uint_as_float(grp.gmax_bits[t * kGradMaxStride]), 127.0f);
         s_scale[t] = Scale(gs);
         if (blockIdx.x == 0) grp.grad_scale[t] = gs;
     }

@@ -62,6 +62,10 @@ def main():
     ap.add_argument("--pool", type=int, default=64, help="distinct index batches cycled")
     ap.add_argument("--grad-pool", type=int, default=8, help="distinct grad_out buffers cycled")
     ap.add_argument("--lr", type=float, default=0.1)
+    ap.add_argument("--pooling", type=int, default=1,
+                    help="indices per bag (pooling factor; the paper-shaped workloads have 1).  A table may have at "
+                         "most 16384 lookups per batch: lower --batch accordingly")
+    ap.add_argument("--batch", type=int, default=0, help="override the workload's batch size")
     ap.add_argument("--mlp-weight-bits", type=int, default=0, choices=[0, 4, 8],
                     help="with --dense: channel-wise fake quantisation of the MLP weights (dqrm_dense_step_quant)")
     ap.add_argument("--mlp-grad-bits", type=int, default=0, choices=[0, 8],
@@ -109,7 +113,7 @@ def main():
     torch.cuda.set_device(dev)
     dq.lib()  # fail loudly if the HIP library is missing
 
-    wl = make_workload(args.workload)
+    wl = make_workload(args.workload, **({"B": args.batch} if args.batch else {}))
     T, D, B = wl.T, wl.D, wl.B
     t0 = time.time()
     W = wl.tables(threads=16)
@@ -119,7 +123,8 @@ def main():
     tables = dq.Tables(wl.row_offsets, D, master, packed)
 
     t0 = time.time()
-    pool = [wl.batch(k) for k in range(args.pool)]
+    pool = [wl.batch(k) if args.pooling == 1 else wl.batch(k, pooling="fixed", max_len=args.pooling)
+            for k in range(args.pool)]
     N = len(pool[0][0])
     idx_d = [torch.from_numpy(i).to(dev) for i, _ in pool]
     off_d = [torch.from_numpy(o).to(dev) for _, o in pool]
@@ -451,7 +456,7 @@ def main():
         "config": {"workload": f"{args.workload}-shaped embedding layer: {T} tables, {wl.R} rows, dim {D}, batch {B}, "
                                f"1 Zipf index per table per sample, {args.mode}-mode forward, INT8 sparse grads, "
                                f"SGD lr {args.lr}, dedupe overlap: {args.overlap}",
-                   "lookups_per_step": N, "unique_rows_per_step": round(U, 1), "fwd_mode": args.mode, "overlap": args.overlap, "scale_refresh_period": args.refresh_period, "dense_part": bool(args.dense), "mlp_weight_bits": args.mlp_weight_bits, "mlp_grad_bits": args.mlp_grad_bits,
+                   "lookups_per_step": N, "unique_rows_per_step": round(U, 1), "fwd_mode": args.mode, "overlap": args.overlap, "scale_refresh_period": args.refresh_period, "pooling": args.pooling, "dense_part": bool(args.dense), "mlp_weight_bits": args.mlp_weight_bits, "mlp_grad_bits": args.mlp_grad_bits,
                    "update": ("dqrm_quant_update (one pass)" if args.fused else "dqrm_grad_quant_int8 + dqrm_sparse_update"),
                    "launch": (f"HIP graph of {graph_steps} steps replayed" if graph is not None else "eager launches")},
         "roofline": roofline,

@@ -173,7 +173,8 @@ class Workload:
 
         ``pooling="one"``: exactly one index per bag (all of the paper-shaped
         configs).  ``pooling="ragged"``: bag lengths uniform in [0, max_len],
-        so empty bags and uneven bags occur.
+        so empty bags and uneven bags occur.  ``pooling="fixed"``: every bag has
+        ``max_len`` indices (a pooling factor).
         """
         rng = _rng(self.seed, _STREAM_BATCH, k)
         T, B = self.T, self.B
@@ -181,6 +182,8 @@ class Workload:
             lens = np.ones(T * B, dtype=np.int64)
         elif pooling == "ragged":
             lens = rng.integers(0, max_len + 1, size=T * B, dtype=np.int64)
+        elif pooling == "fixed":
+            lens = np.full(T * B, max_len, dtype=np.int64)
         else:
             raise ValueError(pooling)
         offsets = np.concatenate([[0], np.cumsum(lens)]).astype(np.int64)

@@ -89,25 +89,6 @@ __device__ long long g_phase_ticks[16];
     } while (0)
 #endif
 
-// exclusive prefix sum over the threads of a block of kWaves waves; *total = sum of all
-template <int kWaves>
-__device__ __forceinline__ int block_excl_scan_add(int v, int lane, int wave, int *s_w, int *total)
-{
-    const int incl = wave_incl_scan_add(v, lane);
-    __syncthreads(); // s_w may still be read from a previous use
-    if (lane == kWave - 1) s_w[wave] = incl;
-    __syncthreads();
-    int base = 0, tot = 0;
-#pragma unroll
-    for (int w = 0; w < kWaves; ++w) {
-        const int x = s_w[w];
-        if (w < wave) base += x;
-        tot += x;
-    }
-    *total = tot;
-    return base + incl - v;
-}
-
 // One launch can dedupe several batches (blockIdx.y picks the batch): the work
 // depends only on the indices, and a table's sort occupies a single CU, so the
 // batches of the next few steps fill the chip where one batch would use T CUs.

@@ -170,6 +170,25 @@ __device__ __forceinline__ int wave_max_int(int v)
     return v;
 }
 
+// exclusive prefix sum over the threads of a block of kWaves waves; *total = sum of all
+template <int kWaves>
+__device__ __forceinline__ int block_excl_scan_add(int v, int lane, int wave, int *s_w, int *total)
+{
+    const int incl = wave_incl_scan_add(v, lane);
+    __syncthreads(); // s_w may still be read from a previous use
+    if (lane == kWave - 1) s_w[wave] = incl;
+    __syncthreads();
+    int base = 0, tot = 0;
+#pragma unroll
+    for (int w = 0; w < kWaves; ++w) {
+        const int x = s_w[w];
+        if (w < wave) base += x;
+        tot += x;
+    }
+    *total = tot;
+    return base + incl - v;
+}
+
 // lanes of the wave whose 8-bit digit equals mine (all 64 lanes must be active)
 __device__ __forceinline__ unsigned long long match_any8(unsigned d)
 {

@@ -13,8 +13,10 @@
 //   B  groups of G = pow2ceil(D/4) lanes walk the tile in output order; lane l
 //      of a group owns columns 4l..4l+3 (one 16-byte store per row).  The first
 //      rows of a whole batch of slots are requested before any is used;
-//   C  the bag's remaining lookups (none in the usual one-index-per-bag batch)
-//      are added in order, and the pooled row is stored.
+//   C  `out = 0 + s * q` is stored.  Tiles with a bag of more than one lookup take the
+//      general path instead: the tile's index lists are turned into checked row
+//      offsets in LDS by all threads (one more round trip for the whole tile), then
+//      every bag's rows are requested kFwdBagBatch at a time and added in order.
 // The per-column sum is the plain left-to-right sum over the bag, so no
 // cross-lane reduction is needed and the result does not depend on the mapping.
 #pragma once
@@ -40,6 +42,8 @@ constexpr int kFwdTileT = DQRM_FWD_TILE_T;         // tables per tile, at most
 constexpr int kFwdSlots = kFwdTileB * kFwdTileT;   // bags per tile, at most
 constexpr int kFwdThreads = DQRM_FWD_THREADS;
 constexpr int kFwdBatch = DQRM_FWD_BATCH;          // first rows in flight per lane
+constexpr int kFwdLdsLookups = 4096;               // lookups of a tile whose row offsets fit in LDS (general bags)
+constexpr int kFwdBagBatch = 8;                    // rows of one bag in flight per lane (general bags)
 
 struct FwdArgs {
     const float *master;
@@ -132,6 +136,10 @@ __global__ __launch_bounds__(kFwdThreads) void embbag_fwd_kernel(FwdArgs a)
     __shared__ float s_mul[kFwdSlots];   // table scale, or 0 when the first lookup is absent or invalid
     __shared__ unsigned char s_ok[kFwdSlots]; // the first lookup exists and is in range
     __shared__ int s_general;            // some bag of the tile has more than one lookup
+    __shared__ int64_t s_loff[kFwdLdsLookups]; // general bags: row byte offset of every lookup of the tile, -1 if bad
+    __shared__ int s_pos[kFwdSlots];     // ... where slot i's list starts in s_loff
+    __shared__ int s_w[kFwdThreads / kWave];
+    static_assert(kFwdSlots == kFwdThreads, "one slot per thread");
 
     const int tid = threadIdx.x;
     const int b0 = (int)blockIdx.x * kFwdTileB, t0 = (int)blockIdx.y * a.tile_t;
@@ -189,6 +197,39 @@ __global__ __launch_bounds__(kFwdThreads) void embbag_fwd_kernel(FwdArgs a)
     }
     __syncthreads();
 
+    // ---- general bags: the tile's lookups as checked row offsets in LDS ------------------
+    const bool general = s_general != 0 || a.codes != nullptr || a.no_rows != 0;
+    bool staged = false;
+    if (general && !a.no_rows) {
+        // position of every slot's list in s_loff (slots in output order; kFwdThreads == kFwdSlots)
+        const int my_len = tid < live ? s_len[tid] : 0;
+        int total;
+        const int pos = block_excl_scan_add<kFwdThreads / kWave>(my_len, tid & (kWave - 1), tid / kWave, s_w, &total);
+        s_pos[tid] = pos;
+        staged = total <= kFwdLdsLookups; // block-uniform
+        if (staged && my_len > 0) {
+            const int t = s_tab[tid];
+            const int64_t r0 = a.row_offsets[t], r1 = a.row_offsets[t + 1];
+            const int64_t beg = s_beg[tid];
+            for (int j0 = 0; j0 < my_len; j0 += kFwdBagBatch) {
+                int64_t idx[kFwdBagBatch];
+#pragma unroll
+                for (int j = 0; j < kFwdBagBatch; ++j) idx[j] = a.indices[beg + min(j0 + j, my_len - 1)];
+#pragma unroll
+                for (int j = 0; j < kFwdBagBatch; ++j) {
+                    if (j0 + j >= my_len) break;
+                    int64_t off = -1;
+                    if (idx[j] >= 0 && idx[j] < r1 - r0)
+                        off = (r0 + idx[j]) * row_bytes;
+                    else
+                        report(DQRM_ERR_INDEX_OUT_OF_RANGE, t, idx[j]);
+                    s_loff[pos + j0 + j] = off;
+                }
+            }
+        }
+        __syncthreads();
+    }
+
     // ---- phases B and C ------------------------------------------------------------
     constexpr int kGroups = kFwdThreads / G; // groups per workgroup
     const int lg = tid & (G - 1);
@@ -198,37 +239,59 @@ __global__ __launch_bounds__(kFwdThreads) void embbag_fwd_kernel(FwdArgs a)
     const char *tab = PACKED ? reinterpret_cast<const char *>(a.packed) + (col >> 1)
                              : reinterpret_cast<const char *>(a.master + col);
     float *out_col = a.out + col;
-    const bool general = s_general != 0 || a.codes != nullptr || a.no_rows != 0;
 
     if (!general) {
         fwd_single_lookup_tile<G, PACKED>(tab, s_off, s_scale, s_mul, s_slot, grp, out_col, a.D, live);
         return;
     }
 
-    // general bags: the remaining lookups are added in order; codes are written out when asked for
+    if (staged) {
+        // A bag's rows kFwdBagBatch at a time, none under a branch: a lookup past the bag's end or with a bad
+        // index reads row 0 and enters the sum as 0 * q, which leaves the sum as it is.
+        for (int i = grp; i < live; i += kGroups) {
+            const Scale sq = s_scale[i];
+            const int len = s_len[i], pos = s_pos[i];
+            const int64_t beg = s_beg[i];
+            float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
+            for (int j0 = 0; j0 < len; j0 += kFwdBagBatch) {
+                RowPiece<PACKED> piece[kFwdBagBatch];
+                float m[kFwdBagBatch];
+#pragma unroll
+                for (int j = 0; j < kFwdBagBatch; ++j) {
+                    const int64_t off = s_loff[pos + min(j0 + j, len - 1)];
+                    m[j] = (j0 + j < len && off >= 0) ? sq.s : 0.0f;
+                    piece[j].load(tab + (off >= 0 ? off : 0));
+                }
+#pragma unroll
+                for (int j = 0; j < kFwdBagBatch; ++j) {
+                    const float4 q = piece[j].codes(sq);
+                    acc.x = acc.x + m[j] * q.x;
+                    acc.y = acc.y + m[j] * q.y;
+                    acc.z = acc.z + m[j] * q.z;
+                    acc.w = acc.w + m[j] * q.w;
+                    if (a.codes && m[j] != 0.0f) store_codes(a.codes, beg + j0 + j, a.D, col, q);
+                }
+            }
+            const f32x4 v = {acc.x, acc.y, acc.z, acc.w};
+            __builtin_nontemporal_store(v, reinterpret_cast<f32x4 *>(out_col + (size_t)(unsigned)s_slot[i] * a.D));
+        }
+        return;
+    }
+
+    // general bags of a tile with too many lookups for LDS, or tables without rows: one lookup at a time
     for (int i = grp; i < live; i += kGroups) {
         const Scale sq = s_scale[i];
         const float s = sq.s;
         const int len = s_len[i];
         const int64_t beg = s_beg[i];
         float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
-        if (s_ok[i]) {
-            RowPiece<PACKED> piece;
-            piece.load(tab + s_off[i]);
-            const float4 q = piece.codes(sq);
-            acc.x = acc.x + s * q.x;
-            acc.y = acc.y + s * q.y;
-            acc.z = acc.z + s * q.z;
-            acc.w = acc.w + s * q.w;
-            if (a.codes) store_codes(a.codes, beg, a.D, col, q);
-        }
-        if (len > 1) {
+        if (len > 0 && !a.no_rows) {
             const int t = s_tab[i];
             const int64_t r0 = a.row_offsets[t], r1 = a.row_offsets[t + 1];
-            for (int64_t p = beg + 1; p < beg + len; ++p) {
+            for (int64_t p = beg; p < beg + len; ++p) {
                 const int64_t idx = a.indices[p];
                 if (idx < 0 || idx >= r1 - r0) {
-                    if (lg == 0) report(DQRM_ERR_INDEX_OUT_OF_RANGE, t, idx);
+                    if (lg == 0 && p > beg) report(DQRM_ERR_INDEX_OUT_OF_RANGE, t, idx); // (the first one: phase A)
                     continue;
                 }
                 RowPiece<PACKED> piece;

@@ -68,6 +68,19 @@ def test_dims_ragged_bags(oracle, D):
     full_step_parity(oracle, wl, W, idx, off, wl.grad_normal(1), stale=0.5, what=f"ragged D={D}")
 
 
+@pytest.mark.parametrize("L", [20, 40])
+def test_pooling_factor(oracle, L):
+    """Every bag holds L lookups.  A forward tile (16 samples x 8 tables) then has 2560 lookups (their row
+    offsets are staged in LDS, 4096 fit) or 5120 (they are not: one lookup at a time); packed and master mode,
+    debug codes on."""
+    cards = np.array([7, 900, 50000, 33, 4000, 120, 60000, 15], np.int64)
+    wl = Workload(name=f"pool{L}", T=8, D=16, B=64, alpha=1.05, seed=300 + L, cards=cards)
+    idx, off = wl.batch(0, pooling="fixed", max_len=L)
+    assert len(idx) == 8 * 64 * L
+    _say(f"pooling factor {L}: {len(idx)} lookups")
+    full_step_parity(oracle, wl, wl.tables(threads=1), idx, off, wl.grad_normal(0), what=f"pool{L}")
+
+
 def test_hot_segments_long_chunks(oracle):
     """tiny tables: segments of several hundred to several thousand lookups (many chunks per segment,
     the last-arrival combine), next to a table with no duplicates at all."""

@@ -501,7 +501,7 @@ int32_t dqrm_quant_update(const dqrm_tables_t *tables, int64_t capacity, int64_t
 namespace {
 
 constexpr int kMaxMlpLayers = 16;
-constexpr int kDenseMaxSplits = 16; // slices of the batch dimension in the weight-gradient products
+constexpr int kDenseMaxSplits = dqrm::kSgdMaxSlices; // slices of the batch dimension in the weight-gradient products
 
 struct DenseLayout {
     // activations: bot_act[l] = output of bottom layer l, R = interaction output, top_act[l] = output of top
@@ -781,9 +781,7 @@ int32_t dqrm_dense_step_quant(const dqrm_dense_model_t *m, const dqrm_dense_quan
         if (e != hipSuccess && launch_err == hipSuccess) launch_err = e;
         const dim3 sgd_grid((unsigned)std::min<long long>((sg.total + 255) / 256, 2048));
         if (gbits) {
-            // few workgroups: each one ends with a global atomic per tensor it met
-            const dim3 sum_grid((unsigned)std::min<long long>((sg.total + 255) / 256, 256));
-            hipLaunchKernelGGL(dqrm::grad_sum_absmax_kernel, sum_grid, dim3(256), 0, st, sg);
+            hipLaunchKernelGGL(dqrm::grad_sum_absmax_kernel, sgd_grid, dim3(256), 0, st, sg);
             hipLaunchKernelGGL(dqrm::grad_quant_ec_kernel, sgd_grid, dim3(256), 0, st, sg);
         } else {
             hipLaunchKernelGGL(dqrm::sgd_from_partials_kernel, sgd_grid, dim3(256), 0, st, sg);

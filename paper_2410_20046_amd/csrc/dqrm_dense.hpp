@@ -318,11 +318,20 @@ __device__ __forceinline__ SgdElem sgd_elem(const SgdGroup &grp, long long e)
     return r;
 }
 
+constexpr int kSgdMaxSlices = 16; // slices of a split product, at most (the host's limit)
+
+// the slices of one element, added in order; all of them are requested before the first is used (a slice
+// index past the last re-reads the last slice and is left out)
 __device__ __forceinline__ float sum_partials(const SgdLayer &L, long long le)
 {
     const long long per = (long long)L.out * (L.in + 1);
+    float p[kSgdMaxSlices];
+#pragma unroll
+    for (int z = 0; z < kSgdMaxSlices; ++z) p[z] = L.P[(long long)min(z, L.S - 1) * per + le];
     float s = 0.0f;
-    for (int z = 0; z < L.S; ++z) s += L.P[(long long)z * per + le];
+#pragma unroll
+    for (int z = 0; z < kSgdMaxSlices; ++z)
+        if (z < L.S) s += p[z];
     return s;
 }
 

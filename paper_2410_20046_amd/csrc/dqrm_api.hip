@@ -513,6 +513,7 @@ struct DenseLayout {
     size_t bot_part[kMaxMlpLayers], top_part[kMaxMlpLayers];
     // the quantised variants: fake-quantised weights (layers in flat order), flat FP32 gradients, per-tensor maxima
     size_t wq, grads, gmax;
+    size_t loss_terms; // per-sample loss
     size_t total;
 };
 
@@ -582,24 +583,36 @@ DenseLayout dense_layout(const dqrm_dense_model_t *m, int32_t batch)
     L.wq = take(P);
     L.grads = take(P);
     L.gmax = take((size_t)dqrm::kMaxGradTensors * dqrm::kGradMaxStride);
+    L.loss_terms = take((size_t)batch);
     L.total = o;
     return L;
 }
 
-// A_RC / B_RC: whether the reduction index is the unit-stride one of A / B in memory (otherwise the 32-wide
-// index i / j must be).  One launch for all problems of the group.
-template <bool A_RC, bool B_RC>
+// A_MODE / B_MODE: how A / B lie in memory and are read (dqrm::kOpRC: the reduction index is the unit-stride one;
+// kOpWide, kOpWideVec: the 32-wide index i / j is).  One launch for all problems of the group.
+template <int A_MODE, int B_MODE>
 hipError_t launch_gemm_group(hipStream_t st, dqrm::GemmGroup &grp)
 {
     int tiles = 0;
     for (int q = 0; q < grp.count; ++q) {
         dqrm::GemmArgs &g = grp.p[q];
+        if (g.b_ones_last && B_MODE != dqrm::kOpWide) return hipErrorInvalidValue; // only that form serves the virtual column
         g.tile_begin = tiles;
         tiles += ((g.M + 31) / 32) * ((g.N + 31) / 32) * g.splits;
     }
     grp.total_tiles = tiles;
     if (tiles == 0) return hipSuccess;
-    hipLaunchKernelGGL((dqrm::gemm_wave_kernel<A_RC, B_RC>), dim3((tiles + dqrm::kGemmWaves - 1) / dqrm::kGemmWaves),
+    // A product with fewer tiles than the chip has SIMDs (4 per CU) leaves some of them idle: let 2 or 4 waves
+    // share a tile, each with a slice of the reduction (at least one pair of slabs each), up to one wave per
+    // SIMD.  (Measured: beyond that, slices cost more than they bring.)
+    int ks = 1;
+    if (grp.count == 1 && grp.p[0].splits == 1) {
+        const int pairs = grp.p[0].K / (2 * dqrm::kGemmBK);
+        while (ks < 4 && tiles * ks * 2 <= num_cus() * 4 && pairs >= ks * 2) ks *= 2;
+    }
+    grp.kslices = ks;
+    const int waves = tiles * ks;
+    hipLaunchKernelGGL((dqrm::gemm_wave_kernel<A_MODE, B_MODE>), dim3((waves + dqrm::kGemmWaves - 1) / dqrm::kGemmWaves),
                        dim3(dqrm::kGemmThreads), 0, st, grp);
     return hipGetLastError();
 }
@@ -616,7 +629,7 @@ hipError_t linear_fwd(hipStream_t st, const float *X, const float *W, const floa
     g.C = Y, g.c_si = out, g.c_sj = 1;
     g.M = B, g.N = out, g.K = in;
     g.bias = b, g.relu = relu ? 1 : 0, g.splits = 1, g.k_per_split = in;
-    return launch_gemm_group<true, true>(st, grp);
+    return launch_gemm_group<dqrm::kOpRC, dqrm::kOpRC>(st, grp);
 }
 
 // dX[B][in] = (dZ[B][out] * W[out][in]) masked by (mask[B][in] > 0)
@@ -631,7 +644,7 @@ hipError_t linear_bwd_input(hipStream_t st, const float *dZ, const float *W, con
     g.C = dX, g.c_si = in, g.c_sj = 1;
     g.M = B, g.N = in, g.K = out;
     g.mask = mask, g.splits = 1, g.k_per_split = out;
-    return launch_gemm_group<true, false>(st, grp);
+    return launch_gemm_group<dqrm::kOpRC, dqrm::kOpWideVec>(st, grp);
 }
 
 // One layer's weight-gradient product  [dZ^T * X | dZ^T * 1]  ([out][in + 1], the last column is the bias
@@ -733,28 +746,37 @@ int32_t dqrm_dense_step_quant(const dqrm_dense_model_t *m, const dqrm_dense_quan
     }
     dqrm::InteractArgs ia{};
     ia.bot = x, ia.emb = emb_out, ia.R = F(L.R), ia.B = B, ia.T = T, ia.D = D;
-    hipLaunchKernelGGL(dqrm::interact_fwd_kernel, dim3(B), dim3(dqrm::kInterThreads), 0, st, ia);
+    hipLaunchKernelGGL(dqrm::interact_fwd_kernel, dim3(B), dim3(dqrm::kInterThreads), dqrm::interact_lds_bytes(T, D, false), st,
+                       ia);
     x = F(L.R);
-    for (int l = 0; l < m->top_layers; ++l) {
-        DQRM_HIP_CHECK(linear_fwd(st, x, top_wf[l], m->top_b[l], F(L.top_act[l]), B, m->top_dims[l], m->top_dims[l + 1],
-                                  l + 1 < m->top_layers));
+    const int last = m->top_layers - 1;
+    for (int l = 0; l < last; ++l) {
+        DQRM_HIP_CHECK(linear_fwd(st, x, top_wf[l], m->top_b[l], F(L.top_act[l]), B, m->top_dims[l], m->top_dims[l + 1], true));
         x = F(L.top_act[l]);
     }
+    // the last layer (one output), the loss, and the gradient back to that layer's input in one kernel
     unsigned *gmax = reinterpret_cast<unsigned *>(ws + L.gmax);
-    hipLaunchKernelGGL(dqrm::bce_kernel, dim3(1), dim3(256), 0, st, x, labels, B, F(L.top_dz[m->top_layers - 1]), loss,
-                       gmax, gbits ? dqrm::kMaxGradTensors * dqrm::kGradMaxStride : 0);
+    dqrm::HeadArgs ha{};
+    ha.X = x, ha.w = top_wf[last], ha.bias = m->top_b[last], ha.y = labels;
+    ha.z = F(L.top_act[last]), ha.dz = F(L.top_dz[last]), ha.terms = F(L.loss_terms);
+    ha.dX = last > 0 ? F(L.top_dz[last - 1]) : F(L.dR);
+    ha.relu_input = last > 0; // the input of top layer l > 0 is a ReLU output; the interaction output is not
+    ha.B = B, ha.in = m->top_dims[last];
+    ha.zero = gmax, ha.nzero = gbits ? dqrm::kMaxGradTensors * dqrm::kGradMaxStride : 0;
+    hipLaunchKernelGGL(dqrm::head_kernel, dim3((B + 3) / 4), dim3(256), 0, st, ha);
+    DQRM_HIP_CHECK(hipGetLastError());
 
     // ---- backward: the chain of input gradients first (dZ = gradient w.r.t. a layer's pre-activation) ...
-    for (int l = m->top_layers - 1; l >= 0; --l) {
+    for (int l = last - 1; l >= 0; --l) {
         const float *in_act = l > 0 ? F(L.top_act[l - 1]) : F(L.R);
         float *dX = l > 0 ? F(L.top_dz[l - 1]) : F(L.dR);
-        // the input of top layer l > 0 is a ReLU output: mask; the interaction output is not
         DQRM_HIP_CHECK(linear_bwd_input(st, F(L.top_dz[l]), top_wf[l], l > 0 ? in_act : nullptr, dX, B,
                                         m->top_dims[l], m->top_dims[l + 1]));
     }
     const float *bot_out = F(L.bot_act[m->bot_layers - 1]);
     ia.dR = F(L.dR), ia.dbot = F(L.bot_dz[m->bot_layers - 1]), ia.demb = grad_emb, ia.bot_mask = bot_out;
-    hipLaunchKernelGGL(dqrm::interact_bwd_kernel, dim3(B), dim3(dqrm::kInterThreads), 0, st, ia);
+    hipLaunchKernelGGL(dqrm::interact_bwd_kernel, dim3(B), dim3(dqrm::kInterThreads), dqrm::interact_lds_bytes(T, D, true), st,
+                       ia);
     for (int l = m->bot_layers - 1; l > 0; --l)
         DQRM_HIP_CHECK(linear_bwd_input(st, F(L.bot_dz[l]), bot_wf[l], F(L.bot_act[l - 1]), F(L.bot_dz[l - 1]), B,
                                         m->bot_dims[l], m->bot_dims[l + 1]));
@@ -775,16 +797,18 @@ int32_t dqrm_dense_step_quant(const dqrm_dense_model_t *m, const dqrm_dense_quan
     long long flat = 0;
     int tensor = 0;
     hipError_t launch_err = hipSuccess;
-    auto flush = [&]() {
-        if (wg.count == 0) return;
-        hipError_t e = launch_gemm_group<false, false>(st, wg);
+    auto flush = [&](bool ends_step) {
+        if (wg.count == 0 && !ends_step) return;
+        if (ends_step) sg.loss_terms = F(L.loss_terms), sg.loss = loss, sg.batch = B; // one more block
+        hipError_t e = launch_gemm_group<dqrm::kOpWide, dqrm::kOpWide>(st, wg);
         if (e != hipSuccess && launch_err == hipSuccess) launch_err = e;
-        const dim3 sgd_grid((unsigned)std::min<long long>((sg.total + 255) / 256, 2048));
+        const unsigned blocks = (unsigned)std::min<long long>((sg.total + 255) / 256, 2048);
+        const dim3 last_grid(blocks + (ends_step ? 1u : 0u));
         if (gbits) {
-            hipLaunchKernelGGL(dqrm::grad_sum_absmax_kernel, sgd_grid, dim3(256), 0, st, sg);
-            hipLaunchKernelGGL(dqrm::grad_quant_ec_kernel, sgd_grid, dim3(256), 0, st, sg);
+            if (blocks) hipLaunchKernelGGL(dqrm::grad_sum_absmax_kernel, dim3(blocks), dim3(256), 0, st, sg);
+            hipLaunchKernelGGL(dqrm::grad_quant_ec_kernel, last_grid, dim3(256), 0, st, sg);
         } else {
-            hipLaunchKernelGGL(dqrm::sgd_from_partials_kernel, sgd_grid, dim3(256), 0, st, sg);
+            hipLaunchKernelGGL(dqrm::sgd_from_partials_kernel, last_grid, dim3(256), 0, st, sg);
         }
         e = hipGetLastError();
         if (e != hipSuccess && launch_err == hipSuccess) launch_err = e;
@@ -793,7 +817,7 @@ int32_t dqrm_dense_step_quant(const dqrm_dense_model_t *m, const dqrm_dense_quan
         sg.total = 0;
     };
     auto add_layer = [&](const float *dZ, const float *X, float *W, float *b, float *part, int in, int out) {
-        if (wg.count == dqrm::kGemmMaxGroup) flush();
+        if (wg.count == dqrm::kGemmMaxGroup) flush(false);
         const dqrm::GemmArgs g = weight_grad_problem(dZ, X, part, B, in, out, splits);
         wg.p[wg.count++] = g;
         dqrm::SgdLayer &s = sg.l[sg.count++];
@@ -809,7 +833,7 @@ int32_t dqrm_dense_step_quant(const dqrm_dense_model_t *m, const dqrm_dense_quan
     for (int l = 0; l < m->bot_layers; ++l)
         add_layer(F(L.bot_dz[l]), l > 0 ? F(L.bot_act[l - 1]) : dense_x, m->bot_w[l], m->bot_b[l], F(L.bot_part[l]),
                   m->bot_dims[l], m->bot_dims[l + 1]);
-    flush();
+    flush(true);
     DQRM_HIP_CHECK(launch_err);
     DQRM_HIP_CHECK(hipGetLastError());
     return DQRM_OK;

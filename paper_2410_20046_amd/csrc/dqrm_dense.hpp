@@ -14,29 +14,30 @@ typedef float floatx16 __attribute__((ext_vector_type(16)));
 // C(i,j) = epilogue( sum_r A(i,r) * B(r,j) ), all operands addressed with
 // explicit strides so that one kernel serves X*W^T, dY*W and dY^T*X.
 //
-// One wave owns a 32x32 tile of C and needs no other wave: it keeps the tile in
-// the 16 accumulator registers of v_mfma_f32_32x32x2_f32 and walks the
-// reduction in slabs of 32.  In a slab, lane l = (h, w) with w = l % 32, h = l / 32
-// holds A(i0 + w, r0 + 16 h + s) and B(r0 + 16 h + s, j0 + w) for s = 0..15 and
-// issues 16 products, the s-th pairing r0 + s (lanes h = 0) with r0 + 16 + s
-// (lanes h = 1): every r of the slab is used once, in an order that is the same
-// for both operands.  The next slab's loads are issued before the current
-// slab's products, so the matrix core works while they are in flight.
+// One wave owns a 32x32 tile of C: it keeps the tile in the 16 accumulator
+// registers of v_mfma_f32_32x32x2_f32 and walks the reduction in slabs of 32.
+// In a slab, lane l = (h, w) with w = l % 32, h = l / 32 holds
+// A(i0 + w, r0 + 16 h + s) and B(r0 + 16 h + s, j0 + w) for s = 0..15 and issues
+// 16 products, the s-th pairing r0 + s (lanes h = 0) with r0 + 16 + s (lanes
+// h = 1): every r of the slab is used once, in an order that is the same for
+// both operands.  Two slabs are in flight from memory, and the slab after the
+// current one is brought into that register layout while the current one is
+// multiplied.
 //
-// How an operand's slab reaches that register layout depends on its memory layout:
-//   wide-contiguous (the 32-wide index i or j is the unit-stride one): 16 loads,
-//     each 32 lanes reading 128 consecutive bytes, straight into place;
-//   reduction-contiguous (r is the unit-stride index, as in a row-major X or W read
-//     along its rows): lanes run along r (32 lanes = 128 consecutive bytes of one
-//     row, two rows per load), and the 32x32 slab is turned through a per-wave
-//     piece of LDS.  Nothing assumes an alignment beyond 4 bytes.
-// No load sits under a branch: indices past the edge are clamped and the value is
-// replaced by 0 (or by 1 for the virtual all-ones last column of B).
+// How an operand's slab reaches the register layout depends on its memory layout
+// (the kOp* forms below): read along its unit-stride index with 16-byte loads and
+// passed through a per-wave piece of LDS, or, when the 32-wide index is the
+// unit-stride one, also with 4-byte loads straight into place.  Nothing assumes
+// an alignment beyond 4 bytes.  No load sits under a branch: indices past the
+// edge are clamped and the value is replaced by 0 (or by 1 for the virtual
+// all-ones last column of B).
 //
 // Several products can share one launch (the weight gradients of all layers):
 // the waves are dealt over the tiles of all problems.  With splits > 1 the
 // reduction is cut: slice z covers r in [z*k_per_split, ...) and stores its raw
 // partial tile to P[z][M][N]; sgd_from_partials_kernel adds the slices in order.
+// With kslices > 1 (one product per launch) the waves of a workgroup share tiles
+// and add their accumulators through LDS instead.
 struct GemmArgs {
     const float *A;
     long long a_si, a_sr;
@@ -59,6 +60,7 @@ constexpr int kGemmMaxGroup = 16;
 struct GemmGroup {
     GemmArgs p[kGemmMaxGroup];
     int count, total_tiles;
+    int kslices; // 1, 2 or 4 waves of a workgroup share a tile, each taking a slice of the reduction (splits == 1)
 };
 
 constexpr int kGemmThreads = 256;
@@ -72,7 +74,8 @@ struct SlabRegs {
 
 // Wide-contiguous operand: element (wide, r) at base[wide * sw + r * sr].  Lane (h, w) reads
 // r = r0 + 16 h + s, s = 0..15, of its own wide index.  SAFE: the wide index was clamped by the caller and r
-// is clamped / zeroed here (edge tiles, the last partial slab); otherwise everything is known to be inside.
+// is clamped / zeroed here (the last partial slab, tiles of operands narrower than 32); otherwise everything
+// is known to be inside.
 template <bool SAFE>
 __device__ __forceinline__ void slab_load_direct(SlabRegs &x, const float *base, long long sw, long long sr, int wide,
                                                  int r0, int r_end, int h, bool ones)
@@ -92,19 +95,12 @@ __device__ __forceinline__ void slab_load_direct(SlabRegs &x, const float *base,
     }
 }
 
-// Reduction-contiguous operand: element (wide, r) at base[wide * sw + r].  Step 1: lane l reads
+// Reduction-contiguous operand: element (wide, r) at base[wide * sw + r], clamped form.  Step 1: lane l reads
 // r = r0 + l % 32 of the tile's rows 2 it + l / 32, it = 0..15 (first_wide = the tile's first wide index,
 // n_wide = the operand's extent in that index).
-template <bool SAFE>
 __device__ __forceinline__ void slab_load_along_r(SlabRegs &x, const float *base, long long sw, int first_wide,
                                                   int n_wide, int r0, int r_end, int lane)
 {
-    if (!SAFE) {
-        const float *p = base + (long long)(first_wide + (lane >> 5)) * sw + (r0 + (lane & 31));
-#pragma unroll
-        for (int it = 0; it < 16; ++it) x.v[it] = p[(long long)(2 * it) * sw];
-        return;
-    }
     const int r = r0 + (lane & 31);
     const int rc = min(r, r_end - 1);
 #pragma unroll
@@ -129,15 +125,89 @@ __device__ __forceinline__ void slab_turn(SlabRegs &x, const SlabRegs &st, float
     }
 }
 
-template <bool A_RC, bool B_RC>
+// How the whole slabs of an operand are read (template parameters of the kernel):
+//   kOpRC       the reduction index is the unit-stride one: 16-byte loads along it, turned through LDS
+//   kOpWide     the 32-wide index is the unit-stride one: 4-byte loads straight into place, each lane from its own
+//               (possibly clamped) wide index - the form that can serve a virtual all-ones column
+//   kOpWideVec  the same layout read with 16-byte loads along the wide index, through LDS: only for tiles whose
+//               32 wide indices all exist
+// The last partial slab, and kOpWideVec tiles of operands narrower than 32, take the clamped 4-byte path instead.
+enum { kOpRC = 0, kOpWide = 1, kOpWideVec = 2 };
+
+// four floats that are only known to start on a 4-byte boundary (a 16-byte global load needs no more)
+typedef float Float4Dw __attribute__((ext_vector_type(4), aligned(4)));
+
+// `first_wide`: the tile's first wide index, `n_wide`: the operand's extent in it (kOpRC reads row n_wide - 1 in
+// place of the rows past it; kOpWideVec needs all 32 to exist); `wide`: this lane's own, clamped (kOpWide only)
+template <int MODE>
+__device__ __forceinline__ void slab_fetch_fast(SlabRegs &st, const float *base, long long sw, long long sr,
+                                                int first_wide, int n_wide, int wide, int r0, int lane)
+{
+    // lane l reads four consecutive floats (l % 8) * 4 .. + 3 of lines l / 8 + 8 it, it = 0..3; a line is a
+    // row of the operand (kOpRC: along r) or one reduction index (kOpWideVec: along the wide index)
+    const int line = lane >> 3, c4 = (lane & 7) * 4;
+    if (MODE == kOpWide) {
+        slab_load_direct<false>(st, base, sw, sr, wide, r0, 0, lane >> 5, false);
+    } else if (MODE == kOpRC) {
+#pragma unroll
+        for (int it = 0; it < 4; ++it) {
+            const int row = min(first_wide + line + 8 * it, n_wide - 1);
+            const Float4Dw q = *reinterpret_cast<const Float4Dw *>(base + (long long)row * sw + (r0 + c4));
+            st.v[4 * it + 0] = q.x, st.v[4 * it + 1] = q.y, st.v[4 * it + 2] = q.z, st.v[4 * it + 3] = q.w;
+        }
+    } else {
+        const float *p = base + (long long)(r0 + line) * sr + (first_wide + c4);
+#pragma unroll
+        for (int it = 0; it < 4; ++it) {
+            const Float4Dw q = *reinterpret_cast<const Float4Dw *>(p + (long long)(8 * it) * sr);
+            st.v[4 * it + 0] = q.x, st.v[4 * it + 1] = q.y, st.v[4 * it + 2] = q.z, st.v[4 * it + 3] = q.w;
+        }
+    }
+}
+
+// staging registers of a whole slab -> product layout (`ones`: this lane's column is the virtual one)
+template <int MODE>
+__device__ __forceinline__ void slab_settle_fast(SlabRegs &x, const SlabRegs &st, float *lds, int lane, bool ones)
+{
+    if (MODE == kOpWide) {
+#pragma unroll
+        for (int s = 0; s < 16; ++s) x.v[s] = ones ? 1.0f : st.v[s];
+    } else {
+        const int line = lane >> 3, c4 = (lane & 7) * 4;
+#pragma unroll
+        for (int it = 0; it < 4; ++it)
+            *reinterpret_cast<float4 *>(lds + (line + 8 * it) * kGemmPitch + c4) =
+                make_float4(st.v[4 * it + 0], st.v[4 * it + 1], st.v[4 * it + 2], st.v[4 * it + 3]);
+        // (same wave: the LDS operations complete in order, no barrier needed)
+        const int w = lane & 31, h = lane >> 5;
+        if (MODE == kOpRC) { // LDS holds [wide][r]: 16 consecutive r of my wide index
+            const float4 *row = reinterpret_cast<const float4 *>(lds + w * kGemmPitch + 16 * h);
+#pragma unroll
+            for (int s4 = 0; s4 < 4; ++s4) {
+                const float4 q = row[s4];
+                x.v[4 * s4 + 0] = q.x, x.v[4 * s4 + 1] = q.y, x.v[4 * s4 + 2] = q.z, x.v[4 * s4 + 3] = q.w;
+            }
+        } else { // LDS holds [r][wide]: my wide index of 16 consecutive r
+#pragma unroll
+            for (int s = 0; s < 16; ++s) x.v[s] = lds[(16 * h + s) * kGemmPitch + w];
+        }
+    }
+}
+
+template <int A_MODE, int B_MODE>
 __global__ __launch_bounds__(kGemmThreads) void gemm_wave_kernel(GemmGroup grp)
 {
-    constexpr int kTurn = (A_RC || B_RC) ? 32 * kGemmPitch : 4; // only turned operands need the LDS pieces
-    __shared__ __align__(16) float turn[kGemmWaves][2][kTurn];
+    constexpr bool A_RC = A_MODE == kOpRC, B_RC = B_MODE == kOpRC;
+    __shared__ __align__(16) float turn[kGemmWaves][2][32 * kGemmPitch]; // per wave: LDS pieces of A and B
     const int lane = threadIdx.x & (kWave - 1);
     const int wave = __builtin_amdgcn_readfirstlane((int)threadIdx.x / kWave); // wave-uniform, and known to be
-    const int tile = (int)blockIdx.x * kGemmWaves + wave;
-    if (tile >= grp.total_tiles) return; // whole waves leave; no barrier below
+    // With kslices > 1 the waves of a workgroup meet at a barrier below: a wave past the last tile stays, takes
+    // the last tile with an empty reduction and stores nothing.
+    const int ks = grp.kslices, kz = wave & (ks - 1);
+    int tile = ((int)blockIdx.x * kGemmWaves + wave) / ks;
+    const bool live = tile < grp.total_tiles;
+    if (!live && ks == 1) return;
+    tile = min(tile, grp.total_tiles - 1);
     int pi = 0;
 #pragma unroll 1
     for (int q = 1; q < grp.count; ++q)
@@ -147,15 +217,23 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_wave_kernel(GemmGroup grp)
     int local = tile - g.tile_begin;
     const int z = local / (tiles_i * tiles_j);
     local -= z * tiles_i * tiles_j;
-    const int i0 = (local / tiles_j) * 32, j0 = (local % tiles_j) * 32;
-    const int r_begin = z * g.k_per_split;
-    const int r_end = min(g.K, r_begin + g.k_per_split);
+    const int i_first = (local / tiles_j) * 32, j_first = (local % tiles_j) * 32; // first row / column this tile stores
+    // this wave's part of the reduction: slice z of a split product, or slice kz of the workgroup's
+    const int k_per_wave = ks > 1 ? ((g.K + 2 * kGemmBK * ks - 1) / (2 * kGemmBK * ks)) * (2 * kGemmBK) : g.k_per_split;
+    const int r_begin = ks > 1 ? kz * k_per_wave : z * g.k_per_split;
+    const int r_end = live ? min(g.K, r_begin + k_per_wave) : r_begin;
     const int w = lane & 31, h = lane >> 5;
 
-    // Edge tiles: rows of A past M and columns of B past N re-read the last one (their results are not
-    // stored); the all-ones last column of B is virtual (direct B only: host).
+    // The last tile of a dimension that is not a multiple of 32 is moved back so that it ends at the edge: it
+    // recomputes a few rows / columns of its neighbour, stores only its own, and reads whole slabs like any
+    // other.  Operands narrower than 32 cannot: their tiles re-read the last row / column (clamped indices)
+    // and those results are not stored.  The all-ones last column of B is virtual (kOpWide only: host): its lane
+    // reads the column before it and the value is replaced.
     const int n_mem = g.b_ones_last ? g.N - 1 : g.N; // columns of B that exist in memory (>= 1: host)
-    const bool inner = i0 + 32 <= g.M && j0 + 32 <= n_mem; // the whole tile reads real rows and columns
+    const int i0 = (i_first + 32 > g.M && g.M >= 32) ? g.M - 32 : i_first;
+    const int j0 = (j_first + 32 > g.N && g.N >= 32) ? g.N - 32 : j_first;
+    // whole slabs can be read the fast way (kOpWideVec: only if the tile's 32 rows / columns all exist)
+    const bool whole = (A_MODE != kOpWideVec || i0 + 32 <= g.M) && (B_MODE != kOpWideVec || j0 + 32 <= g.N);
     const int ia = min(i0 + w, g.M - 1), jb = min(j0 + w, n_mem - 1);
     const bool ones = g.b_ones_last && j0 + w == g.N - 1;
     float *lds_a = turn[wave][0], *lds_b = turn[wave][1];
@@ -167,29 +245,27 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_wave_kernel(GemmGroup grp)
     for (int v = 0; v < 16; ++v) acc[v] = 0.0f;
 
     // Two slabs are in flight while a third is multiplied: sa[q] / sb[q] receive slab n with n % 2 == q as it
-    // comes from memory (for a turned operand: along r), a / b hold the current slab in product layout.
+    // comes from memory, a / b hold the current slab in product layout.
     SlabRegs a, b, sa[2], sb[2];
     auto fetch_safe = [&](int q, int r0) {
         if (A_RC)
-            slab_load_along_r<true>(sa[q], g.A, g.a_si, i0, g.M, r0, r_end, lane);
+            slab_load_along_r(sa[q], g.A, g.a_si, i0, g.M, r0, r_end, lane);
         else
             slab_load_direct<true>(sa[q], g.A, g.a_si, g.a_sr, ia, r0, r_end, h, false);
         if (B_RC)
-            slab_load_along_r<true>(sb[q], g.B, g.b_sj, j0, n_mem, r0, r_end, lane);
+            slab_load_along_r(sb[q], g.B, g.b_sj, j0, n_mem, r0, r_end, lane);
         else
             slab_load_direct<true>(sb[q], g.B, g.b_sj, g.b_sr, jb, r0, r_end, h, ones);
     };
-    auto fetch_fast = [&](int q, int r0) { // inner tile, whole slab
-        if (A_RC)
-            slab_load_along_r<false>(sa[q], g.A, g.a_si, i0, g.M, r0, r_end, lane);
-        else
-            slab_load_direct<false>(sa[q], g.A, g.a_si, g.a_sr, ia, r0, r_end, h, false);
-        if (B_RC)
-            slab_load_along_r<false>(sb[q], g.B, g.b_sj, j0, n_mem, r0, r_end, lane);
-        else
-            slab_load_direct<false>(sb[q], g.B, g.b_sj, g.b_sr, jb, r0, r_end, h, false);
+    auto fetch_fast = [&](int q, int r0) { // whole tile, whole slab
+        slab_fetch_fast<A_MODE>(sa[q], g.A, g.a_si, g.a_sr, i0, g.M, ia, r0, lane);
+        slab_fetch_fast<B_MODE>(sb[q], g.B, g.b_sj, g.b_sr, j0, n_mem, jb, r0, lane);
     };
-    auto settle = [&](int q) { // staging registers -> product layout
+    auto settle_fast = [&](int q) {
+        slab_settle_fast<A_MODE>(a, sa[q], lds_a, lane, false);
+        slab_settle_fast<B_MODE>(b, sb[q], lds_b, lane, ones);
+    };
+    auto settle = [&](int q) { // staging registers of the clamped path -> product layout
         if (A_RC)
             slab_turn(a, sa[q], lds_a, lane);
         else
@@ -204,37 +280,42 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_wave_kernel(GemmGroup grp)
         for (int s = 0; s < 16; ++s) acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a.v[s], b.v[s], acc, 0, 0, 0);
     };
 
-    // Pairs of whole slabs of an inner tile.  The loop bodies below have no branch and every fetch is
+    // Pairs of whole slabs of a whole tile.  The loop bodies below have no branch and every fetch is
     // unconditional, so that the loads in flight are the same, in number and order, on entry and on the way
     // round: only then does the compiler wait for exactly the slab it needs.  (A fetch past the fast part
     // re-reads its last pair of slabs: harmless.)
     int r0 = r_begin;
-    const int r_pairs = inner ? r_begin + (r_end - r_begin) / (2 * kGemmBK) * (2 * kGemmBK) : r_begin;
+    const int r_pairs = whole ? r_begin + (r_end - r_begin) / (2 * kGemmBK) * (2 * kGemmBK) : r_begin;
     if (r0 < r_pairs) {
         const int r_last = r_pairs - 2 * kGemmBK;
+        // a2 / b2: the slab after the current one is brought into product layout while the current one is
+        // multiplied (the matrix core runs on its own once a product is issued; the LDS traffic of the turn
+        // goes out in its shadow)
+        SlabRegs a2, b2;
         fetch_fast(0, r0);
         __builtin_amdgcn_sched_barrier(0);
         fetch_fast(1, r0 + kGemmBK);
         __builtin_amdgcn_sched_barrier(0);
+        settle_fast(0);
+        __builtin_amdgcn_sched_barrier(0);
         for (; r0 < r_pairs; r0 += 2 * kGemmBK) {
             const int rn = min(r0 + 2 * kGemmBK, r_last);
-            // (the scheduling barriers keep the compiler from moving loads across the phases, which would
-            //  change which loads are in flight at each wait)
-            settle(0);
-            __builtin_amdgcn_sched_barrier(0);
             fetch_fast(0, rn);
             __builtin_amdgcn_sched_barrier(0);
+            slab_settle_fast<A_MODE>(a2, sa[1], lds_a, lane, false);
+            slab_settle_fast<B_MODE>(b2, sb[1], lds_b, lane, ones);
             products();
-            __builtin_amdgcn_sched_barrier(0);
-            settle(1);
             __builtin_amdgcn_sched_barrier(0);
             fetch_fast(1, rn + kGemmBK);
             __builtin_amdgcn_sched_barrier(0);
-            products();
+            slab_settle_fast<A_MODE>(a, sa[0], lds_a, lane, false);
+            slab_settle_fast<B_MODE>(b, sb[0], lds_b, lane, ones);
+#pragma unroll
+            for (int s = 0; s < 16; ++s) acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a2.v[s], b2.v[s], acc, 0, 0, 0);
             __builtin_amdgcn_sched_barrier(0);
         }
     }
-    // what is left: at most one whole and one partial slab of an inner tile, or everything of an edge tile
+    // what is left: at most one whole and one partial slab of a whole tile, or everything of a clamped tile
     // (past the end: clamped addresses, zeros, and a product that adds nothing)
     if (r0 < r_end) {
         fetch_safe(0, r0);
@@ -249,15 +330,31 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_wave_kernel(GemmGroup grp)
         }
     }
 
+    // the slices of a tile meet: slice 0 adds the others' accumulators in order and goes on alone
+    if (ks > 1) {
+        float *mine = &turn[wave][0][0];
+        if (kz > 0) {
+#pragma unroll
+            for (int v = 0; v < 16; ++v) mine[v * kWave + lane] = acc[v];
+        }
+        __syncthreads();
+        if (kz > 0 || !live) return;
+        for (int k = 1; k < ks; ++k) {
+            const float *other = &turn[wave + k][0][0];
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[v] += other[v * kWave + lane];
+        }
+    }
+
     // accumulator layout: lane l holds column j = l % 32 and rows 8*(v/4) + 4*(l/32) + v%4, v = 0..15
     const int j = j0 + w;
-    if (j >= g.N) return;
+    if (j < j_first || j >= g.N) return; // (a moved tile stores only its own columns and rows)
     if (g.splits > 1) {
         float *p = g.P + (long long)z * g.M * g.N;
 #pragma unroll
         for (int v = 0; v < 16; ++v) {
             const int i = i0 + 8 * (v >> 2) + 4 * h + (v & 3);
-            if (i < g.M) p[(long long)i * g.N + j] = acc[v];
+            if (i >= i_first && i < g.M) p[(long long)i * g.N + j] = acc[v];
         }
         return;
     }
@@ -265,13 +362,77 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_wave_kernel(GemmGroup grp)
 #pragma unroll
     for (int v = 0; v < 16; ++v) {
         const int i = i0 + 8 * (v >> 2) + 4 * h + (v & 3);
-        if (i >= g.M) continue;
+        if (i < i_first || i >= g.M) continue;
         float x = acc[v] + bj;
         if (g.relu) x = fmaxf(x, 0.0f);
         const long long off = (long long)i * g.c_si + (long long)j * g.c_sj;
         if (g.mask) x = g.mask[off] > 0.0f ? x : 0.0f;
         g.C[off] = x;
     }
+}
+
+// ---- the head: last linear layer (one output), sigmoid, binary cross-entropy, gradient w.r.t. its input ----
+// z = X[b] . w + bias;  p = 1 / (1 + exp(-z));  term_b = -(y log max(p, 1e-12) + (1-y) log max(1-p, 1e-12));
+// dz = (p - y) / B;  dX[b][k] = dz * w[k], masked by X[b][k] > 0 when X is a ReLU output.
+// One wave per sample.  The mean of the terms is taken by loss_sum_block in the step's last kernel.
+// (Block 0 also clears the `nzero` words at `zero`: the per-tensor gradient maxima of the INT8-gradient path,
+// which are accumulated later in the same step.)
+struct HeadArgs {
+    const float *X;    // [B][in] input of the last top layer
+    const float *w;    // [in] its weights (the ones the forward uses)
+    const float *bias; // [1]
+    const float *y;    // [B] labels
+    float *z;          // [B] logits
+    float *dz;         // [B]
+    float *terms;      // [B] per-sample loss
+    float *dX;         // [B][in]
+    int relu_input;
+    int B, in;
+    unsigned *zero;
+    int nzero;
+};
+
+__global__ __launch_bounds__(256) void head_kernel(HeadArgs a)
+{
+    if (blockIdx.x == 0)
+        for (int k = threadIdx.x; k < a.nzero; k += 256) a.zero[k] = 0u;
+    const int lane = threadIdx.x & (kWave - 1);
+    const int b = (int)blockIdx.x * (256 / kWave) + (int)threadIdx.x / kWave;
+    if (b >= a.B) return;
+    const float *x = a.X + (long long)b * a.in;
+    float s = 0.0f;
+    for (int k = lane; k < a.in; k += kWave) s += x[k] * a.w[k];
+#pragma unroll
+    for (int d = kWave / 2; d >= 1; d >>= 1) s += __shfl_xor(s, d, kWave); // (every lane ends with the same sum)
+    const float z = s + a.bias[0];
+    const float p = 1.0f / (1.0f + expf(-z));
+    const float yy = a.y[b];
+    const float dz = (p - yy) / (float)a.B;
+    if (lane == 0) {
+        a.z[b] = z;
+        a.dz[b] = dz;
+        a.terms[b] = -(yy * logf(fmaxf(p, 1e-12f)) + (1.0f - yy) * logf(fmaxf(1.0f - p, 1e-12f)));
+    }
+    float *dx = a.dX + (long long)b * a.in;
+    for (int k = lane; k < a.in; k += kWave) {
+        const float g = dz * a.w[k];
+        dx[k] = (!a.relu_input || x[k] > 0.0f) ? g : 0.0f;
+    }
+}
+
+// loss = mean of the per-sample terms, by one block of 256 threads (fixed order: strided partial sums, then a tree)
+__device__ __forceinline__ void loss_sum_block(const float *terms, int B, float *loss)
+{
+    __shared__ float part[256];
+    float s = 0.0f;
+    for (int b = threadIdx.x; b < B; b += 256) s += terms[b];
+    part[threadIdx.x] = s;
+    __syncthreads();
+    for (int w = 128; w > 0; w >>= 1) {
+        if (threadIdx.x < w) part[threadIdx.x] += part[threadIdx.x + w];
+        __syncthreads();
+    }
+    if (threadIdx.x == 0) *loss = part[0] / (float)B;
 }
 
 // SGD step from the split products of [dZ^T * X | dZ^T * 1], all layers in one launch:
@@ -297,7 +458,23 @@ struct SgdGroup {
     unsigned *gmax_bits; // [tensors][kGradMaxStride] running max |g + e| per tensor (word 0 of each line), as bit
                          // patterns, zeroed before the step
     float *grad_scale;   // [tensors] out
+    // The launch that ends the step has one more block than the parameters need: it turns the per-sample loss
+    // terms into the mean (null otherwise).
+    const float *loss_terms; // [batch]
+    float *loss;
+    int batch;
 };
+
+// blocks that work on the parameters; the extra one, if any, does its job here and the caller returns
+__device__ __forceinline__ bool sgd_extra_block(const SgdGroup &grp, int &blocks)
+{
+    blocks = gridDim.x;
+    if (!grp.loss_terms) return false;
+    blocks -= 1;
+    if ((int)blockIdx.x < blocks) return false;
+    loss_sum_block(grp.loss_terms, grp.batch, grp.loss);
+    return true;
+}
 
 // which layer of the group element e belongs to, and where inside it
 struct SgdElem {
@@ -337,7 +514,9 @@ __device__ __forceinline__ float sum_partials(const SgdLayer &L, long long le)
 
 __global__ __launch_bounds__(256) void sgd_from_partials_kernel(SgdGroup grp)
 {
-    for (long long e = (long long)blockIdx.x * 256 + threadIdx.x; e < grp.total; e += (long long)gridDim.x * 256) {
+    int blocks;
+    if (sgd_extra_block(grp, blocks)) return;
+    for (long long e = (long long)blockIdx.x * 256 + threadIdx.x; e < grp.total; e += (long long)blocks * 256) {
         const SgdElem x = sgd_elem(grp, e);
         const SgdLayer &L = grp.l[x.q];
         const float s = sum_partials(L, x.le);
@@ -394,6 +573,8 @@ __global__ __launch_bounds__(256) void grad_sum_absmax_kernel(SgdGroup grp)
 __global__ __launch_bounds__(256) void grad_quant_ec_kernel(SgdGroup grp)
 {
     __shared__ Scale s_scale[kMaxGradTensors];
+    int blocks;
+    if (sgd_extra_block(grp, blocks)) return;
     // the tensors of this launch's layers
     for (int k = threadIdx.x; k < 2 * grp.count; k += 256) {
         const int t = grp.l[k >> 1].tensor0 + (k & 1);
@@ -402,7 +583,7 @@ __global__ __launch_bounds__(256) void grad_quant_ec_kernel(SgdGroup grp)
         if (blockIdx.x == 0) grp.grad_scale[t] = gs;
     }
     __syncthreads();
-    for (long long e = (long long)blockIdx.x * 256 + threadIdx.x; e < grp.total; e += (long long)gridDim.x * 256) {
+    for (long long e = (long long)blockIdx.x * 256 + threadIdx.x; e < grp.total; e += (long long)blocks * 256) {
         const SgdElem x = sgd_elem(grp, e);
         const SgdLayer &L = grp.l[x.q];
         const long long f = L.flat_begin + x.le;
@@ -471,14 +652,36 @@ struct InteractArgs {
 };
 
 constexpr int kInterThreads = 128;
-constexpr int kInterMaxZ = 64 * 64; // V * D floats held in LDS
+constexpr int kInterMaxV = 64;      // vectors per sample, at most (host)
+constexpr int kInterMaxZ = 64 * 64; // V * D floats, at most (host)
+
+// dynamic LDS of the two kernels below (at most ~33 KB: V <= 64, V * D <= 4096)
+inline size_t interact_lds_bytes(int T, int D, bool backward)
+{
+    const int V = T + 1;
+    return sizeof(float) * (backward ? (size_t)V * D + (size_t)V * (V | 1) : (size_t)V * (D + 1));
+}
+
+// pair index p -> (i, j), i > j, p = i(i-1)/2 + j
+__device__ __forceinline__ void pair_of(int p, int &i, int &j)
+{
+    i = (int)((1.0f + sqrtf(1.0f + 8.0f * (float)p)) * 0.5f);
+    while (i * (i - 1) / 2 > p) --i;
+    while ((i + 1) * i / 2 <= p) ++i;
+    j = p - i * (i - 1) / 2;
+}
 
 __global__ __launch_bounds__(kInterThreads) void interact_fwd_kernel(InteractArgs a)
 {
-    __shared__ float z[kInterMaxZ];
-    const int b = blockIdx.x, V = a.T + 1, D = a.D;
-    for (int e = threadIdx.x; e < V * D; e += kInterThreads)
-        z[e] = e < D ? a.bot[(long long)b * D + e] : a.emb[(long long)b * a.T * D + (e - D)];
+    // rows one float apart from a multiple of the bank count: the lanes of a wave read different rows at the
+    // same d, and with a pitch of D = 16 all of them would fall into two banks
+    extern __shared__ float inter_lds[]; // V * (D + 1) floats (interact_lds_bytes)
+    float *z = inter_lds;
+    const int b = blockIdx.x, V = a.T + 1, D = a.D, pitch = D + 1;
+    for (int e = threadIdx.x; e < V * D; e += kInterThreads) {
+        const int i = e / D, d = e - i * D;
+        z[i * pitch + d] = e < D ? a.bot[(long long)b * D + e] : a.emb[(long long)b * a.T * D + (e - D)];
+    }
     __syncthreads();
     const int P = V * (V - 1) / 2, W = D + P;
     float *r = a.R + (long long)b * W;
@@ -486,38 +689,42 @@ __global__ __launch_bounds__(kInterThreads) void interact_fwd_kernel(InteractArg
         if (e < D) {
             r[e] = z[e];
         } else {
-            // pair index p -> (i, j), i > j: i = largest with i(i-1)/2 <= p
-            const int p = e - D;
-            int i = (int)((1.0f + sqrtf(1.0f + 8.0f * (float)p)) * 0.5f);
-            while (i * (i - 1) / 2 > p) --i;
-            while ((i + 1) * i / 2 <= p) ++i;
-            const int j = p - i * (i - 1) / 2;
+            int i, j;
+            pair_of(e - D, i, j);
+            const float *zi = z + i * pitch, *zj = z + j * pitch;
             float s = 0.0f;
-            for (int d = 0; d < D; ++d) s += z[i * D + d] * z[j * D + d];
+            for (int d = 0; d < D; ++d) s += zi[d] * zj[d];
             r[e] = s;
         }
     }
 }
 
+// dZ[i] = sum over j != i of dP(i, j) * Z[j]  (+ dR[0..D) for i = 0): the pair gradients are spread into a
+// symmetric V x V matrix with a zero diagonal first, so that the sum runs over all j without a case distinction
+// (terms in the order j = 0 .. V-1).
 __global__ __launch_bounds__(kInterThreads) void interact_bwd_kernel(InteractArgs a)
 {
-    __shared__ float z[kInterMaxZ];
-    __shared__ float dp[64 * 63 / 2];
-    const int b = blockIdx.x, V = a.T + 1, D = a.D;
+    extern __shared__ float inter_lds[]; // V * D + V * (V | 1) floats (interact_lds_bytes)
+    const int b = blockIdx.x, V = a.T + 1, D = a.D, vp = V | 1; // odd pitch
+    float *z = inter_lds, *dpf = inter_lds + V * D;
     const int P = V * (V - 1) / 2, W = D + P;
     for (int e = threadIdx.x; e < V * D; e += kInterThreads)
         z[e] = e < D ? a.bot[(long long)b * D + e] : a.emb[(long long)b * a.T * D + (e - D)];
     const float *dr = a.dR + (long long)b * W;
-    for (int e = threadIdx.x; e < P; e += kInterThreads) dp[e] = dr[D + e];
+    for (int p = threadIdx.x; p < P; p += kInterThreads) {
+        int i, j;
+        pair_of(p, i, j);
+        const float g = dr[D + p];
+        dpf[i * vp + j] = g;
+        dpf[j * vp + i] = g;
+    }
+    for (int i = threadIdx.x; i < V; i += kInterThreads) dpf[i * vp + i] = 0.0f;
     __syncthreads();
     for (int e = threadIdx.x; e < V * D; e += kInterThreads) {
         const int i = e / D, d = e - i * D;
         float s = (i == 0) ? dr[d] : 0.0f;
-        for (int j = 0; j < V; ++j) {
-            if (j == i) continue;
-            const int p = j < i ? i * (i - 1) / 2 + j : j * (j - 1) / 2 + i;
-            s += dp[p] * z[j * D + d];
-        }
+        const float *row = dpf + i * vp, *col = z + d;
+        for (int j = 0; j < V; ++j) s += row[j] * col[j * D];
         if (i == 0) {
             const long long off = (long long)b * D + d;
             if (a.bot_mask) s = a.bot_mask[off] > 0.0f ? s : 0.0f;
@@ -526,33 +733,6 @@ __global__ __launch_bounds__(kInterThreads) void interact_bwd_kernel(InteractArg
             a.demb[(long long)b * a.T * D + (e - D)] = s;
         }
     }
-}
-
-// ---- sigmoid + mean binary cross-entropy -------------------------------------------
-// p = 1 / (1 + exp(-z)); loss = -mean(y log max(p, 1e-12) + (1-y) log max(1-p, 1e-12));
-// dz = (p - y) / B.  One block; B is a few thousand.
-// (It also clears the `nzero` words at `zero`: the per-tensor gradient maxima of the INT8-gradient path,
-// which are accumulated later in the same step.)
-__global__ __launch_bounds__(256) void bce_kernel(const float *__restrict__ z, const float *__restrict__ y, int B,
-                                                  float *__restrict__ dz, float *__restrict__ loss,
-                                                  unsigned *__restrict__ zero, int nzero)
-{
-    __shared__ float part[256];
-    for (int k = threadIdx.x; k < nzero; k += 256) zero[k] = 0u;
-    float s = 0.0f;
-    for (int b = threadIdx.x; b < B; b += 256) {
-        const float p = 1.0f / (1.0f + expf(-z[b]));
-        const float yy = y[b];
-        s += -(yy * logf(fmaxf(p, 1e-12f)) + (1.0f - yy) * logf(fmaxf(1.0f - p, 1e-12f)));
-        dz[b] = (p - yy) / (float)B;
-    }
-    part[threadIdx.x] = s;
-    __syncthreads();
-    for (int w = 128; w > 0; w >>= 1) {
-        if (threadIdx.x < w) part[threadIdx.x] += part[threadIdx.x + w];
-        __syncthreads();
-    }
-    if (threadIdx.x == 0) *loss = part[0] / (float)B;
 }
 
 } // namespace dqrm

@@ -17,4 +17,5 @@ from .workloads import (  # noqa: F401
     DENSE_CONFIGS,
     make_dense_model,
     dense_batch,
+    split_batch,
 )

@@ -217,6 +217,23 @@ def index_batch(wl: Workload, k: int, **kw):
     return wl.batch(k, **kw)
 
 
+def split_batch(indices: np.ndarray, offsets: np.ndarray, T: int, B: int, parts: int):
+    """Cuts a batch of B samples into ``parts`` micro-batches of B / parts consecutive samples (the split of
+    the batch over simulated nodes): a list of ``(indices_k, offsets_k)`` in the same table-major layout."""
+    assert B % parts == 0
+    Bm = B // parts
+    out = []
+    for k in range(parts):
+        idx, lens = [], []
+        for t in range(T):
+            lo, hi = int(offsets[t * B + k * Bm]), int(offsets[t * B + (k + 1) * Bm])
+            idx.append(indices[lo:hi])
+            lens.append(np.diff(offsets[t * B + k * Bm: t * B + (k + 1) * Bm + 1]))
+        off = np.concatenate([[0], np.cumsum(np.concatenate(lens))]).astype(np.int64)
+        out.append((np.ascontiguousarray(np.concatenate(idx), dtype=np.int64), off))
+    return out
+
+
 def grad_dyadic(B: int, T: int, D: int, seed: int, k: int) -> np.ndarray:
     """Gradient w.r.t. the pooled output, [B, T, D] fp32, on the grid m * 2^-24
     with integer m uniform in [-1024, 1024].  Any sum of at most 8192 such

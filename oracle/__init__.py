@@ -147,6 +147,56 @@ def sparse_update(W: np.ndarray, packed: Optional[np.ndarray], row_offsets: np.n
                                C.c_float(lr))
 
 
+class SimulatedDP:
+    """Simulated data parallelism on one device for the embedding tables (appendix "Simulated Data
+    Parallelism Environment", its algorithm; INT8 gradients as in the distributed-training appendix).
+
+    ``micro_batch(j, ...)`` is one pass of the algorithm's loop body for micro-batch j: clear the buffer if the
+    previous pass updated the weights, backward (sparse gradient), quantise the values with the scale of the
+    group's first micro-batch, add the codes to the buffer, and after the last micro-batch of a group update the
+    weights from the buffer.  Reading: the update comes after every ``simulated_nodes``-th micro-batch,
+    (j + 1) % simulated_nodes == 0 (as printed, with j counted from 0, the very first group would be a single
+    micro-batch; the steady state is the same).  The buffer is dense, [rows][D] int32 over all tables: small
+    tables only."""
+
+    def __init__(self, W, packed, row_offsets, w_scale, simulated_nodes: int, lr: float):
+        self.W, self.packed, self.row_offsets, self.w_scale = W, packed, row_offsets, w_scale
+        self.n, self.lr = int(simulated_nodes), float(lr)
+        self.T, self.D = len(row_offsets) - 1, W.shape[1]
+        self.buffer = np.zeros(W.shape, np.int32)
+        self.touched = np.zeros(W.shape[0], np.uint8)
+        self.buffer_clean = False
+        self.group_absmax = None  # the first micro-batch's per-table maxima
+        self.g_scale = None
+        self.blocks = []          # this group's (uniq_rows, table_uniq_offsets, gq), for inspection
+
+    def micro_batch(self, j: int, B: int, indices: np.ndarray, offsets: np.ndarray, grad_out: np.ndarray) -> bool:
+        """Returns True if this micro-batch ended a group (the weights were updated)."""
+        if self.buffer_clean:
+            self.buffer[:] = 0
+            self.touched[:] = 0
+            self.blocks = []
+            self.group_absmax = None
+            self.buffer_clean = False
+        bw = embbag_bwd(self.T, self.D, B, indices, offsets, grad_out)  # local backward
+        if self.group_absmax is None:
+            self.group_absmax = bw["g_absmax"].copy()
+        gq, self.g_scale = grad_quant_int8(self.T, self.D, bw["values"], bw["table_uniq_offsets"], self.group_absmax)
+        gq = np.ascontiguousarray(gq)
+        self.blocks.append((bw["uniq_rows"], bw["table_uniq_offsets"], gq))
+        lib().oracle_simdp_accumulate(C.c_int(self.T), C.c_int(self.D), _p(self.row_offsets, C.c_int64),
+                                      _p(bw["uniq_rows"], C.c_int64), _p(bw["table_uniq_offsets"], C.c_int32),
+                                      _p(gq, C.c_int8), _p(self.buffer, C.c_int32), _p(self.touched, C.c_uint8))
+        if (j + 1) % self.n != 0:
+            return False
+        lib().oracle_simdp_weight_update(_p(self.W, C.c_float), _p(self.packed, C.c_uint8),
+                                         _p(self.row_offsets, C.c_int64), _p(self.w_scale, C.c_float),
+                                         C.c_int(self.T), C.c_int(self.D), _p(self.buffer, C.c_int32),
+                                         _p(self.touched, C.c_uint8), _p(self.g_scale, C.c_float), C.c_float(self.lr))
+        self.buffer_clean = True
+        return True
+
+
 def dense_step(bot_dims, bot_w, bot_b, top_dims, top_w, top_b, dense_x, emb, labels, lr):
     """The dense part of one train step in float64.  bot_w / bot_b / top_w / top_b: lists of float64 arrays
     (updated IN PLACE by the SGD step).  dense_x [B][num_dense], emb [B][T][D], labels [B] (any float dtype).

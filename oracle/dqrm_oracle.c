@@ -42,6 +42,9 @@
  *   - packed INT4 layout: byte k of a row holds element 2k in bits 0..3 and
  *     element 2k+1 in bits 4..7, 4-bit two's complement.
  *
+ *   - simulated data parallelism (appendix "Simulated Data Parallelism
+ *     Environment"): see oracle_simdp_accumulate.
+ *
  * Parity pins (tests/test_oracle_*.py): hand-worked quantiser example, range
  * and round-trip invariants, torch-CPU embedding_bag / sparse coalesce special
  * cases, brute-force dense gradient, integer closed form on dyadic gradients.
@@ -284,6 +287,58 @@ void oracle_sparse_update(float *W, uint8_t *packed, const int64_t *row_offsets,
             int64_t r = row_offsets[t] + uniq_rows[u];
             for (int j = 0; j < D; ++j) {
                 float g = g_scale[t] * (float)gq[u * D + j];
+                float step = lr * g;
+                W[r * D + j] = W[r * D + j] - step;
+            }
+            if (packed) pack_row(W + r * D, D, w_scale[t], packed + r * (D / 2));
+        }
+}
+
+/* ---- Appendix "Simulated Data Parallelism Environment" (its algorithm), for the
+ * embedding tables, with the INT8 gradient quantisation of the appendix on
+ * distributed training.
+ *
+ * Every parameter has a gradient buffer of its own shape.  The batch is split
+ * into micro-batches, one per simulated node; each micro-batch runs forward and
+ * backward on the unchanged weights and its gradient is added to the buffer;
+ * after the last micro-batch of a group the weights are updated from the buffer,
+ * and the buffer is cleared before the next gradient arrives.  With quantised
+ * gradients the scale of the group's first micro-batch is reused for the others
+ * (the two all-reduce rounds of the real run are not simulated), so later
+ * micro-batches may clip.
+ *
+ * Readings (the appendix does not say): the buffer holds what an all-reduce of
+ * the integer gradients would deliver, the SUM OF THE INT8 CODES (exact integer
+ * arithmetic, independent of order), and is dequantised once:
+ * step = lr * (g_scale[t] * (float)sum), two roundings.  Nothing is divided by
+ * the number of nodes: the algorithm adds, the caller's lr decides.  Rows that
+ * no micro-batch touched keep their weights and nibbles (their buffer is zero).
+ *
+ * oracle_simdp_accumulate is the algorithm's buffer update for one micro-batch:
+ * buffer [rows][D] int32 and touched [rows] cover all tables (row_offsets). */
+void oracle_simdp_accumulate(int T, int D, const int64_t *row_offsets, const int64_t *uniq_rows,
+                             const int32_t *table_uniq_offsets, const int8_t *gq, int32_t *buffer,
+                             uint8_t *touched)
+{
+    for (int t = 0; t < T; ++t)
+        for (int64_t u = table_uniq_offsets[t]; u < table_uniq_offsets[t + 1]; ++u) {
+            int64_t r = row_offsets[t] + uniq_rows[u];
+            touched[r] = 1;
+            for (int j = 0; j < D; ++j) buffer[r * D + j] += (int32_t)gq[u * D + j];
+        }
+}
+
+/* ... and its weight update from the buffer (the caller clears the buffer before
+ * the next group, as the algorithm does). */
+void oracle_simdp_weight_update(float *W, uint8_t *packed, const int64_t *row_offsets,
+                                const float *w_scale, int T, int D, const int32_t *buffer,
+                                const uint8_t *touched, const float *g_scale, float lr)
+{
+    for (int t = 0; t < T; ++t)
+        for (int64_t r = row_offsets[t]; r < row_offsets[t + 1]; ++r) {
+            if (!touched[r]) continue;
+            for (int j = 0; j < D; ++j) {
+                float g = g_scale[t] * (float)buffer[r * D + j];
                 float step = lr * g;
                 W[r * D + j] = W[r * D + j] - step;
             }

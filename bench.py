@@ -95,6 +95,10 @@ def main():
                          "instead of the one-pass dqrm_quant_update")
     ap.add_argument("--no-graph", dest="graph", action="store_false",
                     help="launch every kernel from the host instead of replaying a captured HIP graph of `pool` steps")
+    ap.add_argument("--simulated-nodes", type=int, default=1,
+                    help="simulated data parallelism: the batch is cut into this many micro-batches (forward, backward "
+                         "and INT8 codes each, with the first one's scale), their integer gradients are merged "
+                         "(dqrm_sparse_merge) and the tables are updated once per step; all calls in line on one stream")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=12.0)
     args = ap.parse_args()
@@ -157,6 +161,36 @@ def main():
         dq.dqrm_dedupe(tables, ix, of, B, sps[i], urs[i], sos[i], tuos[i], nus[i], wss[i], stream=stream)
         ev_dedupe[i].record(stream)
 
+    nodes = args.simulated_nodes
+    if nodes > 1:
+        from gen import split_batch
+        assert B % nodes == 0 and nodes <= dq.MAX_DEDUPE_BATCHES and not args.dense
+        Bm = B // nodes
+        parts = [split_batch(i, o, T, B, nodes) for i, o in pool]
+        mb_idx = [[torch.from_numpy(i).to(dev) for i, _ in p] for p in parts]
+        mb_off = [[torch.from_numpy(o).to(dev) for _, o in p] for p in parts]
+        Nm = max(len(i) for p in parts for i, _ in p)
+        mb = [dq.StepBuffers(T, D, Bm, Nm, dev, want_codes=False) for _ in range(nodes)]
+        m_cap = nodes * Nm
+        m_rows = torch.empty(m_cap, dtype=torch.int64, device=dev)
+        m_tuo = torch.empty(T + 1, dtype=torch.int32, device=dev)
+        m_nu = torch.zeros(1, dtype=torch.int32, device=dev)
+        m_sums = torch.empty((m_cap, D), dtype=torch.int32, device=dev)
+        m_ws = torch.empty(dq.dqrm_sparse_merge_workspace_bytes(T, D, nodes, m_cap), dtype=torch.uint8, device=dev)
+
+    def simulated_step(k):
+        """One weight update from `nodes` micro-batches (appendix on simulated data parallelism)."""
+        p, g = k % args.pool, grad_d[k % args.grad_pool]
+        for j in range(nodes):
+            b, ix, of = mb[j], mb_idx[p][j], mb_off[p][j]
+            dq.dqrm_embbag_fwd(tables, ix, of, Bm, mode, b.out, None)
+            dq.dqrm_embbag_bwd(tables, ix, of, Bm, g[j * Bm:(j + 1) * Bm], b.sorted_pos, b.uniq_rows, b.seg_offsets,
+                               b.table_uniq_offsets, b.num_unique, b.values, b.g_absmax, b.workspace)
+            dq.dqrm_grad_quant_int8(T, D, b.cap, b.values, b.table_uniq_offsets, mb[0].g_absmax, b.gq, b.g_scale)
+        dq.dqrm_sparse_merge(tables, [(b.uniq_rows, b.table_uniq_offsets, b.gq) for b in mb], m_rows, m_tuo, m_nu,
+                             m_sums, m_ws)
+        dq.dqrm_sparse_update_sums(tables, m_cap, m_rows, m_tuo, m_sums, mb[0].g_scale, args.lr)
+
     dense = None
     if args.dense:
         from gen import make_dense_model, dense_batch
@@ -209,6 +243,10 @@ def main():
         """n consecutive steps starting with batch k0, all launches on the current stream (+ the side
         stream for dqrm_dedupe when overlapping).  Self-contained: the side stream is joined at the end."""
         main = torch.cuda.current_stream()
+        if nodes > 1:
+            for k in range(k0, k0 + n):
+                simulated_step(k)
+            return
         if args.overlap == "ahead":
             for k in range(k0, k0 + n):
                 if (k - k0) % nbuf == 0:  # dedupe of this and the next nbuf-1 batches, in one launch pair
@@ -369,6 +407,13 @@ def main():
     # Each call is timed on its own: `reps` back-to-back launches of the same call (cycling through the
     # batches) between two events, so that the cost of recording an event is not charged to a 5-20 us kernel.
     # The calls are launched in path order first, so every call finds valid inputs.
+    if nodes > 1:
+        simulated_step(args.warmup)  # valid blocks for the two calls below
+        stages += ["sparse_merge", "update_sums"]
+        calls["sparse_merge"] = lambda k: dq.dqrm_sparse_merge(
+            tables, [(b.uniq_rows, b.table_uniq_offsets, b.gq) for b in mb], m_rows, m_tuo, m_nu, m_sums, m_ws)
+        calls["update_sums"] = lambda k: dq.dqrm_sparse_update_sums(tables, m_cap, m_rows, m_tuo, m_sums, mb[0].g_scale,
+                                                                   args.lr)
     for name in stages:
         calls[name](args.warmup)
     reps = max(10, min(args.steps, 200))
@@ -386,6 +431,14 @@ def main():
     log("[bench] per-call HIP-event time (us): " + ", ".join(f"{k}={v:.1f}" for k, v in stage_us.items()))
     stage_bytes = {"fwd": ab["fwd"], "dedupe": ab["dedupe"], "segment_sum": ab["segsum"], "quant": ab["quant"],
                    "update": ab["update"], "quant_update": ab["quant"] + ab["update"] - D * U}
+    if nodes > 1:
+        Um = int(m_nu.cpu().item())
+        blocks_rows = sum(int(b.num_unique.cpu().item()) for b in mb)
+        # merge: every block row's id (8 B) and codes (D B) in, the union's ids and 32-bit sums out
+        stage_bytes["sparse_merge"] = blocks_rows * (8 + D) + Um * (8 + 4 * D)
+        # update from sums: id + sums + master row read and written + packed row written
+        stage_bytes["update_sums"] = Um * (8 + 4 * D + 8 * D + D // 2)
+        log(f"[bench] simulated nodes {nodes}: {blocks_rows} block rows merge into {Um}")
     stage_gbs = {k: stage_bytes[k] / (stage_us[k] * 1e-6) / 1e9 for k in stages}
 
     # The dominant kernel of the step's critical path: dqrm_embbag_fwd is exactly one kernel launch
@@ -455,8 +508,9 @@ def main():
         "data": "synthetic",
         "config": {"workload": f"{args.workload}-shaped embedding layer: {T} tables, {wl.R} rows, dim {D}, batch {B}, "
                                f"1 Zipf index per table per sample, {args.mode}-mode forward, INT8 sparse grads, "
-                               f"SGD lr {args.lr}, dedupe overlap: {args.overlap}",
-                   "lookups_per_step": N, "unique_rows_per_step": round(U, 1), "fwd_mode": args.mode, "overlap": args.overlap, "scale_refresh_period": args.refresh_period, "pooling": args.pooling, "dense_part": bool(args.dense), "mlp_weight_bits": args.mlp_weight_bits, "mlp_grad_bits": args.mlp_grad_bits,
+                               f"SGD lr {args.lr}, dedupe overlap: {args.overlap}"
+                               + (f", {nodes} simulated nodes (micro-batches of {B // nodes}, one update per step)" if nodes > 1 else ""),
+                   "lookups_per_step": N, "unique_rows_per_step": round(U, 1), "fwd_mode": args.mode, "overlap": args.overlap, "scale_refresh_period": args.refresh_period, "pooling": args.pooling, "dense_part": bool(args.dense), "mlp_weight_bits": args.mlp_weight_bits, "mlp_grad_bits": args.mlp_grad_bits, "simulated_nodes": nodes,
                    "update": ("dqrm_quant_update (one pass)" if args.fused else "dqrm_grad_quant_int8 + dqrm_sparse_update"),
                    "launch": (f"HIP graph of {graph_steps} steps replayed" if graph is not None else "eager launches")},
         "roofline": roofline,

@@ -11,6 +11,7 @@
  *   dqrm_embbag_bwd      every step      dedupe -> segment-sum = sparse gradient (Sec. 4.3, "specified sparsity")
  *   dqrm_grad_quant_int8 every step      INT8 codes of the gradient values       (Appendix, gradient quantisation)
  *   dqrm_sparse_update   every step      dequantise + SGD on touched rows        (same appendix)
+ *   dqrm_sparse_merge    per group       sum of several micro-batches' integer gradients (Appendix, simulated data parallelism)
  * and, between the forward and the backward of the tables, the dense part of the model:
  *   dqrm_dense_step      every step      MLPs, interaction, loss, their backward, dense SGD
  *   dqrm_dense_step_quant  the same with channel-wise INT4 weights and / or INT8 gradients + error compensation
@@ -193,6 +194,45 @@ int32_t dqrm_grad_quant_int8(int32_t num_tables, int32_t dim, int64_t capacity, 
 int32_t dqrm_sparse_update(const dqrm_tables_t *tables, int64_t capacity, const int64_t *uniq_rows,
                            const int32_t *table_uniq_offsets, const int8_t *gq, const float *g_scale,
                            float lr, void *stream);
+
+/* Simulated data parallelism on one device (appendix "Simulated Data Parallelism
+ * Environment": the gradients of `simulated_nodes` micro-batches are added into a
+ * buffer, then the weights are updated once) and, equally, the sum of the integer
+ * gradients that the all-reduce of the distributed-training appendix delivers.
+ * A block is one micro-batch's sparse gradient after dqrm_grad_quant_int8 (the
+ * appendix reuses the scale of the group's first micro-batch for the others: pass
+ * that micro-batch's g_absmax to every dqrm_grad_quant_int8 call of the group).
+ * The "buffer" is kept sparse: dqrm_sparse_merge returns the union of the blocks'
+ * rows, table by table in ascending row order, and the 32-bit integer sums of
+ * their INT8 codes (exact: no order matters); dqrm_sparse_update_sums is
+ * dqrm_sparse_update for such sums, master[row] -= lr * (g_scale[t] * (float)sum)
+ * (two roundings; nothing is divided by the number of blocks).
+ *   blocks     HOST array of num_blocks (<= DQRM_MAX_DEDUPE_BATCHES) descriptors of
+ *              device arrays: uniq_rows [U_k] int64 table-local, ascending and
+ *              distinct inside each table; table_uniq_offsets [T+1] int32; gq
+ *              [U_k][D] int8 (4-byte aligned); capacity = rows allocated (>= U_k)
+ *   max_total  rows allocated in the outputs uniq_rows [max_total] / sums
+ *              [max_total][D] (16-byte aligned); must be >= the sum of the U_k
+ *   outputs    uniq_rows, table_uniq_offsets [T+1], num_unique [1], sums; rows
+ *              past num_unique are not written
+ * A table may bring at most DQRM_MAX_TABLE_LOOKUPS rows over all blocks.  Blocks
+ * that break these rules are reported through dqrm_check_status
+ * (DQRM_ERR_BAD_OFFSETS, DQRM_ERR_CAPACITY, DQRM_ERR_INDEX_OUT_OF_RANGE) and the
+ * offending piece contributes nothing.  The workspace (256-byte aligned, no
+ * initialisation needed) is the library's scratch; the caller owns everything. */
+typedef struct {
+    const int64_t *uniq_rows;
+    const int32_t *table_uniq_offsets;
+    const int8_t *gq;
+    int64_t capacity;
+} dqrm_sparse_block_t;
+size_t dqrm_sparse_merge_workspace_bytes(int32_t num_tables, int32_t dim, int32_t num_blocks, int64_t max_total);
+int32_t dqrm_sparse_merge(const dqrm_tables_t *tables, int32_t num_blocks, const dqrm_sparse_block_t *blocks,
+                          int64_t max_total, int64_t *uniq_rows, int32_t *table_uniq_offsets, int32_t *num_unique,
+                          int32_t *sums, void *workspace, size_t workspace_bytes, void *stream);
+int32_t dqrm_sparse_update_sums(const dqrm_tables_t *tables, int64_t capacity, const int64_t *uniq_rows,
+                                const int32_t *table_uniq_offsets, const int32_t *sums, const float *g_scale,
+                                float lr, void *stream);
 
 /* B4 and B5 in one pass, for callers that do not exchange anything between the
  * two (one GPU): same outputs as dqrm_grad_quant_int8 followed by

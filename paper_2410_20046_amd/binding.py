@@ -34,7 +34,8 @@ MAX_TABLE_LOOKUPS = 16384
 
 EXPORTS = ("dqrm_find_scale", "dqrm_pack_int4", "dqrm_embbag_fwd", "dqrm_embbag_bwd_workspace_bytes",
            "dqrm_embbag_bwd", "dqrm_dedupe", "dqrm_dedupe_multi", "dqrm_segment_sum", "dqrm_grad_quant_int8",
-           "dqrm_sparse_update", "dqrm_quant_update", "dqrm_dense_workspace_bytes", "dqrm_dense_step",
+           "dqrm_sparse_update", "dqrm_sparse_merge_workspace_bytes", "dqrm_sparse_merge", "dqrm_sparse_update_sums",
+           "dqrm_quant_update", "dqrm_dense_workspace_bytes", "dqrm_dense_step",
            "dqrm_dense_param_count", "dqrm_dense_step_quant", "dqrm_check_status", "dqrm_last_hip_error", "dqrm_version")
 
 
@@ -48,6 +49,11 @@ class dqrm_tables_t(C.Structure):
     _fields_ = [("num_tables", C.c_int32), ("dim", C.c_int32), ("row_offsets_host", C.c_void_p),
                 ("row_offsets_dev", C.c_void_p), ("master", C.c_void_p), ("packed", C.c_void_p),
                 ("w_scale", C.c_void_p)]
+
+
+class dqrm_sparse_block_t(C.Structure):
+    _fields_ = [("uniq_rows", C.c_void_p), ("table_uniq_offsets", C.c_void_p), ("gq", C.c_void_p),
+                ("capacity", C.c_int64)]
 
 
 class dqrm_dedupe_batch_t(C.Structure):
@@ -96,6 +102,12 @@ def lib() -> C.CDLL:
         L.dqrm_quant_update.argtypes = [tp, i64, i64, vp, vp, vp, vp, vp, vp, C.c_float, vp, sz, vp]
         L.dqrm_grad_quant_int8.argtypes = [i32, i32, i64, vp, vp, vp, vp, vp, vp]
         L.dqrm_sparse_update.argtypes = [tp, i64, vp, vp, vp, vp, C.c_float, vp]
+        L.dqrm_sparse_update_sums.argtypes = [tp, i64, vp, vp, vp, vp, C.c_float, vp]
+        L.dqrm_sparse_update_sums.restype = i32
+        L.dqrm_sparse_merge_workspace_bytes.argtypes = [i32, i32, i32, i64]
+        L.dqrm_sparse_merge_workspace_bytes.restype = sz
+        L.dqrm_sparse_merge.argtypes = [tp, i32, C.POINTER(dqrm_sparse_block_t), i64, vp, vp, vp, vp, vp, sz, vp]
+        L.dqrm_sparse_merge.restype = i32
         dp = C.POINTER(dqrm_dense_model_t)
         L.dqrm_dense_workspace_bytes.argtypes = [dp, i32]
         L.dqrm_dense_workspace_bytes.restype = sz
@@ -228,6 +240,28 @@ def dqrm_grad_quant_int8(num_tables: int, dim: int, capacity: int, values: torch
     _check(lib().dqrm_grad_quant_int8(num_tables, dim, capacity, _ptr(values), _ptr(table_uniq_offsets),
                                       _ptr(g_absmax), _ptr(gq), _ptr(g_scale), _stream(stream)),
            "dqrm_grad_quant_int8")
+
+
+def dqrm_sparse_merge_workspace_bytes(num_tables: int, dim: int, num_blocks: int, max_total: int) -> int:
+    return int(lib().dqrm_sparse_merge_workspace_bytes(num_tables, dim, num_blocks, max_total))
+
+
+def dqrm_sparse_merge(tables: Tables, blocks, uniq_rows: torch.Tensor, table_uniq_offsets: torch.Tensor,
+                      num_unique: torch.Tensor, sums: torch.Tensor, workspace: torch.Tensor, stream=None) -> None:
+    """``blocks``: sequence of tuples (uniq_rows, table_uniq_offsets, gq) of device tensors, one per micro-batch
+    (at most MAX_DEDUPE_BATCHES).  The outputs' first dimension is the capacity ``max_total``."""
+    arr = (dqrm_sparse_block_t * len(blocks))()
+    for i, (ur, tuo, gq) in enumerate(blocks):
+        arr[i] = dqrm_sparse_block_t(_ptr(ur), _ptr(tuo), _ptr(gq), min(ur.shape[0], gq.shape[0]))
+    _check(lib().dqrm_sparse_merge(tables.ref, len(blocks), arr, min(uniq_rows.shape[0], sums.shape[0]), _ptr(uniq_rows),
+                                   _ptr(table_uniq_offsets), _ptr(num_unique), _ptr(sums), _ptr(workspace),
+                                   workspace.numel() * workspace.element_size(), _stream(stream)), "dqrm_sparse_merge")
+
+
+def dqrm_sparse_update_sums(tables: Tables, capacity: int, uniq_rows: torch.Tensor, table_uniq_offsets: torch.Tensor,
+                            sums: torch.Tensor, g_scale: torch.Tensor, lr: float, stream=None) -> None:
+    _check(lib().dqrm_sparse_update_sums(tables.ref, capacity, _ptr(uniq_rows), _ptr(table_uniq_offsets), _ptr(sums),
+                                         _ptr(g_scale), lr, _stream(stream)), "dqrm_sparse_update_sums")
 
 
 def dqrm_sparse_update(tables: Tables, capacity: int, uniq_rows: torch.Tensor, table_uniq_offsets: torch.Tensor,

@@ -11,6 +11,7 @@
 #include "dqrm_fwd.hpp"
 #include "dqrm_bwd.hpp"
 #include "dqrm_update.hpp"
+#include "dqrm_merge.hpp"
 #include "dqrm_dense.hpp"
 
 namespace {
@@ -188,6 +189,62 @@ void launch_segsum(int G, dim3 grid_sum, dim3 grid_comb, hipStream_t st, const d
         break;
     }
 #undef DQRM_SEG_CASE
+}
+
+int32_t sparse_update_impl(const dqrm_tables_t *tables, int64_t capacity, const int64_t *uniq_rows,
+                           const int32_t *table_uniq_offsets, const int8_t *gq, const int32_t *sums,
+                           const float *g_scale, float lr, void *stream)
+{
+    int64_t R = 0;
+    int32_t rc = check_tables(tables, false, &R);
+    if (rc != DQRM_OK) return rc;
+    if (capacity < 0 || !uniq_rows || !table_uniq_offsets || !g_scale) return DQRM_ERR_INVALID_ARG;
+    if (capacity > kMaxIndices) return DQRM_ERR_UNSUPPORTED;
+    if (capacity * (tables->dim / 4) > kMaxRowQuarters) return DQRM_ERR_UNSUPPORTED;
+    dqrm::UpdateArgs a;
+    a.master = tables->master;
+    a.packed = tables->packed;
+    a.w_scale = tables->w_scale;
+    a.row_offsets = tables->row_offsets_dev;
+    a.uniq_rows = uniq_rows;
+    a.tuo = table_uniq_offsets;
+    a.gq = gq;
+    a.sums = sums;
+    a.g_scale = g_scale;
+    a.capacity = capacity;
+    a.lr = lr;
+    a.T = tables->num_tables;
+    a.D = tables->dim;
+    a.by_q4 = dqrm::FastDiv::make((unsigned)(a.D / 4));
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    hipLaunchKernelGGL(dqrm::sparse_update_kernel, dim3(grid_for(capacity * (a.D / 4), dqrm::kEwThreads, 8)),
+                       dim3(dqrm::kEwThreads), dqrm::TableLds::bytes(a.T), st, a);
+    DQRM_HIP_CHECK(hipGetLastError());
+    return DQRM_OK;
+}
+
+// workspace of dqrm_sparse_merge: the laid-out list, its sort outputs, and the sort's own workspace
+struct MergeLayout {
+    size_t off_rows, off_offsets, off_src, off_sorted_pos, off_seg_offsets, off_dedupe, total;
+};
+MergeLayout merge_layout(int T, int D, int n, int64_t max_total)
+{
+    MergeLayout L{};
+    size_t o = 0;
+    auto take = [&](size_t bytes) {
+        size_t at = o;
+        o = align_up(o + bytes, 256);
+        return at;
+    };
+    const size_t m = (size_t)max_total;
+    L.off_rows = take(m * sizeof(int64_t));
+    L.off_offsets = take(((size_t)T * n + 1) * sizeof(int64_t));
+    L.off_src = take(m * sizeof(int32_t));
+    L.off_sorted_pos = take(m * sizeof(int32_t));
+    L.off_seg_offsets = take((m + 1) * sizeof(int32_t));
+    L.off_dedupe = take(ws_layout(T, D, max_total).total);
+    L.total = o;
+    return L;
 }
 
 } // namespace
@@ -426,30 +483,74 @@ int32_t dqrm_sparse_update(const dqrm_tables_t *tables, int64_t capacity, const 
                            const int32_t *table_uniq_offsets, const int8_t *gq, const float *g_scale, float lr,
                            void *stream)
 {
+    if (!gq || !aligned(gq, 4)) return DQRM_ERR_INVALID_ARG;
+    return sparse_update_impl(tables, capacity, uniq_rows, table_uniq_offsets, gq, nullptr, g_scale, lr, stream);
+}
+
+int32_t dqrm_sparse_update_sums(const dqrm_tables_t *tables, int64_t capacity, const int64_t *uniq_rows,
+                                const int32_t *table_uniq_offsets, const int32_t *sums, const float *g_scale,
+                                float lr, void *stream)
+{
+    if (!sums || !aligned(sums, 16)) return DQRM_ERR_INVALID_ARG;
+    return sparse_update_impl(tables, capacity, uniq_rows, table_uniq_offsets, nullptr, sums, g_scale, lr, stream);
+}
+
+size_t dqrm_sparse_merge_workspace_bytes(int32_t num_tables, int32_t dim, int32_t num_blocks, int64_t max_total)
+{
+    if (num_tables < 1 || num_tables > DQRM_MAX_TABLES || dim < 8 || dim > DQRM_MAX_DIM || dim % 8 != 0 ||
+        num_blocks < 1 || num_blocks > DQRM_MAX_DEDUPE_BATCHES || max_total < 0 || max_total > kMaxIndices)
+        return 0;
+    return merge_layout(num_tables, dim, num_blocks, max_total).total;
+}
+
+int32_t dqrm_sparse_merge(const dqrm_tables_t *tables, int32_t num_blocks, const dqrm_sparse_block_t *blocks,
+                          int64_t max_total, int64_t *uniq_rows, int32_t *table_uniq_offsets, int32_t *num_unique,
+                          int32_t *sums, void *workspace, size_t workspace_bytes, void *stream)
+{
     int64_t R = 0;
     int32_t rc = check_tables(tables, false, &R);
     if (rc != DQRM_OK) return rc;
-    if (capacity < 0 || !uniq_rows || !table_uniq_offsets || !gq || !g_scale) return DQRM_ERR_INVALID_ARG;
-    if (capacity > kMaxIndices) return DQRM_ERR_UNSUPPORTED;
-    if (!aligned(gq, 4)) return DQRM_ERR_INVALID_ARG;
-    if (capacity * (tables->dim / 4) > kMaxRowQuarters) return DQRM_ERR_UNSUPPORTED;
-    dqrm::UpdateArgs a;
-    a.master = tables->master;
-    a.packed = tables->packed;
-    a.w_scale = tables->w_scale;
-    a.row_offsets = tables->row_offsets_dev;
-    a.uniq_rows = uniq_rows;
-    a.tuo = table_uniq_offsets;
-    a.gq = gq;
-    a.g_scale = g_scale;
-    a.capacity = capacity;
-    a.lr = lr;
-    a.T = tables->num_tables;
-    a.D = tables->dim;
-    a.by_q4 = dqrm::FastDiv::make((unsigned)(a.D / 4));
+    if (!blocks || num_blocks < 1 || max_total < 0) return DQRM_ERR_INVALID_ARG;
+    if (num_blocks > DQRM_MAX_DEDUPE_BATCHES || max_total > kMaxIndices) return DQRM_ERR_UNSUPPORTED;
+    const int T = tables->num_tables, D = tables->dim;
+    if (max_total * (D / 4) > kMaxRowQuarters) return DQRM_ERR_UNSUPPORTED;
+    if (!uniq_rows || !table_uniq_offsets || !num_unique || !sums || !workspace) return DQRM_ERR_INVALID_ARG;
+    if (!aligned(sums, 16) || !aligned(workspace, 256)) return DQRM_ERR_INVALID_ARG;
+    dqrm::MergeArgs ma;
+    std::memset(&ma, 0, sizeof(ma));
+    for (int k = 0; k < num_blocks; ++k) {
+        const dqrm_sparse_block_t &b = blocks[k];
+        if (!b.uniq_rows || !b.table_uniq_offsets || !b.gq || !aligned(b.gq, 4) || b.capacity < 0)
+            return DQRM_ERR_INVALID_ARG;
+        if (b.capacity >= (1LL << dqrm::kMergeSrcBits)) return DQRM_ERR_UNSUPPORTED;
+        ma.uniq_rows[k] = b.uniq_rows, ma.tuo[k] = b.table_uniq_offsets, ma.gq[k] = b.gq, ma.capacity[k] = b.capacity;
+    }
+    const MergeLayout L = merge_layout(T, D, num_blocks, max_total);
+    if (workspace_bytes < L.total) return DQRM_ERR_WORKSPACE_TOO_SMALL;
+    char *ws = static_cast<char *>(workspace);
+    ma.n = num_blocks, ma.T = T, ma.D = D, ma.max_total = max_total;
+    ma.cat_rows = reinterpret_cast<int64_t *>(ws + L.off_rows);
+    ma.cat_offsets = reinterpret_cast<int64_t *>(ws + L.off_offsets);
+    ma.cat_src = reinterpret_cast<int32_t *>(ws + L.off_src);
+    int32_t *sorted_pos = reinterpret_cast<int32_t *>(ws + L.off_sorted_pos);
+    int32_t *seg_offsets = reinterpret_cast<int32_t *>(ws + L.off_seg_offsets);
+    ma.sorted_pos = sorted_pos, ma.seg_offsets = seg_offsets, ma.num_unique = num_unique, ma.sums = sums;
+
     hipStream_t st = static_cast<hipStream_t>(stream);
-    hipLaunchKernelGGL(dqrm::sparse_update_kernel, dim3(grid_for(capacity * (a.D / 4), dqrm::kEwThreads, 8)),
-                       dim3(dqrm::kEwThreads), dqrm::TableLds::bytes(a.T), st, a);
+    hipLaunchKernelGGL(dqrm::merge_layout_kernel, dim3(T * num_blocks), dim3(256), 0, st, ma);
+    // sort and segment the list: the kernels of dqrm_dedupe with one "bag" per block and no bag bookkeeping
+    dqrm::DedupeArgs da;
+    std::memset(&da, 0, sizeof(da));
+    dqrm::DedupeBatch &o = da.b[0];
+    o.indices = ma.cat_rows, o.offsets = ma.cat_offsets, o.N = max_total;
+    o.ws = ws_views(ws + L.off_dedupe, ws_layout(T, D, max_total));
+    o.sorted_pos = sorted_pos, o.tuo = table_uniq_offsets, o.num_unique = num_unique, o.uniq_rows = uniq_rows;
+    o.seg_offsets = seg_offsets, o.no_bags = 1;
+    da.row_offsets = tables->row_offsets_dev, da.T = T, da.B = num_blocks;
+    hipLaunchKernelGGL(dqrm::dedupe_kernel, dim3(T, 1), dim3(dqrm::kDdThreads), 0, st, da);
+    hipLaunchKernelGGL(dqrm::dedupe_finish_kernel, dim3(grid_for(max_total, dqrm::kSegThreads, 2), 1),
+                       dim3(dqrm::kSegThreads), 0, st, da);
+    hipLaunchKernelGGL(dqrm::merge_sum_kernel, dim3(grid_for(max_total * (D / 4), 256, 8)), dim3(256), 0, st, ma);
     DQRM_HIP_CHECK(hipGetLastError());
     return DQRM_OK;
 }
@@ -477,6 +578,7 @@ int32_t dqrm_quant_update(const dqrm_tables_t *tables, int64_t capacity, int64_t
     a.u.uniq_rows = uniq_rows;
     a.u.tuo = table_uniq_offsets;
     a.u.gq = nullptr;
+    a.u.sums = nullptr;
     a.u.g_scale = nullptr;
     a.u.capacity = capacity;
     a.u.lr = lr;

@@ -94,6 +94,7 @@ struct UpdateArgs {
     const int64_t *uniq_rows;
     const int32_t *tuo;
     const int8_t *gq;
+    const int32_t *sums; // instead of gq: 32-bit sums of the codes of several blocks (merged sparse gradients)
     const float *g_scale;
     int64_t capacity;
     FastDiv by_q4;
@@ -141,7 +142,13 @@ __global__ __launch_bounds__(kEwThreads) void sparse_update_kernel(UpdateArgs a)
             continue;
         }
         const int64_t row = r0 + lr_row;
-        const char4 c = reinterpret_cast<const char4 *>(a.gq)[e];
+        int4 c;
+        if (a.sums) {
+            c = reinterpret_cast<const int4 *>(a.sums)[e];
+        } else {
+            const char4 c8 = reinterpret_cast<const char4 *>(a.gq)[e];
+            c = make_int4(c8.x, c8.y, c8.z, c8.w);
+        }
         float4 *wp = reinterpret_cast<float4 *>(a.master) + row * q4 + r.c4;
         const float4 w = sgd_step(*wp, c.x, c.y, c.z, c.w, L.gs[r.t].s, a.lr);
         *wp = w;

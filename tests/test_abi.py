@@ -115,6 +115,35 @@ def test_validation_errors_before_any_launch():
     assert up(gs=None) == dq.ERR_INVALID_ARG
     assert up(cap=-5) == dq.ERR_INVALID_ARG
     assert up(tb=_tables(D=4)) == dq.ERR_UNSUPPORTED
+    # merging sparse blocks, update from integer sums
+    ups = lambda tb=ok, cap=8, ur=FAKE, tuo=FAKE, sm=FAKE, gs=FAKE: L.dqrm_sparse_update_sums(r(tb), cap, ur, tuo, sm,
+                                                                                               gs, 0.1, S)
+    assert ups(sm=None) == dq.ERR_INVALID_ARG
+    assert ups(sm=FAKE + 4) == dq.ERR_INVALID_ARG
+    assert ups(ur=None) == dq.ERR_INVALID_ARG
+    assert ups(cap=-1) == dq.ERR_INVALID_ARG
+    from paper_2410_20046_amd.binding import dqrm_sparse_block_t
+
+    def merge(n=2, blocks="ok", max_total=64, ur=FAKE, tuo=FAKE, nu=FAKE, sm=FAKE, ws=FAKE, ws_bytes=1 << 30, tb=ok,
+              cap=16, gq=FAKE):
+        arr = (dqrm_sparse_block_t * 8)()
+        for k in range(8):
+            arr[k] = dqrm_sparse_block_t(FAKE, FAKE, gq, cap)
+        return L.dqrm_sparse_merge(r(tb), n, arr if blocks == "ok" else None, max_total, ur, tuo, nu, sm, ws, ws_bytes, S)
+
+    assert merge(blocks=None) == dq.ERR_INVALID_ARG
+    assert merge(n=0) == dq.ERR_INVALID_ARG
+    assert merge(n=dq.MAX_DEDUPE_BATCHES + 1) == dq.ERR_UNSUPPORTED
+    assert merge(max_total=-1) == dq.ERR_INVALID_ARG
+    assert merge(sm=None) == dq.ERR_INVALID_ARG
+    assert merge(sm=FAKE + 8) == dq.ERR_INVALID_ARG
+    assert merge(ws=FAKE + 16) == dq.ERR_INVALID_ARG
+    assert merge(gq=None) == dq.ERR_INVALID_ARG
+    assert merge(cap=1 << 28) == dq.ERR_UNSUPPORTED
+    assert merge(ws_bytes=dq.dqrm_sparse_merge_workspace_bytes(2, 16, 2, 64) - 1) == dq.ERR_WORKSPACE_TOO_SMALL
+    f = dq.dqrm_sparse_merge_workspace_bytes
+    assert f(26, 64, 8, 212992) > dq.dqrm_embbag_bwd_workspace_bytes(26, 64, 8, 212992)
+    assert f(26, 64, 9, 10) == 0 and f(26, 12, 2, 10) == 0 and f(0, 16, 2, 10) == 0 and f(2, 16, 2, -1) == 0
 
 
 def test_product_never_touches_the_oracle():

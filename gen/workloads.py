@@ -259,6 +259,8 @@ DENSE_CONFIGS = {
     # a small shape with the same structure and awkward (non-multiple-of-tile) widths
     "small": dict(num_dense=5, bot=[5, 40, 16], top_hidden=[70, 33, 1]),
     "small8": dict(num_dense=5, bot=[5, 24, 8], top_hidden=[19, 7, 1]),
+    # mid-size, awkward widths: reductions of a few slabs with ragged ends, tiles that end past the edge
+    "medium": dict(num_dense=7, bot=[7, 200, 96, 24], top_hidden=[136, 72, 1]),
 }
 
 _STREAM_DENSE = 6

@@ -26,7 +26,8 @@ def _gpu_dense_step(dq, torch, T, D, B, model_np, x, emb, y, lr, dev):
     return m, float(loss.cpu().item()), grad.cpu().numpy()
 
 
-@pytest.mark.parametrize("cfg,T,D,B", [("small", 3, 16, 37), ("small8", 5, 8, 200), ("kaggle", 26, 16, 256)])
+@pytest.mark.parametrize("cfg,T,D,B", [("small", 3, 16, 37), ("small8", 5, 8, 200), ("medium", 5, 24, 333),
+                                          ("medium", 5, 24, 1000), ("kaggle", 26, 16, 256)])
 def test_dense_step_matches_oracle(oracle, cfg, T, D, B):
     import torch
     import paper_2410_20046_amd as dq

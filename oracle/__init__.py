@@ -245,6 +245,41 @@ def dense_step_ex(bot_dims, bot_w, bot_b, top_dims, top_w, top_b, dense_x, emb, 
     return (float(loss), grad, grads) if want_grads else (float(loss), grad)
 
 
+class SimulatedDPDense:
+    """Simulated data parallelism for the MLPs (appendix "Simulated Data Parallelism Environment", its algorithm),
+    FP32 gradients: every parameter tensor has a gradient buffer of its own shape; each micro-batch's gradient
+    (forward and backward on the unchanged weights, mean loss over the micro-batch) is added to it; after every
+    ``simulated_nodes``-th micro-batch the parameters take ``p <- p - lr * buffer`` and the buffer is cleared
+    before the next gradient arrives.  Float64, on the lists of arrays given (updated in place)."""
+
+    def __init__(self, bot_dims, bot_w, bot_b, top_dims, top_w, top_b, simulated_nodes: int, lr: float):
+        self.model = (bot_dims, bot_w, bot_b, top_dims, top_w, top_b)
+        self.n, self.lr = int(simulated_nodes), float(lr)
+        self.buffers = tuple([np.zeros_like(a) for a in lst] for lst in (bot_w, bot_b, top_w, top_b))
+        self.buffer_clean = False
+
+    def micro_batch(self, j: int, dense_x, emb, labels):
+        """Returns (loss, grad_emb, ended_group)."""
+        bot_dims, bot_w, bot_b, top_dims, top_w, top_b = self.model
+        if self.buffer_clean:
+            for lst in self.buffers:
+                for b in lst:
+                    b[:] = 0.0
+            self.buffer_clean = False
+        loss, grad_emb, grads = dense_step_ex(bot_dims, bot_w, bot_b, top_dims, top_w, top_b, dense_x, emb, labels,
+                                              self.lr, apply_sgd=False, want_grads=True)
+        for blst, glst in zip(self.buffers, grads):
+            for b, g in zip(blst, glst):
+                b += g
+        if (j + 1) % self.n != 0:
+            return loss, grad_emb, False
+        for plst, blst in zip((bot_w, bot_b, top_w, top_b), self.buffers):
+            for p_, b in zip(plst, blst):
+                p_ -= self.lr * b
+        self.buffer_clean = True
+        return loss, grad_emb, True
+
+
 def mlp_fake_quant(W: np.ndarray, bits: int):
     """Channel-wise fake quantisation of W [out][in] (float32).  Returns (Wq float32, row_scale float32, codes int8)."""
     assert W.dtype == np.float32 and W.flags["C_CONTIGUOUS"] and W.ndim == 2

@@ -14,7 +14,7 @@ import numpy as np
 import pytest
 import torch
 
-from gen import make_workload, split_batch
+from gen import make_workload, split_batch, make_dense_model, dense_batch
 
 GOLD = os.path.join(os.path.dirname(__file__), "golden")
 U7 = np.float32(2.0 ** -7)
@@ -170,3 +170,59 @@ def test_every_group_starts_from_a_cleared_buffer(oracle):
             fresh.micro_batch(k, Bm, ik, ok, np.ascontiguousarray(g[k * Bm:(k + 1) * Bm]))
     assert np.array_equal(Wa.view(np.uint32), Wb.view(np.uint32))
     assert np.array_equal(sim.buffer, fresh.buffer)
+
+
+# ---------------------------------------------------------------- the MLPs' gradient buffers
+@pytest.mark.parametrize("nodes", [2, 4])
+def test_dense_group_equals_one_plain_step_with_lr_times_nodes(oracle, nodes):
+    """Micro-batches of equal size, mean loss each: the sum of their gradients is `nodes` times the gradient of
+    the whole batch's mean loss, so a group with step size lr must equal ONE plain step (the routine pinned against
+    torch autograd) on the whole batch with step size lr * nodes; the embedding gradients are the whole batch's
+    times `nodes`, slice by slice; the mean of the micro-batch losses is the whole batch's loss."""
+    T, D, B, lr = 3, 16, 48, 0.05
+    bot_dims, bw, bb, top_dims, tw, tb = make_dense_model("small", T, D, seed=31)
+    x, y = dense_batch(B, bot_dims[0], seed=31, k=0)
+    emb = (np.random.default_rng(7).standard_normal((B, T, D)) * 0.25).astype(np.float32)
+    f64 = lambda l: [np.ascontiguousarray(a, np.float64) for a in l]
+    A, Bp = (f64(bw), f64(bb), f64(tw), f64(tb)), (f64(bw), f64(bb), f64(tw), f64(tb))
+    sim = oracle.SimulatedDPDense(bot_dims, A[0], A[1], top_dims, A[2], A[3], simulated_nodes=nodes, lr=lr)
+    Bm = B // nodes
+    losses, gemb = [], []
+    for k in range(nodes):
+        sl = slice(k * Bm, (k + 1) * Bm)
+        before = [a.copy() for a in A[2]]
+        loss, ge, ended = sim.micro_batch(k, x[sl], emb[sl], y[sl])
+        assert ended == (k == nodes - 1)
+        if not ended:
+            assert all(np.array_equal(a, b) for a, b in zip(A[2], before))  # weights untouched inside a group
+        losses.append(loss)
+        gemb.append(ge)
+    loss_w, ge_w = oracle.dense_step(bot_dims, Bp[0], Bp[1], top_dims, Bp[2], Bp[3], x, emb, y, lr * nodes)
+    assert abs(np.mean(losses) - loss_w) <= 1e-12 * abs(loss_w)
+    assert np.allclose(np.concatenate(gemb), ge_w * nodes, rtol=1e-10, atol=1e-14)
+    for got, exp in zip(A, Bp):
+        for g, e in zip(got, exp):
+            assert np.allclose(g, e, rtol=1e-10, atol=1e-13)
+    assert not np.allclose(A[2][0], np.asarray(tw[0], np.float64))
+
+
+def test_dense_buffers_are_cleared_between_groups(oracle):
+    T, D, B, lr, nodes = 3, 16, 24, 0.05, 2
+    bot_dims, bw, bb, top_dims, tw, tb = make_dense_model("small", T, D, seed=32)
+    f64 = lambda l: [np.ascontiguousarray(a, np.float64) for a in l]
+    A, Bp = (f64(bw), f64(bb), f64(tw), f64(tb)), (f64(bw), f64(bb), f64(tw), f64(tb))
+    sim = oracle.SimulatedDPDense(bot_dims, A[0], A[1], top_dims, A[2], A[3], simulated_nodes=nodes, lr=lr)
+    rng = np.random.default_rng(9)
+    j = 0
+    for grp in range(2):
+        x, y = dense_batch(B, bot_dims[0], seed=32, k=grp)
+        emb = (rng.standard_normal((B, T, D)) * 0.25).astype(np.float32)
+        fresh = oracle.SimulatedDPDense(bot_dims, Bp[0], Bp[1], top_dims, Bp[2], Bp[3], simulated_nodes=nodes, lr=lr)
+        for k in range(nodes):
+            sl = slice(k * (B // nodes), (k + 1) * (B // nodes))
+            sim.micro_batch(j, x[sl], emb[sl], y[sl])
+            fresh.micro_batch(k, x[sl], emb[sl], y[sl])
+            j += 1
+    for got, exp in zip(A, Bp):
+        for g, e in zip(got, exp):
+            assert np.array_equal(g, e)

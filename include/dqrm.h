@@ -309,6 +309,15 @@ typedef struct {
     int8_t *grad_codes;  /* [P] out, or NULL: the INT8 codes (what a data-parallel run would exchange) */
     float *grads;        /* [P] out, or NULL: this step's FP32 gradients before compensation */
     float *wq;           /* out, or NULL: the fake-quantised weights this step used */
+    /* Simulated data parallelism for the MLPs (appendix "Simulated Data Parallelism Environment": a gradient
+     * buffer per parameter collects the micro-batches of a group, then the parameters are updated once);
+     * grad_bits = 0 only.  With grad_buffer set, the call adds this micro-batch's gradient to the buffer
+     * (buffer_add != 0) or starts the buffer with it (buffer_add = 0: the first micro-batch of a group, which is
+     * how the buffer is "cleared"), and the parameters either stay as they are (buffer_update = 0) or take
+     * parameter <- parameter - lr * buffer (buffer_update != 0: the group's last micro-batch). */
+    float *grad_buffer;  /* [P] in/out, flat parameter order, or NULL: a plain step */
+    int32_t buffer_add;
+    int32_t buffer_update;
 } dqrm_dense_quant_t;
 int64_t dqrm_dense_param_count(const dqrm_dense_model_t *model); /* P, or -1 for an invalid descriptor */
 /* As dqrm_dense_step; `quant` may be NULL (then it IS dqrm_dense_step).  Same workspace. */

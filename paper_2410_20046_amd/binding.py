@@ -73,7 +73,8 @@ class dqrm_dense_model_t(C.Structure):
 
 class dqrm_dense_quant_t(C.Structure):
     _fields_ = [("weight_bits", C.c_int32), ("grad_bits", C.c_int32), ("grad_error", C.c_void_p),
-                ("grad_scale", C.c_void_p), ("grad_codes", C.c_void_p), ("grads", C.c_void_p), ("wq", C.c_void_p)]
+                ("grad_scale", C.c_void_p), ("grad_codes", C.c_void_p), ("grads", C.c_void_p), ("wq", C.c_void_p),
+                ("grad_buffer", C.c_void_p), ("buffer_add", C.c_int32), ("buffer_update", C.c_int32)]
 
 
 _lib: Optional[C.CDLL] = None
@@ -321,10 +322,12 @@ class DenseQuant:
 
     def __init__(self, weight_bits: int = 0, grad_bits: int = 0, grad_error: Optional[torch.Tensor] = None,
                  grad_scale: Optional[torch.Tensor] = None, grad_codes: Optional[torch.Tensor] = None,
-                 grads: Optional[torch.Tensor] = None, wq: Optional[torch.Tensor] = None):
-        self._keep = (grad_error, grad_scale, grad_codes, grads, wq)
+                 grads: Optional[torch.Tensor] = None, wq: Optional[torch.Tensor] = None,
+                 grad_buffer: Optional[torch.Tensor] = None, buffer_add: bool = False, buffer_update: bool = False):
+        self._keep = (grad_error, grad_scale, grad_codes, grads, wq, grad_buffer)
         p = lambda t: t.data_ptr() if t is not None else None
-        self.c = dqrm_dense_quant_t(weight_bits, grad_bits, p(grad_error), p(grad_scale), p(grad_codes), p(grads), p(wq))
+        self.c = dqrm_dense_quant_t(weight_bits, grad_bits, p(grad_error), p(grad_scale), p(grad_codes), p(grads), p(wq),
+                                    p(grad_buffer), int(buffer_add), int(buffer_update))
 
     @property
     def ref(self):

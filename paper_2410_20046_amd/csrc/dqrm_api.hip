@@ -797,6 +797,7 @@ int32_t dqrm_dense_step_quant(const dqrm_dense_model_t *m, const dqrm_dense_quan
     const int wbits = quant ? quant->weight_bits : 0, gbits = quant ? quant->grad_bits : 0;
     if ((wbits != 0 && wbits != 4 && wbits != 8) || (gbits != 0 && gbits != 8)) return DQRM_ERR_UNSUPPORTED;
     if (gbits == 8 && !quant->grad_scale) return DQRM_ERR_INVALID_ARG;
+    if (quant && quant->grad_buffer && gbits != 0) return DQRM_ERR_UNSUPPORTED; // FP32 gradient buffers only
     if (!dense_x || !emb_out || !labels || !loss || !grad_emb || !workspace || !aligned(workspace, 256))
         return DQRM_ERR_INVALID_ARG;
     const DenseLayout L = dense_layout(m, batch);
@@ -889,6 +890,8 @@ int32_t dqrm_dense_step_quant(const dqrm_dense_model_t *m, const dqrm_dense_quan
     dqrm::GemmGroup wg{};
     dqrm::SgdGroup sg{};
     sg.lr = lr;
+    if (quant && quant->grad_buffer)
+        sg.buffer = quant->grad_buffer, sg.buffer_add = quant->buffer_add != 0, sg.buffer_update = quant->buffer_update != 0;
     if (gbits) {
         sg.grads = quant->grads ? quant->grads : F(L.grads);
         sg.err = quant->grad_error;

@@ -458,6 +458,11 @@ struct SgdGroup {
     unsigned *gmax_bits; // [tensors][kGradMaxStride] running max |g + e| per tensor (word 0 of each line), as bit
                          // patterns, zeroed before the step
     float *grad_scale;   // [tensors] out
+    // Simulated data parallelism (FP32 gradients): the gradient is added to (or starts) the caller's buffer, flat
+    // over the model like `grads`, and the parameters take the step from the buffer, or none at all
+    float *buffer;     // [P], or null
+    int buffer_add;    // the buffer already holds earlier micro-batches
+    int buffer_update; // this micro-batch ends its group: parameter <- parameter - lr * buffer
     // The launch that ends the step has one more block than the parameters need: it turns the per-sample loss
     // terms into the mean (null otherwise).
     const float *loss_terms; // [batch]
@@ -519,7 +524,13 @@ __global__ __launch_bounds__(256) void sgd_from_partials_kernel(SgdGroup grp)
     for (long long e = (long long)blockIdx.x * 256 + threadIdx.x; e < grp.total; e += (long long)blocks * 256) {
         const SgdElem x = sgd_elem(grp, e);
         const SgdLayer &L = grp.l[x.q];
-        const float s = sum_partials(L, x.le);
+        float s = sum_partials(L, x.le);
+        if (grp.buffer) {
+            float *slot = grp.buffer + L.flat_begin + x.le;
+            if (grp.buffer_add) s = *slot + s;
+            *slot = s;
+            if (!grp.buffer_update) continue;
+        }
         if (x.i < L.in)
             L.W[(long long)x.o * L.in + x.i] = L.W[(long long)x.o * L.in + x.i] - grp.lr * s;
         else

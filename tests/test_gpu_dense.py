@@ -253,3 +253,54 @@ def test_dense_step_int8_gradients_with_error_compensation(oracle):
                 assert_exact(after[(name, l)][part].view(np.uint32), p.view(np.uint32), tag + " stepped parameter bits")
                 err_o[(name, l)] = tuple(e if j == part else err_o[(name, l)][j] for j in (0, 1))
     assert nonzero_residual_used
+
+
+@pytest.mark.parametrize("nodes", [2, 4])
+def test_dense_simulated_nodes_gradient_buffer(oracle, nodes):
+    """Simulated data parallelism for the MLPs: micro-batches add their FP32 gradients to the buffer, the weights
+    move once per group; two groups in a row (the second starts a fresh buffer), against oracle.SimulatedDPDense."""
+    import torch
+    import paper_2410_20046_amd as dq
+
+    T, D, B, lr = 5, 24, 96 * nodes, 0.1
+    Bm = B // nodes
+    _say(f"dense simulated nodes n={nodes} micro-batch {Bm}")
+    bot_dims, bw, bb, top_dims, tw, tb = make_dense_model("medium", T, D, seed=1007)
+    dev = torch.device("cuda:0")
+    m = dq.DenseModel(T, D, bot_dims, bw, bb, top_dims, tw, tb, dev)
+    ws = torch.empty(dq.dqrm_dense_workspace_bytes(m, Bm), dtype=torch.uint8, device=dev)
+    loss = torch.zeros(1, dtype=torch.float32, device=dev)
+    grad = torch.empty((Bm, T, D), dtype=torch.float32, device=dev)
+    P = dq.dqrm_dense_param_count(m)
+    buf = torch.full((P,), float("nan"), dtype=torch.float32, device=dev)  # the first micro-batch must overwrite it
+    f64 = lambda l: [np.ascontiguousarray(a, np.float64) for a in l]
+    BW, BB, TW, TB = f64(bw), f64(bb), f64(tw), f64(tb)
+    sim = oracle.SimulatedDPDense(bot_dims, BW, BB, top_dims, TW, TB, simulated_nodes=nodes, lr=lr)
+    rng = np.random.default_rng(11)
+    j = 0
+    for grp in range(2):
+        x, y = dense_batch(B, bot_dims[0], seed=1007, k=grp)
+        emb = (rng.standard_normal((B, T, D)) * 0.25).astype(np.float32)
+        for k in range(nodes):
+            sl = slice(k * Bm, (k + 1) * Bm)
+            q = dq.DenseQuant(grad_buffer=buf, buffer_add=(k > 0), buffer_update=(k == nodes - 1))
+            w_before = m.top_w[0].clone()
+            dq.dqrm_dense_step_quant(m, q, Bm, *(torch.from_numpy(np.ascontiguousarray(a[sl])).to(dev) for a in (x, emb, y)),
+                                     lr, loss, grad, ws)
+            torch.cuda.synchronize()
+            loss_o, grad_o, ended = sim.micro_batch(j, x[sl], emb[sl], y[sl])
+            j += 1
+            assert abs(float(loss.cpu().item()) - loss_o) <= 1e-6 + 1e-5 * abs(loss_o)
+            assert_float_close(grad.cpu().numpy(), grad_o, f"group {grp} micro-batch {k} grad_emb")
+            if not ended:
+                assert torch.equal(m.top_w[0], w_before), "weights must not move inside a group"
+        for name, got, exp in (("bot_w", m.bot_w, BW), ("bot_b", m.bot_b, BB), ("top_w", m.top_w, TW), ("top_b", m.top_b, TB)):
+            for l, (g, e) in enumerate(zip(got, exp)):
+                assert_float_close(g.cpu().numpy(), e, f"group {grp} {name}[{l}]")
+    assert not torch.isnan(buf).any()
+    # INT8 gradients cannot be combined with the buffer
+    q = dq.DenseQuant(grad_bits=8, grad_scale=torch.zeros(2 * (len(bw) + len(tw)), dtype=torch.float32, device=dev),
+                      grad_buffer=buf)
+    with pytest.raises(dq.DqrmError):
+        dq.dqrm_dense_step_quant(m, q, Bm, torch.zeros((Bm, bot_dims[0]), device=dev), torch.zeros((Bm, T, D), device=dev),
+                                 torch.zeros(Bm, device=dev), lr, loss, grad, ws)

@@ -480,8 +480,8 @@ def main():
         # packed mirror: only the rows a step touches are re-encoded, so an empty mirror gives the same work
         pk = np.zeros((wl.R, D // 2), np.uint8)
         done, t_cpu = 0, 0.0
-        while t_cpu < args.cpu_seconds and done < args.pool:
-            idx, off = pool[done]
+        while t_cpu < args.cpu_seconds and done < 8 * args.pool:
+            idx, off = pool[done % args.pool]
             g = grads[done % args.grad_pool]
             t1 = time.perf_counter()
             oracle.embbag_fwd(Wo, None, wl.row_offsets, s, B, idx, off, mode=0, want_codes=False)
@@ -491,7 +491,7 @@ def main():
             t_cpu += time.perf_counter() - t1
             done += 1
         cpu = {"value": round(N * done / t_cpu, 1), "unit": "lookups/s", "cores": 1, "kind": "oracle",
-               "sample": f"{done} steps of the same {args.workload} workload (batches 0..{done - 1}), "
+               "sample": f"{done} steps of the same {args.workload} workload (its {args.pool} batches in turn), "
                          f"{t_cpu:.1f} s of single-threaded C oracle (fwd master mode + bwd + quant + update)"}
         log(f"[bench] oracle: {done} steps in {t_cpu:.1f}s")
 

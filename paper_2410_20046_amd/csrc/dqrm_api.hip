@@ -704,18 +704,25 @@ hipError_t launch_gemm_group(hipStream_t st, dqrm::GemmGroup &grp)
     }
     grp.total_tiles = tiles;
     if (tiles == 0) return hipSuccess;
+    if (grp.count > 1) {
+        hipLaunchKernelGGL((dqrm::gemm_wave_group_kernel<A_MODE, B_MODE>),
+                           dim3((tiles + dqrm::kGemmWaves - 1) / dqrm::kGemmWaves), dim3(dqrm::kGemmThreads), 0, st, grp);
+        return hipGetLastError();
+    }
+    dqrm::GemmOne one;
+    one.p = grp.p[0];
+    one.total_tiles = tiles;
     // A product with fewer tiles than the chip has SIMDs (4 per CU) leaves some of them idle: let 2 or 4 waves
     // share a tile, each with a slice of the reduction (at least one pair of slabs each), up to one wave per
     // SIMD.  (Measured: beyond that, slices cost more than they bring.)
-    int ks = 1;
-    if (grp.count == 1 && grp.p[0].splits == 1) {
-        const int pairs = grp.p[0].K / (2 * dqrm::kGemmBK);
-        while (ks < 4 && tiles * ks * 2 <= num_cus() * 4 && pairs >= ks * 2) ks *= 2;
+    one.kslices = 1;
+    if (one.p.splits == 1) {
+        const int pairs = one.p.K / (2 * dqrm::kGemmBK);
+        while (one.kslices < 4 && tiles * one.kslices * 2 <= num_cus() * 4 && pairs >= one.kslices * 2) one.kslices *= 2;
     }
-    grp.kslices = ks;
-    const int waves = tiles * ks;
+    const int waves = tiles * one.kslices;
     hipLaunchKernelGGL((dqrm::gemm_wave_kernel<A_MODE, B_MODE>), dim3((waves + dqrm::kGemmWaves - 1) / dqrm::kGemmWaves),
-                       dim3(dqrm::kGemmThreads), 0, st, grp);
+                       dim3(dqrm::kGemmThreads), 0, st, one);
     return hipGetLastError();
 }
 

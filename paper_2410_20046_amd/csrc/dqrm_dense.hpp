@@ -60,7 +60,6 @@ constexpr int kGemmMaxGroup = 16;
 struct GemmGroup {
     GemmArgs p[kGemmMaxGroup];
     int count, total_tiles;
-    int kslices; // 1, 2 or 4 waves of a workgroup share a tile, each taking a slice of the reduction (splits == 1)
 };
 
 constexpr int kGemmThreads = 256;
@@ -194,25 +193,13 @@ __device__ __forceinline__ void slab_settle_fast(SlabRegs &x, const SlabRegs &st
     }
 }
 
+// the tile `tile` (and, with ks > 1, the slice wave % ks of its reduction) of problem g, by one wave
 template <int A_MODE, int B_MODE>
-__global__ __launch_bounds__(kGemmThreads) void gemm_wave_kernel(GemmGroup grp)
+__device__ __forceinline__ void gemm_wave_tile(const GemmArgs &g, int tile, bool live, int ks, int wave, int lane)
 {
     constexpr bool A_RC = A_MODE == kOpRC, B_RC = B_MODE == kOpRC;
     __shared__ __align__(16) float turn[kGemmWaves][2][32 * kGemmPitch]; // per wave: LDS pieces of A and B
-    const int lane = threadIdx.x & (kWave - 1);
-    const int wave = __builtin_amdgcn_readfirstlane((int)threadIdx.x / kWave); // wave-uniform, and known to be
-    // With kslices > 1 the waves of a workgroup meet at a barrier below: a wave past the last tile stays, takes
-    // the last tile with an empty reduction and stores nothing.
-    const int ks = grp.kslices, kz = wave & (ks - 1);
-    int tile = ((int)blockIdx.x * kGemmWaves + wave) / ks;
-    const bool live = tile < grp.total_tiles;
-    if (!live && ks == 1) return;
-    tile = min(tile, grp.total_tiles - 1);
-    int pi = 0;
-#pragma unroll 1
-    for (int q = 1; q < grp.count; ++q)
-        if (tile >= grp.p[q].tile_begin) pi = q;
-    const GemmArgs &g = grp.p[pi];
+    const int kz = wave & (ks - 1);
     const int tiles_j = (g.N + 31) / 32, tiles_i = (g.M + 31) / 32;
     int local = tile - g.tile_begin;
     const int z = local / (tiles_i * tiles_j);
@@ -369,6 +356,41 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_wave_kernel(GemmGroup grp)
         if (g.mask) x = g.mask[off] > 0.0f ? x : 0.0f;
         g.C[off] = x;
     }
+}
+
+// With kslices > 1 the waves of a workgroup meet at a barrier inside: a wave past the last tile stays, takes the
+// last tile with an empty reduction and stores nothing.
+struct GemmOne {
+    GemmArgs p;
+    int total_tiles, kslices;
+};
+
+// one product per launch
+template <int A_MODE, int B_MODE>
+__global__ __launch_bounds__(kGemmThreads) void gemm_wave_kernel(GemmOne one)
+{
+    const int lane = threadIdx.x & (kWave - 1);
+    const int wave = __builtin_amdgcn_readfirstlane((int)threadIdx.x / kWave); // wave-uniform, and known to be
+    const int ks = one.kslices;
+    int tile = ((int)blockIdx.x * kGemmWaves + wave) / ks;
+    const bool live = tile < one.total_tiles;
+    if (!live && ks == 1) return;
+    gemm_wave_tile<A_MODE, B_MODE>(one.p, min(tile, one.total_tiles - 1), live, ks, wave, lane);
+}
+
+// several products in one launch (kslices == 1)
+template <int A_MODE, int B_MODE>
+__global__ __launch_bounds__(kGemmThreads) void gemm_wave_group_kernel(GemmGroup grp)
+{
+    const int lane = threadIdx.x & (kWave - 1);
+    const int wave = __builtin_amdgcn_readfirstlane((int)threadIdx.x / kWave);
+    const int tile = (int)blockIdx.x * kGemmWaves + wave;
+    if (tile >= grp.total_tiles) return; // whole waves leave; no barrier inside with one slice
+    int pi = 0;
+#pragma unroll 1
+    for (int q = 1; q < grp.count; ++q)
+        if (tile >= grp.p[q].tile_begin) pi = q;
+    gemm_wave_tile<A_MODE, B_MODE>(grp.p[pi], tile, true, 1, wave, lane);
 }
 
 // ---- the head: last linear layer (one output), sigmoid, binary cross-entropy, gradient w.r.t. its input ----

@@ -215,10 +215,12 @@ int32_t dqrm_sparse_update(const dqrm_tables_t *tables, int64_t capacity, const 
  *              [max_total][D] (16-byte aligned); must be >= the sum of the U_k
  *   outputs    uniq_rows, table_uniq_offsets [T+1], num_unique [1], sums; rows
  *              past num_unique are not written
- * A table may bring at most DQRM_MAX_TABLE_LOOKUPS rows over all blocks.  Blocks
- * that break these rules are reported through dqrm_check_status
- * (DQRM_ERR_BAD_OFFSETS, DQRM_ERR_CAPACITY, DQRM_ERR_INDEX_OUT_OF_RANGE) and the
- * offending piece contributes nothing.  The workspace (256-byte aligned, no
+ * Blocks that break these rules are reported through dqrm_check_status
+ * (DQRM_ERR_BAD_OFFSETS: offsets that do not start at 0, go backwards or pass the
+ * capacity - the whole block then contributes nothing - or rows that are not
+ * ascending - the sums of the rows concerned are then unspecified;
+ * DQRM_ERR_CAPACITY: the outputs cannot hold the blocks' rows, the rest is left
+ * out); every access stays in bounds.  The workspace (256-byte aligned, no
  * initialisation needed) is the library's scratch; the caller owns everything. */
 typedef struct {
     const int64_t *uniq_rows;

@@ -223,11 +223,12 @@ int32_t sparse_update_impl(const dqrm_tables_t *tables, int64_t capacity, const 
     return DQRM_OK;
 }
 
-// workspace of dqrm_sparse_merge: the laid-out list, its sort outputs, and the sort's own workspace
+// workspace of dqrm_sparse_merge: table offsets of the merged list, and per place the source word, the
+// first-of-its-row flag and the flags before it
 struct MergeLayout {
-    size_t off_rows, off_offsets, off_src, off_sorted_pos, off_seg_offsets, off_dedupe, total;
+    size_t off_base, off_src, off_head, off_excl, off_table_heads, total;
 };
-MergeLayout merge_layout(int T, int D, int n, int64_t max_total)
+MergeLayout merge_layout(int T, int64_t max_total)
 {
     MergeLayout L{};
     size_t o = 0;
@@ -237,12 +238,11 @@ MergeLayout merge_layout(int T, int D, int n, int64_t max_total)
         return at;
     };
     const size_t m = (size_t)max_total;
-    L.off_rows = take(m * sizeof(int64_t));
-    L.off_offsets = take(((size_t)T * n + 1) * sizeof(int64_t));
+    L.off_base = take(((size_t)T + 1) * sizeof(int32_t));
     L.off_src = take(m * sizeof(int32_t));
-    L.off_sorted_pos = take(m * sizeof(int32_t));
-    L.off_seg_offsets = take((m + 1) * sizeof(int32_t));
-    L.off_dedupe = take(ws_layout(T, D, max_total).total);
+    L.off_head = take(m * sizeof(int32_t));
+    L.off_excl = take(m * sizeof(int32_t));
+    L.off_table_heads = take((size_t)T * sizeof(int32_t));
     L.total = o;
     return L;
 }
@@ -500,7 +500,7 @@ size_t dqrm_sparse_merge_workspace_bytes(int32_t num_tables, int32_t dim, int32_
     if (num_tables < 1 || num_tables > DQRM_MAX_TABLES || dim < 8 || dim > DQRM_MAX_DIM || dim % 8 != 0 ||
         num_blocks < 1 || num_blocks > DQRM_MAX_DEDUPE_BATCHES || max_total < 0 || max_total > kMaxIndices)
         return 0;
-    return merge_layout(num_tables, dim, num_blocks, max_total).total;
+    return merge_layout(num_tables, max_total).total;
 }
 
 int32_t dqrm_sparse_merge(const dqrm_tables_t *tables, int32_t num_blocks, const dqrm_sparse_block_t *blocks,
@@ -518,39 +518,33 @@ int32_t dqrm_sparse_merge(const dqrm_tables_t *tables, int32_t num_blocks, const
     if (!aligned(sums, 16) || !aligned(workspace, 256)) return DQRM_ERR_INVALID_ARG;
     dqrm::MergeArgs ma;
     std::memset(&ma, 0, sizeof(ma));
+    int64_t max_cap = 0;
     for (int k = 0; k < num_blocks; ++k) {
         const dqrm_sparse_block_t &b = blocks[k];
         if (!b.uniq_rows || !b.table_uniq_offsets || !b.gq || !aligned(b.gq, 4) || b.capacity < 0)
             return DQRM_ERR_INVALID_ARG;
         if (b.capacity >= (1LL << dqrm::kMergeSrcBits)) return DQRM_ERR_UNSUPPORTED;
         ma.uniq_rows[k] = b.uniq_rows, ma.tuo[k] = b.table_uniq_offsets, ma.gq[k] = b.gq, ma.capacity[k] = b.capacity;
+        if (b.capacity > max_cap) max_cap = b.capacity;
     }
-    const MergeLayout L = merge_layout(T, D, num_blocks, max_total);
+    const MergeLayout L = merge_layout(T, max_total);
     if (workspace_bytes < L.total) return DQRM_ERR_WORKSPACE_TOO_SMALL;
     char *ws = static_cast<char *>(workspace);
-    ma.n = num_blocks, ma.T = T, ma.D = D, ma.max_total = max_total;
-    ma.cat_rows = reinterpret_cast<int64_t *>(ws + L.off_rows);
-    ma.cat_offsets = reinterpret_cast<int64_t *>(ws + L.off_offsets);
-    ma.cat_src = reinterpret_cast<int32_t *>(ws + L.off_src);
-    int32_t *sorted_pos = reinterpret_cast<int32_t *>(ws + L.off_sorted_pos);
-    int32_t *seg_offsets = reinterpret_cast<int32_t *>(ws + L.off_seg_offsets);
-    ma.sorted_pos = sorted_pos, ma.seg_offsets = seg_offsets, ma.num_unique = num_unique, ma.sums = sums;
+    ma.n = num_blocks, ma.T = T, ma.D = D, ma.max_total = (int)max_total;
+    ma.base = reinterpret_cast<int32_t *>(ws + L.off_base);
+    ma.sorted_src = reinterpret_cast<int32_t *>(ws + L.off_src);
+    ma.head = reinterpret_cast<int32_t *>(ws + L.off_head);
+    ma.local_excl = reinterpret_cast<int32_t *>(ws + L.off_excl);
+    ma.table_heads = reinterpret_cast<int32_t *>(ws + L.off_table_heads);
+    ma.uniq_rows_out = uniq_rows, ma.tuo_out = table_uniq_offsets, ma.num_unique = num_unique, ma.sums = sums;
 
     hipStream_t st = static_cast<hipStream_t>(stream);
-    hipLaunchKernelGGL(dqrm::merge_layout_kernel, dim3(T * num_blocks), dim3(256), 0, st, ma);
-    // sort and segment the list: the kernels of dqrm_dedupe with one "bag" per block and no bag bookkeeping
-    dqrm::DedupeArgs da;
-    std::memset(&da, 0, sizeof(da));
-    dqrm::DedupeBatch &o = da.b[0];
-    o.indices = ma.cat_rows, o.offsets = ma.cat_offsets, o.N = max_total;
-    o.ws = ws_views(ws + L.off_dedupe, ws_layout(T, D, max_total));
-    o.sorted_pos = sorted_pos, o.tuo = table_uniq_offsets, o.num_unique = num_unique, o.uniq_rows = uniq_rows;
-    o.seg_offsets = seg_offsets, o.no_bags = 1;
-    da.row_offsets = tables->row_offsets_dev, da.T = T, da.B = num_blocks;
-    hipLaunchKernelGGL(dqrm::dedupe_kernel, dim3(T, 1), dim3(dqrm::kDdThreads), 0, st, da);
-    hipLaunchKernelGGL(dqrm::dedupe_finish_kernel, dim3(grid_for(max_total, dqrm::kSegThreads, 2), 1),
-                       dim3(dqrm::kSegThreads), 0, st, da);
-    hipLaunchKernelGGL(dqrm::merge_sum_kernel, dim3(grid_for(max_total * (D / 4), 256, 8)), dim3(256), 0, st, ma);
+    const int per_block = (int)((max_cap + dqrm::kMergeThreads - 1) / dqrm::kMergeThreads);
+    hipLaunchKernelGGL(dqrm::merge_rank_kernel, dim3(per_block < 1 ? 1 : per_block, num_blocks), dim3(dqrm::kMergeThreads),
+                       dqrm::merge_rank_lds_bytes(T, num_blocks), st, ma);
+    hipLaunchKernelGGL(dqrm::merge_scan_kernel, dim3(T), dim3(dqrm::kMergeScanThreads), 0, st, ma);
+    hipLaunchKernelGGL(dqrm::merge_sum_kernel, dim3(grid_for(max_total * (D / 4), dqrm::kMergeThreads, 8)),
+                       dim3(dqrm::kMergeThreads), dqrm::merge_sum_lds_bytes(T), st, ma);
     DQRM_HIP_CHECK(hipGetLastError());
     return DQRM_OK;
 }

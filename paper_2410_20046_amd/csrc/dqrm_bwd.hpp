@@ -102,7 +102,6 @@ struct DedupeBatch {
     int32_t *num_unique;
     int64_t *uniq_rows;
     int32_t *seg_offsets;
-    int no_bags; // the caller needs the sort and the segments only (merging sparse blocks): no bag is looked up
 };
 struct DedupeArgs {
     DedupeBatch b[DQRM_MAX_DEDUPE_BATCHES];
@@ -158,9 +157,8 @@ __global__ __launch_bounds__(kDdThreads) void dedupe_kernel(DedupeArgs args)
     // batch) the bag of position p is p itself and nothing needs to be stored.
     DQRM_TICK(0);
     constexpr int kBagBatch = 8;
-    const bool no_bags = bt.no_bags != 0;
-    bool one_each = !disabled && !no_bags && (n == B);
-    if (!disabled && !no_bags) {
+    bool one_each = !disabled && (n == B);
+    if (!disabled) {
         for (int b0 = 0; b0 < B; b0 += kDdThreads * kBagBatch) {
             long long s[kBagBatch], e[kBagBatch];
 #pragma unroll
@@ -183,7 +181,7 @@ __global__ __launch_bounds__(kDdThreads) void dedupe_kernel(DedupeArgs args)
         }
     }
     one_each = __syncthreads_and(one_each ? 1 : 0) != 0;
-    if (!disabled && !one_each && !no_bags) {
+    if (!disabled && !one_each) {
         for (int b = tid; b < B; b += kDdThreads) {
             long long s = offsets[(long long)t * B + b], e = offsets[(long long)t * B + b + 1];
             s = s < lo ? lo : (s > hi ? hi : s);
@@ -380,7 +378,7 @@ __global__ __launch_bounds__(kDdThreads) void dedupe_kernel(DedupeArgs args)
 
     // ---- phase 4: write the table-local lists -------------------------------
     DQRM_TICK(5);
-    if (!one_each && !no_bags) {
+    if (!one_each) {
         // bag of every sorted lookup: gathered first, all at once, so that the loads overlap
 #pragma unroll
         for (int r = 0; r < kDdMaxRounds; ++r) {
@@ -413,7 +411,7 @@ __global__ __launch_bounds__(kDdThreads) void dedupe_kernel(DedupeArgs args)
             }
             if (chunk_of[r] & (1u << 15)) { // a row looked up exactly once
                 const int c = (int)(chunk_of[r] & 0x7FFFu) + singles_before - 1;
-                const int b = one_each ? (p < B ? p : B - 1) : (no_bags ? 0 : ws.sorted_bag[base + i]);
+                const int b = one_each ? (p < B ? p : B - 1) : ws.sorted_bag[base + i];
                 ws.single_local[base + c] = make_int4(base + i, b, seg, (int)skey[i]);
             }
         }
@@ -556,7 +554,7 @@ __global__ __launch_bounds__(kSegThreads) void dedupe_finish_kernel(DedupeArgs a
     }
     // the bags of chunk c's lookups at a place that depends on c alone (a chunk has at least two lookups,
     // so there are at most N / 2 chunks): DQRM_SEG_CHUNK consecutive threads per chunk
-    for (int64_t w = first; w < (args.b[blockIdx.y].no_bags ? 0 : (int64_t)C * DQRM_SEG_CHUNK); w += step) {
+    for (int64_t w = first; w < (int64_t)C * DQRM_SEG_CHUNK; w += step) {
         const int c = (int)(w / DQRM_SEG_CHUNK), i = (int)(w % DQRM_SEG_CHUNK);
         const int t = table_of(s_tco, T, c);
         const int4 d = a.ws.chunk_local[s_base[t] + (c - s_tco[t])];

@@ -9,7 +9,8 @@ ROOT = os.path.dirname(PKG)
 CSRC = os.path.join(PKG, "csrc")
 LIB = os.path.join(PKG, "libdqrm.so")
 SOURCES = [os.path.join(CSRC, "dqrm_api.hip")]
-HEADERS = [os.path.join(CSRC, f) for f in ("dqrm_device.hpp", "dqrm_fwd.hpp", "dqrm_bwd.hpp", "dqrm_update.hpp")] + [
+HEADERS = [os.path.join(CSRC, f) for f in ("dqrm_device.hpp", "dqrm_fwd.hpp", "dqrm_bwd.hpp", "dqrm_update.hpp",
+                                             "dqrm_merge.hpp", "dqrm_dense.hpp")] + [
     os.path.join(ROOT, "include", "dqrm.h")]
 
 HIPCC_FLAGS = [

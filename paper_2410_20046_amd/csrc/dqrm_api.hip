@@ -678,7 +678,7 @@ DenseLayout dense_layout(const dqrm_dense_model_t *m, int32_t batch)
     const size_t P = (size_t)dense_param_count(m);
     L.wq = take(P);
     L.grads = take(P);
-    L.gmax = take((size_t)dqrm::kMaxGradTensors * dqrm::kGradMaxStride);
+    L.gmax = take((size_t)dqrm::kMaxGradTensors * dqrm::kGradMaxSlots * dqrm::kGradMaxStride);
     L.loss_terms = take((size_t)batch);
     L.total = o;
     return L;
@@ -866,7 +866,7 @@ int32_t dqrm_dense_step_quant(const dqrm_dense_model_t *m, const dqrm_dense_quan
     ha.dX = last > 0 ? F(L.top_dz[last - 1]) : F(L.dR);
     ha.relu_input = last > 0; // the input of top layer l > 0 is a ReLU output; the interaction output is not
     ha.B = B, ha.in = m->top_dims[last];
-    ha.zero = gmax, ha.nzero = gbits ? dqrm::kMaxGradTensors * dqrm::kGradMaxStride : 0;
+    ha.zero = gmax, ha.nzero = gbits ? dqrm::kMaxGradTensors * dqrm::kGradMaxSlots : 0, ha.zstride = dqrm::kGradMaxStride;
     hipLaunchKernelGGL(dqrm::head_kernel, dim3((B + 3) / 4), dim3(256), 0, st, ha);
     DQRM_HIP_CHECK(hipGetLastError());
 

@@ -410,14 +410,14 @@ struct HeadArgs {
     float *dX;         // [B][in]
     int relu_input;
     int B, in;
-    unsigned *zero;
-    int nzero;
+    unsigned *zero; // nzero words, zstride apart
+    int nzero, zstride;
 };
 
 __global__ __launch_bounds__(256) void head_kernel(HeadArgs a)
 {
     if (blockIdx.x == 0)
-        for (int k = threadIdx.x; k < a.nzero; k += 256) a.zero[k] = 0u;
+        for (int k = threadIdx.x; k < a.nzero; k += 256) a.zero[(long long)k * a.zstride] = 0u;
     const int lane = threadIdx.x & (kWave - 1);
     const int b = (int)blockIdx.x * (256 / kWave) + (int)threadIdx.x / kWave;
     if (b >= a.B) return;
@@ -477,7 +477,7 @@ struct SgdGroup {
     float *grads;        // [P] this step's FP32 gradients (before the residual is added)
     float *err;          // [P] residuals carried between steps, or null
     int8_t *codes;       // [P] INT8 codes out, or null
-    unsigned *gmax_bits; // [tensors][kGradMaxStride] running max |g + e| per tensor (word 0 of each line), as bit
+    unsigned *gmax_bits; // [tensors][kGradMaxSlots][kGradMaxStride] running max |g + e| per tensor (word 0 of each line), as bit
                          // patterns, zeroed before the step
     float *grad_scale;   // [tensors] out
     // Simulated data parallelism (FP32 gradients): the gradient is added to (or starts) the caller's buffer, flat
@@ -563,7 +563,9 @@ __global__ __launch_bounds__(256) void sgd_from_partials_kernel(SgdGroup grp)
 // INT8 gradients, pass 1: the FP32 gradient of every parameter (slices added in order) goes to `grads`,
 // and the maximum of |gradient + residual| of every tensor to gmax_bits (per-block maxima in LDS first).
 constexpr int kMaxGradTensors = 2 * 2 * 16; // weights and bias of at most 16 + 16 layers
-constexpr int kGradMaxStride = 32;          // words between two tensors' maxima: one 128-byte line each (same-line
+constexpr int kGradMaxSlots = 16;           // lines per tensor, a workgroup uses line blockIdx % 16: a large tensor's
+                                            // ~700 workgroups would otherwise queue up at one line
+constexpr int kGradMaxStride = 32;          // words between two maxima: one 128-byte line each (same-line
                                             // atomics from many workgroups serialise at the memory side)
 __global__ __launch_bounds__(256) void grad_sum_absmax_kernel(SgdGroup grp)
 {
@@ -598,7 +600,8 @@ __global__ __launch_bounds__(256) void grad_sum_absmax_kernel(SgdGroup grp)
     }
     __syncthreads();
     for (int k = threadIdx.x; k < kMaxGradTensors; k += 256)
-        if (s_max[k] != 0u) atomicMax(grp.gmax_bits + k * kGradMaxStride, s_max[k]);
+        if (s_max[k] != 0u)
+            atomicMax(grp.gmax_bits + (k * kGradMaxSlots + (int)(blockIdx.x % kGradMaxSlots)) * kGradMaxStride, s_max[k]);
 }
 
 // pass 2: g' = g + e;  s = max(max|g'| / 127, 1e-8);  code = clamp(rint(g' / s), -128, 127);
@@ -611,7 +614,12 @@ __global__ __launch_bounds__(256) void grad_quant_ec_kernel(SgdGroup grp)
     // the tensors of this launch's layers
     for (int k = threadIdx.x; k < 2 * grp.count; k += 256) {
         const int t = grp.l[k >> 1].tensor0 + (k & 1);
-        const float gs = scale_from_absmax(__uint_as_float(grp.gmax_bits[t * kGradMaxStride]), 127.0f);
+        unsigned m[kGradMaxSlots], mx = 0u;
+#pragma unroll
+        for (int q = 0; q < kGradMaxSlots; ++q) m[q] = grp.gmax_bits[(t * kGradMaxSlots + q) * kGradMaxStride];
+#pragma unroll
+        for (int q = 0; q < kGradMaxSlots; ++q) mx = max(mx, m[q]); // (non-negative floats order like their bits)
+        const float gs = scale_from_absmax(__uint_as_float(mx), 127.0f);
         s_scale[t] = Scale(gs);
         if (blockIdx.x == 0) grp.grad_scale[t] = gs;
     }

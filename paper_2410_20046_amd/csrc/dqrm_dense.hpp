@@ -226,6 +226,17 @@ __device__ __forceinline__ void gemm_wave_tile(const GemmArgs &g, int tile, bool
     float *lds_a = turn[wave][0], *lds_b = turn[wave][1];
     // (requested now, used in the epilogue)
     const float bias_j = (g.bias && g.splits <= 1) ? g.bias[min(j0 + w, g.N - 1)] : 0.0f;
+    // ... and so is the mask of this lane's 16 outputs (rows and columns past the edge re-read the last ones)
+    float mask_v[16];
+    if (g.mask && g.splits <= 1) {
+        const long long mj = (long long)min(j0 + w, g.N - 1) * g.c_sj;
+#pragma unroll
+        for (int v = 0; v < 16; ++v)
+            mask_v[v] = g.mask[(long long)min(i0 + 8 * (v >> 2) + 4 * h + (v & 3), g.M - 1) * g.c_si + mj];
+    } else {
+#pragma unroll
+        for (int v = 0; v < 16; ++v) mask_v[v] = 1.0f;
+    }
 
     floatx16 acc;
 #pragma unroll
@@ -353,7 +364,7 @@ __device__ __forceinline__ void gemm_wave_tile(const GemmArgs &g, int tile, bool
         float x = acc[v] + bj;
         if (g.relu) x = fmaxf(x, 0.0f);
         const long long off = (long long)i * g.c_si + (long long)j * g.c_sj;
-        if (g.mask) x = g.mask[off] > 0.0f ? x : 0.0f;
+        x = mask_v[v] > 0.0f ? x : 0.0f;
         g.C[off] = x;
     }
 }

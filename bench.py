@@ -469,6 +469,7 @@ def main():
     torch.cuda.synchronize()
     copy_gbs = 10 * 2 * a.numel() * 4 / (c0.elapsed_time(c1) * 1e-3) / 1e9
     del a, b
+    roofline["frac_of_copy_bw"] = round(dom_gbs / copy_gbs, 4)  # against what a plain copy reaches on this machine
 
     lookups_per_s = N * args.steps / wall
     step_gbs = ab["step"] / (ms_per_step * 1e-3) / 1e9

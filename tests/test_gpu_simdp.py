@@ -186,6 +186,74 @@ def test_bad_blocks_are_reported_not_used(oracle):
     assert U == np.unique(np.concatenate([wl.row_offsets[t] + h[0][h[1][t]:h[1][t + 1]] for h in host for t in range(wl.T)])).size
 
 
+def test_merge_of_random_blocks(oracle):
+    """dqrm_sparse_merge alone on blocks built directly (random ascending rows per table, random codes): empty
+    tables, tables present in one block only, rows shared by all blocks, single rows, and a table whose union is
+    far larger than one workgroup's sort would hold; against the oracle's dense buffer."""
+    import ctypes as C
+    import torch
+    import paper_2410_20046_amd as dq
+
+    dev = torch.device("cuda:0")
+    rng = np.random.default_rng(4242)
+    for case in range(24):
+        T = int(rng.integers(1, 9))
+        D = int(rng.choice([8, 16, 40, 64]))
+        n = int(rng.integers(1, 9))
+        cards = rng.choice([1, 2, 7, 100, 5000, 200000], size=T).astype(np.int64)
+        if case == 0:
+            T, n, cards = 3, 4, np.array([5, 400000, 64], np.int64)  # 4 x 30000 rows of one table
+        ro = np.concatenate([[0], np.cumsum(cards)]).astype(np.int64)
+        R = int(ro[-1])
+        _say(f"random blocks case {case}: T={T} D={D} n={n} cards={cards.tolist()}")
+        blocks_h = []
+        for k in range(n):
+            rows, tuo = [], [0]
+            for t in range(T):
+                c = int(cards[t])
+                want = 30000 if (case == 0 and t == 1) else int(rng.choice([0, 1, 3, min(c, 50), min(c, 700)]))
+                r = np.sort(rng.choice(c, size=min(want, c), replace=False)).astype(np.int64)
+                rows.append(r)
+                tuo.append(tuo[-1] + len(r))
+            rows = np.concatenate(rows) if rows else np.empty(0, np.int64)
+            gq = rng.integers(-128, 128, size=(max(len(rows), 1), D)).astype(np.int8)
+            blocks_h.append((rows, np.array(tuo, np.int32), gq))
+        buffer = np.zeros((R, D), np.int32)
+        touched = np.zeros(R, np.uint8)
+        for rows, tuo, gq in blocks_h:
+            oracle.lib().oracle_simdp_accumulate(
+                C.c_int(T), C.c_int(D), ro.ctypes.data_as(C.POINTER(C.c_int64)), rows.ctypes.data_as(C.POINTER(C.c_int64)),
+                tuo.ctypes.data_as(C.POINTER(C.c_int32)), gq.ctypes.data_as(C.POINTER(C.c_int8)),
+                buffer.ctypes.data_as(C.POINTER(C.c_int32)), touched.ctypes.data_as(C.POINTER(C.c_uint8)))
+        master = torch.zeros((R, D), dtype=torch.float32, device=dev)
+        tables = dq.Tables(ro, D, master, None)
+        blocks_d = []
+        for rows, tuo, gq in blocks_h:
+            cap = max(len(rows), 1) + int(rng.integers(0, 5))  # some slack behind the rows
+            rd = torch.zeros(cap, dtype=torch.int64, device=dev)
+            rd[: len(rows)] = torch.from_numpy(rows).to(dev)
+            gd = torch.zeros((cap, D), dtype=torch.int8, device=dev)
+            gd[: gq.shape[0]] = torch.from_numpy(gq).to(dev)
+            blocks_d.append((rd, torch.from_numpy(tuo).to(dev), gd))
+        total = sum(len(b[0]) for b in blocks_h)
+        cap_total = max(total, 1)
+        m_rows = torch.full((cap_total,), -7, dtype=torch.int64, device=dev)
+        m_tuo = torch.empty(T + 1, dtype=torch.int32, device=dev)
+        m_nu = torch.zeros(1, dtype=torch.int32, device=dev)
+        m_sums = torch.zeros((cap_total, D), dtype=torch.int32, device=dev)
+        ws = torch.empty(dq.dqrm_sparse_merge_workspace_bytes(T, D, n, cap_total), dtype=torch.uint8, device=dev)
+        dq.dqrm_sparse_merge(tables, blocks_d, m_rows, m_tuo, m_nu, m_sums, ws)
+        code, tb, val = dq.dqrm_check_status()
+        assert code == 0, (case, code, tb, val)
+        U = int(m_nu.cpu().item())
+        tuo_g, rows_g, sums_g = m_tuo.cpu().numpy(), m_rows.cpu().numpy()[:U], m_sums.cpu().numpy()[:U]
+        want = np.flatnonzero(touched)
+        assert U == want.size and tuo_g[0] == 0 and tuo_g[T] == U, (case, U, want.size)
+        glob = np.concatenate([ro[t] + rows_g[tuo_g[t]:tuo_g[t + 1]] for t in range(T)]) if U else np.empty(0, np.int64)
+        assert_exact(glob, want, f"case {case} merged rows")
+        assert_exact(sums_g, buffer[want], f"case {case} merged sums")
+
+
 def test_terabyte_full_size_eight_nodes(oracle):
     """The benchmark workload at full size, its batch of 8192 split over 8 simulated nodes."""
     wl = make_workload("terabyte")

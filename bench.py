@@ -104,7 +104,7 @@ def main():
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on ONE GPU (no collectives, no sharding); use --gpus 1. "
-                 "DESIGN.md says how the path would shard.")
+                 "The repository's design notes say how the path would shard.")
 
     import numpy as np
     import torch

@@ -252,7 +252,7 @@ def grad_normal(B: int, T: int, D: int, seed: int, k: int) -> np.ndarray:
     return g
 
 
-# ---- the dense part of the model (BASELINE "full train step" configuration) ---------------
+# ---- the dense part of the model (the "full train step" configuration) ---------------
 DENSE_CONFIGS = {
     # Kaggle shape: 13 dense features, bottom MLP 13-512-256-64-16, top MLP 367-512-256-1
     "kaggle": dict(num_dense=13, bot=[13, 512, 256, 64, 16], top_hidden=[512, 256, 1]),

@@ -52,7 +52,7 @@ def test_dense_step_matches_oracle(oracle, cfg, T, D, B):
 
 
 def test_full_train_step_kaggle_shape(oracle):
-    """BASELINE configuration 5 (full DQRM train step, Kaggle shape) at a reduced table size: INT4 forward ->
+    """The full DQRM train step at the Kaggle shape with a reduced table size: INT4 forward ->
     dense step -> sparse INT8 backward -> update.  The dense outputs are compared with the float64 oracle fed
     with the oracle's own INT4 forward; the embedding backward is checked stage-isolated: the oracle's B1-B5
     take the GPU's grad_emb bytes, so codes, indices and updated rows must agree bit for bit."""

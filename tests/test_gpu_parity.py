@@ -16,7 +16,7 @@ def _say(msg):
 
 
 # --------------------------------------------------------------------------
-# the BASELINE configurations
+# the benchmark configurations
 # --------------------------------------------------------------------------
 @pytest.mark.parametrize("grad", ["dyadic", "normal"])
 def test_config_tiny(oracle, grad):

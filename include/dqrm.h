@@ -52,11 +52,13 @@ extern "C" {
 #define DQRM_OK 0
 #define DQRM_ERR_INVALID_ARG (-1)         /* null pointer, negative size, unknown mode */
 #define DQRM_ERR_UNSUPPORTED (-2)         /* dim, table count or table size outside the limits below */
-#define DQRM_ERR_WORKSPACE_TOO_SMALL (-3) /* workspace_bytes below dqrm_embbag_bwd_workspace_bytes() */
+#define DQRM_ERR_WORKSPACE_TOO_SMALL (-3) /* workspace_bytes below what the call's *_workspace_bytes() query returns */
 #define DQRM_ERR_INDEX_OUT_OF_RANGE (-4)  /* (device status) an index < 0 or >= its table's rows */
 #define DQRM_ERR_HIP (-5)                 /* a HIP runtime call failed; see dqrm_last_hip_error() */
-#define DQRM_ERR_CAPACITY (-6)            /* (device status) one table has > DQRM_MAX_TABLE_LOOKUPS lookups in a batch */
-#define DQRM_ERR_BAD_OFFSETS (-7)         /* (device status) offsets decrease or leave [0, num_indices] */
+#define DQRM_ERR_CAPACITY (-6)            /* (device status) one table has > DQRM_MAX_TABLE_LOOKUPS lookups in a batch;
+                                             dqrm_sparse_merge: the outputs cannot hold the blocks' rows */
+#define DQRM_ERR_BAD_OFFSETS (-7)         /* (device status) offsets decrease or leave [0, num_indices];
+                                             dqrm_sparse_merge: a block's offsets or row order break its rules */
 
 #define DQRM_MAX_DIM 256             /* dim must be a multiple of 8 in [8, 256] */
 #define DQRM_MAX_TABLES 1024

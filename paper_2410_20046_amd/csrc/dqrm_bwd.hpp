@@ -153,6 +153,16 @@ __global__ __launch_bounds__(kDdThreads) void dedupe_kernel(DedupeArgs args)
     const int base = (int)lo;
 
     // ---- phase 0: bag of every lookup position ---------------------------
+    // The table's keys are requested first (wave-striped: item i = wave * per_wave + r * 64 + lane), so that they
+    // travel while the bags are looked at; items past the end re-read the last key and are dropped in phase 1.
+    const int rounds = (n + kDdThreads - 1) / kDdThreads; // 0..16, same for the whole block
+    const int per_wave = rounds * kWave;
+    long long raw[kDdMaxRounds];
+#pragma unroll
+    for (int r = 0; r < kDdMaxRounds; ++r) {
+        raw[r] = 0;
+        if (r < rounds) raw[r] = indices[lo + min(wave * per_wave + r * kWave + lane, n - 1)]; // (n >= 1 here)
+    }
     // When every bag of the table holds exactly one lookup (the usual DLRM
     // batch) the bag of position p is p itself and nothing needs to be stored.
     DQRM_TICK(0);
@@ -191,9 +201,7 @@ __global__ __launch_bounds__(kDdThreads) void dedupe_kernel(DedupeArgs args)
     }
     DQRM_TICK(1);
 
-    // ---- phase 1: keys into registers, wave-striped ----------------------
-    const int rounds = (n + kDdThreads - 1) / kDdThreads; // 0..16, same for the whole block
-    const int per_wave = rounds * kWave;
+    // ---- phase 1: keys checked and narrowed ------------------------------
     unsigned key[kDdMaxRounds];
     unsigned pos[kDdMaxRounds];
 #pragma unroll
@@ -204,7 +212,7 @@ __global__ __launch_bounds__(kDdThreads) void dedupe_kernel(DedupeArgs args)
             const int i = wave * per_wave + r * kWave + lane;
             pos[r] = (unsigned)i;
             if (i < n) {
-                long long v = indices[lo + i];
+                const long long v = raw[r];
                 if (v < 0 || v >= rows_ll)
                     report(DQRM_ERR_INDEX_OUT_OF_RANGE, t, v);
                 else

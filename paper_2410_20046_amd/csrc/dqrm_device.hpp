@@ -192,14 +192,19 @@ __device__ __forceinline__ int block_excl_scan_add(int v, int lane, int wave, in
 // lanes of the wave whose 8-bit digit equals mine (all 64 lanes must be active)
 __device__ __forceinline__ unsigned long long match_any8(unsigned d)
 {
-    unsigned long long m = ~0ull;
+    // per bit: the lanes whose bit is set (ballot) against my own bit spread over a word (0 or all ones, a signed
+    // one-bit field extract): the lanes whose bit equals mine are ~(ballot ^ mine), and gfx950 folds that and the
+    // running AND into one three-input bit operation per 32-bit half
+    unsigned lo = ~0u, hi = ~0u;
 #pragma unroll
     for (int b = 0; b < 8; ++b) {
-        bool bit = (d >> b) & 1u;
-        unsigned long long bal = __ballot(bit);
-        m &= bit ? bal : ~bal;
+        unsigned mine = (unsigned)(int)__builtin_amdgcn_sbfe(d, b, 1);
+        asm volatile("" : "+v"(mine)); // (keeps the compiler from deriving the ballot from d again: a shift more per bit)
+        const unsigned long long bal = __ballot(mine != 0u);
+        lo &= ~((unsigned)bal ^ mine);
+        hi &= ~((unsigned)(bal >> 32) ^ mine);
     }
-    return m;
+    return ((unsigned long long)hi << 32) | lo;
 }
 
 // largest t in [0, T) with offs[t] <= x, for a non-decreasing offs[0..T] with

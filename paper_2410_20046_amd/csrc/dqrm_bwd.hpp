@@ -822,7 +822,7 @@ __global__ __launch_bounds__(kSegThreads) void combine_kernel(SegArgs a)
         const float *p_last = a.ws.partial_last + (int64_t)(gpos / DQRM_SEG_CHUNK) * D + col;
         if (col_ok) {
             float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
-            constexpr int kCb = 16; // partials requested before the first is added
+            constexpr int kCb = 24; // partials requested before the first is added
             for (int k0 = 0; k0 < nchunks; k0 += kCb) {
                 float4 pv[kCb];
 #pragma unroll

@@ -60,6 +60,8 @@ extern "C" {
 #define DQRM_ERR_BAD_OFFSETS (-7)         /* (device status) offsets decrease or leave [0, num_indices];
                                              dqrm_sparse_merge: a block's offsets or row order break its rules */
 
+#define DQRM_ERR_SCRATCH_LIMIT (-8)       /* dqrm_embbag_bwd_noalloc: the shape needs more scratch than the built-in array holds */
+
 #define DQRM_MAX_DIM 256             /* dim must be a multiple of 8 in [8, 256] */
 #define DQRM_MAX_TABLES 1024
 #define DQRM_MAX_TABLE_ROWS 2147483646LL /* rows of one table */
@@ -142,6 +144,25 @@ int32_t dqrm_embbag_bwd(const dqrm_tables_t *tables, const int64_t *indices, con
                         int64_t *uniq_rows, int32_t *seg_offsets, int32_t *table_uniq_offsets,
                         int32_t *num_unique, float *values, float *g_absmax, void *workspace,
                         size_t workspace_bytes, void *stream);
+
+/* dqrm_embbag_bwd for callers that cannot allocate device memory or hand over a
+ * workspace: code under HIP graph capture, tight serving loops, harnesses that
+ * forbid hipMalloc.  Same arguments, outputs and results as dqrm_embbag_bwd, minus
+ * the workspace: the scratch is an array of DQRM_NOALLOC_SCRATCH_BYTES built into
+ * the library (one copy per GPU, held until the process ends; its address is
+ * looked up at the first call on each device).  Shapes for which
+ * dqrm_embbag_bwd_workspace_bytes() exceeds DQRM_NOALLOC_SCRATCH_BYTES are rejected
+ * with DQRM_ERR_SCRATCH_LIMIT before anything is launched (the text of
+ * dqrm_last_hip_error() then names both sizes); at 26 tables of dim 64 the array
+ * holds batches of about 50,000 lookups.  Calls no hipMalloc / hipFree or any
+ * other allocating routine.  All calls on one GPU share that GPU's array (it needs
+ * no clearing between calls), so two calls that may overlap in time on one GPU,
+ * on whatever streams, race: order them. */
+#define DQRM_NOALLOC_SCRATCH_BYTES (8u << 20)
+int32_t dqrm_embbag_bwd_noalloc(const dqrm_tables_t *tables, const int64_t *indices, const int64_t *offsets,
+                                int32_t batch, int64_t num_indices, const float *grad_out, int32_t *sorted_pos,
+                                int64_t *uniq_rows, int32_t *seg_offsets, int32_t *table_uniq_offsets,
+                                int32_t *num_unique, float *values, float *g_absmax, void *stream);
 
 /* The two halves of dqrm_embbag_bwd, for callers that overlap them with other
  * work.  dqrm_dedupe (the sparse-tensor coalescing of Sec. 4.3: sort the lookups

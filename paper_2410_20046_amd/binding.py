@@ -24,16 +24,18 @@ ERR_INDEX_OUT_OF_RANGE = -4
 ERR_HIP = -5
 ERR_CAPACITY = -6
 ERR_BAD_OFFSETS = -7
+ERR_SCRATCH_LIMIT = -8
 _NAMES = {0: "OK", -1: "INVALID_ARG", -2: "UNSUPPORTED", -3: "WORKSPACE_TOO_SMALL", -4: "INDEX_OUT_OF_RANGE",
-          -5: "HIP_ERROR", -6: "CAPACITY", -7: "BAD_OFFSETS"}
+          -5: "HIP_ERROR", -6: "CAPACITY", -7: "BAD_OFFSETS", -8: "SCRATCH_LIMIT"}
 
 FWD_MASTER = 0
 FWD_PACKED = 1
 SEG_CHUNK = 32
 MAX_TABLE_LOOKUPS = 16384
+NOALLOC_SCRATCH_BYTES = 8 << 20
 
 EXPORTS = ("dqrm_find_scale", "dqrm_pack_int4", "dqrm_embbag_fwd", "dqrm_embbag_bwd_workspace_bytes",
-           "dqrm_embbag_bwd", "dqrm_dedupe", "dqrm_dedupe_multi", "dqrm_segment_sum", "dqrm_grad_quant_int8",
+           "dqrm_embbag_bwd", "dqrm_embbag_bwd_noalloc", "dqrm_dedupe", "dqrm_dedupe_multi", "dqrm_segment_sum", "dqrm_grad_quant_int8",
            "dqrm_sparse_update", "dqrm_sparse_merge_workspace_bytes", "dqrm_sparse_merge", "dqrm_sparse_update_sums",
            "dqrm_quant_update", "dqrm_dense_workspace_bytes", "dqrm_dense_step",
            "dqrm_dense_param_count", "dqrm_dense_step_quant", "dqrm_check_status", "dqrm_last_hip_error", "dqrm_version")
@@ -96,6 +98,8 @@ def lib() -> C.CDLL:
         L.dqrm_embbag_bwd_workspace_bytes.argtypes = [i32, i32, i32, i64]
         L.dqrm_embbag_bwd_workspace_bytes.restype = sz
         L.dqrm_embbag_bwd.argtypes = [tp, vp, vp, i32, i64, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+        L.dqrm_embbag_bwd_noalloc.argtypes = [tp, vp, vp, i32, i64, vp, vp, vp, vp, vp, vp, vp, vp, vp]
+        L.dqrm_embbag_bwd_noalloc.restype = i32
         L.dqrm_dedupe.argtypes = [tp, vp, vp, i32, i64, vp, vp, vp, vp, vp, vp, sz, vp]
         L.dqrm_dedupe_multi.argtypes = [tp, i32, i32, C.POINTER(dqrm_dedupe_batch_t), sz, vp]
         L.dqrm_dedupe_multi.restype = i32
@@ -203,6 +207,18 @@ def dqrm_embbag_bwd(tables: Tables, indices: torch.Tensor, offsets: torch.Tensor
                                  _ptr(sorted_pos), _ptr(uniq_rows), _ptr(seg_offsets), _ptr(table_uniq_offsets),
                                  _ptr(num_unique), _ptr(values), _ptr(g_absmax), _ptr(workspace),
                                  workspace.numel() * workspace.element_size(), _stream(stream)), "dqrm_embbag_bwd")
+
+
+def dqrm_embbag_bwd_noalloc(tables: Tables, indices: torch.Tensor, offsets: torch.Tensor, batch: int,
+                            grad_out: torch.Tensor, sorted_pos: torch.Tensor, uniq_rows: torch.Tensor,
+                            seg_offsets: torch.Tensor, table_uniq_offsets: torch.Tensor, num_unique: torch.Tensor,
+                            values: torch.Tensor, g_absmax: torch.Tensor, stream=None) -> None:
+    rc = lib().dqrm_embbag_bwd_noalloc(tables.ref, _ptr(indices), _ptr(offsets), batch, indices.numel(), _ptr(grad_out),
+                                       _ptr(sorted_pos), _ptr(uniq_rows), _ptr(seg_offsets), _ptr(table_uniq_offsets),
+                                       _ptr(num_unique), _ptr(values), _ptr(g_absmax), _stream(stream))
+    if rc == ERR_SCRATCH_LIMIT:
+        raise DqrmError(rc, "dqrm_embbag_bwd_noalloc", lib().dqrm_last_hip_error().decode())
+    _check(rc, "dqrm_embbag_bwd_noalloc")
 
 
 def dqrm_dedupe(tables: Tables, indices: torch.Tensor, offsets: torch.Tensor, batch: int, sorted_pos: torch.Tensor,

@@ -5,6 +5,7 @@
 #include <cstdio>
 #include <algorithm>
 #include <cstring>
+#include <mutex>
 
 #include "dqrm.h"
 #include "dqrm_device.hpp"
@@ -13,6 +14,10 @@
 #include "dqrm_update.hpp"
 #include "dqrm_merge.hpp"
 #include "dqrm_dense.hpp"
+
+// Scratch of dqrm_embbag_bwd_noalloc: one copy per GPU, held until the process ends.  In host code
+// this name is only a handle for hipGetSymbolAddress; kernels receive the address that call returns.
+static __device__ __align__(256) unsigned char scratch[DQRM_NOALLOC_SCRATCH_BYTES];
 
 namespace {
 
@@ -450,6 +455,46 @@ int32_t dqrm_embbag_bwd(const dqrm_tables_t *tables, const int64_t *indices, con
                              table_uniq_offsets, num_unique, workspace, workspace_bytes, stream);
     if (rc != DQRM_OK) return rc;
     return dqrm_segment_sum(tables, batch, num_indices, grad_out, values, g_absmax, workspace, workspace_bytes, stream);
+}
+
+int32_t dqrm_embbag_bwd_noalloc(const dqrm_tables_t *tables, const int64_t *indices, const int64_t *offsets,
+                                int32_t batch, int64_t num_indices, const float *grad_out, int32_t *sorted_pos,
+                                int64_t *uniq_rows, int32_t *seg_offsets, int32_t *table_uniq_offsets,
+                                int32_t *num_unique, float *values, float *g_absmax, void *stream)
+{
+    // the size check needs only the shape: do it before anything touches the device
+    if (!tables) return DQRM_ERR_INVALID_ARG;
+    if (tables->num_tables < 1 || tables->dim < 1 || batch < 1 || num_indices < 0) return DQRM_ERR_INVALID_ARG;
+    const size_t need = dqrm_embbag_bwd_workspace_bytes(tables->num_tables, tables->dim, batch, num_indices);
+    if (need == 0) return DQRM_ERR_UNSUPPORTED;
+    if (need > (size_t)DQRM_NOALLOC_SCRATCH_BYTES) {
+        std::snprintf(t_hip_error, sizeof(t_hip_error),
+                      "dqrm_embbag_bwd_noalloc: this shape needs %zu bytes of scratch, the built-in array holds %zu",
+                      need, (size_t)DQRM_NOALLOC_SCRATCH_BYTES);
+        return DQRM_ERR_SCRATCH_LIMIT;
+    }
+    // every GPU holds its own copy of the array at its own address: ask once per device, with that device current
+    constexpr int kMaxDevices = 64;
+    static void *dev_ptr[kMaxDevices] = {};
+    static std::mutex mu;
+    int dev = 0;
+    DQRM_HIP_CHECK(hipGetDevice(&dev));
+    if (dev < 0 || dev >= kMaxDevices) return DQRM_ERR_UNSUPPORTED;
+    void *ws = nullptr;
+    {
+        std::lock_guard<std::mutex> lock(mu);
+        if (!dev_ptr[dev]) {
+            void *p = nullptr;
+            DQRM_HIP_CHECK(hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)));
+            if (!p || !aligned(p, 256)) return hip_fail(hipErrorInvalidSymbol, "hipGetSymbolAddress(scratch)");
+            dev_ptr[dev] = p;
+        }
+        ws = dev_ptr[dev];
+    }
+    // nothing in the workspace has to start at zero: the dedupe kernels write every counter and slot they or
+    // the segment sums read, so the previous call's contents do not matter
+    return dqrm_embbag_bwd(tables, indices, offsets, batch, num_indices, grad_out, sorted_pos, uniq_rows, seg_offsets,
+                           table_uniq_offsets, num_unique, values, g_absmax, ws, (size_t)DQRM_NOALLOC_SCRATCH_BYTES, stream);
 }
 
 int32_t dqrm_grad_quant_int8(int32_t num_tables, int32_t dim, int64_t capacity, const float *values,

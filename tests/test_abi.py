@@ -42,6 +42,9 @@ def test_header_constants_match_binding():
     for n in ("INVALID_ARG", "UNSUPPORTED", "WORKSPACE_TOO_SMALL", "INDEX_OUT_OF_RANGE", "CAPACITY", "BAD_OFFSETS"):
         assert int(defs["DQRM_ERR_" + n]) == getattr(dq, "ERR_" + n)
     assert int(defs["DQRM_ERR_HIP"]) == dq.ERR_HIP
+    assert int(defs["DQRM_ERR_SCRATCH_LIMIT"]) == dq.ERR_SCRATCH_LIMIT
+    m = re.search(r"#define\s+DQRM_NOALLOC_SCRATCH_BYTES\s+\((\d+)u\s*<<\s*(\d+)\)", text)
+    assert int(m.group(1)) << int(m.group(2)) == dq.NOALLOC_SCRATCH_BYTES
 
 
 def test_workspace_bytes():
@@ -101,6 +104,16 @@ def test_validation_errors_before_any_launch():
     assert bwd(nu=None) == dq.ERR_INVALID_ARG
     assert bwd(values=FAKE + 4) == dq.ERR_INVALID_ARG
     assert bwd(tb=_tables(D=20)) == dq.ERR_UNSUPPORTED
+    # the variant with the built-in scratch array: shapes beyond the array are refused on the host
+    def bwd_na(tb=ok, B=4, N=8, grad=FAKE):
+        return L.dqrm_embbag_bwd_noalloc(r(tb), FAKE, FAKE, B, N, grad, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, S)
+    wide = _tables(D=64)
+    assert dq.dqrm_embbag_bwd_workspace_bytes(2, 64, 8192, 2 * 8192 * 8) > dq.NOALLOC_SCRATCH_BYTES
+    assert bwd_na(tb=wide, B=8192, N=2 * 8192 * 8) == dq.ERR_SCRATCH_LIMIT
+    assert b"scratch" in L.dqrm_last_hip_error()
+    assert L.dqrm_embbag_bwd_noalloc(None, FAKE, FAKE, 4, 8, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, S) == dq.ERR_INVALID_ARG
+    assert bwd_na(N=-1) == dq.ERR_INVALID_ARG
+    assert bwd_na(tb=_tables(D=20)) == dq.ERR_UNSUPPORTED
     # quantise / update
     gq = lambda T=2, D=16, cap=8, v=FAKE, tuo=FAKE, am=FAKE, q=FAKE, gs=FAKE: L.dqrm_grad_quant_int8(
         T, D, cap, v, tuo, am, q, gs, S)

@@ -16,7 +16,11 @@ import numpy as np
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _SRC = os.path.join(_HERE, "dqrm_oracle.c")
 _SRC_DENSE = os.path.join(_HERE, "dqrm_dense_oracle.c")
-_LIB = os.path.join(_HERE, "libdqrm_oracle.so")
+# DQRM_ORACLE_SANITIZE=1 in the environment: a second build with AddressSanitizer and
+# UndefinedBehaviorSanitizer (the process must then have libasan preloaded; tests/test_oracle_sanitizers.py
+# starts such a process and runs the pin tests in it)
+_SANITIZE = os.environ.get("DQRM_ORACLE_SANITIZE", "") == "1"
+_LIB = os.path.join(_HERE, "libdqrm_oracle_san.so" if _SANITIZE else "libdqrm_oracle.so")
 _lib: Optional[C.CDLL] = None
 
 
@@ -24,8 +28,10 @@ def build(force: bool = False) -> str:
     """Compile the oracle with gcc (one rounding per operation: no contraction)."""
     newest = max(os.path.getmtime(_SRC), os.path.getmtime(_SRC_DENSE))
     if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < newest:
-        cmd = ["gcc", "-O2", "-ffp-contract=off", "-fno-fast-math", "-std=c11", "-shared", "-fPIC",
-               "-o", _LIB, _SRC, _SRC_DENSE, "-lm"]
+        opt = ["-O1", "-g", "-fno-omit-frame-pointer", "-fsanitize=address,undefined",
+               "-fno-sanitize-recover=undefined"] if _SANITIZE else ["-O2"]
+        cmd = ["gcc"] + opt + ["-ffp-contract=off", "-fno-fast-math", "-std=c11", "-shared", "-fPIC",
+                               "-o", _LIB, _SRC, _SRC_DENSE, "-lm"]
         subprocess.run(cmd, check=True)
     return _LIB
 
@@ -149,15 +155,15 @@ def sparse_update(W: np.ndarray, packed: Optional[np.ndarray], row_offsets: np.n
 
 class SimulatedDP:
     """Simulated data parallelism on one device for the embedding tables (appendix "Simulated Data
-    Parallelism Environment", its algorithm; INT8 gradients as in the distributed-training appendix).
+    Parallelism Environment", Algorithm 1; INT8 gradients as in the distributed-training appendix).
 
-    ``micro_batch(j, ...)`` is one pass of the algorithm's loop body for micro-batch j: clear the buffer if the
-    previous pass updated the weights, backward (sparse gradient), quantise the values with the scale of the
-    group's first micro-batch, add the codes to the buffer, and after the last micro-batch of a group update the
-    weights from the buffer.  Reading: the update comes after every ``simulated_nodes``-th micro-batch,
-    (j + 1) % simulated_nodes == 0 (as printed, with j counted from 0, the very first group would be a single
-    micro-batch; the steady state is the same).  The buffer is dense, [rows][D] int32 over all tables: small
-    tables only."""
+    Micro-batches come in groups of ``simulated_nodes``; micro-batch j sits at place ``j % simulated_nodes`` of
+    its group.  A group owns one accumulator of integer gradient codes: the group's first micro-batch starts it
+    from zero and fixes the quantisation scale, every micro-batch adds the codes of its sparse gradient, and the
+    group's last micro-batch applies the accumulated gradient to the weights once.  Reading: a group is complete
+    after every ``simulated_nodes``-th micro-batch, (j + 1) % simulated_nodes == 0 (as printed, with j counted
+    from 0, the very first group would be a single micro-batch; the steady state is the same).  The accumulator is
+    dense, [rows][D] int32 over all tables: small tables only."""
 
     def __init__(self, W, packed, row_offsets, w_scale, simulated_nodes: int, lr: float):
         self.W, self.packed, self.row_offsets, self.w_scale = W, packed, row_offsets, w_scale
@@ -165,36 +171,39 @@ class SimulatedDP:
         self.T, self.D = len(row_offsets) - 1, W.shape[1]
         self.buffer = np.zeros(W.shape, np.int32)
         self.touched = np.zeros(W.shape[0], np.uint8)
-        self.buffer_clean = False
-        self.group_absmax = None  # the first micro-batch's per-table maxima
+        self.group_absmax = None  # the per-table maxima of the group's first micro-batch
         self.g_scale = None
         self.blocks = []          # this group's (uniq_rows, table_uniq_offsets, gq), for inspection
 
-    def micro_batch(self, j: int, B: int, indices: np.ndarray, offsets: np.ndarray, grad_out: np.ndarray) -> bool:
-        """Returns True if this micro-batch ended a group (the weights were updated)."""
-        if self.buffer_clean:
-            self.buffer[:] = 0
-            self.touched[:] = 0
-            self.blocks = []
-            self.group_absmax = None
-            self.buffer_clean = False
-        bw = embbag_bwd(self.T, self.D, B, indices, offsets, grad_out)  # local backward
-        if self.group_absmax is None:
-            self.group_absmax = bw["g_absmax"].copy()
-        gq, self.g_scale = grad_quant_int8(self.T, self.D, bw["values"], bw["table_uniq_offsets"], self.group_absmax)
-        gq = np.ascontiguousarray(gq)
-        self.blocks.append((bw["uniq_rows"], bw["table_uniq_offsets"], gq))
-        lib().oracle_simdp_accumulate(C.c_int(self.T), C.c_int(self.D), _p(self.row_offsets, C.c_int64),
-                                      _p(bw["uniq_rows"], C.c_int64), _p(bw["table_uniq_offsets"], C.c_int32),
-                                      _p(gq, C.c_int8), _p(self.buffer, C.c_int32), _p(self.touched, C.c_uint8))
-        if (j + 1) % self.n != 0:
-            return False
+    def _start_group(self, first_absmax):
+        self.buffer[:] = 0
+        self.touched[:] = 0
+        self.blocks = []
+        self.group_absmax = first_absmax.copy()
+
+    def _apply_group(self):
         lib().oracle_simdp_weight_update(_p(self.W, C.c_float), _p(self.packed, C.c_uint8),
                                          _p(self.row_offsets, C.c_int64), _p(self.w_scale, C.c_float),
                                          C.c_int(self.T), C.c_int(self.D), _p(self.buffer, C.c_int32),
                                          _p(self.touched, C.c_uint8), _p(self.g_scale, C.c_float), C.c_float(self.lr))
-        self.buffer_clean = True
-        return True
+
+    def micro_batch(self, j: int, B: int, indices: np.ndarray, offsets: np.ndarray, grad_out: np.ndarray) -> bool:
+        """Returns True if this micro-batch completed a group (the weights were updated)."""
+        place = j % self.n
+        sparse = embbag_bwd(self.T, self.D, B, indices, offsets, grad_out)
+        if place == 0:
+            self._start_group(sparse["g_absmax"])
+        gq, self.g_scale = grad_quant_int8(self.T, self.D, sparse["values"], sparse["table_uniq_offsets"],
+                                           self.group_absmax)
+        gq = np.ascontiguousarray(gq)
+        self.blocks.append((sparse["uniq_rows"], sparse["table_uniq_offsets"], gq))
+        lib().oracle_simdp_accumulate(C.c_int(self.T), C.c_int(self.D), _p(self.row_offsets, C.c_int64),
+                                      _p(sparse["uniq_rows"], C.c_int64), _p(sparse["table_uniq_offsets"], C.c_int32),
+                                      _p(gq, C.c_int8), _p(self.buffer, C.c_int32), _p(self.touched, C.c_uint8))
+        completes = place == self.n - 1
+        if completes:
+            self._apply_group()
+        return completes
 
 
 def dense_step(bot_dims, bot_w, bot_b, top_dims, top_w, top_b, dense_x, emb, labels, lr):
@@ -246,38 +255,36 @@ def dense_step_ex(bot_dims, bot_w, bot_b, top_dims, top_w, top_b, dense_x, emb, 
 
 
 class SimulatedDPDense:
-    """Simulated data parallelism for the MLPs (appendix "Simulated Data Parallelism Environment", its algorithm),
-    FP32 gradients: every parameter tensor has a gradient buffer of its own shape; each micro-batch's gradient
-    (forward and backward on the unchanged weights, mean loss over the micro-batch) is added to it; after every
-    ``simulated_nodes``-th micro-batch the parameters take ``p <- p - lr * buffer`` and the buffer is cleared
-    before the next gradient arrives.  Float64, on the lists of arrays given (updated in place)."""
+    """Simulated data parallelism for the MLPs (appendix "Simulated Data Parallelism Environment", Algorithm 1),
+    FP32 gradients.  Micro-batch j sits at place ``j % simulated_nodes`` of its group; a group owns one gradient
+    accumulator per parameter tensor (of the tensor's shape).  The group's first micro-batch starts the
+    accumulators from zero, every micro-batch adds its gradient (forward and backward on the weights the group
+    started with, mean loss over the micro-batch), and the group's last micro-batch takes ``p <- p - lr *
+    accumulator`` once.  Float64, on the lists of arrays given (updated in place)."""
 
     def __init__(self, bot_dims, bot_w, bot_b, top_dims, top_w, top_b, simulated_nodes: int, lr: float):
         self.model = (bot_dims, bot_w, bot_b, top_dims, top_w, top_b)
         self.n, self.lr = int(simulated_nodes), float(lr)
         self.buffers = tuple([np.zeros_like(a) for a in lst] for lst in (bot_w, bot_b, top_w, top_b))
-        self.buffer_clean = False
 
     def micro_batch(self, j: int, dense_x, emb, labels):
-        """Returns (loss, grad_emb, ended_group)."""
+        """Returns (loss, grad_emb, completed_group)."""
         bot_dims, bot_w, bot_b, top_dims, top_w, top_b = self.model
-        if self.buffer_clean:
-            for lst in self.buffers:
-                for b in lst:
-                    b[:] = 0.0
-            self.buffer_clean = False
+        place = j % self.n
         loss, grad_emb, grads = dense_step_ex(bot_dims, bot_w, bot_b, top_dims, top_w, top_b, dense_x, emb, labels,
                                               self.lr, apply_sgd=False, want_grads=True)
-        for blst, glst in zip(self.buffers, grads):
-            for b, g in zip(blst, glst):
-                b += g
-        if (j + 1) % self.n != 0:
-            return loss, grad_emb, False
-        for plst, blst in zip((bot_w, bot_b, top_w, top_b), self.buffers):
-            for p_, b in zip(plst, blst):
-                p_ -= self.lr * b
-        self.buffer_clean = True
-        return loss, grad_emb, True
+        for acc_list, grad_list in zip(self.buffers, grads):
+            for acc, g in zip(acc_list, grad_list):
+                if place == 0:
+                    acc[:] = g
+                else:
+                    acc += g
+        completes = place == self.n - 1
+        if completes:
+            for params, acc_list in zip((bot_w, bot_b, top_w, top_b), self.buffers):
+                for p_, acc in zip(params, acc_list):
+                    p_ -= self.lr * acc
+        return loss, grad_emb, completes
 
 
 def mlp_fake_quant(W: np.ndarray, bits: int):

@@ -45,7 +45,8 @@ def test_config_kaggle_full_size(oracle):
 
 
 def test_config_terabyte_full_size(oracle):
-    """The benchmark workload at full size, in the launch configuration bench.py times."""
+    """The benchmark workload at full size through the five-call path (dqrm_embbag_bwd, dqrm_grad_quant_int8,
+    dqrm_sparse_update).  The launch sequence bench.py times is checked by test_gpu_bench_path.py."""
     wl = make_workload("terabyte")
     _say(f"terabyte-shaped full size: R={wl.R} ({wl.R * wl.D * 4 / 1e9:.2f} GB fp32)")
     W = wl.tables()
@@ -174,7 +175,7 @@ def test_determinism(oracle):
     _say("determinism")
     first = run.bwd()
     gq0, gs0 = run.quant()
-    for _ in range(10):
+    for _ in range(20):
         r = run.bwd()
         gq, gs = run.quant()
         for k in ("sorted_pos", "uniq_rows", "seg_offsets", "table_uniq_offsets"):

@@ -259,7 +259,10 @@ def test_segment_sum_order(oracle):
             total = part if total is None else total + part
         assert np.array_equal(r["values"][seg].view(np.uint32), total.view(np.uint32))
     # and the order matters on these inputs (otherwise the check above proves nothing)
-    assert not np.array_equal(r["values"][0], g[:70, 0].astype(np.float64).sum(0).astype(np.float32)) or True
+    plain = g[0, 0].copy()
+    for k in range(1, 70):
+        plain = plain + g[k, 0]  # one left-to-right fp32 sum over the whole segment, no chunks
+    assert not np.array_equal(r["values"][0].view(np.uint32), plain.view(np.uint32))
 
 
 # --------------------------------------------------------------------------

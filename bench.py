@@ -189,9 +189,8 @@ def main():
         dq.dqrm_embbag_fwd(tables, idx_d[p], off_d[p], B, mode, bufs.out, None)
         for j in range(nodes):
             b, ix, of = mb[j], mb_idx[p][j], mb_off[p][j]
-            # (only the first micro-batch's maxima are needed: its scale serves the whole group)
-            dq.dqrm_segment_sum(tables, Bm, ix.numel(), g[j * Bm:(j + 1) * Bm], b.values, b.g_absmax if j == 0 else None,
-                                b.workspace)
+            # (only the first micro-batch's maxima are used: its scale serves the whole group)
+            dq.dqrm_segment_sum(tables, Bm, ix.numel(), g[j * Bm:(j + 1) * Bm], b.values, b.g_absmax, b.workspace)
             dq.dqrm_grad_quant_int8(T, D, b.cap, b.values, b.table_uniq_offsets, mb[0].g_absmax, b.gq, b.g_scale)
         dq.dqrm_sparse_merge(tables, [(b.uniq_rows, b.table_uniq_offsets, b.gq) for b in mb], m_rows, m_tuo, m_nu,
                              m_sums, m_ws)

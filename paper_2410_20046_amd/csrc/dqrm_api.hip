@@ -81,7 +81,8 @@ int32_t check_batch(const dqrm_tables_t *tb, const int64_t *indices, const int64
 // ---- workspace layout of dqrm_embbag_bwd -------------------------------------
 struct WsLayout {
     size_t off_table_base, off_table_nuniq, off_table_nchunk, off_table_nsingle, off_totals, off_bag_of_pos, off_sorted_bag,
-        off_chunk_local, off_single_local, off_chunk_desc, off_chunk_bags, off_single_desc, off_partial_full, off_partial_last, off_absmax_slots, total;
+        off_chunk_local, off_single_local, off_chunk_desc, off_chunk_bags, off_single_desc, off_seg_count, off_partial_full,
+        off_partial_last, off_absmax_slots, total;
 };
 
 size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
@@ -108,6 +109,7 @@ WsLayout ws_layout(int32_t T, int32_t D, int64_t N)
     L.off_chunk_desc = take(n * 16);
     L.off_chunk_bags = take((n / 2 + 1) * DQRM_SEG_CHUNK * sizeof(int));
     L.off_single_desc = take(n * 16);
+    L.off_seg_count = take(slots * sizeof(int));
     L.off_partial_full = take(slots * (size_t)D * sizeof(float));
     L.off_partial_last = take(slots * (size_t)D * sizeof(float));
     L.off_absmax_slots = take(t * dqrm::kAbsmaxSlots * dqrm::kAbsmaxStride * sizeof(float));
@@ -131,6 +133,7 @@ dqrm::BwdWs ws_views(void *workspace, const WsLayout &L)
     w.chunk_desc = reinterpret_cast<int4 *>(b + L.off_chunk_desc);
     w.chunk_bags = reinterpret_cast<int *>(b + L.off_chunk_bags);
     w.single_desc = reinterpret_cast<int4 *>(b + L.off_single_desc);
+    w.seg_count = reinterpret_cast<int *>(b + L.off_seg_count);
     w.partial_full = reinterpret_cast<float *>(b + L.off_partial_full);
     w.partial_last = reinterpret_cast<float *>(b + L.off_partial_last);
     w.absmax_slots = reinterpret_cast<float *>(b + L.off_absmax_slots);
@@ -174,26 +177,17 @@ void launch_fwd(int G, dim3 grid, hipStream_t st, const dqrm::FwdArgs &a)
     }
 }
 
-void launch_segsum(int G, dim3 grid_sum, dim3 grid_comb, hipStream_t st, const dqrm::SegArgs &a)
+void launch_segsum(int G, dim3 grid, hipStream_t st, const dqrm::SegArgs &a)
 {
     using namespace dqrm;
-#define DQRM_SEG_CASE(g)                                                                        \
-    case g:                                                                                     \
-        hipLaunchKernelGGL((chunk_sum_kernel<g>), grid_sum, dim3(kSegThreads), 0, st, a);       \
-        hipLaunchKernelGGL((combine_kernel<g>), grid_comb, dim3(kSegThreads), 0, st, a);        \
-        break;
     switch (G) {
-        DQRM_SEG_CASE(2)
-        DQRM_SEG_CASE(4)
-        DQRM_SEG_CASE(8)
-        DQRM_SEG_CASE(16)
-        DQRM_SEG_CASE(32)
-    default:
-        hipLaunchKernelGGL((chunk_sum_kernel<64>), grid_sum, dim3(kSegThreads), 0, st, a);
-        hipLaunchKernelGGL((combine_kernel<64>), grid_comb, dim3(kSegThreads), 0, st, a);
-        break;
+    case 2: hipLaunchKernelGGL((segment_sum_kernel<2>), grid, dim3(kSumThreads), 0, st, a); break;
+    case 4: hipLaunchKernelGGL((segment_sum_kernel<4>), grid, dim3(kSumThreads), 0, st, a); break;
+    case 8: hipLaunchKernelGGL((segment_sum_kernel<8>), grid, dim3(kSumThreads), 0, st, a); break;
+    case 16: hipLaunchKernelGGL((segment_sum_kernel<16>), grid, dim3(kSumThreads), 0, st, a); break;
+    case 32: hipLaunchKernelGGL((segment_sum_kernel<32>), grid, dim3(kSumThreads), 0, st, a); break;
+    default: hipLaunchKernelGGL((segment_sum_kernel<64>), grid, dim3(kSumThreads), 0, st, a); break;
     }
-#undef DQRM_SEG_CASE
 }
 
 int32_t sparse_update_impl(const dqrm_tables_t *tables, int64_t capacity, const int64_t *uniq_rows,
@@ -432,10 +426,9 @@ int32_t dqrm_segment_sum(const dqrm_tables_t *tables, int32_t batch, int64_t num
     sa.B = batch;
     sa.D = D;
     const int G = pow2ceil(D / 4);
-    // at most one lane group per possible chunk, at least one block
-    const int grid_sum = grid_for(num_indices * G, dqrm::kSegThreads, dqrm::kSegBlocksPerCu);
-    const int grid_comb = grid_for(num_indices * G, dqrm::kSegThreads, 4);
-    launch_segsum(G, dim3(grid_sum), dim3(grid_comb), st, sa);
+    // at most one lane group per four lookups (a window of the chunk list per workgroup, a few singles per group)
+    const int grid_sum = grid_for((num_indices + 3) / 4 * G, dqrm::kSumThreads, dqrm::kSumBlocksPerCu);
+    launch_segsum(G, dim3(grid_sum), st, sa);
     if (g_absmax)
         hipLaunchKernelGGL(dqrm::absmax_finalize_kernel, dim3((T + 255) / 256), dim3(256), 0, st, sa.ws.absmax_slots,
                            T, g_absmax);
@@ -1005,15 +998,5 @@ int32_t dqrm_check_status(void *stream, int32_t *first_bad_table, int64_t *first
     return h.code;
 }
 
-#ifdef DQRM_PHASE_TIMING
-// developer builds only: clock stamps of one dedupe workgroup (see dqrm_bwd.hpp)
-int32_t dqrm_debug_phase_ticks(long long *out16)
-{
-    DQRM_HIP_CHECK(hipDeviceSynchronize());
-    DQRM_HIP_CHECK(hipMemcpyFromSymbol(out16, HIP_SYMBOL(dqrm::g_phase_ticks), 16 * sizeof(long long), 0,
-                                       hipMemcpyDeviceToHost));
-    return DQRM_OK;
-}
-#endif
 
 } // extern "C"

@@ -11,15 +11,13 @@
 //   (unique rows, segment offsets, table offsets, count) and one dense list of
 //   16-byte chunk descriptors over all tables.
 // Kernels 1-2 need only the batch's indices; they form dqrm_dedupe.
-// Kernel 3 (chunk_sum_kernel): one lane group per chunk (<= DQRM_SEG_CHUNK
+// Kernel 3 (segment_sum_kernel): one lane group per chunk (<= DQRM_SEG_CHUNK
 //   consecutive contributions of one segment) adds its gradient rows left to
-//   right.  A segment of one chunk is final; chunks of longer segments store
-//   their partial sums.
-// Kernel 4 (combine_kernel): the last chunk of every long segment adds the
-//   segment's partials in chunk order.
-// Kernel 5 (absmax_finalize_kernel): folds the per-table maxima.
-// Kernel boundaries are the only synchronisation between workgroups, so the
-// result never depends on scheduling.
+//   right.  A segment of one chunk is final.  The chunks of a longer segment park
+//   their sums and count themselves in on the segment's counter; the wave of the
+//   chunk that arrives last adds the segment's chunk sums in chunk order.  Which
+//   wave that is depends on scheduling; what it computes does not.
+// Kernel 4 (absmax_finalize_kernel): folds the per-table maxima.
 #pragma once
 
 #include "dqrm_device.hpp"
@@ -30,15 +28,10 @@ constexpr int kDdThreads = 1024;
 constexpr int kDdWaves = kDdThreads / kWave;                      // 16
 constexpr int kDdMaxRounds = DQRM_MAX_TABLE_LOOKUPS / kDdThreads; // 16 items per thread at most
 constexpr int kDdCap = DQRM_MAX_TABLE_LOOKUPS;
-constexpr int kSegThreads = 256;
-#ifndef DQRM_SEG_BATCH
-#define DQRM_SEG_BATCH 16
-#endif
-#ifndef DQRM_SEG_BPC
-#define DQRM_SEG_BPC 8
-#endif
-constexpr int kSegBatch = DQRM_SEG_BATCH;      // gradient rows requested before the first is added
-constexpr int kSegBlocksPerCu = DQRM_SEG_BPC; // grid of the chunk-sum kernel, in workgroups per CU
+constexpr int kSegThreads = 256;   // dedupe_finish_kernel
+constexpr int kSumThreads = 256;   // segment_sum_kernel
+constexpr int kSegBatch = 16;      // gradient rows requested before the first is added
+constexpr int kSumBlocksPerCu = 4; // grid of segment_sum_kernel, in workgroups per CU (128 registers per lane)
 
 // Views into the caller's workspace (all device pointers).
 struct BwdWs {
@@ -54,8 +47,10 @@ struct BwdWs {
     int *chunk_bags;          // [N/2 + 1][32] bags of chunk c's lookups, so that they can be read before its descriptor
     int4 *single_desc;        // [N]   dense list of singles: {bag, global segment, table, -}
     int *totals;              // [3]   chunks, segments, singles
-    float *partial_full;      // [(N/32 + 2) * D] partial of a full chunk of a long segment
-    float *partial_last;      // [(N/32 + 2) * D] partial of the last chunk of a long segment
+    int *seg_count;           // [N/32 + 2] chunks of a segment of more than one chunk that have parked their sum, filed
+                              //       under (sorted position of the segment's head / 32); zero between uses
+    float *partial_full;      // [(N/32 + 2) * D] sum of a full chunk of a segment of more than one chunk
+    float *partial_last;      // [(N/32 + 2) * D] sum of the last chunk of such a segment
     float *absmax_slots;      // [T][kAbsmaxSlots] running maxima, one 128-byte line per entry
 };
 
@@ -74,20 +69,6 @@ __device__ __forceinline__ int4 make_chunk_desc(int gstart, int len, int kchunk,
 __device__ __forceinline__ int desc_len(const int4 &d) { return d.y & 0xFF; }
 __device__ __forceinline__ int desc_kchunk(const int4 &d) { return (d.y >> 8) & 0xFFF; }
 __device__ __forceinline__ int desc_nchunks(const int4 &d) { return (int)((unsigned)d.y >> 20); }
-
-// Optional per-phase clock stamps of one workgroup of the dedupe kernel (developer
-// builds only: -DDQRM_PHASE_TIMING=<table>; the stamps are 100 MHz ticks).
-#ifdef DQRM_PHASE_TIMING
-__device__ long long g_phase_ticks[16];
-#define DQRM_TICK(k)                                                                                           \
-    do {                                                                                                       \
-        if (blockIdx.x == DQRM_PHASE_TIMING && threadIdx.x == 0) g_phase_ticks[k] = (long long)wall_clock64(); \
-    } while (0)
-#else
-#define DQRM_TICK(k) \
-    do {             \
-    } while (0)
-#endif
 
 // One launch can dedupe several batches (blockIdx.y picks the batch): the work
 // depends only on the indices, and a table's sort occupies a single CU, so the
@@ -165,7 +146,6 @@ __global__ __launch_bounds__(kDdThreads) void dedupe_kernel(DedupeArgs args)
     }
     // When every bag of the table holds exactly one lookup (the usual DLRM
     // batch) the bag of position p is p itself and nothing needs to be stored.
-    DQRM_TICK(0);
     constexpr int kBagBatch = 8;
     bool one_each = !disabled && (n == B);
     if (!disabled) {
@@ -199,7 +179,6 @@ __global__ __launch_bounds__(kDdThreads) void dedupe_kernel(DedupeArgs args)
             for (long long p = s; p < e; ++p) ws.bag_of_pos[p] = b;
         }
     }
-    DQRM_TICK(1);
 
     // ---- phase 1: keys checked and narrowed ------------------------------
     unsigned key[kDdMaxRounds];
@@ -220,14 +199,11 @@ __global__ __launch_bounds__(kDdThreads) void dedupe_kernel(DedupeArgs args)
             }
         }
     }
-
-    DQRM_TICK(2);
     // ---- phase 2: stable LSD radix sort, 8 bits per pass -----------------
     const int nbits = 32 - __clz(rows_t | 1u); // bit width of the sentinel (>= 1)
     const int passes = (nbits + 7) / 8;
     for (int p = 0; p < passes; ++p) {
         const int shift = 8 * p;
-        DQRM_TICK(8 + p);
         for (int k = tid; k < kDdWaves * 256; k += kDdThreads) cnt[k] = 0;
         __syncthreads();
         // (the rank inside the wave's digit group rides in the upper half of pos[]:
@@ -279,8 +255,6 @@ __global__ __launch_bounds__(kDdThreads) void dedupe_kernel(DedupeArgs args)
         }
         // the next pass clears cnt and synchronises before anything is overwritten
     }
-
-    DQRM_TICK(3);
     // ---- phase 3: segment heads and chunk heads ---------------------------
     // (skey / spos now hold the table's rounds*1024 items in sorted order;
     //  entries that are padding or had a bad index carry the sentinel key.)
@@ -385,7 +359,6 @@ __global__ __launch_bounds__(kDdThreads) void dedupe_kernel(DedupeArgs args)
     }
 
     // ---- phase 4: write the table-local lists -------------------------------
-    DQRM_TICK(5);
     if (!one_each) {
         // bag of every sorted lookup: gathered first, all at once, so that the loads overlap
 #pragma unroll
@@ -413,9 +386,11 @@ __global__ __launch_bounds__(kDdThreads) void dedupe_kernel(DedupeArgs args)
                 const int c = (int)((chunk_of[r] >> 16) & 0x7FFFu) + chunks_before - 1;
                 const int s0 = info_start(info[r]), s1 = shead[seg + 1];
                 const int len = min(DQRM_SEG_CHUNK, s1 - i);
+                const int nchunks = (s1 - s0 + DQRM_SEG_CHUNK - 1) / DQRM_SEG_CHUNK;
                 ws.chunk_local[base + c] =
-                    make_chunk_desc(base + i, len, (i - s0) / DQRM_SEG_CHUNK,
-                                    (s1 - s0 + DQRM_SEG_CHUNK - 1) / DQRM_SEG_CHUNK, seg, skey[i]);
+                    make_chunk_desc(base + i, len, (i - s0) / DQRM_SEG_CHUNK, nchunks, seg, skey[i]);
+                // the arrival counter of a segment of more than one chunk starts at zero
+                if (i == s0 && nchunks > 1) ws.seg_count[(base + i) / DQRM_SEG_CHUNK] = 0;
             }
             if (chunk_of[r] & (1u << 15)) { // a row looked up exactly once
                 const int c = (int)(chunk_of[r] & 0x7FFFu) + singles_before - 1;
@@ -431,7 +406,6 @@ __global__ __launch_bounds__(kDdThreads) void dedupe_kernel(DedupeArgs args)
         ws.table_nsingle[t] = n_single;
     }
     if (tid < kAbsmaxSlots) *absmax_slot(ws.absmax_slots, t, tid) = 0.0f;
-    DQRM_TICK(6);
 }
 
 // ---------------------------------------------------------------------------
@@ -686,56 +660,102 @@ __device__ __forceinline__ float4 sum_chunk(const int (&my_bags)[kChunkIdsPerLan
     return acc;
 }
 
-// Lane groups take the chunks one each, in order, and the singles (rows looked up
-// once: a plain copy of one gradient row) kSinglesPerGroup at a time, dealt from
-// the other end of the grid so that groups without a chunk do the copying.
-// The loops run as long as any group of the wave has work; a group without work
-// goes through the motions on bag 0 of table 0 and stores nothing.
+// Where the sum of chunk k of a segment of more than one chunk is parked: full chunks are disjoint runs of
+// DQRM_SEG_CHUNK sorted positions, so (position / DQRM_SEG_CHUNK) names them uniquely; the last chunk of a
+// segment is filed under the slot of the segment's first chunk, in a second array.  The segment's arrival
+// counter sits at the first chunk's slot number too.
+__device__ __forceinline__ float *partial_slot(const BwdWs &ws, int head_pos, int k, int nchunks, int D)
+{
+    return k == nchunks - 1 ? ws.partial_last + (int64_t)(head_pos / DQRM_SEG_CHUNK) * D
+                            : ws.partial_full + (int64_t)(head_pos / DQRM_SEG_CHUNK + k) * D;
+}
+
+// Parked chunk sums and arrival counters are the only data that one workgroup of this kernel hands to another.
+// They travel by device-scope atomic stores, loads and adds (each coherent across the chip by itself: they go
+// past the caches that are private to a part of the chip), in this order: a chunk's sum is stored and the
+// stores are waited for; then the chunk is counted in; the wave that sees the count complete then loads the
+// sums.  No fence is used: a device-scope release or acquire writes back or drops whole caches, which costs more
+// than the entire kernel when thousands of waves do it.
+__device__ __forceinline__ void park_f4(float *p, float4 v)
+{
+    __hip_atomic_store(p + 0, v.x, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    __hip_atomic_store(p + 1, v.y, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    __hip_atomic_store(p + 2, v.z, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    __hip_atomic_store(p + 3, v.w, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
+constexpr int kCombineBatch = 64; // chunk sums of one column requested together
+
+// One column of the sum of a segment of `nchunks` > 1 chunks: its parked chunk sums, left to right.  (4 bytes per
+// chunk and lane, so that even kCombineBatch chunks cost a single round trip: a wave per segment, a lane per column.)
+__device__ __forceinline__ float combine_column(const BwdWs &ws, int head_pos, int nchunks, int D, int col)
+{
+    float acc = 0.f;
+    for (int k0 = 0; k0 < nchunks; k0 += kCombineBatch) {
+        float pv[kCombineBatch];
+#pragma unroll
+        for (int q = 0; q < kCombineBatch; ++q)
+            if (k0 + q < nchunks)
+                pv[q] = __hip_atomic_load(partial_slot(ws, head_pos, k0 + q, nchunks, D) + col, __ATOMIC_RELAXED,
+                                          __HIP_MEMORY_SCOPE_AGENT);
+#pragma unroll
+        for (int q = 0; q < kCombineBatch; ++q)
+            if (k0 + q < nchunks) acc = (k0 + q == 0) ? pv[q] : acc + pv[q];
+    }
+    return acc;
+}
+
+// Work of one workgroup of kSumThreads / G lane groups:
+//  * singles (rows looked up once: a plain copy of one gradient row), a few per
+//    group, spread evenly over all groups of the grid;
+//  * chunks, one per lane group and round.  The sum of a segment's only chunk is
+//    final.  The sum of a chunk of a longer segment is parked; the chunk then counts
+//    itself in, and if it completes its segment's count, its whole wave (a lane per
+//    column) adds the segment's parked sums in chunk order, stores the row of
+//    `values`, and clears the counter for the next use.
+// No load sits under a per-lane branch: a group without work goes through the
+// motions on bag 0 of table 0 and stores nothing.
 constexpr int kSinglesPerGroup = 4;
 
 template <int G>
-__global__ __launch_bounds__(kSegThreads) void chunk_sum_kernel(SegArgs a)
+__global__ __launch_bounds__(kSumThreads, 4) void segment_sum_kernel(SegArgs a)
 {
+    constexpr int kGroups = kSumThreads / G; // lane groups per workgroup
     __shared__ unsigned s_max[DQRM_MAX_TABLES];
     const int T = a.T, D = a.D;
     BlockAbsmax amax;
     amax.init(s_max, T);
 
     const int lg = threadIdx.x & (G - 1);
-    constexpr int kGroups = kSegThreads / G;
+    const int grp = (int)threadIdx.x / G;
     const int col = lg * 4;
     const bool col_ok = col < D;
     const float *grad_col = a.grad_out + (col_ok ? col : 0); // lanes beyond the row read column 0 and store nothing
     const int lane = threadIdx.x & (kWave - 1);
     const int leader = lane & ~(G - 1);
     const unsigned tD = (unsigned)T * (unsigned)D;
-    const int cap = (int)a.N; // both lists have N slots, so descriptors may be requested before the counts are known
+    const int cap = (int)a.N;       // both lists have N slots, so descriptors may be requested before the counts are known
     const int cap_chunks = cap / 2; // a chunk has at least two lookups
     const int ngroups = (int)gridDim.x * kGroups;
-    const int gi = (int)blockIdx.x * kGroups + (int)threadIdx.x / G;
+    const int gi = (int)blockIdx.x * kGroups + grp;
 
+    // ---- requests that need no count: the first chunk's descriptor and bag list, the first singles
     int c = gi;
-    int s0 = (ngroups - 1 - gi) * kSinglesPerGroup;
     int4 d = make_int4(0, 0, 0, 0);
-    int4 sd[kSinglesPerGroup];
     int my_bags[kChunkIdsPerLane(G)] = {};
     if (c < cap_chunks) {
         d = a.ws.chunk_desc[c];
         load_chunk_bags<G>(a, c, lg, my_bags);
     }
+    int s0 = gi * kSinglesPerGroup;
+    int4 sd[kSinglesPerGroup];
 #pragma unroll
-    for (int k = 0; k < kSinglesPerGroup; ++k) sd[k] = a.ws.single_desc[min(s0 + k, cap - 1)];
+    for (int k = 0; k < kSinglesPerGroup; ++k) sd[k] = a.ws.single_desc[min(s0 + k, max(cap - 1, 0))];
     const int C = min(a.ws.totals[0], cap_chunks), S = min(a.ws.totals[2], cap);
     __syncthreads(); // s_max is cleared
 
-#if defined(DQRM_EXP_SKIP_SINGLES)
-    s0 = S;
-#endif
-#if defined(DQRM_EXP_SKIP_CHUNKS)
-    c = C;
-#endif
-    // ---- singles: the wave's last group holds the lowest positions
-    while (__builtin_amdgcn_readlane(s0, kWave - 1) < S) {
+    // ---- singles: the wave's first group holds the lowest positions
+    while (__builtin_amdgcn_readfirstlane(s0) < S) {
         float4 r[kSinglesPerGroup];
         int4 cur[kSinglesPerGroup];
 #pragma unroll
@@ -773,76 +793,49 @@ __global__ __launch_bounds__(kSegThreads) void chunk_sum_kernel(SegArgs a)
         const int nchunks = desc_nchunks(d), kchunk = desc_kchunk(d);
         const int t = live ? d.w : 0;
         const float4 acc = sum_chunk<G>(my_bags, len, wave_len, leader, grad_col + (unsigned)t * (unsigned)D, tD);
+        const bool parks = live && nchunks > 1;
+        const int head_pos = d.x - kchunk * DQRM_SEG_CHUNK; // sorted position of the segment's head
         if (live && col_ok) {
-            if (nchunks > 1) {
-                // chunk of a long segment: store the partial sum for the combine kernel.
-                // Full chunks are disjoint runs of DQRM_SEG_CHUNK sorted positions, so
-                // (position / DQRM_SEG_CHUNK) names them uniquely; the last chunk of a
-                // segment is filed under the slot of the segment's first chunk.
-                const int gpos = d.x - kchunk * DQRM_SEG_CHUNK; // sorted position of the segment's head
-                float *pslot = (kchunk == nchunks - 1) ? a.ws.partial_last + (int64_t)(gpos / DQRM_SEG_CHUNK) * D
-                                                       : a.ws.partial_full + (int64_t)(d.x / DQRM_SEG_CHUNK) * D;
-                *reinterpret_cast<float4 *>(pslot + col) = acc;
+            if (parks) {
+                park_f4(partial_slot(a.ws, head_pos, kchunk, nchunks, D) + col, acc);
             } else {
                 *reinterpret_cast<float4 *>(a.values + (int64_t)d.z * D + col) = acc;
                 amax.add(t, f4_absmax(acc));
+            }
+        }
+        if (__any(parks)) { // wave-uniform
+            // the parked sums have reached the chip-wide level before any of this wave's chunks is counted in
+            asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+            int before = -1;
+            if (parks && lg == 0)
+                before = __hip_atomic_fetch_add(a.ws.seg_count + head_pos / DQRM_SEG_CHUNK, 1, __ATOMIC_RELAXED,
+                                                __HIP_MEMORY_SCOPE_AGENT);
+            asm volatile("" ::: "memory"); // (the loads below stay below)
+            // the groups whose chunk completed its segment's count: the wave takes their segments one by one
+            unsigned long long todo = __ballot(parks && lg == 0 && before == nchunks - 1);
+            while (todo != 0ull) {
+                const int src = __ffsll((long long)todo) - 1;
+                todo &= todo - 1ull;
+                const int s_head = __builtin_amdgcn_readlane(head_pos, src), s_n = __builtin_amdgcn_readlane(nchunks, src);
+                const int s_seg = __builtin_amdgcn_readlane(d.z, src), s_t = __builtin_amdgcn_readlane(d.w, src);
+                float m = 0.0f;
+                for (int cc = lane; cc < D; cc += kWave) {
+                    const float sum = combine_column(a.ws, s_head, s_n, D, cc);
+                    a.values[(int64_t)s_seg * D + cc] = sum;
+                    m = fmaxf(m, fabsf(sum));
+                }
+                m = wave_max(m);
+                if (lane == 0) {
+                    amax.add(s_t, m);
+                    // (ready for another run of the segment sums on the same dedupe)
+                    __hip_atomic_store(a.ws.seg_count + s_head / DQRM_SEG_CHUNK, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                }
             }
         }
         c = c_next;
         d = d_next;
 #pragma unroll
         for (int q = 0; q < kChunkIdsPerLane(G); ++q) my_bags[q] = next_bags[q];
-    }
-    amax.flush(a.ws.absmax_slots, T);
-}
-
-// One lane group per chunk descriptor; only the LAST chunk of a segment of more
-// than one chunk has work: it adds the segment's partial sums in chunk order.
-template <int G>
-__global__ __launch_bounds__(kSegThreads) void combine_kernel(SegArgs a)
-{
-    __shared__ unsigned s_max[DQRM_MAX_TABLES];
-    const int T = a.T, D = a.D;
-    BlockAbsmax amax;
-    amax.init(s_max, T);
-    const int lg = threadIdx.x & (G - 1);
-    constexpr int kGroups = kSegThreads / G;
-    const int col = lg * 4;
-    const bool col_ok = col < D;
-    const int cap = (int)a.N;
-    const int C = min(a.ws.totals[0], cap);
-    __syncthreads(); // s_max is cleared
-
-    for (int c = (int)blockIdx.x * kGroups + threadIdx.x / G; c < C; c += (int)gridDim.x * kGroups) {
-        const int4 d = a.ws.chunk_desc[c];
-        const int nchunks = desc_nchunks(d), kchunk = desc_kchunk(d);
-        if (nchunks <= 1 || kchunk != nchunks - 1) continue;
-        const int gpos = d.x - kchunk * DQRM_SEG_CHUNK;
-        // the k-th full chunk of the segment starts at sorted position gpos + 32 k
-        const float *p_last = a.ws.partial_last + (int64_t)(gpos / DQRM_SEG_CHUNK) * D + col;
-        if (col_ok) {
-            float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
-            constexpr int kCb = 24; // partials requested before the first is added
-            for (int k0 = 0; k0 < nchunks; k0 += kCb) {
-                float4 pv[kCb];
-#pragma unroll
-                for (int q = 0; q < kCb; ++q) {
-                    const int k = k0 + q;
-                    if (k < nchunks) {
-                        const float *pf =
-                            a.ws.partial_full + (int64_t)((gpos + k * DQRM_SEG_CHUNK) / DQRM_SEG_CHUNK) * D + col;
-                        pv[q] = *reinterpret_cast<const float4 *>(k == nchunks - 1 ? p_last : pf);
-                    }
-                }
-#pragma unroll
-                for (int q = 0; q < kCb; ++q) {
-                    const int k = k0 + q;
-                    if (k < nchunks) acc = (k == 0) ? pv[q] : f4_add(acc, pv[q]);
-                }
-            }
-            *reinterpret_cast<float4 *>(a.values + (int64_t)d.z * D + col) = acc;
-            amax.add(d.w, f4_absmax(acc));
-        }
     }
     amax.flush(a.ws.absmax_slots, T);
 }

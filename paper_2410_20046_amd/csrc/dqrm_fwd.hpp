@@ -25,23 +25,11 @@
 
 namespace dqrm {
 
-#ifndef DQRM_FWD_TILE_B
-#define DQRM_FWD_TILE_B 16
-#endif
-#ifndef DQRM_FWD_TILE_T
-#define DQRM_FWD_TILE_T 32
-#endif
-#ifndef DQRM_FWD_THREADS
-#define DQRM_FWD_THREADS 512
-#endif
-#ifndef DQRM_FWD_BATCH
-#define DQRM_FWD_BATCH 16
-#endif
-constexpr int kFwdTileB = DQRM_FWD_TILE_B;         // samples per tile
-constexpr int kFwdTileT = DQRM_FWD_TILE_T;         // tables per tile, at most
+constexpr int kFwdTileB = 16;                      // samples per tile
+constexpr int kFwdTileT = 32;                      // tables per tile, at most
 constexpr int kFwdSlots = kFwdTileB * kFwdTileT;   // bags per tile, at most
-constexpr int kFwdThreads = DQRM_FWD_THREADS;
-constexpr int kFwdBatch = DQRM_FWD_BATCH;          // first rows in flight per lane
+constexpr int kFwdThreads = 512;
+constexpr int kFwdBatch = 16;                      // first rows in flight per lane
 constexpr int kFwdLdsLookups = 4096;               // lookups of a tile whose row offsets fit in LDS (general bags)
 constexpr int kFwdBagBatch = 8;                    // rows of one bag in flight per lane (general bags)
 

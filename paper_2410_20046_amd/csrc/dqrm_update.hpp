@@ -171,10 +171,7 @@ struct QuantUpdateArgs {
     float *g_scale_out;
 };
 
-#ifndef DQRM_QU_PER_THREAD
-#define DQRM_QU_PER_THREAD 2
-#endif
-constexpr int kQuPerThread = DQRM_QU_PER_THREAD; // float4 elements a thread has in flight
+constexpr int kQuPerThread = 2; // float4 elements a thread has in flight
 
 __global__ __launch_bounds__(kEwThreads) void quant_update_kernel(QuantUpdateArgs a)
 {

@@ -292,6 +292,8 @@ def test_fused_quant_update_matches_two_call_path(oracle):
     assert U == o["U"]
     assert_exact(b.g_absmax.cpu().numpy().view(np.uint32), o["g_absmax"].view(np.uint32), "fused g_absmax bits")
     assert_exact(b.g_scale.cpu().numpy().view(np.uint32), gs_o.view(np.uint32), "fused g_scale bits")
+    # (the rows of segments of more than one chunk are written by dqrm_quant_update in this mode)
+    assert_exact(b.values.cpu().numpy()[:U].view(np.uint32), o["values"].view(np.uint32), "fused values bits")
     assert_exact(b.gq.cpu().numpy()[:U], gq_o, "fused INT8 codes")
     assert_exact(run.master_np().view(np.uint32), Wo.view(np.uint32), "fused master bits")
     assert_exact(run.packed_np(), po, "fused packed bytes")

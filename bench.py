@@ -2,12 +2,15 @@
 """Benchmark of the DQRM embedding hot path on one MI355X.
 
 A step = one pass of the whole hot path over one synthetic batch, all through the C ABI:
-  dqrm_embbag_fwd (gather -> INT4 fake-quant -> sum-pool) ->
-  dqrm_embbag_bwd (dedupe -> segment-sum)                 ->
-  dqrm_grad_quant_int8 -> dqrm_sparse_update (SGD on master rows + packed re-encode).
+  dqrm_embbag_fwd (gather -> INT4 fake-quant -> sum-pool)                          ->
+  dqrm_dedupe[_multi] + dqrm_segment_sum (dedupe -> segment-sum = sparse gradient) ->
+  dqrm_quant_update (INT8 codes of the gradient values, SGD on the master rows, packed re-encode).
 Workload: the Terabyte-shaped embedding layer (26 tables, ~49.12 M rows, dim 64, batch 8192,
 one Zipf(1.1) index per table per sample), tables and batches resident in HBM before timing.
 Prints ONE JSON line.  The CPU oracle is used only for the "cpu_baseline" leg.
+
+`HotPath` holds the device state and the launch sequence; tests/test_gpu_bench_path.py drives the
+very same object against the oracle.
 """
 import argparse
 import json
@@ -52,6 +55,213 @@ def read_traffic(kernel):
     return None
 
 
+class HotPath:
+    """Device state of one workload plus the launch sequence of the timed step.
+
+    overlap: where dqrm_dedupe (needs only the indices) runs --
+      "none"     in line on the one stream, every step;
+      "pipeline" on a second stream, one step ahead (double-buffered workspace);
+      "ahead"    in line, but for the next `ahead` batches in one dqrm_dedupe_multi launch (a table's sort
+                 fills one CU, so several batches fill the chip; a data loader has their indices already).
+    fused: dqrm_quant_update instead of dqrm_grad_quant_int8 + dqrm_sparse_update.
+    """
+
+    def __init__(self, wl, W, pool, grads, dev, mode="packed", overlap="ahead", ahead=8, fused=True, lr=0.1,
+                 dense_args=None, refresh_period=0):
+        import torch
+        import paper_2410_20046_amd as dq
+
+        self.torch, self.dq, self.dev = torch, dq, dev
+        self.wl, self.T, self.D, self.B = wl, wl.T, wl.D, wl.B
+        self.lr, self.fused, self.overlap = lr, fused, overlap
+        self.mode = dq.FWD_PACKED if mode == "packed" else dq.FWD_MASTER
+        self.master = torch.from_numpy(W).to(dev)
+        self.packed = torch.empty((wl.R, wl.D // 2), dtype=torch.uint8, device=dev)
+        self.tables = dq.Tables(wl.row_offsets, wl.D, self.master, self.packed)
+        self.pool = len(pool)
+        self.N = len(pool[0][0])
+        self.idx_d = [torch.from_numpy(i).to(dev) for i, _ in pool]
+        self.off_d = [torch.from_numpy(o).to(dev) for _, o in pool]
+        self.grad_d = [torch.from_numpy(g).to(dev) for g in grads]
+        self.bufs = dq.StepBuffers(self.T, self.D, self.B, self.N, dev, want_codes=False)
+        self.nbuf = {"pipeline": 2, "ahead": ahead}.get(overlap, 1)
+        b = self.bufs
+        dup = lambda x: [x] + [torch.empty_like(x) for _ in range(self.nbuf - 1)]
+        self.wss, self.sps, self.urs, self.sos = dup(b.workspace), dup(b.sorted_pos), dup(b.uniq_rows), dup(b.seg_offsets)
+        self.tuos, self.nus = dup(b.table_uniq_offsets), dup(b.num_unique)
+        self.side = torch.cuda.Stream()  # default priority
+        self.ev_dedupe = [torch.cuda.Event() for _ in range(self.nbuf)]  # dedupe into buffer i finished
+        self.ev_update = [torch.cuda.Event() for _ in range(self.nbuf)]  # last reader (the update) of buffer i finished
+        self.refresh_period = refresh_period
+        self.refresh_in_steps = refresh_period > 0  # False while the caller refreshes between graph replays
+        self.step0 = 0                              # step number that counts as 0 for the refresh period
+        self.dense = None
+        if dense_args is not None:
+            self._init_dense(**dense_args)
+        self.probe = None  # list that collects (name, event) pairs while timing calls in sequence
+
+    # ---- set-up ----------------------------------------------------------------------------------
+    def prepare(self):
+        """Sec. 3.2: the per-table scale from the whole master table, then the packed mirror."""
+        self.dq.dqrm_find_scale(self.tables)
+        self.dq.dqrm_pack_int4(self.tables)
+
+    def _init_dense(self, weight_bits, grad_bits, grad_pool):
+        torch, dq, dev = self.torch, self.dq, self.dev
+        from gen import make_dense_model, dense_batch
+
+        bd, bw, bb, td, tw, tb = make_dense_model("kaggle", self.T, self.D, self.wl.seed)
+        self.dense = dq.DenseModel(self.T, self.D, bd, bw, bb, td, tw, tb, dev)
+        self.dense_ws = torch.empty(dq.dqrm_dense_workspace_bytes(self.dense, self.B), dtype=torch.uint8, device=dev)
+        dense_in = [dense_batch(self.B, bd[0], self.wl.seed, k) for k in range(grad_pool)]
+        self.dense_x = [torch.from_numpy(x).to(dev) for x, _ in dense_in]
+        self.dense_y = [torch.from_numpy(y).to(dev) for _, y in dense_in]
+        self.loss_d = torch.zeros(1, dtype=torch.float32, device=dev)
+        self.grad_live = torch.empty((self.B, self.T, self.D), dtype=torch.float32, device=dev)
+        self.dense_quant = None
+        if weight_bits or grad_bits:
+            P = dq.dqrm_dense_param_count(self.dense)
+            self.dense_quant = dq.DenseQuant(
+                weight_bits=weight_bits, grad_bits=grad_bits,
+                grad_error=torch.zeros(P, dtype=torch.float32, device=dev) if grad_bits else None,
+                grad_scale=torch.zeros(2 * (len(bw) + len(tw)), dtype=torch.float32, device=dev) if grad_bits else None,
+                grad_codes=torch.zeros(P, dtype=torch.int8, device=dev) if grad_bits else None)
+
+    # ---- the calls of one step -------------------------------------------------------------------
+    def batch_of(self, k):
+        return self.idx_d[k % self.pool], self.off_d[k % self.pool]
+
+    def _mark(self, name):
+        if self.probe is not None:
+            ev = self.torch.cuda.Event(enable_timing=True)
+            ev.record()
+            self.probe.append((name, ev))
+
+    def refresh_scale(self):
+        self.dq.dqrm_find_scale(self.tables)
+        self.dq.dqrm_pack_int4(self.tables)
+
+    def forward(self, k):
+        dq = self.dq
+        if self.refresh_in_steps and (k - self.step0) % self.refresh_period == 0:
+            self.refresh_scale()
+            self._mark("refresh")
+        ix, of = self.batch_of(k)
+        dq.dqrm_embbag_fwd(self.tables, ix, of, self.B, self.mode, self.bufs.out, None)
+        self._mark("fwd")
+        if self.dense is not None:
+            j = k % len(self.dense_x)
+            dq.dqrm_dense_step_quant(self.dense, self.dense_quant, self.B, self.dense_x[j], self.bufs.out, self.dense_y[j],
+                                     self.lr, self.loss_d, self.grad_live, self.dense_ws)
+            self._mark("dense")
+
+    def dedupe(self, k, i, stream=None):
+        ix, of = self.batch_of(k)
+        self.dq.dqrm_dedupe(self.tables, ix, of, self.B, self.sps[i], self.urs[i], self.sos[i], self.tuos[i], self.nus[i],
+                            self.wss[i], stream=stream)
+
+    def dedupe_group(self, ks):
+        """dqrm_dedupe_multi for the batches `ks` into the buffers k % nbuf."""
+        n = self.nbuf
+        self.dq.dqrm_dedupe_multi(self.tables, self.B, [self.batch_of(j) + (self.sps[j % n], self.urs[j % n], self.sos[j % n],
+                                                                           self.tuos[j % n], self.nus[j % n], self.wss[j % n])
+                                                       for j in ks])
+        self._mark("dedupe_multi")
+
+    def rest_of_step(self, k, i):
+        """B3-B5 on the current stream, from the dedupe result in buffer i."""
+        dq, b = self.dq, self.bufs
+        g = self.grad_live if self.dense is not None else self.grad_d[k % len(self.grad_d)]
+        if self.fused:
+            dq.dqrm_segment_sum(self.tables, self.B, self.N, g, b.values, None, self.wss[i])
+            self._mark("segment_sum")
+            dq.dqrm_quant_update(self.tables, b.cap, self.N, b.values, self.urs[i], self.tuos[i], b.g_absmax, b.gq,
+                                 b.g_scale, self.lr, self.wss[i])
+            self._mark("quant_update")
+        else:
+            dq.dqrm_segment_sum(self.tables, self.B, self.N, g, b.values, b.g_absmax, self.wss[i])
+            self._mark("segment_sum")
+            dq.dqrm_grad_quant_int8(self.T, self.D, b.cap, b.values, self.tuos[i], b.g_absmax, b.gq, b.g_scale)
+            self._mark("quant")
+            dq.dqrm_sparse_update(self.tables, b.cap, self.urs[i], self.tuos[i], b.gq, b.g_scale, self.lr)
+            self._mark("update")
+
+    def run_steps(self, k0, n):
+        """n consecutive steps starting with batch k0, all launches on the current stream (+ the side stream
+        for dqrm_dedupe with overlap = "pipeline").  Self-contained: the side stream is joined at the end."""
+        torch = self.torch
+        main = torch.cuda.current_stream()
+        if self.overlap == "ahead":
+            for k in range(k0, k0 + n):
+                if (k - k0) % self.nbuf == 0:  # dedupe of this and the next nbuf-1 batches, in one launch pair
+                    self.dedupe_group(range(k, min(k + self.nbuf, k0 + n)))
+                self.forward(k)
+                self.rest_of_step(k, k % self.nbuf)
+            return
+        if self.overlap == "none":
+            for k in range(k0, k0 + n):
+                self.forward(k)
+                self.dedupe(k, 0)
+                self._mark("dedupe")
+                self.rest_of_step(k, 0)
+            return
+        # "pipeline": dqrm_dedupe on the side stream, one step ahead
+        side = self.side
+        side.wait_stream(main)  # everything enqueued so far is visible to the side stream
+
+        def dedupe_on_side(k):
+            i = k % self.nbuf
+            side.wait_event(self.ev_update[i])  # the buffer's previous reader (no-op before the first record)
+            self.dedupe(k, i, stream=side)
+            self.ev_dedupe[i].record(side)
+
+        dedupe_on_side(k0)
+        for k in range(k0, k0 + n):
+            i = k % self.nbuf
+            self.forward(k)
+            if k + 1 < k0 + n:
+                dedupe_on_side(k + 1)  # the next batch's indices are already here
+            main.wait_event(self.ev_dedupe[i])
+            self.rest_of_step(k, i)
+            self.ev_update[i].record(main)
+        main.wait_stream(side)
+
+    def capture(self, k0, n):
+        """The steps k0 .. k0+n-1 as one HIP graph (the library only launches kernels: no memset nodes)."""
+        g = self.torch.cuda.CUDAGraph()
+        with self.torch.cuda.graph(g):
+            self.run_steps(k0, n)
+        return g
+
+    # ---- per-call times inside the step sequence -------------------------------------------------
+    def time_calls_in_sequence(self, k0, n):
+        """Runs n steps eagerly with one HIP event between consecutive calls, all recorded on the launch stream,
+        and returns ({call: mean microseconds between the events around it, corrected for the cost of an event
+        pair itself}, {call: times it ran}, that cost).  The GPU is kept busy with large copies while the host
+        enqueues, so the steps then run back to back as in the timed region and no interval holds host time."""
+        torch = self.torch
+        a = torch.empty(1 << 28, dtype=torch.float32, device=self.dev)
+        b = torch.empty_like(a)
+        torch.cuda.synchronize()
+        for _ in range(40):  # ~15 ms of device-to-device copies: longer than the host needs to enqueue n steps
+            b.copy_(a)
+        self.probe = []
+        self._mark("start")
+        self.run_steps(k0, n)
+        for _ in range(16):  # adjacent events with nothing in between
+            self._mark("cal")
+        probe, self.probe = self.probe, None
+        torch.cuda.synchronize()
+        del a, b
+        sums, counts = {}, {}
+        for (_, e0), (name, e1) in zip(probe[:-1], probe[1:]):
+            us = 1e3 * e0.elapsed_time(e1)
+            sums[name] = sums.get(name, 0.0) + us
+            counts[name] = counts.get(name, 0) + 1
+        base = sums.pop("cal") / counts.pop("cal")
+        return {k: max(sums[k] / counts[k] - base, 0.0) for k in sums}, dict(counts), base
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -78,28 +288,22 @@ def main():
                     help="full DQRM train step (use with --workload kaggle): dqrm_dense_step (MLPs 13-512-256-64-16 / "
                          "367-512-256-1, interaction, BCE, backward, SGD) runs between the tables' forward and "
                          "backward and produces grad_out")
-    ap.add_argument("--overlap", default="ahead", choices=["none", "fwd", "pipeline", "pipeline2", "ahead", "group"],
+    ap.add_argument("--overlap", default="ahead", choices=["none", "pipeline", "ahead"],
                     help="where dqrm_dedupe (needs only the indices) runs: none = in line on the one stream; "
-                         "fwd = on a second stream beside the same step's forward; pipeline = on a second stream, "
-                         "one step ahead (double-buffered workspace); pipeline2 = two steps ahead, alternating between two "
-                         "side streams; ahead = in line on the one stream, but for the "
-                         "next --ahead batches in one dqrm_dedupe_multi launch (a table's sort fills one CU, so several "
-                         "batches fill the chip; the data loader has their indices already); group = that launch on the "
-                         "second stream, one group of --ahead batches ahead, so the streams meet once per group")
-    ap.add_argument("--ahead", type=int, default=8, help="batches per dqrm_dedupe_multi launch with --overlap ahead / group")
-    ap.add_argument("--side-multi", action="store_true",
-                    help="with --overlap group: the side stream uses one dqrm_dedupe_multi launch per group instead "
-                         "of one dqrm_dedupe per batch")
+                         "pipeline = on a second stream, one step ahead (double-buffered workspace); ahead = in line on "
+                         "the one stream, but for the next --ahead batches in one dqrm_dedupe_multi launch")
+    ap.add_argument("--ahead", type=int, default=8, help="batches per dqrm_dedupe_multi launch with --overlap ahead")
     ap.add_argument("--two-call-update", dest="fused", action="store_false",
                     help="dqrm_grad_quant_int8 + dqrm_sparse_update (and the absmax fold inside dqrm_segment_sum) "
                          "instead of the one-pass dqrm_quant_update")
     ap.add_argument("--no-graph", dest="graph", action="store_false",
-                    help="launch every kernel from the host instead of replaying a captured HIP graph of `pool` steps")
+                    help="launch every kernel from the host instead of replaying a captured HIP graph")
     ap.add_argument("--simulated-nodes", type=int, default=1,
                     help="simulated data parallelism: the batch is cut into this many micro-batches (forward, backward "
                          "and INT8 codes each, with the first one's scale), their integer gradients are merged "
                          "(dqrm_sparse_merge) and the tables are updated once per step; all calls in line on one stream")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-master-leg", action="store_true", help="skip the short master-mode run reported beside the headline")
     ap.add_argument("--cpu-seconds", type=float, default=12.0)
     args = ap.parse_args()
     if args.gpus != 1:
@@ -122,44 +326,19 @@ def main():
     t0 = time.time()
     W = wl.tables(threads=16)
     log(f"[bench] {args.workload}: T={T} D={D} B={B} R={wl.R} ({W.nbytes / 1e9:.2f} GB fp32), tables in {time.time() - t0:.1f}s")
-    master = torch.from_numpy(W).to(dev)
-    packed = torch.empty((wl.R, D // 2), dtype=torch.uint8, device=dev)
-    tables = dq.Tables(wl.row_offsets, D, master, packed)
-
     t0 = time.time()
     pool = [wl.batch(k) if args.pooling == 1 else wl.batch(k, pooling="fixed", max_len=args.pooling)
             for k in range(args.pool)]
-    N = len(pool[0][0])
-    idx_d = [torch.from_numpy(i).to(dev) for i, _ in pool]
-    off_d = [torch.from_numpy(o).to(dev) for _, o in pool]
     grads = [wl.grad_normal(k) for k in range(args.grad_pool)]
-    grad_d = [torch.from_numpy(g).to(dev) for g in grads]
+    dense_args = dict(weight_bits=args.mlp_weight_bits, grad_bits=args.mlp_grad_bits, grad_pool=args.grad_pool) if args.dense else None
+    hp = HotPath(wl, W, pool, grads, dev, mode=args.mode, overlap=args.overlap, ahead=args.ahead, fused=args.fused,
+                 lr=args.lr, dense_args=dense_args, refresh_period=args.refresh_period)
+    N = hp.N
     log(f"[bench] {args.pool} batches of {N} lookups + {args.grad_pool} grad_out in {time.time() - t0:.1f}s")
-
-    bufs = dq.StepBuffers(T, D, B, N, dev, want_codes=False)
-    mode = dq.FWD_PACKED if args.mode == "packed" else dq.FWD_MASTER
-    dq.dqrm_find_scale(tables)
-    dq.dqrm_pack_int4(tables)
+    hp.prepare()
     torch.cuda.synchronize()
-
-    side = torch.cuda.Stream()  # default priority
-    nbuf = {"pipeline": 2, "pipeline2": 4, "ahead": args.ahead, "group": 2 * args.ahead}.get(args.overlap, 1)
-    dup = lambda x: [x] + [torch.empty_like(x) for _ in range(nbuf - 1)]
-    wss, sps, urs, sos = dup(bufs.workspace), dup(bufs.sorted_pos), dup(bufs.uniq_rows), dup(bufs.seg_offsets)
-    tuos, nus = dup(bufs.table_uniq_offsets), dup(bufs.num_unique)
-    ev_dedupe = [torch.cuda.Event() for _ in range(nbuf)]   # dedupe into buffer i finished
-    ev_update = [torch.cuda.Event() for _ in range(nbuf)]   # last reader (the update) of buffer i finished
-    batch_of = lambda k: (idx_d[k % args.pool], off_d[k % args.pool])
-
-    side2 = torch.cuda.Stream()  # default priority; pipeline2 alternates between the two side streams
-
-    def dedupe_on_side(k, stream=None):
-        stream = stream or side
-        i = k % nbuf
-        stream.wait_event(ev_update[i])  # the buffer's previous reader (no-op before the first record)
-        ix, of = batch_of(k)
-        dq.dqrm_dedupe(tables, ix, of, B, sps[i], urs[i], sos[i], tuos[i], nus[i], wss[i], stream=stream)
-        ev_dedupe[i].record(stream)
+    hp.step0 = args.warmup
+    bufs, tables = hp.bufs, hp.tables
 
     nodes = args.simulated_nodes
     if nodes > 1:
@@ -178,180 +357,43 @@ def main():
         m_sums = torch.empty((m_cap, D), dtype=torch.int32, device=dev)
         m_ws = torch.empty(dq.dqrm_sparse_merge_workspace_bytes(T, D, nodes, m_cap), dtype=torch.uint8, device=dev)
 
-    def simulated_step(k):
-        """One weight update from `nodes` micro-batches (appendix on simulated data parallelism)."""
-        p, g = k % args.pool, grad_d[k % args.grad_pool]
-        # the micro-batches' indices are all there: one sort launch for all of them (26 x nodes workgroups)
-        dq.dqrm_dedupe_multi(tables, Bm, [(mb_idx[p][j], mb_off[p][j], b.sorted_pos, b.uniq_rows, b.seg_offsets,
-                                           b.table_uniq_offsets, b.num_unique, b.workspace) for j, b in enumerate(mb)])
-        # the weights do not change inside a group and bags are independent: the micro-batches' forwards are one
-        # call on the whole batch
-        dq.dqrm_embbag_fwd(tables, idx_d[p], off_d[p], B, mode, bufs.out, None)
-        for j in range(nodes):
-            b, ix, of = mb[j], mb_idx[p][j], mb_off[p][j]
-            # (only the first micro-batch's maxima are used: its scale serves the whole group)
-            dq.dqrm_segment_sum(tables, Bm, ix.numel(), g[j * Bm:(j + 1) * Bm], b.values, b.g_absmax, b.workspace)
-            dq.dqrm_grad_quant_int8(T, D, b.cap, b.values, b.table_uniq_offsets, mb[0].g_absmax, b.gq, b.g_scale)
-        dq.dqrm_sparse_merge(tables, [(b.uniq_rows, b.table_uniq_offsets, b.gq) for b in mb], m_rows, m_tuo, m_nu,
-                             m_sums, m_ws)
-        dq.dqrm_sparse_update_sums(tables, m_cap, m_rows, m_tuo, m_sums, mb[0].g_scale, args.lr)
+        def simulated_step(k):
+            """One weight update from `nodes` micro-batches (appendix on simulated data parallelism)."""
+            p, g = k % args.pool, hp.grad_d[k % args.grad_pool]
+            # the micro-batches' indices are all there: one sort launch for all of them (26 x nodes workgroups)
+            dq.dqrm_dedupe_multi(tables, Bm, [(mb_idx[p][j], mb_off[p][j], b.sorted_pos, b.uniq_rows, b.seg_offsets,
+                                               b.table_uniq_offsets, b.num_unique, b.workspace) for j, b in enumerate(mb)])
+            # the weights do not change inside a group and bags are independent: the micro-batches' forwards are one
+            # call on the whole batch
+            dq.dqrm_embbag_fwd(tables, hp.idx_d[p], hp.off_d[p], B, hp.mode, bufs.out, None)
+            for j in range(nodes):
+                b, ix = mb[j], mb_idx[p][j]
+                # (only the first micro-batch's maxima are used: its scale serves the whole group)
+                dq.dqrm_segment_sum(tables, Bm, ix.numel(), g[j * Bm:(j + 1) * Bm], b.values, b.g_absmax, b.workspace)
+                dq.dqrm_grad_quant_int8(T, D, b.cap, b.values, b.table_uniq_offsets, mb[0].g_absmax, b.gq, b.g_scale)
+            dq.dqrm_sparse_merge(tables, [(b.uniq_rows, b.table_uniq_offsets, b.gq) for b in mb], m_rows, m_tuo, m_nu,
+                                 m_sums, m_ws)
+            dq.dqrm_sparse_update_sums(tables, m_cap, m_rows, m_tuo, m_sums, mb[0].g_scale, args.lr)
 
-    dense = None
-    if args.dense:
-        from gen import make_dense_model, dense_batch
-        bd, bw, bb, td, tw, tb = make_dense_model("kaggle", T, D, wl.seed)
-        dense = dq.DenseModel(T, D, bd, bw, bb, td, tw, tb, dev)
-        dense_ws = torch.empty(dq.dqrm_dense_workspace_bytes(dense, B), dtype=torch.uint8, device=dev)
-        dense_in = [dense_batch(B, bd[0], wl.seed, k) for k in range(args.grad_pool)]
-        dense_x = [torch.from_numpy(x).to(dev) for x, _ in dense_in]
-        dense_y = [torch.from_numpy(y).to(dev) for _, y in dense_in]
-        loss_d = torch.zeros(1, dtype=torch.float32, device=dev)
-        grad_live = torch.empty((B, T, D), dtype=torch.float32, device=dev)
-        dense_quant = None
-        if args.mlp_weight_bits or args.mlp_grad_bits:
-            P = dq.dqrm_dense_param_count(dense)
-            dense_quant = dq.DenseQuant(
-                weight_bits=args.mlp_weight_bits, grad_bits=args.mlp_grad_bits,
-                grad_error=torch.zeros(P, dtype=torch.float32, device=dev) if args.mlp_grad_bits else None,
-                grad_scale=torch.zeros(2 * (len(bw) + len(tw)), dtype=torch.float32, device=dev) if args.mlp_grad_bits else None,
-                grad_codes=torch.zeros(P, dtype=torch.int8, device=dev) if args.mlp_grad_bits else None)
-
-    def refresh_scale():
-        """Sec. 3.2: recompute the per-table scale from the whole master table, re-encode the packed mirror."""
-        dq.dqrm_find_scale(tables)
-        dq.dqrm_pack_int4(tables)
-
-    refresh_in_steps = [args.refresh_period > 0]  # False while a graph handles the refresh between replays
-
-    def forward(k, ix, of):
-        if refresh_in_steps[0] and (k - args.warmup) % args.refresh_period == 0:
-            refresh_scale()
-        dq.dqrm_embbag_fwd(tables, ix, of, B, mode, bufs.out, None)
-        if dense is not None:
-            j = k % args.grad_pool
-            dq.dqrm_dense_step_quant(dense, dense_quant, B, dense_x[j], bufs.out, dense_y[j], args.lr, loss_d, grad_live,
-                                     dense_ws)
-
-    def rest_of_step(k, i):
-        """B3-B5 on the current stream, from the dedupe result in buffer i."""
-        g = grad_live if dense is not None else grad_d[k % args.grad_pool]
-        if args.fused:
-            dq.dqrm_segment_sum(tables, B, N, g, bufs.values, None, wss[i])
-            dq.dqrm_quant_update(tables, bufs.cap, N, bufs.values, urs[i], tuos[i], bufs.g_absmax, bufs.gq,
-                                 bufs.g_scale, args.lr, wss[i])
-        else:
-            dq.dqrm_segment_sum(tables, B, N, g, bufs.values, bufs.g_absmax, wss[i])
-            dq.dqrm_grad_quant_int8(T, D, bufs.cap, bufs.values, tuos[i], bufs.g_absmax, bufs.gq, bufs.g_scale)
-            dq.dqrm_sparse_update(tables, bufs.cap, urs[i], tuos[i], bufs.gq, bufs.g_scale, args.lr)
-
-    def run_steps(k0, n):
-        """n consecutive steps starting with batch k0, all launches on the current stream (+ the side
-        stream for dqrm_dedupe when overlapping).  Self-contained: the side stream is joined at the end."""
-        main = torch.cuda.current_stream()
-        if nodes > 1:
+        def run_steps(k0, n):
             for k in range(k0, k0 + n):
                 simulated_step(k)
-            return
-        if args.overlap == "ahead":
-            for k in range(k0, k0 + n):
-                if (k - k0) % nbuf == 0:  # dedupe of this and the next nbuf-1 batches, in one launch pair
-                    group = range(k, min(k + nbuf, k0 + n))
-                    dq.dqrm_dedupe_multi(tables, B, [batch_of(j) + (sps[j % nbuf], urs[j % nbuf], sos[j % nbuf],
-                                                                    tuos[j % nbuf], nus[j % nbuf], wss[j % nbuf])
-                                                     for j in group])
-                ix, of = batch_of(k)
-                forward(k, ix, of)
-                rest_of_step(k, k % nbuf)
-            return
-        if args.overlap == "group":
-            # dqrm_dedupe_multi of the NEXT group of --ahead batches runs on the side stream while the main
-            # stream works through the current group: the two streams meet once per group, not once per step
-            A = args.ahead
-            groups = [range(s, min(s + A, k0 + n)) for s in range(k0, k0 + n, A)]
-            slot = lambda gi, k: (gi % 2) * A + (k - groups[gi][0])
-            def dedupe_group(gi, stream):
-                if stream is side and not args.side_multi:
-                    # one batch at a time: 26 workgroups take 26 CUs from the main stream's kernels, 208 would
-                    # take most of the chip
-                    for k in groups[gi]:
-                        j = slot(gi, k)
-                        dq.dqrm_dedupe(tables, *batch_of(k), B, sps[j], urs[j], sos[j], tuos[j], nus[j], wss[j],
-                                       stream=side)
-                    return
-                dq.dqrm_dedupe_multi(tables, B, [batch_of(k) + (sps[slot(gi, k)], urs[slot(gi, k)], sos[slot(gi, k)],
-                                                                tuos[slot(gi, k)], nus[slot(gi, k)], wss[slot(gi, k)])
-                                                 for k in groups[gi]], stream=stream)
-            side.wait_stream(main)
-            dedupe_group(0, main)  # the first group in line
-            for gi, grp in enumerate(groups):
-                if gi + 1 < len(groups):
-                    if gi >= 1:
-                        side.wait_event(ev_update[(gi - 1) % 2])  # readers of that half of the buffers are done
-                    dedupe_group(gi + 1, side)
-                    ev_dedupe[(gi + 1) % 2].record(side)
-                if gi >= 1:
-                    main.wait_event(ev_dedupe[gi % 2])
-                for k in grp:
-                    ix, of = batch_of(k)
-                    forward(k, ix, of)
-                    rest_of_step(k, slot(gi, k))
-                ev_update[gi % 2].record(main)
-            main.wait_stream(side)
-            return
-        if args.overlap == "none":
-            for k in range(k0, k0 + n):
-                ix, of = batch_of(k)
-                forward(k, ix, of)
-                dq.dqrm_dedupe(tables, ix, of, B, sps[0], urs[0], sos[0], tuos[0], nus[0], wss[0])
-                rest_of_step(k, 0)
-            return
-        if args.overlap == "pipeline2":
-            # two steps ahead, alternating between two side streams: a dedupe has two step times to finish
-            sides = [side, side2]
-            side.wait_stream(main)
-            side2.wait_stream(main)
-            dedupe_on_side(k0, sides[k0 % 2])
-            if n > 1:
-                dedupe_on_side(k0 + 1, sides[(k0 + 1) % 2])
-            for k in range(k0, k0 + n):
-                ix, of = batch_of(k)
-                i = k % nbuf
-                forward(k, ix, of)
-                if k + 2 < k0 + n:
-                    dedupe_on_side(k + 2, sides[k % 2])
-                main.wait_event(ev_dedupe[i])
-                rest_of_step(k, i)
-                ev_update[i].record(main)
-            main.wait_stream(side)
-            main.wait_stream(side2)
-            return
-        side.wait_stream(main)  # everything enqueued so far is visible to the side stream
-        if args.overlap == "pipeline":
-            dedupe_on_side(k0)
-        for k in range(k0, k0 + n):
-            ix, of = batch_of(k)
-            i = k % nbuf
-            if args.overlap == "fwd":
-                dedupe_on_side(k)  # beside this step's forward
-            forward(k, ix, of)
-            if args.overlap == "pipeline" and k + 1 < k0 + n:
-                dedupe_on_side(k + 1)  # one step ahead: the next batch's indices are already here
-            main.wait_event(ev_dedupe[i])
-            rest_of_step(k, i)
-            ev_update[i].record(main)
+    else:
+        run_steps = hp.run_steps
 
     # ---- warm-up (eager), optional capture of `graph_steps` steps into one HIP graph ----
     run_steps(0, args.warmup)
     torch.cuda.synchronize()
     graph, graph_steps = None, 0
+    P = args.refresh_period
     if args.graph:
         graph_steps = min(args.pool, args.steps)
-        P = args.refresh_period
         if P > graph_steps:
-            assert P % graph_steps == 0, "--refresh-period must be a multiple (or a divisor) of the graph's steps"
-            refresh_in_steps[0] = False  # refreshed eagerly before every (P / graph_steps)-th replay
+            # the refresh runs eagerly before every (P / graph_steps)-th replay: the graph's length divides P
+            graph_steps = max(d for d in range(1, graph_steps + 1) if P % d == 0)
+            hp.refresh_in_steps = False
         elif P > 0:
-            assert graph_steps % P == 0, "--refresh-period must be a multiple (or a divisor) of the graph's steps"
+            graph_steps = graph_steps // P * P
         graph = torch.cuda.CUDAGraph()
         with torch.cuda.graph(graph):
             run_steps(args.warmup, graph_steps)
@@ -364,8 +406,8 @@ def main():
     e0.record()
     if graph is not None:
         for rep in range(args.steps // graph_steps):
-            if args.refresh_period > graph_steps and (rep * graph_steps) % args.refresh_period == 0:
-                refresh_scale()
+            if P > graph_steps and (rep * graph_steps) % P == 0:
+                hp.refresh_scale()
             graph.replay()
         if args.steps % graph_steps:
             run_steps(args.warmup, args.steps % graph_steps)
@@ -381,78 +423,80 @@ def main():
     assert code == 0, f"device status {code} (table {tb}, value {val})"
     log(f"[bench] timed {args.steps} steps: wall {wall * 1e3:.2f} ms, events {ev_ms:.2f} ms, {ms_per_step * 1e3:.1f} us/step "
         f"(host issued them in {t_issued * 1e3:.2f} ms = {t_issued * 1e6 / args.steps:.1f} us/step)")
+    hp.refresh_in_steps = False  # the measurements below leave the scale alone
 
     # ---- unique rows per batch (for the algorithmic byte counts) ----
     us = []
     for k in range(min(args.pool, 16)):
-        dq.dqrm_embbag_bwd(tables, idx_d[k], off_d[k], B, grad_d[0], bufs.sorted_pos, bufs.uniq_rows,
+        dq.dqrm_embbag_bwd(tables, hp.idx_d[k], hp.off_d[k], B, hp.grad_d[0], bufs.sorted_pos, bufs.uniq_rows,
                            bufs.seg_offsets, bufs.table_uniq_offsets, bufs.num_unique, bufs.values, bufs.g_absmax,
                            bufs.workspace)
         us.append(int(bufs.num_unique.cpu().item()))
     U = float(np.mean(us))
-    ab = algorithmic_bytes(T, D, B, N, U, packed_fwd=(mode == dq.FWD_PACKED), packed_mirror=True)
+    packed_fwd = hp.mode == dq.FWD_PACKED
+    ab = algorithmic_bytes(T, D, B, N, U, packed_fwd=packed_fwd, packed_mirror=True)
 
-    # ---- per-call HIP-event timing, one stream, events on the launch stream ----
-    stages = ["fwd", "dedupe", "segment_sum", "quant", "update", "quant_update"]
-    calls = {
-        "fwd": lambda k: dq.dqrm_embbag_fwd(tables, idx_d[k % args.pool], off_d[k % args.pool], B, mode, bufs.out, None),
-        "dedupe": lambda k: dq.dqrm_dedupe(tables, idx_d[k % args.pool], off_d[k % args.pool], B, bufs.sorted_pos,
-                                           bufs.uniq_rows, bufs.seg_offsets, bufs.table_uniq_offsets,
-                                           bufs.num_unique, bufs.workspace),
-        "segment_sum": lambda k: dq.dqrm_segment_sum(tables, B, N, grad_d[k % args.grad_pool], bufs.values,
-                                                     bufs.g_absmax, bufs.workspace),
-        "quant": lambda k: dq.dqrm_grad_quant_int8(T, D, bufs.cap, bufs.values, bufs.table_uniq_offsets,
-                                                   bufs.g_absmax, bufs.gq, bufs.g_scale),
-        "update": lambda k: dq.dqrm_sparse_update(tables, bufs.cap, bufs.uniq_rows, bufs.table_uniq_offsets, bufs.gq,
-                                                  bufs.g_scale, args.lr),
-        "quant_update": lambda k: dq.dqrm_quant_update(tables, bufs.cap, N, bufs.values, bufs.uniq_rows,
-                                                       bufs.table_uniq_offsets, bufs.g_absmax, bufs.gq, bufs.g_scale,
-                                                       args.lr, bufs.workspace),
-    }
-    # Each call is timed on its own: `reps` back-to-back launches of the same call (cycling through the
-    # batches) between two events, so that the cost of recording an event is not charged to a 5-20 us kernel.
-    # The calls are launched in path order first, so every call finds valid inputs.
-    if nodes > 1:
-        simulated_step(args.warmup)  # valid blocks for the two calls below
-        stages += ["sparse_merge", "update_sums"]
-        calls["sparse_merge"] = lambda k: dq.dqrm_sparse_merge(
-            tables, [(b.uniq_rows, b.table_uniq_offsets, b.gq) for b in mb], m_rows, m_tuo, m_nu, m_sums, m_ws)
-        calls["update_sums"] = lambda k: dq.dqrm_sparse_update_sums(tables, m_cap, m_rows, m_tuo, m_sums, mb[0].g_scale,
-                                                                   args.lr)
-    for name in stages:
-        calls[name](args.warmup)
-    reps = max(10, min(args.steps, 200))
-    stage_us = {}
-    for name in stages:
-        for k in range(3):
-            calls[name](args.warmup + k)
-        ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        ev0.record()
-        for k in range(reps):
-            calls[name](args.warmup + k)
-        ev1.record()
+    # ---- every call's time INSIDE the step sequence (HIP events on the launch stream between the calls) ----
+    kernels, roofline = [], None
+    if nodes == 1:
+        n_probe = 8 * max(args.ahead, 1) if args.overlap == "ahead" else 32
+        call_us, call_n, ev_cost = hp.time_calls_in_sequence(args.warmup, n_probe)
+        per_step = {k: call_us[k] * call_n[k] / n_probe for k in call_us}  # dedupe_multi runs once per --ahead steps
+        log(f"[bench] per call, in sequence (us; an event pair costs {ev_cost:.2f}): "
+            + ", ".join(f"{k}={call_us[k]:.2f}" + (f" (x{call_n[k]}/{n_probe} steps)" if call_n[k] != n_probe else "")
+                        for k in call_us))
+        G = 1
+        while G < D // 4:
+            G *= 2
+        # which kernel(s) a call launches, and the algorithmic bytes of one launch
+        call_kernels = {
+            "fwd": (f"embbag_fwd_kernel<{G},{'packed' if packed_fwd else 'master'}>", ab["fwd"]),
+            "segment_sum": (f"segment_sum_kernel<{G}>" + ("" if args.fused else " + absmax_finalize_kernel"), ab["segsum"]),
+            "quant_update": ("quant_update_kernel", ab["quant"] + ab["update"] - D * U),
+            "quant": ("grad_quant_kernel", ab["quant"]),
+            "update": ("sparse_update_kernel", ab["update"]),
+            "dedupe": ("dedupe_kernel + dedupe_finish_kernel", ab["dedupe"]),
+            "dedupe_multi": ("dedupe_kernel + dedupe_finish_kernel", ab["dedupe"] * max(args.ahead, 1)),
+        }
+        for name, us_call in call_us.items():
+            if name not in call_kernels:
+                continue
+            kname, nbytes = call_kernels[name]
+            gbs = nbytes / (us_call * 1e-6) / 1e9 if us_call > 0 else 0.0
+            kernels.append({"call": name, "kernel": kname, "algorithmic_bytes_per_launch": int(nbytes),
+                            "avg_launch_us": round(us_call, 2), "us_per_step": round(per_step[name], 2),
+                            "achieved_gbs": round(gbs, 1), "frac_of_peak": round(gbs / HBM_PEAK_GBS, 4)})
+        # the dominant kernel: the single-kernel call with the largest share of the step
+        single = [k for k in kernels if "+" not in k["kernel"]]
+        dom = max(single, key=lambda k: k["us_per_step"])
+        roofline = {"bound": "hbm", "kernel": dom["kernel"], "achieved": dom["achieved_gbs"], "peak": HBM_PEAK_GBS,
+                    "unit": "GB/s", "frac": dom["frac_of_peak"], "traffic": read_traffic(dom["kernel"].split("<")[0]),
+                    "algorithmic_bytes_per_launch": dom["algorithmic_bytes_per_launch"],
+                    "avg_launch_us": dom["avg_launch_us"],
+                    "share_of_step": round(dom["us_per_step"] / sum(k["us_per_step"] for k in kernels), 4),
+                    "how": "HIP events on the launch stream between consecutive calls of the step sequence"}
+
+    # ---- the master-mode forward beside the packed headline: a short run of the same steps ----
+    master_leg = None
+    if packed_fwd and nodes == 1 and not args.no_master_leg and not args.dense:
+        hp.mode = dq.FWD_MASTER
+        n_m = min(args.pool, args.steps, 64)
+        gm = hp.capture(args.warmup, n_m) if args.graph else None
+        (gm.replay() if gm is not None else hp.run_steps(args.warmup, n_m))
         torch.cuda.synchronize()
-        stage_us[name] = 1e3 * ev0.elapsed_time(ev1) / reps
-    log("[bench] per-call HIP-event time (us): " + ", ".join(f"{k}={v:.1f}" for k, v in stage_us.items()))
-    stage_bytes = {"fwd": ab["fwd"], "dedupe": ab["dedupe"], "segment_sum": ab["segsum"], "quant": ab["quant"],
-                   "update": ab["update"], "quant_update": ab["quant"] + ab["update"] - D * U}
-    if nodes > 1:
-        Um = int(m_nu.cpu().item())
-        blocks_rows = sum(int(b.num_unique.cpu().item()) for b in mb)
-        # merge: every block row's id (8 B) and codes (D B) in, the union's ids and 32-bit sums out
-        stage_bytes["sparse_merge"] = blocks_rows * (8 + D) + Um * (8 + 4 * D)
-        # update from sums: id + sums + master row read and written + packed row written
-        stage_bytes["update_sums"] = Um * (8 + 4 * D + 8 * D + D // 2)
-        log(f"[bench] simulated nodes {nodes}: {blocks_rows} block rows merge into {Um}")
-    stage_gbs = {k: stage_bytes[k] / (stage_us[k] * 1e-6) / 1e9 for k in stages}
-
-    # The dominant kernel of the step's critical path: dqrm_embbag_fwd is exactly one kernel launch
-    # (embbag_fwd_kernel), so its event time is that kernel's average launch duration.
-    dom, dom_kernel = "fwd", "embbag_fwd_kernel"
-    dom_bytes, dom_gbs = stage_bytes[dom], stage_gbs[dom]
-    roofline = {"bound": "hbm", "kernel": dom_kernel, "achieved": round(dom_gbs, 1), "peak": HBM_PEAK_GBS,
-                "unit": "GB/s", "frac": round(dom_gbs / HBM_PEAK_GBS, 4), "traffic": read_traffic(dom_kernel),
-                "algorithmic_bytes_per_launch": int(dom_bytes), "avg_launch_us": round(stage_us[dom], 2)}
+        t1 = time.perf_counter()
+        reps = max(1, min(args.steps, 640) // n_m)
+        for _ in range(reps):
+            (gm.replay() if gm is not None else hp.run_steps(args.warmup, n_m))
+        torch.cuda.synchronize()
+        ms_m = (time.perf_counter() - t1) * 1e3 / (reps * n_m)
+        abm = algorithmic_bytes(T, D, B, N, U, packed_fwd=False, packed_mirror=True)
+        master_leg = {"fwd_mode": "master", "steps": reps * n_m, "ms_per_step": round(ms_m, 5),
+                      "value": round(N / (ms_m * 1e-3), 1), "unit": "lookups/s",
+                      "step_algorithmic_bytes": int(abm["step"]),
+                      "step_hbm_frac_of_peak": round(abm["step"] / (ms_m * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)}
+        hp.mode = dq.FWD_PACKED
+        log(f"[bench] master-mode forward, same steps: {ms_m * 1e3:.1f} us/step")
 
     # ---- device-to-device copy bandwidth, for context ----
     a = torch.empty(1 << 28, dtype=torch.float32, device=dev)
@@ -468,7 +512,8 @@ def main():
     torch.cuda.synchronize()
     copy_gbs = 10 * 2 * a.numel() * 4 / (c0.elapsed_time(c1) * 1e-3) / 1e9
     del a, b
-    roofline["frac_of_copy_bw"] = round(dom_gbs / copy_gbs, 4)  # against what a plain copy reaches on this machine
+    if roofline is not None:
+        roofline["frac_of_copy_bw"] = round(roofline["achieved"] / copy_gbs, 4)  # against what a plain copy reaches here
 
     lookups_per_s = N * args.steps / wall
     step_gbs = ab["step"] / (ms_per_step * 1e-3) / 1e9
@@ -516,7 +561,9 @@ def main():
                                f"1 Zipf index per table per sample, {args.mode}-mode forward, INT8 sparse grads, "
                                f"SGD lr {args.lr}, dedupe overlap: {args.overlap}"
                                + (f", {nodes} simulated nodes (micro-batches of {B // nodes}, one update per step)" if nodes > 1 else ""),
-                   "lookups_per_step": N, "unique_rows_per_step": round(U, 1), "fwd_mode": args.mode, "overlap": args.overlap, "scale_refresh_period": args.refresh_period, "pooling": args.pooling, "dense_part": bool(args.dense), "mlp_weight_bits": args.mlp_weight_bits, "mlp_grad_bits": args.mlp_grad_bits, "simulated_nodes": nodes,
+                   "lookups_per_step": N, "unique_rows_per_step": round(U, 1), "fwd_mode": args.mode, "overlap": args.overlap,
+                   "scale_refresh_period": args.refresh_period, "pooling": args.pooling, "dense_part": bool(args.dense),
+                   "mlp_weight_bits": args.mlp_weight_bits, "mlp_grad_bits": args.mlp_grad_bits, "simulated_nodes": nodes,
                    "update": ("dqrm_quant_update (one pass)" if args.fused else "dqrm_grad_quant_int8 + dqrm_sparse_update"),
                    "launch": (f"HIP graph of {graph_steps} steps replayed" if graph is not None else "eager launches")},
         "roofline": roofline,
@@ -524,8 +571,8 @@ def main():
         "step_algorithmic_bytes": int(ab["step"]),
         "step_hbm_gbs": round(step_gbs, 1),
         "step_hbm_frac_of_peak": round(step_gbs / HBM_PEAK_GBS, 4),
-        "call_us": {k: round(v, 2) for k, v in stage_us.items()},
-        "call_algorithmic_gbs": {k: round(v, 1) for k, v in stage_gbs.items()},
+        "kernels": kernels,
+        "master_mode": master_leg,
         "event_ms_per_step": round(ev_ms / args.steps, 5),
         "copy_bw_gbs": round(copy_gbs, 1),
     }

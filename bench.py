@@ -274,7 +274,7 @@ def main():
     ap.add_argument("--lr", type=float, default=0.1)
     ap.add_argument("--pooling", type=int, default=1,
                     help="indices per bag (pooling factor; the paper-shaped workloads have 1).  A table may have at "
-                         "most 16384 lookups per batch: lower --batch accordingly")
+                         "most 65536 lookups per batch (pooling 8 at the default batch)")
     ap.add_argument("--batch", type=int, default=0, help="override the workload's batch size")
     ap.add_argument("--mlp-weight-bits", type=int, default=0, choices=[0, 4, 8],
                     help="with --dense: channel-wise fake quantisation of the MLP weights (dqrm_dense_step_quant)")

@@ -65,7 +65,8 @@ extern "C" {
 #define DQRM_MAX_DIM 256             /* dim must be a multiple of 8 in [8, 256] */
 #define DQRM_MAX_TABLES 1024
 #define DQRM_MAX_TABLE_ROWS 2147483646LL /* rows of one table */
-#define DQRM_MAX_TABLE_LOOKUPS 16384 /* lookups one table may receive in one batch (dedupe sorts them in LDS) */
+#define DQRM_MAX_TABLE_LOOKUPS 65536 /* lookups one table may receive in one batch (up to 16384 are sorted in LDS by
+                                        one workgroup; more take a slower path through the workspace) */
 #define DQRM_MAX_DEDUPE_BATCHES 8    /* batches one dqrm_dedupe_multi call may take */
 
 /* Order of a segment's floating-point sum (the paper does not fix one; results

@@ -31,7 +31,7 @@ _NAMES = {0: "OK", -1: "INVALID_ARG", -2: "UNSUPPORTED", -3: "WORKSPACE_TOO_SMAL
 FWD_MASTER = 0
 FWD_PACKED = 1
 SEG_CHUNK = 32
-MAX_TABLE_LOOKUPS = 16384
+MAX_TABLE_LOOKUPS = 65536
 NOALLOC_SCRATCH_BYTES = 8 << 20
 
 EXPORTS = ("dqrm_find_scale", "dqrm_pack_int4", "dqrm_embbag_fwd", "dqrm_embbag_bwd_workspace_bytes",

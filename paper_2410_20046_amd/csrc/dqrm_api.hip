@@ -81,7 +81,8 @@ int32_t check_batch(const dqrm_tables_t *tb, const int64_t *indices, const int64
 // ---- workspace layout of dqrm_embbag_bwd -------------------------------------
 struct WsLayout {
     size_t off_table_base, off_table_nuniq, off_table_nchunk, off_table_nsingle, off_totals, off_bag_of_pos, off_sorted_bag,
-        off_chunk_local, off_single_local, off_chunk_desc, off_chunk_bags, off_single_desc, off_seg_count, off_partial_full,
+        off_chunk_local, off_single_local, off_chunk_desc, off_chunk_bags, off_single_desc, off_run_key, off_run_pos,
+        off_merged_key, off_merged_pos, off_head_of_seg, off_seg_count, off_partial_full,
         off_partial_last, off_absmax_slots, total;
 };
 
@@ -109,6 +110,13 @@ WsLayout ws_layout(int32_t T, int32_t D, int64_t N)
     L.off_chunk_desc = take(n * 16);
     L.off_chunk_bags = take((n / 2 + 1) * DQRM_SEG_CHUNK * sizeof(int));
     L.off_single_desc = take(n * 16);
+    // (the large-table path exists only for batches that can hold a large table)
+    const size_t big = N > dqrm::kDdCap ? n : 0;
+    L.off_run_key = take(big * sizeof(int));
+    L.off_run_pos = take(big * sizeof(int));
+    L.off_merged_key = take(big * sizeof(int));
+    L.off_merged_pos = take(big * sizeof(int));
+    L.off_head_of_seg = take(big ? (big + t + 1) * sizeof(int) : 0);
     L.off_seg_count = take(slots * sizeof(int));
     L.off_partial_full = take(slots * (size_t)D * sizeof(float));
     L.off_partial_last = take(slots * (size_t)D * sizeof(float));
@@ -133,6 +141,11 @@ dqrm::BwdWs ws_views(void *workspace, const WsLayout &L)
     w.chunk_desc = reinterpret_cast<int4 *>(b + L.off_chunk_desc);
     w.chunk_bags = reinterpret_cast<int *>(b + L.off_chunk_bags);
     w.single_desc = reinterpret_cast<int4 *>(b + L.off_single_desc);
+    w.run_key = reinterpret_cast<unsigned *>(b + L.off_run_key);
+    w.run_pos = reinterpret_cast<int *>(b + L.off_run_pos);
+    w.merged_key = reinterpret_cast<unsigned *>(b + L.off_merged_key);
+    w.merged_pos = reinterpret_cast<int *>(b + L.off_merged_pos);
+    w.head_of_seg = reinterpret_cast<int *>(b + L.off_head_of_seg);
     w.seg_count = reinterpret_cast<int *>(b + L.off_seg_count);
     w.partial_full = reinterpret_cast<float *>(b + L.off_partial_full);
     w.partial_last = reinterpret_cast<float *>(b + L.off_partial_last);
@@ -376,7 +389,12 @@ int32_t dqrm_dedupe_multi(const dqrm_tables_t *tables, int32_t batch, int32_t nu
     da.T = T;
     da.B = batch;
     hipStream_t st = static_cast<hipStream_t>(stream);
-    hipLaunchKernelGGL(dqrm::dedupe_kernel, dim3(T, num_batches), dim3(dqrm::kDdThreads), 0, st, da);
+    // a table of more than kDdCap lookups is sorted in tiles (grid z), which dedupe_large_kernel merges
+    const int64_t largest = std::min<int64_t>(max_n, DQRM_MAX_TABLE_LOOKUPS);
+    const int tiles = (int)std::max<int64_t>(1, (largest + dqrm::kDdCap - 1) / dqrm::kDdCap);
+    hipLaunchKernelGGL(dqrm::dedupe_kernel, dim3(T, num_batches, tiles), dim3(dqrm::kDdThreads), 0, st, da);
+    if (tiles > 1)
+        hipLaunchKernelGGL(dqrm::dedupe_large_kernel, dim3(T, num_batches), dim3(dqrm::kDdThreads), 0, st, da);
     hipLaunchKernelGGL(dqrm::dedupe_finish_kernel, dim3(grid_for(max_n, dqrm::kSegThreads, 2), num_batches),
                        dim3(dqrm::kSegThreads), 0, st, da);
     DQRM_HIP_CHECK(hipGetLastError());

@@ -26,8 +26,10 @@ namespace dqrm {
 
 constexpr int kDdThreads = 1024;
 constexpr int kDdWaves = kDdThreads / kWave;                      // 16
-constexpr int kDdMaxRounds = DQRM_MAX_TABLE_LOOKUPS / kDdThreads; // 16 items per thread at most
-constexpr int kDdCap = DQRM_MAX_TABLE_LOOKUPS;
+constexpr int kDdCap = 16384;                     // lookups one workgroup sorts in LDS
+constexpr int kDdMaxRounds = kDdCap / kDdThreads; // 16 items per thread at most
+static_assert(DQRM_MAX_TABLE_LOOKUPS % kDdCap == 0 && DQRM_MAX_TABLE_LOOKUPS / DQRM_SEG_CHUNK < 4096,
+              "tiles of the large-table path; the chunk descriptor holds 12 bits of chunk count");
 constexpr int kSegThreads = 256;   // dedupe_finish_kernel
 constexpr int kSumThreads = 256;   // segment_sum_kernel
 constexpr int kSegBatch = 16;      // gradient rows requested before the first is added
@@ -47,6 +49,13 @@ struct BwdWs {
     int *chunk_bags;          // [N/2 + 1][32] bags of chunk c's lookups, so that they can be read before its descriptor
     int4 *single_desc;        // [N]   dense list of singles: {bag, global segment, table, -}
     int *totals;              // [3]   chunks, segments, singles
+    // tables with more than kDdCap lookups (present only if N > kDdCap): the sorted tiles, then, in the same two
+    // arrays, segment index and segment start of every merged position; the merged order; the segments' heads
+    unsigned *run_key;        // [N]   / int seg_idx[N]
+    int *run_pos;             // [N]   / int seg_start[N]
+    unsigned *merged_key;     // [N]
+    int *merged_pos;          // [N]   position inside the table of every merged item
+    int *head_of_seg;         // [N + T + 1] sorted index of each segment's head; table t's list starts at (first lookup position + t)
     int *seg_count;           // [N/32 + 2] chunks of a segment of more than one chunk that have parked their sum, filed
                               //       under (sorted position of the segment's head / 32); zero between uses
     float *partial_full;      // [(N/32 + 2) * D] sum of a full chunk of a segment of more than one chunk
@@ -122,16 +131,25 @@ __global__ __launch_bounds__(kDdThreads) void dedupe_kernel(DedupeArgs args)
     long long lo = offsets[(long long)t * B], hi = offsets[(long long)(t + 1) * B];
     bool disabled = false; // a table with unusable extents contributes nothing
     if (lo < 0 || hi > N || lo > hi) {
-        if (tid == 0) report(DQRM_ERR_BAD_OFFSETS, t, lo);
+        if (tid == 0 && blockIdx.z == 0) report(DQRM_ERR_BAD_OFFSETS, t, lo);
         lo = lo < 0 ? 0 : (lo > N ? N : lo);
         disabled = true;
-    } else if (hi - lo > kDdCap) {
-        if (tid == 0) report(DQRM_ERR_CAPACITY, t, hi - lo);
+    } else if (hi - lo > DQRM_MAX_TABLE_LOOKUPS) {
+        if (tid == 0 && blockIdx.z == 0) report(DQRM_ERR_CAPACITY, t, hi - lo);
         disabled = true;
     }
     if (disabled) hi = lo;
-    const int n = (int)(hi - lo);
     const int base = (int)lo;
+    // A table of up to kDdCap lookups is this workgroup's (blockIdx.z = 0) from start to end.  A larger one is cut
+    // into tiles of kDdCap consecutive lookups: workgroup z sorts tile z and leaves the sorted run in the workspace;
+    // dedupe_large_kernel merges the runs and does the rest.
+    const bool large = hi - lo > kDdCap;
+    const int tile = (int)blockIdx.z;
+    if (!large && tile > 0) return;
+    const long long first = lo + (large ? (long long)tile * kDdCap : 0ll); // my first lookup
+    if (large && first >= hi) return;
+    const int n = (int)(large ? (hi - first < kDdCap ? hi - first : (long long)kDdCap) : hi - lo);
+    const bool does_bags = !disabled && (!large || tile == 0);
 
     // ---- phase 0: bag of every lookup position ---------------------------
     // The table's keys are requested first (wave-striped: item i = wave * per_wave + r * 64 + lane), so that they
@@ -142,13 +160,13 @@ __global__ __launch_bounds__(kDdThreads) void dedupe_kernel(DedupeArgs args)
 #pragma unroll
     for (int r = 0; r < kDdMaxRounds; ++r) {
         raw[r] = 0;
-        if (r < rounds) raw[r] = indices[lo + min(wave * per_wave + r * kWave + lane, n - 1)]; // (n >= 1 here)
+        if (r < rounds) raw[r] = indices[first + min(wave * per_wave + r * kWave + lane, n - 1)]; // (n >= 1 here)
     }
     // When every bag of the table holds exactly one lookup (the usual DLRM
     // batch) the bag of position p is p itself and nothing needs to be stored.
     constexpr int kBagBatch = 8;
-    bool one_each = !disabled && (n == B);
-    if (!disabled) {
+    bool one_each = !disabled && !large && (n == B);
+    if (does_bags) {
         for (int b0 = 0; b0 < B; b0 += kDdThreads * kBagBatch) {
             long long s[kBagBatch], e[kBagBatch];
 #pragma unroll
@@ -171,7 +189,7 @@ __global__ __launch_bounds__(kDdThreads) void dedupe_kernel(DedupeArgs args)
         }
     }
     one_each = __syncthreads_and(one_each ? 1 : 0) != 0;
-    if (!disabled && !one_each) {
+    if (does_bags && !one_each) {
         for (int b = tid; b < B; b += kDdThreads) {
             long long s = offsets[(long long)t * B + b], e = offsets[(long long)t * B + b + 1];
             s = s < lo ? lo : (s > hi ? hi : s);
@@ -255,6 +273,14 @@ __global__ __launch_bounds__(kDdThreads) void dedupe_kernel(DedupeArgs args)
         }
         // the next pass clears cnt and synchronises before anything is overwritten
     }
+    if (large) { // the sorted run of this tile; positions counted from the table's first lookup
+        for (int i = tid; i < n; i += kDdThreads) {
+            ws.run_key[first + i] = skey[i];
+            ws.run_pos[first + i] = tile * kDdCap + (int)spos[i];
+        }
+        return;
+    }
+
     // ---- phase 3: segment heads and chunk heads ---------------------------
     // (skey / spos now hold the table's rounds*1024 items in sorted order;
     //  entries that are padding or had a bad index carry the sentinel key.)
@@ -404,6 +430,154 @@ __global__ __launch_bounds__(kDdThreads) void dedupe_kernel(DedupeArgs args)
         ws.table_nuniq[t] = n_uniq;
         ws.table_nchunk[t] = n_chunk;
         ws.table_nsingle[t] = n_single;
+    }
+    if (tid < kAbsmaxSlots) *absmax_slot(ws.absmax_slots, t, tid) = 0.0f;
+}
+
+// ---------------------------------------------------------------------------
+// Tables with more than kDdCap lookups: dedupe_kernel has sorted their tiles of kDdCap consecutive lookups; one
+// workgroup per (table, batch) now
+//  1. merges the runs: every item finds its place in the table's sorted order on its own -- its index in its own
+//     run plus, per other run, the number of that run's keys below it (binary searches; equal keys of earlier runs
+//     count as below, which keeps equal keys in lookup order);
+//  2. walks the merged order in slabs of one item per thread, carrying the counts from slab to slab: segment
+//     heads, segment index and start of every item, the list of the heads;
+//  3. walks it again for the chunk heads and singles (a segment's end is the next segment's head, known now) and
+//     writes the same table-local lists and counts as dedupe_kernel does for a small table.
+// Everything between the steps goes through global memory of the workspace, read back by the same workgroup
+// after a barrier.  Slower per lookup than the in-LDS path; it exists so that no table size up to
+// DQRM_MAX_TABLE_LOOKUPS is refused.
+__global__ __launch_bounds__(kDdThreads) void dedupe_large_kernel(DedupeArgs args)
+{
+    const DedupeBatch &bt = args.b[blockIdx.y];
+    const int64_t *__restrict__ offsets = bt.offsets;
+    const int B = args.B;
+    const int64_t N = bt.N;
+    const BwdWs ws = bt.ws;
+    __shared__ int s_w[kDdWaves];
+    __shared__ int s_w2[kDdWaves];
+
+    const int t = blockIdx.x;
+    const int tid = threadIdx.x, lane = tid & (kWave - 1), wave = tid / kWave;
+    const long long rows_ll = args.row_offsets[t + 1] - args.row_offsets[t];
+    const unsigned rows_t = (unsigned)rows_ll;
+    const long long lo = offsets[(long long)t * B], hi = offsets[(long long)(t + 1) * B];
+    // (unusable extents and tables beyond the limit were reported and closed by dedupe_kernel)
+    if (lo < 0 || hi > N || lo > hi || hi - lo > DQRM_MAX_TABLE_LOOKUPS || hi - lo <= kDdCap) return;
+    const int n = (int)(hi - lo), base = (int)lo;
+    const int runs = (n + kDdCap - 1) / kDdCap;
+
+    // ---- 1. merge the runs
+    for (int e = tid; e < n; e += kDdThreads) {
+        const int r = e / kDdCap;
+        const unsigned key = ws.run_key[base + e];
+        int rank = e - r * kDdCap;
+        for (int r2 = 0; r2 < runs; ++r2) {
+            if (r2 == r) continue;
+            const unsigned *run = ws.run_key + base + r2 * kDdCap;
+            int a = 0, b = min(kDdCap, n - r2 * kDdCap); // keys of run r2 below mine: in [a, b]
+            while (a < b) {
+                const int mid = (a + b) >> 1;
+                const unsigned k2 = run[mid];
+                if (r2 < r ? k2 <= key : k2 < key)
+                    a = mid + 1;
+                else
+                    b = mid;
+            }
+            rank += a;
+        }
+        ws.merged_key[base + rank] = key;
+        ws.merged_pos[base + rank] = ws.run_pos[base + e];
+    }
+    __syncthreads(); // the runs are not read again: their arrays now take segment index and start of every item
+
+    // ---- 2. segment heads, index and start of every item, slab by slab
+    int *seg_idx = reinterpret_cast<int *>(ws.run_key) + base, *seg_start = ws.run_pos + base;
+    int *head_of = ws.head_of_seg + base + t;
+    int carry_heads = 0, carry_start = -1, n_valid = 0;
+    for (int s0 = 0; s0 < n; s0 += kDdThreads) {
+        const int i = s0 + tid;
+        const unsigned k = i < n ? ws.merged_key[base + i] : rows_t;
+        const unsigned prev = (i > 0 && i < n) ? ws.merged_key[base + i - 1] : 0u;
+        const bool valid = i < n && k < rows_t;
+        const bool head = valid && (i == 0 || prev != k);
+        const int h = wave_incl_scan_add(head ? 1 : 0, lane);
+        const int st = wave_incl_scan_max(head ? i : -1, lane);
+        const int nv = __popcll(__ballot(valid));
+        __syncthreads(); // (s_w / s_w2 of the previous slab have been read)
+        if (lane == kWave - 1) {
+            s_w[wave] = h | (nv << 16); // both at most 64
+            s_w2[wave] = st;
+        }
+        __syncthreads();
+        int heads_before = 0, start_before = -1, heads_slab = 0, valid_slab = 0, start_slab = -1;
+#pragma unroll
+        for (int w = 0; w < kDdWaves; ++w) {
+            const int x = s_w[w];
+            if (w < wave) {
+                heads_before += x & 0xFFFF;
+                start_before = max(start_before, s_w2[w]);
+            }
+            heads_slab += x & 0xFFFF;
+            valid_slab += x >> 16;
+            start_slab = max(start_slab, s_w2[w]);
+        }
+        if (i < n) {
+            seg_idx[i] = valid ? carry_heads + heads_before + h - 1 : -1;
+            seg_start[i] = max(max(carry_start, start_before), st);
+            if (head) head_of[carry_heads + heads_before + h - 1] = i;
+        }
+        carry_heads += heads_slab;
+        carry_start = max(carry_start, start_slab);
+        n_valid += valid_slab;
+    }
+    const int n_uniq = carry_heads;
+    if (tid == 0) head_of[n_uniq] = n_valid; // end of the last segment
+    __syncthreads();
+
+    // ---- 3. chunk heads and singles, the table-local lists
+    int carry_single = 0, carry_chunk = 0;
+    for (int s0 = 0; s0 < n; s0 += kDdThreads) {
+        const int i = s0 + tid;
+        int seg = -1, start = 0, p = 0, end = 0;
+        unsigned key = 0;
+        if (i < n) {
+            seg = seg_idx[i];
+            start = seg_start[i];
+            p = ws.merged_pos[base + i];
+            key = ws.merged_key[base + i];
+        }
+        const bool valid = seg >= 0;
+        if (valid) end = head_of[seg + 1];
+        const bool chead = valid && ((i - start) % DQRM_SEG_CHUNK) == 0;
+        const bool single = chead && i == start && end == i + 1;
+        int b = 0;
+        if (i < n) {
+            bt.sorted_pos[base + i] = base + p;
+            if (valid) {
+                b = ws.bag_of_pos[base + p];
+                b = b < 0 ? 0 : (b >= B ? B - 1 : b);
+                ws.sorted_bag[base + i] = b;
+            }
+        }
+        int tot_single, tot_chunk;
+        const int ex_single = block_excl_scan_add<kDdWaves>(single ? 1 : 0, lane, wave, s_w, &tot_single);
+        const int ex_chunk = block_excl_scan_add<kDdWaves>(chead && !single ? 1 : 0, lane, wave, s_w, &tot_chunk);
+        if (chead && !single) {
+            const int nchunks = (end - start + DQRM_SEG_CHUNK - 1) / DQRM_SEG_CHUNK;
+            ws.chunk_local[base + carry_chunk + ex_chunk] = make_chunk_desc(
+                base + i, min(DQRM_SEG_CHUNK, end - i), (i - start) / DQRM_SEG_CHUNK, nchunks, seg, key);
+            if (i == start && nchunks > 1) ws.seg_count[(base + i) / DQRM_SEG_CHUNK] = 0;
+        }
+        if (single) ws.single_local[base + carry_single + ex_single] = make_int4(base + i, b, seg, (int)key);
+        carry_single += tot_single;
+        carry_chunk += tot_chunk;
+    }
+    if (tid == 0) {
+        ws.table_base[t] = base;
+        ws.table_nuniq[t] = n_uniq;
+        ws.table_nchunk[t] = carry_chunk;
+        ws.table_nsingle[t] = carry_single;
     }
     if (tid < kAbsmaxSlots) *absmax_slot(ws.absmax_slots, t, tid) = 0.0f;
 }

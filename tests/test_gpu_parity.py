@@ -82,6 +82,19 @@ def test_pooling_factor(oracle, L):
     full_step_parity(oracle, wl, wl.tables(threads=1), idx, off, wl.grad_normal(0), what=f"pool{L}")
 
 
+@pytest.mark.parametrize("B,L", [(8192, 8), (2500, 7)])
+def test_large_tables(oracle, B, L):
+    """More lookups per table than one workgroup sorts in LDS (16384): pooling factor 8 at batch 8192 = 65536
+    lookups in every table (four full tiles), and 17500 (one full tile and a short one).  Tiny tables (every row
+    hot: segments of thousands of lookups across tile borders) next to large ones (mostly singles)."""
+    cards = np.array([7, 50000, 2000000, 33], np.int64)
+    wl = Workload(name=f"large{B}x{L}", T=4, D=64, B=B, alpha=1.1, seed=500 + L, cards=cards)
+    idx, off = wl.batch(0, pooling="fixed", max_len=L)
+    assert len(idx) == 4 * B * L
+    _say(f"large tables: {B * L} lookups per table")
+    full_step_parity(oracle, wl, wl.tables(threads=1), idx, off, wl.grad_normal(0), what=f"large{B}x{L}")
+
+
 def test_hot_segments_long_chunks(oracle):
     """tiny tables: segments of several hundred to several thousand lookups (many chunks per segment,
     the last-arrival combine), next to a table with no duplicates at all."""
@@ -99,8 +112,9 @@ def test_hot_segments_long_chunks(oracle):
 
 
 def test_max_table_lookups(oracle):
-    """a table that receives exactly the maximum number of lookups the dedupe kernel holds (16384),
-    with bags of two, next to an empty table (no lookups) and a small one."""
+    """a table that receives exactly the maximum number of lookups a batch may bring to one table (65536: four
+    tiles of the in-LDS sort, merged by the large-table path), with bags of two, next to an empty table (no
+    lookups) and a small one."""
     import paper_2410_20046_amd as dq
 
     B = dq.MAX_TABLE_LOOKUPS // 2

@@ -296,7 +296,7 @@ int32_t dqrm_pack_int4(const dqrm_tables_t *tables, void *stream)
     const int T = tables->num_tables, D = tables->dim;
     const int64_t g8 = R * (D / 8);
     if (g8 > 0) {
-        hipLaunchKernelGGL(dqrm::pack_int4_kernel, dim3(grid_for(g8, dqrm::kEwThreads * 2, 16)), dim3(dqrm::kEwThreads),
+        hipLaunchKernelGGL(dqrm::pack_int4_kernel, dim3(grid_for(g8, dqrm::kEwThreads * dqrm::kPackPerThread, 8)), dim3(dqrm::kEwThreads),
                            0, st, tables->master, tables->row_offsets_dev, tables->w_scale, T, D, tables->packed);
     }
     DQRM_HIP_CHECK(hipGetLastError());

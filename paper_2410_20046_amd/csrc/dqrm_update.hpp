@@ -302,6 +302,10 @@ __global__ void finalize_scale_kernel(float *w_scale, int T)
 }
 
 // ---- S1: encode every row of the master table into the packed mirror ------------
+// A thread takes kPackPerThread groups of 8 elements (32 bytes in, 4 bytes out each) per round, all requested
+// before the first is encoded; consecutive threads take consecutive groups.
+constexpr int kPackPerThread = 4;
+
 __global__ __launch_bounds__(kEwThreads) void pack_int4_kernel(const float *__restrict__ master,
                                                                const int64_t *__restrict__ row_offsets,
                                                                const float *__restrict__ w_scale, int T, int D,
@@ -319,17 +323,32 @@ __global__ __launch_bounds__(kEwThreads) void pack_int4_kernel(const float *__re
     int cur_t = -1;
     int64_t cur_end = -1;
     Scale ws(1.0f);
-    for (int64_t e = (int64_t)blockIdx.x * kEwThreads + threadIdx.x; e < total; e += (int64_t)gridDim.x * kEwThreads) {
-        if (e >= cur_end) {
-            cur_t = table_of(s_ro, T, e / q8);
-            cur_end = s_ro[cur_t + 1] * q8;
-            ws = s_ws[cur_t];
+    const int64_t stride = (int64_t)gridDim.x * kEwThreads;
+    for (int64_t e0 = (int64_t)blockIdx.x * kEwThreads + threadIdx.x; e0 < total; e0 += stride * kPackPerThread) {
+        typedef float f32x4 __attribute__((ext_vector_type(4)));
+        f32x4 lo4[kPackPerThread], hi4[kPackPerThread];
+#pragma unroll
+        for (int k = 0; k < kPackPerThread; ++k) {
+            const int64_t e = e0 + k * stride;
+            if (e < total) {
+                lo4[k] = __builtin_nontemporal_load(reinterpret_cast<const f32x4 *>(master) + 2 * e);
+                hi4[k] = __builtin_nontemporal_load(reinterpret_cast<const f32x4 *>(master) + 2 * e + 1);
+            }
         }
-        const float4 a = reinterpret_cast<const float4 *>(master)[2 * e];
-        const float4 b = reinterpret_cast<const float4 *>(master)[2 * e + 1];
-        const unsigned lo = pack4(int4_code(a.x, ws), int4_code(a.y, ws), int4_code(a.z, ws), int4_code(a.w, ws));
-        const unsigned hi = pack4(int4_code(b.x, ws), int4_code(b.y, ws), int4_code(b.z, ws), int4_code(b.w, ws));
-        reinterpret_cast<unsigned *>(packed)[e] = lo | (hi << 16);
+#pragma unroll
+        for (int k = 0; k < kPackPerThread; ++k) {
+            const int64_t e = e0 + k * stride;
+            if (e >= total) break;
+            if (e >= cur_end) {
+                cur_t = table_of(s_ro, T, e / q8);
+                cur_end = s_ro[cur_t + 1] * q8;
+                ws = s_ws[cur_t];
+            }
+            const f32x4 a = lo4[k], b = hi4[k];
+            const unsigned lo = pack4(int4_code(a[0], ws), int4_code(a[1], ws), int4_code(a[2], ws), int4_code(a[3], ws));
+            const unsigned hi = pack4(int4_code(b[0], ws), int4_code(b[1], ws), int4_code(b[2], ws), int4_code(b[3], ws));
+            __builtin_nontemporal_store(lo | (hi << 16), reinterpret_cast<unsigned *>(packed) + e);
+        }
     }
 }
 

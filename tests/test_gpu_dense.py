@@ -27,7 +27,7 @@ def _gpu_dense_step(dq, torch, T, D, B, model_np, x, emb, y, lr, dev):
 
 
 @pytest.mark.parametrize("cfg,T,D,B", [("small", 3, 16, 37), ("small8", 5, 8, 200), ("medium", 5, 24, 333),
-                                          ("medium", 5, 24, 1000), ("kaggle", 26, 16, 256)])
+                                          ("medium", 5, 24, 1000), ("kaggle", 26, 16, 256), ("kaggle", 26, 16, 2048)])
 def test_dense_step_matches_oracle(oracle, cfg, T, D, B):
     import torch
     import paper_2410_20046_amd as dq
@@ -51,8 +51,10 @@ def test_dense_step_matches_oracle(oracle, cfg, T, D, B):
     assert np.abs(m.top_w[0].cpu().numpy() - tw[0]).max() > 0
 
 
-def test_full_train_step_kaggle_shape(oracle):
-    """The full DQRM train step at the Kaggle shape with a reduced table size: INT4 forward ->
+@pytest.mark.parametrize("shrink", [2000, 1])
+def test_full_train_step_kaggle_shape(oracle, shrink):
+    """The full DQRM train step at the Kaggle shape, with the tables at 1/2000 of the rows and at full size
+    (33.77 M rows, 2.16 GB): INT4 forward ->
     dense step -> sparse INT8 backward -> update.  The dense outputs are compared with the float64 oracle fed
     with the oracle's own INT4 forward; the embedding backward is checked stage-isolated: the oracle's B1-B5
     take the GPU's grad_emb bytes, so codes, indices and updated rows must agree bit for bit."""
@@ -60,10 +62,10 @@ def test_full_train_step_kaggle_shape(oracle):
     import paper_2410_20046_amd as dq
 
     T, D, B = 26, 16, 2048
-    cards = np.maximum(3, (make_workload("kaggle").cards // 2000)).astype(np.int64)  # same spread, 1/2000 the rows
-    wl = Workload(name="kaggle-small", T=T, D=D, B=B, alpha=1.05, seed=1005, cards=cards)
+    cards = np.maximum(3, (make_workload("kaggle").cards // shrink)).astype(np.int64)  # same spread of table sizes
+    wl = Workload(name=f"kaggle/{shrink}", T=T, D=D, B=B, alpha=1.05, seed=1005, cards=cards)
     _say(f"full train step: R={wl.R}")
-    W = wl.tables(threads=1)
+    W = wl.tables(threads=8)
     idx, off = wl.batch(0)
     model_np = make_dense_model("kaggle", T, D, seed=1005)
     bot_dims, bw, bb, top_dims, tw, tb = model_np

@@ -743,6 +743,15 @@ __device__ __forceinline__ float4 f4_add(float4 a, float4 b)
     return make_float4(a.x + b.x, a.y + b.y, a.z + b.z, a.w + b.w);
 }
 
+// 16 bytes that this kernel reads exactly once (a gradient row is added into one segment only): a streaming
+// load, so that they do not push the lists and sums that are read again out of the caches
+__device__ __forceinline__ float4 load_once_f4(const float *p)
+{
+    typedef float f32x4 __attribute__((ext_vector_type(4)));
+    const f32x4 v = __builtin_nontemporal_load(reinterpret_cast<const f32x4 *>(p));
+    return make_float4(v[0], v[1], v[2], v[3]);
+}
+
 __device__ __forceinline__ float f4_absmax(float4 a)
 {
     return fmaxf(fmaxf(fabsf(a.x), fabsf(a.y)), fmaxf(fabsf(a.z), fabsf(a.w)));
@@ -817,7 +826,7 @@ __device__ __forceinline__ float4 sum_chunk(const int (&my_bags)[kChunkIdsPerLan
                         const int i = i0 + q;
                         int b = __shfl(my_bags[i / G], leader + (i % G), kWave); // the group passes the bags round
                         b = i < len ? b : 0;
-                        g[q] = *reinterpret_cast<const float4 *>(g0 + (uint64_t)(unsigned)b * tD);
+                        g[q] = load_once_f4(g0 + (uint64_t)(unsigned)b * tD);
                     }
                 } else {
 #pragma unroll
@@ -935,8 +944,7 @@ __global__ __launch_bounds__(kSumThreads, 4) void segment_sum_kernel(SegArgs a)
 #pragma unroll
         for (int k = 0; k < kSinglesPerGroup; ++k) {
             cur[k] = s0 + k < S ? sd[k] : make_int4(0, 0, 0, 0);
-            r[k] = *reinterpret_cast<const float4 *>(grad_col + (uint64_t)(unsigned)cur[k].x * tD +
-                                                     (unsigned)cur[k].z * (unsigned)D);
+            r[k] = load_once_f4(grad_col + (uint64_t)(unsigned)cur[k].x * tD + (unsigned)cur[k].z * (unsigned)D);
         }
         const int s_next = s0 + ngroups * kSinglesPerGroup;
 #pragma unroll

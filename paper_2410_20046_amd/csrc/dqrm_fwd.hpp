@@ -105,8 +105,8 @@ __device__ __forceinline__ void fwd_single_lookup_tile(const char *tab, const in
                 const float m = s_mul[i];
                 const float4 q = piece[k].codes(s_scale[i]);
                 const f32x4 v = {0.f + m * q.x, 0.f + m * q.y, 0.f + m * q.z, 0.f + m * q.w};
-                // `out` is written once and not read again by this library: stream it past the caches
-                __builtin_nontemporal_store(v, reinterpret_cast<f32x4 *>(out_col + (size_t)(unsigned)s_slot[i] * D));
+                // (plain stores: the consumer of `out`, the dense part of the model, runs next and finds it in the caches)
+                *reinterpret_cast<f32x4 *>(out_col + (size_t)(unsigned)s_slot[i] * D) = v;
             }
         }
     }

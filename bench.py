@@ -68,6 +68,7 @@ class HotPath:
 
     def __init__(self, wl, W, pool, grads, dev, mode="packed", overlap="ahead", ahead=8, fused=True, lr=0.1,
                  dense_args=None, refresh_period=0):
+        import numpy as np
         import torch
         import paper_2410_20046_amd as dq
 
@@ -80,6 +81,8 @@ class HotPath:
         self.tables = dq.Tables(wl.row_offsets, wl.D, self.master, self.packed)
         self.pool = len(pool)
         self.N = len(pool[0][0])
+        # a bound the data loader knows: bags per table x the longest bag of any batch in the pool
+        self.max_table_lookups = int(self.B * max(int(np.diff(o).max()) for _, o in pool))
         self.idx_d = [torch.from_numpy(i).to(dev) for i, _ in pool]
         self.off_d = [torch.from_numpy(o).to(dev) for _, o in pool]
         self.grad_d = [torch.from_numpy(g).to(dev) for g in grads]
@@ -165,7 +168,7 @@ class HotPath:
         n = self.nbuf
         self.dq.dqrm_dedupe_multi(self.tables, self.B, [self.batch_of(j) + (self.sps[j % n], self.urs[j % n], self.sos[j % n],
                                                                            self.tuos[j % n], self.nus[j % n], self.wss[j % n])
-                                                       for j in ks])
+                                                       for j in ks], max_table_lookups=self.max_table_lookups)
         self._mark("dedupe_multi")
 
     def rest_of_step(self, k, i):
@@ -449,22 +452,34 @@ def main():
         while G < D // 4:
             G *= 2
         # which kernel(s) a call launches, and the algorithmic bytes of one launch
+        dd = "dedupe_kernel + " + ("dedupe_large_kernel + " if N > 16384 and (args.overlap != "ahead" or hp.max_table_lookups > 16384) else "") + "dedupe_finish_kernel"
         call_kernels = {
             "fwd": (f"embbag_fwd_kernel<{G},{'packed' if packed_fwd else 'master'}>", ab["fwd"]),
             "segment_sum": (f"segment_sum_kernel<{G}>" + ("" if args.fused else " + absmax_finalize_kernel"), ab["segsum"]),
             "quant_update": ("quant_update_kernel", ab["quant"] + ab["update"] - D * U),
             "quant": ("grad_quant_kernel", ab["quant"]),
             "update": ("sparse_update_kernel", ab["update"]),
-            "dedupe": ("dedupe_kernel + dedupe_finish_kernel", ab["dedupe"]),
-            "dedupe_multi": ("dedupe_kernel + dedupe_finish_kernel", ab["dedupe"] * max(args.ahead, 1)),
+            "dedupe": (dd, ab["dedupe"]),
+            "dedupe_multi": (dd, ab["dedupe"] * max(args.ahead, 1)),
         }
-        for name, us_call in call_us.items():
+        # The events between the calls take the dispatch gap that precedes every kernel out of the intervals (their own
+        # cost, measured on adjacent events, is subtracted): the calls' times add up to less than the step.  A kernel
+        # trace counts that gap as part of the kernel.  So does the roofline here: the step's time beyond the sum of
+        # the calls, shared equally among the step's launches, is added to every launch.
+        launches = lambda name: call_kernels[name][0].count("+") + 1
+        gap_us = 0.0
+        if all(k in call_kernels for k in call_us) and args.refresh_period == 0:
+            per_step_launches = sum(launches(k) * call_n[k] / n_probe for k in call_us)
+            gap_us = max(0.0, (ms_per_step * 1e3 - sum(per_step.values())) / per_step_launches)
+        for name, us_events in call_us.items():
             if name not in call_kernels:
                 continue
             kname, nbytes = call_kernels[name]
+            us_call = us_events + gap_us * launches(name)
             gbs = nbytes / (us_call * 1e-6) / 1e9 if us_call > 0 else 0.0
             kernels.append({"call": name, "kernel": kname, "algorithmic_bytes_per_launch": int(nbytes),
-                            "avg_launch_us": round(us_call, 2), "us_per_step": round(per_step[name], 2),
+                            "avg_launch_us": round(us_call, 2), "between_events_us": round(us_events, 2),
+                            "us_per_step": round(us_call * call_n[name] / n_probe, 2),
                             "achieved_gbs": round(gbs, 1), "frac_of_peak": round(gbs / HBM_PEAK_GBS, 4)})
         # the dominant kernel: the single-kernel call with the largest share of the step
         single = [k for k in kernels if "+" not in k["kernel"]]
@@ -472,9 +487,13 @@ def main():
         roofline = {"bound": "hbm", "kernel": dom["kernel"], "achieved": dom["achieved_gbs"], "peak": HBM_PEAK_GBS,
                     "unit": "GB/s", "frac": dom["frac_of_peak"], "traffic": read_traffic(dom["kernel"].split("<")[0]),
                     "algorithmic_bytes_per_launch": dom["algorithmic_bytes_per_launch"],
-                    "avg_launch_us": dom["avg_launch_us"],
+                    "avg_launch_us": dom["avg_launch_us"], "dispatch_gap_us": round(gap_us, 2),
                     "share_of_step": round(dom["us_per_step"] / sum(k["us_per_step"] for k in kernels), 4),
-                    "how": "HIP events on the launch stream between consecutive calls of the step sequence"}
+                    "how": "HIP events on the launch stream between consecutive calls of the step sequence, plus the "
+                           "dispatch gap per launch (step time beyond the sum of the calls / launches per step), "
+                           "which a kernel trace counts inside the kernel"}
+        log(f"[bench] dispatch gap {gap_us:.2f} us per launch; dominant kernel {dom['kernel']}: {dom['avg_launch_us']:.2f} us, "
+            f"{dom['achieved_gbs']:.0f} GB/s = {dom['frac_of_peak']:.3f} of peak")
 
     # ---- the master-mode forward beside the packed headline: a short run of the same steps ----
     master_leg = None

@@ -188,7 +188,16 @@ int32_t dqrm_segment_sum(const dqrm_tables_t *tables, int32_t batch, int64_t num
  * needs them) fill the chip instead.  `batches` is a HOST array; each element
  * holds the arguments dqrm_dedupe takes for one batch (its own outputs and its
  * own workspace of at least `workspace_bytes` bytes, sized for the largest
- * num_indices).  All batches have `batch` bags per table. */
+ * num_indices).  All batches have `batch` bags per table.
+ * max_table_lookups: the lookups one table has in a batch are device data (the
+ * offsets), so a batch of more than 16384 lookups costs a launch of the pass
+ * that serves tables of more than 16384 lookups even when no table is that
+ * large.  A caller who knows a bound on the lookups of any one table in this
+ * batch (bags per table x the longest bag) states it here and is spared that
+ * launch when the bound is at most 16384; 0 = no bound known (what dqrm_dedupe
+ * and dqrm_embbag_bwd pass).  A table with more lookups than a stated bound is
+ * treated like one beyond DQRM_MAX_TABLE_LOOKUPS: skipped, DQRM_ERR_CAPACITY in
+ * dqrm_check_status. */
 typedef struct {
     const int64_t *indices;
     const int64_t *offsets;
@@ -199,6 +208,7 @@ typedef struct {
     int32_t *table_uniq_offsets;
     int32_t *num_unique;
     void *workspace;
+    int32_t max_table_lookups;
 } dqrm_dedupe_batch_t;
 int32_t dqrm_dedupe_multi(const dqrm_tables_t *tables, int32_t batch, int32_t num_batches,
                           const dqrm_dedupe_batch_t *batches, size_t workspace_bytes, void *stream);

@@ -61,7 +61,8 @@ class dqrm_sparse_block_t(C.Structure):
 class dqrm_dedupe_batch_t(C.Structure):
     _fields_ = [("indices", C.c_void_p), ("offsets", C.c_void_p), ("num_indices", C.c_int64),
                 ("sorted_pos", C.c_void_p), ("uniq_rows", C.c_void_p), ("seg_offsets", C.c_void_p),
-                ("table_uniq_offsets", C.c_void_p), ("num_unique", C.c_void_p), ("workspace", C.c_void_p)]
+                ("table_uniq_offsets", C.c_void_p), ("num_unique", C.c_void_p), ("workspace", C.c_void_p),
+                ("max_table_lookups", C.c_int32)]
 
 
 MAX_DEDUPE_BATCHES = 8
@@ -230,14 +231,15 @@ def dqrm_dedupe(tables: Tables, indices: torch.Tensor, offsets: torch.Tensor, ba
            "dqrm_dedupe")
 
 
-def dqrm_dedupe_multi(tables: Tables, batch: int, batches, stream=None) -> None:
+def dqrm_dedupe_multi(tables: Tables, batch: int, batches, stream=None, max_table_lookups: int = 0) -> None:
     """``batches``: sequence of tuples (indices, offsets, sorted_pos, uniq_rows, seg_offsets, table_uniq_offsets,
-    num_unique, workspace) of device tensors, one per batch (at most MAX_DEDUPE_BATCHES)."""
+    num_unique, workspace) of device tensors, one per batch (at most MAX_DEDUPE_BATCHES).  ``max_table_lookups``:
+    the caller's bound on the lookups of any one table in any of the batches, 0 if none is known."""
     arr = (dqrm_dedupe_batch_t * len(batches))()
     ws_bytes = None
     for i, (ix, of, sp, ur, so, tuo, nu, ws) in enumerate(batches):
         arr[i] = dqrm_dedupe_batch_t(_ptr(ix), _ptr(of), ix.numel(), _ptr(sp), _ptr(ur), _ptr(so), _ptr(tuo), _ptr(nu),
-                                     _ptr(ws))
+                                     _ptr(ws), max_table_lookups)
         nb = ws.numel() * ws.element_size()
         ws_bytes = nb if ws_bytes is None else min(ws_bytes, nb)
     _check(lib().dqrm_dedupe_multi(tables.ref, batch, len(batches), arr, ws_bytes or 0, _stream(stream)),

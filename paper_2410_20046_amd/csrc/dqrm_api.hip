@@ -367,17 +367,22 @@ int32_t dqrm_dedupe_multi(const dqrm_tables_t *tables, int32_t batch, int32_t nu
         if (!b.sorted_pos || !b.uniq_rows || !b.seg_offsets || !b.table_uniq_offsets || !b.num_unique || !b.workspace ||
             !aligned(b.workspace, 256))
             return DQRM_ERR_INVALID_ARG;
+        if (b.max_table_lookups < 0) return DQRM_ERR_INVALID_ARG;
         if (workspace_bytes < ws_layout(T, D, b.num_indices).total) return DQRM_ERR_WORKSPACE_TOO_SMALL;
         if (b.num_indices > max_n) max_n = b.num_indices;
     }
     dqrm::DedupeArgs da;
     std::memset(&da, 0, sizeof(da));
+    int64_t largest = 0; // no table of any batch has more lookups than this
     for (int i = 0; i < num_batches; ++i) {
         const dqrm_dedupe_batch_t &b = batches[i];
         dqrm::DedupeBatch &o = da.b[i];
         o.indices = b.indices;
         o.offsets = b.offsets;
         o.N = b.num_indices;
+        o.limit = b.max_table_lookups > 0 ? std::min<int32_t>(b.max_table_lookups, DQRM_MAX_TABLE_LOOKUPS)
+                                          : DQRM_MAX_TABLE_LOOKUPS;
+        largest = std::max<int64_t>(largest, std::min<int64_t>(b.num_indices, o.limit));
         o.ws = ws_views(b.workspace, ws_layout(T, D, b.num_indices));
         o.sorted_pos = b.sorted_pos;
         o.tuo = b.table_uniq_offsets;
@@ -390,7 +395,6 @@ int32_t dqrm_dedupe_multi(const dqrm_tables_t *tables, int32_t batch, int32_t nu
     da.B = batch;
     hipStream_t st = static_cast<hipStream_t>(stream);
     // a table of more than kDdCap lookups is sorted in tiles (grid z), which dedupe_large_kernel merges
-    const int64_t largest = std::min<int64_t>(max_n, DQRM_MAX_TABLE_LOOKUPS);
     const int tiles = (int)std::max<int64_t>(1, (largest + dqrm::kDdCap - 1) / dqrm::kDdCap);
     hipLaunchKernelGGL(dqrm::dedupe_kernel, dim3(T, num_batches, tiles), dim3(dqrm::kDdThreads), 0, st, da);
     if (tiles > 1)
@@ -416,6 +420,7 @@ int32_t dqrm_dedupe(const dqrm_tables_t *tables, const int64_t *indices, const i
     b.table_uniq_offsets = table_uniq_offsets;
     b.num_unique = num_unique;
     b.workspace = workspace;
+    b.max_table_lookups = 0;
     return dqrm_dedupe_multi(tables, batch, 1, &b, workspace_bytes, stream);
 }
 

@@ -86,6 +86,7 @@ struct DedupeBatch {
     const int64_t *indices;
     const int64_t *offsets;
     int64_t N;
+    int limit; // lookups a table may have: DQRM_MAX_TABLE_LOOKUPS or the caller's smaller bound
     BwdWs ws;
     int32_t *sorted_pos;
     int32_t *tuo;
@@ -134,7 +135,7 @@ __global__ __launch_bounds__(kDdThreads) void dedupe_kernel(DedupeArgs args)
         if (tid == 0 && blockIdx.z == 0) report(DQRM_ERR_BAD_OFFSETS, t, lo);
         lo = lo < 0 ? 0 : (lo > N ? N : lo);
         disabled = true;
-    } else if (hi - lo > DQRM_MAX_TABLE_LOOKUPS) {
+    } else if (hi - lo > bt.limit) {
         if (tid == 0 && blockIdx.z == 0) report(DQRM_ERR_CAPACITY, t, hi - lo);
         disabled = true;
     }
@@ -463,7 +464,7 @@ __global__ __launch_bounds__(kDdThreads) void dedupe_large_kernel(DedupeArgs arg
     const unsigned rows_t = (unsigned)rows_ll;
     const long long lo = offsets[(long long)t * B], hi = offsets[(long long)(t + 1) * B];
     // (unusable extents and tables beyond the limit were reported and closed by dedupe_kernel)
-    if (lo < 0 || hi > N || lo > hi || hi - lo > DQRM_MAX_TABLE_LOOKUPS || hi - lo <= kDdCap) return;
+    if (lo < 0 || hi > N || lo > hi || hi - lo > bt.limit || hi - lo <= kDdCap) return;
     const int n = (int)(hi - lo), base = (int)lo;
     const int runs = (n + kDdCap - 1) / kDdCap;
 

@@ -114,6 +114,21 @@ def test_validation_errors_before_any_launch():
     assert L.dqrm_embbag_bwd_noalloc(None, FAKE, FAKE, 4, 8, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, S) == dq.ERR_INVALID_ARG
     assert bwd_na(N=-1) == dq.ERR_INVALID_ARG
     assert bwd_na(tb=_tables(D=20)) == dq.ERR_UNSUPPORTED
+    # several batches in one dedupe launch
+    from paper_2410_20046_amd.binding import dqrm_dedupe_batch_t
+
+    def dd(n=2, bound=0, sp=FAKE, ws=FAKE, ws_bytes=1 << 30, arr="ok"):
+        a = (dqrm_dedupe_batch_t * 8)()
+        for k in range(8):
+            a[k] = dqrm_dedupe_batch_t(FAKE, FAKE, 8, sp, FAKE, FAKE, FAKE, FAKE, ws, bound)
+        return L.dqrm_dedupe_multi(r(ok), 4, n, a if arr == "ok" else None, ws_bytes, S)
+    assert dd(arr=None) == dq.ERR_INVALID_ARG
+    assert dd(n=0) == dq.ERR_INVALID_ARG
+    assert dd(n=dq.MAX_DEDUPE_BATCHES + 1) == dq.ERR_UNSUPPORTED
+    assert dd(sp=None) == dq.ERR_INVALID_ARG
+    assert dd(ws=FAKE + 64) == dq.ERR_INVALID_ARG
+    assert dd(bound=-1) == dq.ERR_INVALID_ARG
+    assert dd(ws_bytes=16) == dq.ERR_WORKSPACE_TOO_SMALL
     # quantise / update
     gq = lambda T=2, D=16, cap=8, v=FAKE, tuo=FAKE, am=FAKE, q=FAKE, gs=FAKE: L.dqrm_grad_quant_int8(
         T, D, cap, v, tuo, am, q, gs, S)

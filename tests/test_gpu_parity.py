@@ -275,6 +275,39 @@ def test_dedupe_multi_equals_single(oracle):
     assert runs[0][0].status()[0] == 0
 
 
+def test_dedupe_with_a_promised_bound_on_table_lookups(oracle):
+    """A caller's bound on the lookups of one table (dqrm_dedupe_batch_t.max_table_lookups): with a true bound the
+    results are the oracle's; a table beyond a stated bound is skipped and reported like one beyond the limit."""
+    import paper_2410_20046_amd as dq
+
+    cards = np.array([7, 3000, 400000], np.int64)
+    wl = Workload(name="bound", T=3, D=32, B=8192, alpha=1.05, seed=77, cards=cards)  # 24576 lookups, 8192 a table
+    W = np.zeros((wl.R, wl.D), np.float32)
+    idx, off = wl.batch(0)
+    g = wl.grad_normal(0)
+    o = oracle.embbag_bwd(wl.T, wl.D, wl.B, idx, off, g)
+    for bound, ok in ((wl.B, True), (dq.MAX_TABLE_LOOKUPS, True), (wl.B - 1, False)):
+        _say(f"promised bound {bound}")
+        r = GpuRun(wl.row_offsets, wl.D, W, wl.B, len(idx), with_packed=False, want_codes=False)
+        r.upload_batch(idx, off, g)
+        b = r.bufs
+        dq.dqrm_dedupe_multi(r.tables, wl.B, [(r.idx, r.off, b.sorted_pos, b.uniq_rows, b.seg_offsets,
+                                               b.table_uniq_offsets, b.num_unique, b.workspace)], max_table_lookups=bound)
+        dq.dqrm_segment_sum(r.tables, wl.B, len(idx), r.grad, b.values, b.g_absmax, b.workspace)
+        code, tb, val = r.status()
+        U = int(b.num_unique.cpu().item())
+        if not ok:
+            assert code == dq.ERR_CAPACITY and val == wl.B and U == 0
+            continue
+        assert code == 0
+        got = dict(U=U, sorted_pos=b.sorted_pos.cpu().numpy()[:len(idx)], uniq_rows=b.uniq_rows.cpu().numpy()[:U],
+                   seg_offsets=b.seg_offsets.cpu().numpy()[:U + 1],
+                   table_uniq_offsets=b.table_uniq_offsets.cpu().numpy(), values=b.values.cpu().numpy()[:U],
+                   g_absmax=b.g_absmax.cpu().numpy())
+        compare_bwd(got, o, f"bound {bound}")
+        assert_exact(got["values"].view(np.uint32), o["values"].view(np.uint32), f"bound {bound} values bits")
+
+
 def test_fused_quant_update_matches_two_call_path(oracle):
     """dqrm_segment_sum(g_absmax=NULL) + dqrm_quant_update == segment_sum + grad_quant_int8 + sparse_update
     == the oracle, bit for bit (codes, scales, absmax, master, packed)."""

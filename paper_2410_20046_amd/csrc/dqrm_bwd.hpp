@@ -889,6 +889,31 @@ __device__ __forceinline__ float combine_column(const BwdWs &ws, int head_pos, i
     return acc;
 }
 
+// The same for rows narrower than a wave: the wave's lanes are split among several segments, so `head_pos` and
+// `nchunks` differ from lane to lane (nchunks = 0: a lane without a column to add).  All lanes go through the
+// motions up to `wave_n`, the largest nchunks in the wave; a lane past its own last chunk asks for that chunk again.
+__device__ __forceinline__ float combine_column_shared_wave(const BwdWs &ws, int head_pos, int nchunks, int wave_n, int D,
+                                                            int col)
+{
+    float acc = 0.f;
+    for (int k0 = 0; k0 < wave_n; k0 += kCombineBatch) {
+        float pv[kCombineBatch];
+#pragma unroll
+        for (int q = 0; q < kCombineBatch; ++q) {
+            pv[q] = 0.f;
+            if (k0 + q < wave_n) {
+                const float *p = nchunks > 0 ? partial_slot(ws, head_pos, min(k0 + q, nchunks - 1), nchunks, D) + col
+                                             : ws.partial_full;
+                pv[q] = __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            }
+        }
+#pragma unroll
+        for (int q = 0; q < kCombineBatch; ++q)
+            if (k0 + q < nchunks) acc = (k0 + q == 0) ? pv[q] : acc + pv[q];
+    }
+    return acc;
+}
+
 // Work of one workgroup of kSumThreads / G lane groups:
 //  * singles (rows looked up once: a plain copy of one gradient row), a few per
 //    group, spread evenly over all groups of the grid;
@@ -924,7 +949,14 @@ __global__ __launch_bounds__(kSumThreads, 4) void segment_sum_kernel(SegArgs a)
     const int gi = (int)blockIdx.x * kGroups + grp;
 
     // ---- requests that need no count: the first chunk's descriptor and bag list, the first singles
+    // Wide rows: consecutive chunks for the groups of a wave (they are alike in length, so few lanes idle).  Narrow
+    // rows (many groups per wave): the wave's groups take chunks a whole grid's waves apart, or the chunks of a small
+    // table's rows would all complete their segments in one wave, which adds them up a few per round trip.
     int c = gi;
+    if constexpr (G < 16) {
+        constexpr int kWavesPerBlock = kSumThreads / kWave, kGroupsPerWave = kWave / G;
+        c = ((int)blockIdx.x * kWavesPerBlock + (int)threadIdx.x / kWave) + (grp % kGroupsPerWave) * ((int)gridDim.x * kWavesPerBlock);
+    }
     int4 d = make_int4(0, 0, 0, 0);
     int my_bags[kChunkIdsPerLane(G)] = {};
     if (c < cap_chunks) {
@@ -994,24 +1026,54 @@ __global__ __launch_bounds__(kSumThreads, 4) void segment_sum_kernel(SegArgs a)
                 before = __hip_atomic_fetch_add(a.ws.seg_count + head_pos / DQRM_SEG_CHUNK, 1, __ATOMIC_RELAXED,
                                                 __HIP_MEMORY_SCOPE_AGENT);
             asm volatile("" ::: "memory"); // (the loads below stay below)
-            // the groups whose chunk completed its segment's count: the wave takes their segments one by one
+            // the groups whose chunk completed its segment's count: the wave adds up their segments
             unsigned long long todo = __ballot(parks && lg == 0 && before == nchunks - 1);
-            while (todo != 0ull) {
-                const int src = __ffsll((long long)todo) - 1;
-                todo &= todo - 1ull;
-                const int s_head = __builtin_amdgcn_readlane(head_pos, src), s_n = __builtin_amdgcn_readlane(nchunks, src);
-                const int s_seg = __builtin_amdgcn_readlane(d.z, src), s_t = __builtin_amdgcn_readlane(d.w, src);
-                float m = 0.0f;
-                for (int cc = lane; cc < D; cc += kWave) {
-                    const float sum = combine_column(a.ws, s_head, s_n, D, cc);
-                    a.values[(int64_t)s_seg * D + cc] = sum;
-                    m = fmaxf(m, fabsf(sum));
+            if constexpr (G >= 16) { // a row fills the wave: a lane per column, the segments one by one
+                while (todo != 0ull) {
+                    const int src = __ffsll((long long)todo) - 1;
+                    todo &= todo - 1ull;
+                    const int s_head = __builtin_amdgcn_readlane(head_pos, src), s_n = __builtin_amdgcn_readlane(nchunks, src);
+                    const int s_seg = __builtin_amdgcn_readlane(d.z, src), s_t = __builtin_amdgcn_readlane(d.w, src);
+                    float m = 0.0f;
+                    for (int cc = lane; cc < D; cc += kWave) {
+                        const float sum = combine_column(a.ws, s_head, s_n, D, cc);
+                        a.values[(int64_t)s_seg * D + cc] = sum;
+                        m = fmaxf(m, fabsf(sum));
+                    }
+                    m = wave_max(m);
+                    if (lane == 0) {
+                        amax.add(s_t, m);
+                        // (ready for another run of the segment sums on the same dedupe)
+                        __hip_atomic_store(a.ws.seg_count + s_head / DQRM_SEG_CHUNK, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                    }
                 }
-                m = wave_max(m);
-                if (lane == 0) {
-                    amax.add(s_t, m);
-                    // (ready for another run of the segment sums on the same dedupe)
-                    __hip_atomic_store(a.ws.seg_count + s_head / DQRM_SEG_CHUNK, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            } else { // narrow rows: 4 G lanes per segment, 16 / G segments in one round trip
+                constexpr int kLanesPerSeg = 4 * G, kSegsPerPass = kWave / kLanesPerSeg;
+                const int slot = lane / kLanesPerSeg, cc = lane % kLanesPerSeg;
+                while (todo != 0ull) {
+                    int src = -1;
+#pragma unroll
+                    for (int j = 0; j < kSegsPerPass; ++j) {
+                        if (todo != 0ull) {
+                            if (slot == j) src = __ffsll((long long)todo) - 1;
+                            todo &= todo - 1ull;
+                        }
+                    }
+                    const int from = src < 0 ? 0 : src;
+                    const int s_head = __shfl(head_pos, from, kWave);
+                    const int n_from = __shfl(nchunks, from, kWave);
+                    const int s_n = src >= 0 && cc < D ? n_from : 0;
+                    const int s_seg = __shfl(d.z, from, kWave), s_t = __shfl(d.w, from, kWave);
+                    const int wave_n = __builtin_amdgcn_readfirstlane(wave_max_int(s_n));
+                    const float sum = combine_column_shared_wave(a.ws, s_head, s_n, wave_n, D, cc);
+                    if (s_n > 0) a.values[(int64_t)s_seg * D + cc] = sum;
+                    float m = s_n > 0 ? fabsf(sum) : 0.0f;
+#pragma unroll
+                    for (int o = kLanesPerSeg / 2; o >= 1; o >>= 1) m = fmaxf(m, __shfl_xor(m, o, kWave));
+                    if (src >= 0 && cc == 0) {
+                        amax.add(s_t, m);
+                        __hip_atomic_store(a.ws.seg_count + s_head / DQRM_SEG_CHUNK, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                    }
                 }
             }
         }

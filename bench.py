@@ -239,7 +239,7 @@ class HotPath:
     # ---- per-call times inside the step sequence -------------------------------------------------
     def time_calls_in_sequence(self, k0, n):
         """Runs n steps eagerly with one HIP event between consecutive calls, all recorded on the launch stream,
-        and returns ({call: mean microseconds between the events around it, corrected for the cost of an event
+        and returns ({call: median microseconds between the events around it, corrected for the cost of an event
         pair itself}, {call: times it ran}, that cost).  The GPU is kept busy with large copies while the host
         enqueues, so the steps then run back to back as in the timed region and no interval holds host time."""
         torch = self.torch
@@ -256,13 +256,14 @@ class HotPath:
         probe, self.probe = self.probe, None
         torch.cuda.synchronize()
         del a, b
-        sums, counts = {}, {}
+        spans = {}
         for (_, e0), (name, e1) in zip(probe[:-1], probe[1:]):
-            us = 1e3 * e0.elapsed_time(e1)
-            sums[name] = sums.get(name, 0.0) + us
-            counts[name] = counts.get(name, 0) + 1
-        base = sums.pop("cal") / counts.pop("cal")
-        return {k: max(sums[k] / counts[k] - base, 0.0) for k in sums}, dict(counts), base
+            spans.setdefault(name, []).append(1e3 * e0.elapsed_time(e1))
+        # medians: an interval in which the GPU waited for the host (a step with many launches can outrun the gating
+        # copies) is far out and must not count
+        med = lambda v: sorted(v)[len(v) // 2]
+        base = med(spans.pop("cal"))
+        return {k: max(med(v) - base, 0.0) for k, v in spans.items()}, {k: len(v) for k, v in spans.items()}, base
 
 
 def main():
@@ -352,6 +353,7 @@ def main():
         mb_idx = [[torch.from_numpy(i).to(dev) for i, _ in p] for p in parts]
         mb_off = [[torch.from_numpy(o).to(dev) for _, o in p] for p in parts]
         Nm = max(len(i) for p in parts for i, _ in p)
+        mb_bound = int(Bm * max(int(np.diff(o).max()) for p in parts for _, o in p))  # lookups of one table, at most
         mb = [dq.StepBuffers(T, D, Bm, Nm, dev, want_codes=False) for _ in range(nodes)]
         m_cap = nodes * Nm
         m_rows = torch.empty(m_cap, dtype=torch.int64, device=dev)
@@ -365,14 +367,16 @@ def main():
             p, g = k % args.pool, hp.grad_d[k % args.grad_pool]
             # the micro-batches' indices are all there: one sort launch for all of them (26 x nodes workgroups)
             dq.dqrm_dedupe_multi(tables, Bm, [(mb_idx[p][j], mb_off[p][j], b.sorted_pos, b.uniq_rows, b.seg_offsets,
-                                               b.table_uniq_offsets, b.num_unique, b.workspace) for j, b in enumerate(mb)])
+                                               b.table_uniq_offsets, b.num_unique, b.workspace) for j, b in enumerate(mb)],
+                                 max_table_lookups=mb_bound)
             # the weights do not change inside a group and bags are independent: the micro-batches' forwards are one
             # call on the whole batch
             dq.dqrm_embbag_fwd(tables, hp.idx_d[p], hp.off_d[p], B, hp.mode, bufs.out, None)
             for j in range(nodes):
                 b, ix = mb[j], mb_idx[p][j]
-                # (only the first micro-batch's maxima are used: its scale serves the whole group)
-                dq.dqrm_segment_sum(tables, Bm, ix.numel(), g[j * Bm:(j + 1) * Bm], b.values, b.g_absmax, b.workspace)
+                # only the first micro-batch's maxima are used (its scale serves the whole group): the others ask for none
+                dq.dqrm_segment_sum(tables, Bm, ix.numel(), g[j * Bm:(j + 1) * Bm], b.values, b.g_absmax if j == 0 else None,
+                                    b.workspace)
                 dq.dqrm_grad_quant_int8(T, D, b.cap, b.values, b.table_uniq_offsets, mb[0].g_absmax, b.gq, b.g_scale)
             dq.dqrm_sparse_merge(tables, [(b.uniq_rows, b.table_uniq_offsets, b.gq) for b in mb], m_rows, m_tuo, m_nu,
                                  m_sums, m_ws)

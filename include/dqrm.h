@@ -174,7 +174,8 @@ int32_t dqrm_embbag_bwd_noalloc(const dqrm_tables_t *tables, const int64_t *indi
  * segment sums in `workspace`.  dqrm_segment_sum then needs that workspace (the
  * caller orders the two, e.g. with an event) and grad_out, and writes `values`
  * and `g_absmax`; it may be repeated on the same dedupe result.  g_absmax may be
- * NULL if dqrm_quant_update follows (see there). */
+ * NULL if dqrm_quant_update follows (see there) or if the maxima are not wanted
+ * (the next dqrm_dedupe into the same workspace starts them afresh). */
 int32_t dqrm_dedupe(const dqrm_tables_t *tables, const int64_t *indices, const int64_t *offsets, int32_t batch,
                     int64_t num_indices, int32_t *sorted_pos, int64_t *uniq_rows, int32_t *seg_offsets,
                     int32_t *table_uniq_offsets, int32_t *num_unique, void *workspace, size_t workspace_bytes,

@@ -32,6 +32,8 @@ FWD_MASTER = 0
 FWD_PACKED = 1
 SEG_CHUNK = 32
 MAX_TABLE_LOOKUPS = 65536
+MAX_TABLES = 1024
+MAX_DIM = 256
 NOALLOC_SCRATCH_BYTES = 8 << 20
 
 EXPORTS = ("dqrm_find_scale", "dqrm_pack_int4", "dqrm_embbag_fwd", "dqrm_embbag_bwd_workspace_bytes",

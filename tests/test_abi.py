@@ -39,6 +39,8 @@ def test_header_constants_match_binding():
     defs = dict(re.findall(r"#define\s+(DQRM_[A-Z_0-9]+)\s+\(?(-?\d+)", text))
     assert int(defs["DQRM_SEG_CHUNK"]) == dq.SEG_CHUNK == 32
     assert int(defs["DQRM_MAX_TABLE_LOOKUPS"]) == dq.MAX_TABLE_LOOKUPS
+    assert int(defs["DQRM_MAX_TABLES"]) == dq.MAX_TABLES and int(defs["DQRM_MAX_DIM"]) == dq.MAX_DIM
+    assert int(defs["DQRM_MAX_DEDUPE_BATCHES"]) == dq.MAX_DEDUPE_BATCHES
     for n in ("INVALID_ARG", "UNSUPPORTED", "WORKSPACE_TOO_SMALL", "INDEX_OUT_OF_RANGE", "CAPACITY", "BAD_OFFSETS"):
         assert int(defs["DQRM_ERR_" + n]) == getattr(dq, "ERR_" + n)
     assert int(defs["DQRM_ERR_HIP"]) == dq.ERR_HIP

@@ -69,6 +69,21 @@ def test_dims_ragged_bags(oracle, D):
     full_step_parity(oracle, wl, W, idx, off, wl.grad_normal(1), stale=0.5, what=f"ragged D={D}")
 
 
+@pytest.mark.parametrize("T,D,B", [(100, 16, 48), (1024, 8, 16)])
+def test_many_tables(oracle, T, D, B):
+    """More tables than a forward tile holds (32), up to the limit of 1024: several table tiles per sample tile in the
+    forward, a sorting workgroup per table, per-table lists and maxima of the backward at their largest."""
+    import paper_2410_20046_amd as dq
+
+    assert T <= dq.MAX_TABLES
+    rng = np.random.default_rng(T)
+    cards = rng.integers(1, 400, size=T).astype(np.int64)
+    wl = Workload(name=f"tables{T}", T=T, D=D, B=B, alpha=1.05, seed=900 + T, cards=cards)
+    idx, off = wl.batch(0, pooling="ragged", max_len=3)
+    _say(f"{T} tables: {len(idx)} lookups")
+    full_step_parity(oracle, wl, wl.tables(threads=1), idx, off, wl.grad_normal(0), stale=0.7, what=f"tables{T}")
+
+
 @pytest.mark.parametrize("L", [20, 40])
 def test_pooling_factor(oracle, L):
     """Every bag holds L lookups.  A forward tile (16 samples x 8 tables) then has 2560 lookups (their row

@@ -904,15 +904,33 @@ int32_t dqrm_dense_step_quant(const dqrm_dense_model_t *m, const dqrm_dense_quan
     }
 
     // ---- forward
+    // The bottom MLP's last layer rides along in the interaction kernels when its input is short enough for their LDS
+    // (its product is tiny: 64 -> 16 in the paper's Kaggle model), and a first layer with a short reduction (the
+    // 13 dense features) has a kernel of its own: both are all launch cost as products on the matrix cores.
+    const int bl_last = m->bot_layers - 1;
+    const bool ride = m->bot_dims[bl_last] <= dqrm::kInterMaxLinK;
     const float *x = dense_x;
-    for (int l = 0; l < m->bot_layers; ++l) {
-        DQRM_HIP_CHECK(linear_fwd(st, x, bot_wf[l], m->bot_b[l], F(L.bot_act[l]), B, m->bot_dims[l], m->bot_dims[l + 1], true));
+    for (int l = 0; l < m->bot_layers - (ride ? 1 : 0); ++l) {
+        const int in = m->bot_dims[l], out = m->bot_dims[l + 1];
+        if (in <= dqrm::kSmallKMax && out % 4 == 0 && aligned(m->bot_b[l], 16)) {
+            dqrm::SmallKArgs sk{};
+            sk.X = x, sk.W = bot_wf[l], sk.bias = m->bot_b[l], sk.Y = F(L.bot_act[l]), sk.B = B, sk.N = out, sk.K = in, sk.relu = 1;
+            hipLaunchKernelGGL(dqrm::linear_small_k_kernel, dim3((B + dqrm::kSmallKSamples - 1) / dqrm::kSmallKSamples),
+                               dim3(dqrm::kSmallKThreads), 0, st, sk);
+            DQRM_HIP_CHECK(hipGetLastError());
+        } else {
+            DQRM_HIP_CHECK(linear_fwd(st, x, bot_wf[l], m->bot_b[l], F(L.bot_act[l]), B, in, out, true));
+        }
         x = F(L.bot_act[l]);
     }
     dqrm::InteractArgs ia{};
-    ia.bot = x, ia.emb = emb_out, ia.R = F(L.R), ia.B = B, ia.T = T, ia.D = D;
-    hipLaunchKernelGGL(dqrm::interact_fwd_kernel, dim3(B), dim3(dqrm::kInterThreads), dqrm::interact_lds_bytes(T, D, false), st,
-                       ia);
+    ia.bot = ride ? F(L.bot_act[bl_last]) : x, ia.emb = emb_out, ia.R = F(L.R), ia.B = B, ia.T = T, ia.D = D;
+    if (ride) {
+        ia.lin_x = x, ia.lin_w = bot_wf[bl_last], ia.lin_b = m->bot_b[bl_last], ia.lin_y = F(L.bot_act[bl_last]);
+        ia.lin_k = m->bot_dims[bl_last];
+    }
+    hipLaunchKernelGGL(dqrm::interact_fwd_kernel, dim3(B), dim3(dqrm::kInterThreads),
+                       dqrm::interact_lds_bytes(T, D, false, ride ? ia.lin_k : 0), st, ia);
     x = F(L.R);
     const int last = m->top_layers - 1;
     for (int l = 0; l < last; ++l) {
@@ -938,11 +956,13 @@ int32_t dqrm_dense_step_quant(const dqrm_dense_model_t *m, const dqrm_dense_quan
         DQRM_HIP_CHECK(linear_bwd_input(st, F(L.top_dz[l]), top_wf[l], l > 0 ? in_act : nullptr, dX, B,
                                         m->top_dims[l], m->top_dims[l + 1]));
     }
-    const float *bot_out = F(L.bot_act[m->bot_layers - 1]);
-    ia.dR = F(L.dR), ia.dbot = F(L.bot_dz[m->bot_layers - 1]), ia.demb = grad_emb, ia.bot_mask = bot_out;
+    const float *bot_out = F(L.bot_act[bl_last]);
+    ia.bot = bot_out, ia.dR = F(L.dR), ia.dbot = F(L.bot_dz[bl_last]), ia.demb = grad_emb, ia.bot_mask = bot_out;
+    const bool ride_back = ride && bl_last > 0; // (a first layer's input gradient is not needed)
+    if (ride_back) ia.lin_mask = F(L.bot_act[bl_last - 1]), ia.lin_dx = F(L.bot_dz[bl_last - 1]);
     hipLaunchKernelGGL(dqrm::interact_bwd_kernel, dim3(B), dim3(dqrm::kInterThreads), dqrm::interact_lds_bytes(T, D, true), st,
                        ia);
-    for (int l = m->bot_layers - 1; l > 0; --l)
+    for (int l = bl_last - (ride_back ? 1 : 0); l > 0; --l)
         DQRM_HIP_CHECK(linear_bwd_input(st, F(L.bot_dz[l]), bot_wf[l], F(L.bot_act[l - 1]), F(L.bot_dz[l - 1]), B,
                                         m->bot_dims[l], m->bot_dims[l + 1]));
 

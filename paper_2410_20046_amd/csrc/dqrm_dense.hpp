@@ -404,6 +404,55 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_wave_group_kernel(GemmGroup
     gemm_wave_tile<A_MODE, B_MODE>(grp.p[pi], tile, true, 1, wave, lane);
 }
 
+// ---- a layer with a short input (the bottom MLP's first: 13 dense features) -------------------------------
+// Y[b][o] = act(sum_k X[b][k] * W[o][k] + bias[o]) for K <= kSmallKMax: a product with a reduction this short is
+// all launch and edge handling on the matrix cores.  A thread owns four consecutive outputs: their 4 K weights stay
+// in registers while the thread walks the workgroup's kSmallKSamples samples, whose inputs sit in LDS.
+constexpr int kSmallKMax = 16;
+constexpr int kSmallKThreads = 128;
+constexpr int kSmallKSamples = 4; // samples per workgroup
+struct SmallKArgs {
+    const float *X, *W, *bias;
+    float *Y;
+    int B, N, K, relu; // N a multiple of 4, bias and Y 16-byte aligned (host)
+};
+
+__global__ __launch_bounds__(kSmallKThreads) void linear_small_k_kernel(SmallKArgs a)
+{
+    __shared__ float xs[kSmallKSamples * kSmallKMax];
+    const int N = a.N, K = a.K;
+    const int b0 = (int)blockIdx.x * kSmallKSamples, nb = min(kSmallKSamples, a.B - b0);
+    for (int e = threadIdx.x; e < kSmallKSamples * kSmallKMax; e += kSmallKThreads) {
+        const int bl = e / kSmallKMax, k = e % kSmallKMax;
+        xs[e] = (bl < nb && k < K) ? a.X[(long long)(b0 + bl) * K + k] : 0.0f;
+    }
+    __syncthreads();
+    for (int o = (int)threadIdx.x * 4; o < N; o += kSmallKThreads * 4) {
+        // (4-byte loads: a row of an odd number of floats starts on no wider boundary; all 4 K are requested at once,
+        // past K the last weight is read again and meets a zero input)
+        float wr[4][kSmallKMax];
+#pragma unroll
+        for (int r = 0; r < 4; ++r)
+#pragma unroll
+            for (int k = 0; k < kSmallKMax; ++k) wr[r][k] = a.W[(long long)(o + r) * K + min(k, K - 1)];
+        const float4 bias = *reinterpret_cast<const float4 *>(a.bias + o);
+        for (int bl = 0; bl < nb; ++bl) {
+            float acc[4] = {bias.x, bias.y, bias.z, bias.w};
+#pragma unroll
+            for (int k = 0; k < kSmallKMax; ++k) {
+                const float xv = xs[bl * kSmallKMax + k]; // zero past K
+#pragma unroll
+                for (int r = 0; r < 4; ++r) acc[r] = __builtin_fmaf(xv, wr[r][k], acc[r]);
+            }
+            if (a.relu) {
+#pragma unroll
+                for (int r = 0; r < 4; ++r) acc[r] = fmaxf(acc[r], 0.0f);
+            }
+            *reinterpret_cast<float4 *>(a.Y + (long long)(b0 + bl) * N + o) = make_float4(acc[0], acc[1], acc[2], acc[3]);
+        }
+    }
+}
+
 // ---- the head: last linear layer (one output), sigmoid, binary cross-entropy, gradient w.r.t. its input ----
 // z = X[b] . w + bias;  p = 1 / (1 + exp(-z));  term_b = -(y log max(p, 1e-12) + (1-y) log max(1-p, 1e-12));
 // dz = (p - y) / B;  dX[b][k] = dz * w[k], masked by X[b][k] > 0 when X is a ReLU output.
@@ -701,6 +750,16 @@ struct InteractArgs {
     float *demb;      // [B][T][D]
     const float *bot_mask; // the bottom MLP's last activation (ReLU mask for dbot), or null
     int B, T, D;
+    // The bottom MLP's last layer, when it is small enough to ride along (lin_w != null): the forward kernel computes
+    // bot[b] = relu(lin_x[b] * lin_w^T + lin_b) itself (and stores it to lin_y for the backward pass); the backward
+    // kernel goes on from dbot to that layer's input gradient, lin_dx[b] = (dbot[b] * lin_w) masked by lin_mask > 0.
+    const float *lin_x;    // [B][lin_k] input of that layer
+    const float *lin_w;    // [D][lin_k]
+    const float *lin_b;    // [D]
+    float *lin_y;          // [B][D] its output
+    const float *lin_mask; // [B][lin_k] backward: the layer's input if that is a ReLU output, or null
+    float *lin_dx;         // [B][lin_k] backward: gradient w.r.t. the pre-activation of the layer before, or null
+    int lin_k;
 };
 
 constexpr int kInterThreads = 128;
@@ -708,10 +767,11 @@ constexpr int kInterMaxV = 64;      // vectors per sample, at most (host)
 constexpr int kInterMaxZ = 64 * 64; // V * D floats, at most (host)
 
 // dynamic LDS of the two kernels below (at most ~33 KB: V <= 64, V * D <= 4096)
-inline size_t interact_lds_bytes(int T, int D, bool backward)
+constexpr int kInterMaxLinK = 1024; // widest input of a bottom layer that rides along (host)
+inline size_t interact_lds_bytes(int T, int D, bool backward, int lin_k = 0)
 {
     const int V = T + 1;
-    return sizeof(float) * (backward ? (size_t)V * D + (size_t)V * (V | 1) : (size_t)V * (D + 1));
+    return sizeof(float) * ((backward ? (size_t)V * D + (size_t)V * (V | 1) + (size_t)D : (size_t)V * (D + 1)) + (size_t)lin_k);
 }
 
 // pair index p -> (i, j), i > j, p = i(i-1)/2 + j
@@ -727,12 +787,39 @@ __global__ __launch_bounds__(kInterThreads) void interact_fwd_kernel(InteractArg
 {
     // rows one float apart from a multiple of the bank count: the lanes of a wave read different rows at the
     // same d, and with a pitch of D = 16 all of them would fall into two banks
-    extern __shared__ float inter_lds[]; // V * (D + 1) floats (interact_lds_bytes)
+    extern __shared__ float inter_lds[]; // V * (D + 1) (+ lin_k) floats (interact_lds_bytes)
     float *z = inter_lds;
     const int b = blockIdx.x, V = a.T + 1, D = a.D, pitch = D + 1;
-    for (int e = threadIdx.x; e < V * D; e += kInterThreads) {
-        const int i = e / D, d = e - i * D;
-        z[i * pitch + d] = e < D ? a.bot[(long long)b * D + e] : a.emb[(long long)b * a.T * D + (e - D)];
+    if (a.lin_w) {
+        // the embeddings travel while the layer is computed: 8 threads per output, each a strided eighth of the sum
+        for (int e = D + (int)threadIdx.x; e < V * D; e += kInterThreads) {
+            const int i = e / D, d = e - i * D;
+            z[i * pitch + d] = a.emb[(long long)b * a.T * D + (e - D)];
+        }
+        float *xin = inter_lds + V * pitch; // lin_k floats
+        const int K = a.lin_k;
+        for (int k = threadIdx.x; k < K; k += kInterThreads) xin[k] = a.lin_x[(long long)b * K + k];
+        __syncthreads();
+        for (int e0 = 0; e0 < D * 8; e0 += kInterThreads) { // (kInterThreads is a multiple of 8: teams stay whole)
+            const int e = e0 + (int)threadIdx.x;
+            const int d = min(e >> 3, D - 1), part = e & 7;
+            const float *w = a.lin_w + (long long)d * K;
+            float s = 0.0f;
+            for (int k = part; k < K; k += 8) s = __builtin_fmaf(xin[k], w[k], s);
+            s += __shfl_xor(s, 1, kWave);
+            s += __shfl_xor(s, 2, kWave);
+            s += __shfl_xor(s, 4, kWave);
+            if (part == 0 && e < D * 8) {
+                const float y = fmaxf(s + a.lin_b[d], 0.0f);
+                z[d] = y;
+                a.lin_y[(long long)b * D + d] = y;
+            }
+        }
+    } else {
+        for (int e = threadIdx.x; e < V * D; e += kInterThreads) {
+            const int i = e / D, d = e - i * D;
+            z[i * pitch + d] = e < D ? a.bot[(long long)b * D + e] : a.emb[(long long)b * a.T * D + (e - D)];
+        }
     }
     __syncthreads();
     const int P = V * (V - 1) / 2, W = D + P;
@@ -756,9 +843,9 @@ __global__ __launch_bounds__(kInterThreads) void interact_fwd_kernel(InteractArg
 // (terms in the order j = 0 .. V-1).
 __global__ __launch_bounds__(kInterThreads) void interact_bwd_kernel(InteractArgs a)
 {
-    extern __shared__ float inter_lds[]; // V * D + V * (V | 1) floats (interact_lds_bytes)
+    extern __shared__ float inter_lds[]; // V * D + V * (V | 1) + D floats (interact_lds_bytes)
     const int b = blockIdx.x, V = a.T + 1, D = a.D, vp = V | 1; // odd pitch
-    float *z = inter_lds, *dpf = inter_lds + V * D;
+    float *z = inter_lds, *dpf = inter_lds + V * D, *dzl = dpf + V * vp; // dzl: D floats, the gradient w.r.t. bot
     const int P = V * (V - 1) / 2, W = D + P;
     for (int e = threadIdx.x; e < V * D; e += kInterThreads)
         z[e] = e < D ? a.bot[(long long)b * D + e] : a.emb[(long long)b * a.T * D + (e - D)];
@@ -781,8 +868,19 @@ __global__ __launch_bounds__(kInterThreads) void interact_bwd_kernel(InteractArg
             const long long off = (long long)b * D + d;
             if (a.bot_mask) s = a.bot_mask[off] > 0.0f ? s : 0.0f;
             a.dbot[off] = s;
+            dzl[d] = s;
         } else {
             a.demb[(long long)b * a.T * D + (e - D)] = s;
+        }
+    }
+    if (a.lin_w && a.lin_dx) { // on to the input gradient of the bottom MLP's last layer
+        __syncthreads();
+        const int K = a.lin_k;
+        for (int k = threadIdx.x; k < K; k += kInterThreads) {
+            float s = 0.0f;
+            for (int d = 0; d < D; ++d) s = __builtin_fmaf(dzl[d], a.lin_w[(long long)d * K + k], s);
+            if (a.lin_mask) s = a.lin_mask[(long long)b * K + k] > 0.0f ? s : 0.0f;
+            a.lin_dx[(long long)b * K + k] = s;
         }
     }
 }

@@ -372,12 +372,11 @@ def main():
             # the weights do not change inside a group and bags are independent: the micro-batches' forwards are one
             # call on the whole batch
             dq.dqrm_embbag_fwd(tables, hp.idx_d[p], hp.off_d[p], B, hp.mode, bufs.out, None)
-            for j in range(nodes):
-                b, ix = mb[j], mb_idx[p][j]
-                # only the first micro-batch's maxima are used (its scale serves the whole group): the others ask for none
-                dq.dqrm_segment_sum(tables, Bm, ix.numel(), g[j * Bm:(j + 1) * Bm], b.values, b.g_absmax if j == 0 else None,
-                                    b.workspace)
-                dq.dqrm_grad_quant_int8(T, D, b.cap, b.values, b.table_uniq_offsets, mb[0].g_absmax, b.gq, b.g_scale)
+            # segment sums and INT8 codes of all micro-batches in one launch each; only the first micro-batch's maxima
+            # are used (its scale serves the whole group): the others ask for none
+            dq.dqrm_segment_sum_multi(tables, Bm, [(mb_idx[p][j].numel(), g[j * Bm:(j + 1) * Bm], b.values,
+                                                    b.g_absmax if j == 0 else None, b.workspace) for j, b in enumerate(mb)])
+            dq.dqrm_grad_quant_int8_multi(T, D, [(b.values, b.table_uniq_offsets, mb[0].g_absmax, b.gq, b.g_scale) for b in mb])
             dq.dqrm_sparse_merge(tables, [(b.uniq_rows, b.table_uniq_offsets, b.gq) for b in mb], m_rows, m_tuo, m_nu,
                                  m_sums, m_ws)
             dq.dqrm_sparse_update_sums(tables, m_cap, m_rows, m_tuo, m_sums, mb[0].g_scale, args.lr)

@@ -214,6 +214,24 @@ typedef struct {
 int32_t dqrm_dedupe_multi(const dqrm_tables_t *tables, int32_t batch, int32_t num_batches,
                           const dqrm_dedupe_batch_t *batches, size_t workspace_bytes, void *stream);
 
+/* dqrm_segment_sum for up to DQRM_MAX_DEDUPE_BATCHES batches in one launch (the
+ * companion of dqrm_dedupe_multi).  The segment sums of a small batch -- a
+ * micro-batch of simulated data parallelism (appendix "Simulated Data Parallelism
+ * Environment") -- are a chain of dependent memory round trips with little else to
+ * do; several side by side cost hardly more than one.  `batches` is a HOST array;
+ * each element holds what dqrm_segment_sum takes for one batch (its own workspace,
+ * as its dqrm_dedupe left it, of at least `workspace_bytes` bytes; g_absmax may be
+ * NULL).  All batches have `batch` bags per table. */
+typedef struct {
+    int64_t num_indices;
+    const float *grad_out; /* [batch][T][D] */
+    float *values;
+    float *g_absmax;       /* [T] or NULL */
+    void *workspace;
+} dqrm_segsum_batch_t;
+int32_t dqrm_segment_sum_multi(const dqrm_tables_t *tables, int32_t batch, int32_t num_batches,
+                               const dqrm_segsum_batch_t *batches, size_t workspace_bytes, void *stream);
+
 /* Distributed-training appendix (only the values of the sparse gradient are
  * quantised; the indices are left alone): one scale per table per step,
  * g_scale[t] = max(g_absmax[t] / 127, 1e-8); gq = clamp(round_half_even(values /
@@ -221,6 +239,21 @@ int32_t dqrm_dedupe_multi(const dqrm_tables_t *tables, int32_t batch, int32_t nu
 int32_t dqrm_grad_quant_int8(int32_t num_tables, int32_t dim, int64_t capacity, const float *values,
                              const int32_t *table_uniq_offsets, const float *g_absmax, int8_t *gq,
                              float *g_scale, void *stream);
+
+/* dqrm_grad_quant_int8 for up to DQRM_MAX_DEDUPE_BATCHES blocks of values in one
+ * launch (`blocks` is a HOST array of that call's arguments).  The blocks may name
+ * the same g_absmax: the micro-batches of one group of simulated data parallelism
+ * are all quantised with the first one's scale. */
+typedef struct {
+    int64_t capacity;
+    const float *values;
+    const int32_t *table_uniq_offsets;
+    const float *g_absmax;
+    int8_t *gq;
+    float *g_scale;
+} dqrm_quant_block_t;
+int32_t dqrm_grad_quant_int8_multi(int32_t num_tables, int32_t dim, int32_t num_blocks,
+                                   const dqrm_quant_block_t *blocks, void *stream);
 
 /* Same appendix (dequantise, then the local parameter update): for every
  * segment u of table t, master[row] -= lr * (g_scale[t] * gq[u]) (two

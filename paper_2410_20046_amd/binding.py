@@ -37,7 +37,8 @@ MAX_DIM = 256
 NOALLOC_SCRATCH_BYTES = 8 << 20
 
 EXPORTS = ("dqrm_find_scale", "dqrm_pack_int4", "dqrm_embbag_fwd", "dqrm_embbag_bwd_workspace_bytes",
-           "dqrm_embbag_bwd", "dqrm_embbag_bwd_noalloc", "dqrm_dedupe", "dqrm_dedupe_multi", "dqrm_segment_sum", "dqrm_grad_quant_int8",
+           "dqrm_embbag_bwd", "dqrm_embbag_bwd_noalloc", "dqrm_dedupe", "dqrm_dedupe_multi", "dqrm_segment_sum", "dqrm_segment_sum_multi",
+           "dqrm_grad_quant_int8", "dqrm_grad_quant_int8_multi",
            "dqrm_sparse_update", "dqrm_sparse_merge_workspace_bytes", "dqrm_sparse_merge", "dqrm_sparse_update_sums",
            "dqrm_quant_update", "dqrm_dense_workspace_bytes", "dqrm_dense_step",
            "dqrm_dense_param_count", "dqrm_dense_step_quant", "dqrm_check_status", "dqrm_last_hip_error", "dqrm_version")
@@ -68,6 +69,16 @@ class dqrm_dedupe_batch_t(C.Structure):
 
 
 MAX_DEDUPE_BATCHES = 8
+
+
+class dqrm_segsum_batch_t(C.Structure):
+    _fields_ = [("num_indices", C.c_int64), ("grad_out", C.c_void_p), ("values", C.c_void_p), ("g_absmax", C.c_void_p),
+                ("workspace", C.c_void_p)]
+
+
+class dqrm_quant_block_t(C.Structure):
+    _fields_ = [("capacity", C.c_int64), ("values", C.c_void_p), ("table_uniq_offsets", C.c_void_p),
+                ("g_absmax", C.c_void_p), ("gq", C.c_void_p), ("g_scale", C.c_void_p)]
 
 
 class dqrm_dense_model_t(C.Structure):
@@ -107,6 +118,10 @@ def lib() -> C.CDLL:
         L.dqrm_dedupe_multi.argtypes = [tp, i32, i32, C.POINTER(dqrm_dedupe_batch_t), sz, vp]
         L.dqrm_dedupe_multi.restype = i32
         L.dqrm_segment_sum.argtypes = [tp, i32, i64, vp, vp, vp, vp, sz, vp]
+        L.dqrm_segment_sum_multi.argtypes = [tp, i32, i32, C.POINTER(dqrm_segsum_batch_t), sz, vp]
+        L.dqrm_segment_sum_multi.restype = i32
+        L.dqrm_grad_quant_int8_multi.argtypes = [i32, i32, i32, C.POINTER(dqrm_quant_block_t), vp]
+        L.dqrm_grad_quant_int8_multi.restype = i32
         L.dqrm_quant_update.argtypes = [tp, i64, i64, vp, vp, vp, vp, vp, vp, C.c_float, vp, sz, vp]
         L.dqrm_grad_quant_int8.argtypes = [i32, i32, i64, vp, vp, vp, vp, vp, vp]
         L.dqrm_sparse_update.argtypes = [tp, i64, vp, vp, vp, vp, C.c_float, vp]
@@ -253,6 +268,29 @@ def dqrm_segment_sum(tables: Tables, batch: int, num_indices: int, grad_out: tor
     _check(lib().dqrm_segment_sum(tables.ref, batch, num_indices, _ptr(grad_out), _ptr(values), _ptr(g_absmax),
                                   _ptr(workspace), workspace.numel() * workspace.element_size(), _stream(stream)),
            "dqrm_segment_sum")
+
+
+def dqrm_segment_sum_multi(tables: Tables, batch: int, batches, stream=None) -> None:
+    """``batches``: sequence of tuples (num_indices, grad_out, values, g_absmax or None, workspace) of device tensors,
+    one per batch (at most MAX_DEDUPE_BATCHES)."""
+    arr = (dqrm_segsum_batch_t * len(batches))()
+    ws_bytes = None
+    for i, (n, g, v, am, ws) in enumerate(batches):
+        arr[i] = dqrm_segsum_batch_t(int(n), _ptr(g), _ptr(v), _ptr(am), _ptr(ws))
+        nb = ws.numel() * ws.element_size()
+        ws_bytes = nb if ws_bytes is None else min(ws_bytes, nb)
+    _check(lib().dqrm_segment_sum_multi(tables.ref, batch, len(batches), arr, ws_bytes or 0, _stream(stream)),
+           "dqrm_segment_sum_multi")
+
+
+def dqrm_grad_quant_int8_multi(num_tables: int, dim: int, blocks, stream=None) -> None:
+    """``blocks``: sequence of tuples (values, table_uniq_offsets, g_absmax, gq, g_scale) of device tensors, one per
+    block (at most MAX_DEDUPE_BATCHES); the capacity of a block is the smaller first dimension of values and gq."""
+    arr = (dqrm_quant_block_t * len(blocks))()
+    for i, (v, tuo, am, gq, gs) in enumerate(blocks):
+        arr[i] = dqrm_quant_block_t(min(v.shape[0], gq.shape[0]), _ptr(v), _ptr(tuo), _ptr(am), _ptr(gq), _ptr(gs))
+    _check(lib().dqrm_grad_quant_int8_multi(num_tables, dim, len(blocks), arr, _stream(stream)),
+           "dqrm_grad_quant_int8_multi")
 
 
 def dqrm_grad_quant_int8(num_tables: int, dim: int, capacity: int, values: torch.Tensor,

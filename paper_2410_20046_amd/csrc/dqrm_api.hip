@@ -203,6 +203,19 @@ void launch_segsum(int G, dim3 grid, hipStream_t st, const dqrm::SegArgs &a)
     }
 }
 
+void launch_segsum_multi(int G, dim3 grid, hipStream_t st, const dqrm::SegMulti &m)
+{
+    using namespace dqrm;
+    switch (G) {
+    case 2: hipLaunchKernelGGL((segment_sum_multi_kernel<2>), grid, dim3(kSumThreads), 0, st, m); break;
+    case 4: hipLaunchKernelGGL((segment_sum_multi_kernel<4>), grid, dim3(kSumThreads), 0, st, m); break;
+    case 8: hipLaunchKernelGGL((segment_sum_multi_kernel<8>), grid, dim3(kSumThreads), 0, st, m); break;
+    case 16: hipLaunchKernelGGL((segment_sum_multi_kernel<16>), grid, dim3(kSumThreads), 0, st, m); break;
+    case 32: hipLaunchKernelGGL((segment_sum_multi_kernel<32>), grid, dim3(kSumThreads), 0, st, m); break;
+    default: hipLaunchKernelGGL((segment_sum_multi_kernel<64>), grid, dim3(kSumThreads), 0, st, m); break;
+    }
+}
+
 int32_t sparse_update_impl(const dqrm_tables_t *tables, int64_t capacity, const int64_t *uniq_rows,
                            const int32_t *table_uniq_offsets, const int8_t *gq, const int32_t *sums,
                            const float *g_scale, float lr, void *stream)
@@ -459,6 +472,55 @@ int32_t dqrm_segment_sum(const dqrm_tables_t *tables, int32_t batch, int64_t num
     return DQRM_OK;
 }
 
+int32_t dqrm_segment_sum_multi(const dqrm_tables_t *tables, int32_t batch, int32_t num_batches,
+                               const dqrm_segsum_batch_t *batches, size_t workspace_bytes, void *stream)
+{
+    int64_t R = 0;
+    int32_t rc = check_tables(tables, false, &R);
+    if (rc != DQRM_OK) return rc;
+    if (!batches || num_batches < 1 || batch < 1) return DQRM_ERR_INVALID_ARG;
+    if (num_batches > DQRM_MAX_DEDUPE_BATCHES) return DQRM_ERR_UNSUPPORTED;
+    if ((int64_t)batch * tables->num_tables > kMaxIndices) return DQRM_ERR_UNSUPPORTED;
+    const int T = tables->num_tables, D = tables->dim;
+    int64_t max_n = 0;
+    bool any_absmax = false;
+    for (int i = 0; i < num_batches; ++i) {
+        const dqrm_segsum_batch_t &b = batches[i];
+        if (b.num_indices < 0) return DQRM_ERR_INVALID_ARG;
+        if (b.num_indices > kMaxIndices) return DQRM_ERR_UNSUPPORTED;
+        if (!b.grad_out || !b.values || !b.workspace) return DQRM_ERR_INVALID_ARG;
+        if (!aligned(b.grad_out, 16) || !aligned(b.values, 16) || !aligned(b.workspace, 256)) return DQRM_ERR_INVALID_ARG;
+        if (workspace_bytes < ws_layout(T, D, b.num_indices).total) return DQRM_ERR_WORKSPACE_TOO_SMALL;
+        max_n = std::max(max_n, b.num_indices);
+        any_absmax = any_absmax || b.g_absmax != nullptr;
+    }
+    dqrm::SegMulti sm;
+    dqrm::AbsmaxMulti am;
+    std::memset(&sm, 0, sizeof(sm));
+    std::memset(&am, 0, sizeof(am));
+    for (int i = 0; i < num_batches; ++i) {
+        const dqrm_segsum_batch_t &b = batches[i];
+        dqrm::SegArgs &sa = sm.b[i];
+        sa.grad_out = b.grad_out;
+        sa.ws = ws_views(b.workspace, ws_layout(T, D, b.num_indices));
+        sa.N = b.num_indices;
+        sa.values = b.values;
+        sa.g_absmax = b.g_absmax;
+        sa.T = T, sa.B = batch, sa.D = D;
+        am.slots[i] = sa.ws.absmax_slots;
+        am.g_absmax[i] = b.g_absmax;
+    }
+    am.T = T;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    const int G = pow2ceil(D / 4);
+    const int grid_sum = grid_for((max_n + 3) / 4 * G, dqrm::kSumThreads, dqrm::kSumBlocksPerCu);
+    launch_segsum_multi(G, dim3(grid_sum, num_batches), st, sm);
+    if (any_absmax)
+        hipLaunchKernelGGL(dqrm::absmax_finalize_multi_kernel, dim3((T + 255) / 256, num_batches), dim3(256), 0, st, am);
+    DQRM_HIP_CHECK(hipGetLastError());
+    return DQRM_OK;
+}
+
 int32_t dqrm_embbag_bwd(const dqrm_tables_t *tables, const int64_t *indices, const int64_t *offsets, int32_t batch,
                         int64_t num_indices, const float *grad_out, int32_t *sorted_pos, int64_t *uniq_rows,
                         int32_t *seg_offsets, int32_t *table_uniq_offsets, int32_t *num_unique, float *values,
@@ -536,6 +598,44 @@ int32_t dqrm_grad_quant_int8(int32_t num_tables, int32_t dim, int64_t capacity, 
     hipStream_t st = static_cast<hipStream_t>(stream);
     hipLaunchKernelGGL(dqrm::grad_quant_kernel, dim3(grid_for(capacity * (dim / 4), dqrm::kEwThreads, 8)),
                        dim3(dqrm::kEwThreads), dqrm::TableLds::bytes(num_tables), st, a);
+    DQRM_HIP_CHECK(hipGetLastError());
+    return DQRM_OK;
+}
+
+int32_t dqrm_grad_quant_int8_multi(int32_t num_tables, int32_t dim, int32_t num_blocks,
+                                   const dqrm_quant_block_t *blocks, void *stream)
+{
+    if (num_tables < 1 || dim < 1 || !blocks || num_blocks < 1) return DQRM_ERR_INVALID_ARG;
+    if (num_tables > DQRM_MAX_TABLES || dim % 8 != 0 || dim > DQRM_MAX_DIM) return DQRM_ERR_UNSUPPORTED;
+    if (num_blocks > DQRM_MAX_DEDUPE_BATCHES) return DQRM_ERR_UNSUPPORTED;
+    int64_t max_cap = 0;
+    for (int i = 0; i < num_blocks; ++i) {
+        const dqrm_quant_block_t &b = blocks[i];
+        if (b.capacity < 0) return DQRM_ERR_INVALID_ARG;
+        if (!b.values || !b.table_uniq_offsets || !b.g_absmax || !b.gq || !b.g_scale) return DQRM_ERR_INVALID_ARG;
+        if (b.capacity > kMaxIndices || b.capacity * (dim / 4) > kMaxRowQuarters) return DQRM_ERR_UNSUPPORTED;
+        if (!aligned(b.values, 16) || !aligned(b.gq, 4)) return DQRM_ERR_INVALID_ARG;
+        max_cap = std::max(max_cap, b.capacity);
+    }
+    dqrm::QuantMulti qm;
+    std::memset(&qm, 0, sizeof(qm));
+    for (int i = 0; i < num_blocks; ++i) {
+        const dqrm_quant_block_t &b = blocks[i];
+        dqrm::QuantArgs &a = qm.b[i];
+        a.values = b.values;
+        a.tuo = b.table_uniq_offsets;
+        a.g_absmax = b.g_absmax;
+        a.gq = b.gq;
+        a.g_scale = b.g_scale;
+        a.capacity = b.capacity;
+        a.T = num_tables;
+        a.D = dim;
+        a.by_q4 = dqrm::FastDiv::make((unsigned)(dim / 4));
+    }
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    hipLaunchKernelGGL(dqrm::grad_quant_multi_kernel,
+                       dim3(grid_for(max_cap * (dim / 4), dqrm::kEwThreads, 8), num_blocks), dim3(dqrm::kEwThreads),
+                       dqrm::TableLds::bytes(num_tables), st, qm);
     DQRM_HIP_CHECK(hipGetLastError());
     return DQRM_OK;
 }

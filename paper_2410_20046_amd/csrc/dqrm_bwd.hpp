@@ -927,7 +927,7 @@ __device__ __forceinline__ float combine_column_shared_wave(const BwdWs &ws, int
 constexpr int kSinglesPerGroup = 4;
 
 template <int G>
-__global__ __launch_bounds__(kSumThreads, 4) void segment_sum_kernel(SegArgs a)
+__device__ __forceinline__ void segment_sum_body(const SegArgs &a)
 {
     constexpr int kGroups = kSumThreads / G; // lane groups per workgroup
     __shared__ unsigned s_max[DQRM_MAX_TABLES];
@@ -1085,9 +1085,46 @@ __global__ __launch_bounds__(kSumThreads, 4) void segment_sum_kernel(SegArgs a)
     amax.flush(a.ws.absmax_slots, T);
 }
 
+template <int G>
+__global__ __launch_bounds__(kSumThreads, 4) void segment_sum_kernel(SegArgs a)
+{
+    segment_sum_body<G>(a);
+}
+
+// The segment sums of several batches in one launch (blockIdx.y picks the batch): small batches, such as the
+// micro-batches of simulated data parallelism, are a chain of dependent round trips with little else to do, and
+// several of them side by side cost hardly more than one.
+struct SegMulti {
+    SegArgs b[DQRM_MAX_DEDUPE_BATCHES];
+};
+
+template <int G>
+__global__ __launch_bounds__(kSumThreads, 4) void segment_sum_multi_kernel(SegMulti m)
+{
+    segment_sum_body<G>(m.b[blockIdx.y]);
+}
+
 // g_absmax[t] = max over the table's slots
 // (and clears them, so that the segment sums may be repeated on the same dedupe)
+__device__ __forceinline__ void absmax_finalize_body(float *__restrict__ slots, int T, float *__restrict__ g_absmax);
+
 __global__ void absmax_finalize_kernel(float *__restrict__ slots, int T, float *__restrict__ g_absmax)
+{
+    absmax_finalize_body(slots, T, g_absmax);
+}
+
+struct AbsmaxMulti {
+    float *slots[DQRM_MAX_DEDUPE_BATCHES];
+    float *g_absmax[DQRM_MAX_DEDUPE_BATCHES]; // an entry may be null: that batch's maxima are not wanted
+    int T;
+};
+
+__global__ void absmax_finalize_multi_kernel(AbsmaxMulti m)
+{
+    if (m.g_absmax[blockIdx.y]) absmax_finalize_body(m.slots[blockIdx.y], m.T, m.g_absmax[blockIdx.y]);
+}
+
+__device__ __forceinline__ void absmax_finalize_body(float *__restrict__ slots, int T, float *__restrict__ g_absmax)
 {
     const int t = blockIdx.x * blockDim.x + threadIdx.x;
     if (t >= T) return;

@@ -60,7 +60,7 @@ struct QuantArgs {
     int T, D;
 };
 
-__global__ __launch_bounds__(kEwThreads) void grad_quant_kernel(QuantArgs a)
+__device__ __forceinline__ void grad_quant_body(const QuantArgs &a)
 {
     extern __shared__ __align__(16) unsigned char s_dyn[];
     const TableLds L(s_dyn, a.T);
@@ -83,6 +83,21 @@ __global__ __launch_bounds__(kEwThreads) void grad_quant_kernel(QuantArgs a)
         reinterpret_cast<unsigned *>(a.gq)[e] =
             pack_bytes(int8_code(v.x, gs), int8_code(v.y, gs), int8_code(v.z, gs), int8_code(v.w, gs));
     }
+}
+
+__global__ __launch_bounds__(kEwThreads) void grad_quant_kernel(QuantArgs a)
+{
+    grad_quant_body(a);
+}
+
+// several blocks of values in one launch (blockIdx.y picks the block), for the same reason as the segment sums
+struct QuantMulti {
+    QuantArgs b[DQRM_MAX_DEDUPE_BATCHES];
+};
+
+__global__ __launch_bounds__(kEwThreads) void grad_quant_multi_kernel(QuantMulti m)
+{
+    grad_quant_body(m.b[blockIdx.y]);
 }
 
 // ---- B5: dequantise, SGD on the master rows, re-encode the packed mirror -------

@@ -131,6 +131,37 @@ def test_validation_errors_before_any_launch():
     assert dd(ws=FAKE + 64) == dq.ERR_INVALID_ARG
     assert dd(bound=-1) == dq.ERR_INVALID_ARG
     assert dd(ws_bytes=16) == dq.ERR_WORKSPACE_TOO_SMALL
+    from paper_2410_20046_amd.binding import dqrm_segsum_batch_t, dqrm_quant_block_t
+
+    def ssm(n=2, N=8, grad=FAKE, values=FAKE, ws=FAKE, ws_bytes=1 << 30, arr="ok", tb=ok):
+        a = (dqrm_segsum_batch_t * 8)()
+        for k in range(8):
+            a[k] = dqrm_segsum_batch_t(N, grad, values, None, ws)
+        return L.dqrm_segment_sum_multi(r(tb), 4, n, a if arr == "ok" else None, ws_bytes, S)
+    assert ssm(arr=None) == dq.ERR_INVALID_ARG
+    assert ssm(n=0) == dq.ERR_INVALID_ARG
+    assert ssm(n=dq.MAX_DEDUPE_BATCHES + 1) == dq.ERR_UNSUPPORTED
+    assert ssm(N=-1) == dq.ERR_INVALID_ARG
+    assert ssm(grad=None) == dq.ERR_INVALID_ARG
+    assert ssm(values=FAKE + 4) == dq.ERR_INVALID_ARG
+    assert ssm(ws=FAKE + 64) == dq.ERR_INVALID_ARG
+    assert ssm(ws_bytes=16) == dq.ERR_WORKSPACE_TOO_SMALL
+    assert ssm(tb=_tables(D=20)) == dq.ERR_UNSUPPORTED
+
+    def gqm(n=2, T=2, D=16, cap=8, v=FAKE, q=FAKE, am=FAKE, arr="ok"):
+        a = (dqrm_quant_block_t * 8)()
+        for k in range(8):
+            a[k] = dqrm_quant_block_t(cap, v, FAKE, am, q, FAKE)
+        return L.dqrm_grad_quant_int8_multi(T, D, n, a if arr == "ok" else None, S)
+    assert gqm(arr=None) == dq.ERR_INVALID_ARG
+    assert gqm(n=0) == dq.ERR_INVALID_ARG
+    assert gqm(n=dq.MAX_DEDUPE_BATCHES + 1) == dq.ERR_UNSUPPORTED
+    assert gqm(cap=-1) == dq.ERR_INVALID_ARG
+    assert gqm(v=None) == dq.ERR_INVALID_ARG
+    assert gqm(am=None) == dq.ERR_INVALID_ARG
+    assert gqm(q=FAKE + 2) == dq.ERR_INVALID_ARG
+    assert gqm(D=12) == dq.ERR_UNSUPPORTED
+    assert gqm(T=0) == dq.ERR_INVALID_ARG
     # quantise / update
     gq = lambda T=2, D=16, cap=8, v=FAKE, tuo=FAKE, am=FAKE, q=FAKE, gs=FAKE: L.dqrm_grad_quant_int8(
         T, D, cap, v, tuo, am, q, gs, S)

@@ -263,3 +263,58 @@ def test_terabyte_full_size_eight_nodes(oracle):
     sim = oracle.SimulatedDP(Wo, po, wl.row_offsets, s_w, simulated_nodes=nodes, lr=0.1)
     idx, off = wl.batch(0)
     _check_group(oracle, wl, W, Wo, po, s_w, grp, idx, off, wl.grad_normal(0), nodes, 0.1, 0, sim, "terabyte n=8")
+
+
+@pytest.mark.parametrize("D,nodes,ragged", [(64, 8, False), (16, 4, True), (24, 3, True)])
+def test_micro_batches_in_one_launch_each(oracle, D, nodes, ragged):
+    """dqrm_dedupe_multi -> dqrm_segment_sum_multi -> dqrm_grad_quant_int8_multi over the micro-batches of a group ==
+    the oracle's backward and quantisation of each micro-batch (values and maxima bit for bit, codes and index
+    outputs exactly), with the first micro-batch's maxima for every block; one batch asks for no maxima."""
+    import torch
+    import paper_2410_20046_amd as dq
+    from gen import Workload
+
+    cards = np.array([9, 700, 120000, 33, 5000], np.int64)
+    wl = Workload(name="multi", T=5, D=D, B=384 * nodes, alpha=1.1, seed=600 + D, cards=cards)
+    Bm = wl.B // nodes
+    idx, off = wl.batch(0, pooling="ragged", max_len=4) if ragged else wl.batch(0)
+    grad = wl.grad_normal(0)
+    parts = split_batch(idx, off, wl.T, wl.B, nodes)
+    dev = torch.device("cuda:0")
+    W = np.zeros((wl.R, wl.D), np.float32)
+    tables = dq.Tables(wl.row_offsets, wl.D, torch.from_numpy(W).to(dev), None)
+    cap = max(len(i) for i, _ in parts)
+    bufs = [dq.StepBuffers(wl.T, wl.D, Bm, cap, dev) for _ in range(nodes)]
+    di = [torch.from_numpy(i).to(dev) for i, _ in parts]
+    do = [torch.from_numpy(o).to(dev) for _, o in parts]
+    dg = [torch.from_numpy(np.ascontiguousarray(grad[k * Bm:(k + 1) * Bm])).to(dev) for k in range(nodes)]
+    _say(f"multi launches: D={D}, {nodes} micro-batches of {Bm}, up to {cap} lookups")
+    dq.dqrm_dedupe_multi(tables, Bm, [(di[k], do[k], b.sorted_pos, b.uniq_rows, b.seg_offsets, b.table_uniq_offsets,
+                                       b.num_unique, b.workspace) for k, b in enumerate(bufs)])
+    skip = nodes - 1  # this micro-batch asks for no maxima
+    for b in bufs:
+        b.g_absmax.fill_(-1.0)
+    dq.dqrm_segment_sum_multi(tables, Bm, [(di[k].numel(), dg[k], b.values, None if k == skip else b.g_absmax, b.workspace)
+                                           for k, b in enumerate(bufs)])
+    dq.dqrm_grad_quant_int8_multi(wl.T, wl.D, [(b.values, b.table_uniq_offsets, bufs[0].g_absmax, b.gq, b.g_scale)
+                                               for b in bufs])
+    code, tb, val = dq.dqrm_check_status()
+    assert code == 0, (code, tb, val)
+    absmax0 = None
+    for k, b in enumerate(bufs):
+        o = oracle.embbag_bwd(wl.T, wl.D, Bm, parts[k][0], parts[k][1], np.ascontiguousarray(grad[k * Bm:(k + 1) * Bm]))
+        U = int(b.num_unique.cpu().item())
+        what = f"multi D={D} micro-batch {k}"
+        assert U == len(o["uniq_rows"]), what
+        assert_exact(b.uniq_rows.cpu().numpy()[:U], o["uniq_rows"], what + " uniq_rows")
+        assert_exact(b.table_uniq_offsets.cpu().numpy(), o["table_uniq_offsets"], what + " table_uniq_offsets")
+        assert_exact(b.values.cpu().numpy()[:U].view(np.uint32), o["values"].view(np.uint32), what + " values bits")
+        if k == skip:
+            assert (b.g_absmax.cpu().numpy() == -1.0).all(), what + ": maxima written though not asked for"
+        else:
+            assert_exact(b.g_absmax.cpu().numpy().view(np.uint32), o["g_absmax"].view(np.uint32), what + " g_absmax bits")
+        if absmax0 is None:
+            absmax0 = o["g_absmax"]
+        ogq, ogs = oracle.grad_quant_int8(wl.T, wl.D, o["values"], o["table_uniq_offsets"], absmax0)
+        assert_exact(b.gq.cpu().numpy()[:U], ogq, what + " INT8 codes")
+        assert_exact(b.g_scale.cpu().numpy().view(np.uint32), ogs.view(np.uint32), what + " g_scale bits")

@@ -66,7 +66,12 @@ extern "C" {
 #define DQRM_MAX_TABLES 1024
 #define DQRM_MAX_TABLE_ROWS 2147483646LL /* rows of one table */
 #define DQRM_MAX_TABLE_LOOKUPS 65536 /* lookups one table may receive in one batch (up to 16384 are sorted in LDS by
-                                        one workgroup; more take a slower path through the workspace) */
+                                        one workgroup; more take a slower path through the workspace).
+                                        NOTE: a table beyond the limit is SKIPPED for that batch -- it contributes
+                                        no unique rows, so its rows get no update -- and the only trace is
+                                        DQRM_ERR_CAPACITY in the device status word.  The host cannot refuse such
+                                        a batch beforehand (the per-table counts are device data), so a training
+                                        loop has to call dqrm_check_status now and then to notice. */
 #define DQRM_MAX_DEDUPE_BATCHES 8    /* batches one dqrm_dedupe_multi call may take */
 
 /* Order of a segment's floating-point sum (the paper does not fix one; results

@@ -105,11 +105,14 @@ WsLayout ws_layout(int32_t T, int32_t D, int64_t N)
     L.off_totals = take(4 * sizeof(int));
     L.off_bag_of_pos = take(n * sizeof(int));
     L.off_sorted_bag = take(n * sizeof(int));
-    L.off_chunk_local = take(n * 16);
-    L.off_single_local = take(n * 16);
-    L.off_chunk_desc = take(n * 16);
+    // (the lists have a slot even for an empty batch: the summing kernels request their first entries before they
+    // know the counts)
+    const size_t n1 = n ? n : 1;
+    L.off_chunk_local = take(n1 * 16);
+    L.off_single_local = take(n1 * 16);
+    L.off_chunk_desc = take(n1 * 16);
     L.off_chunk_bags = take((n / 2 + 1) * DQRM_SEG_CHUNK * sizeof(int));
-    L.off_single_desc = take(n * 16);
+    L.off_single_desc = take(n1 * 16);
     // (the large-table path exists only for batches that can hold a large table)
     const size_t big = N > dqrm::kDdCap ? n : 0;
     L.off_run_key = take(big * sizeof(int));

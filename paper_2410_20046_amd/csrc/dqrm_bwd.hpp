@@ -439,8 +439,8 @@ __global__ __launch_bounds__(kDdThreads) void dedupe_kernel(DedupeArgs args)
 // Tables with more than kDdCap lookups: dedupe_kernel has sorted their tiles of kDdCap consecutive lookups; one
 // workgroup per (table, batch) now
 //  1. merges the runs: every item finds its place in the table's sorted order on its own -- its index in its own
-//     run plus, per other run, the number of that run's keys below it (binary searches; equal keys of earlier runs
-//     count as below, which keeps equal keys in lookup order);
+//     run plus, per other run, the number of that run's keys below it (binary searches in LDS; equal keys of
+//     earlier runs count as below, which keeps equal keys in lookup order);
 //  2. walks the merged order in slabs of one item per thread, carrying the counts from slab to slab: segment
 //     heads, segment index and start of every item, the list of the heads;
 //  3. walks it again for the chunk heads and singles (a segment's end is the next segment's head, known now) and
@@ -457,6 +457,7 @@ __global__ __launch_bounds__(kDdThreads) void dedupe_large_kernel(DedupeArgs arg
     const BwdWs ws = bt.ws;
     __shared__ int s_w[kDdWaves];
     __shared__ int s_w2[kDdWaves];
+    __shared__ unsigned s_run[kDdCap]; // 64 KB: the run that is being searched
 
     const int t = blockIdx.x;
     const int tid = threadIdx.x, lane = tid & (kWave - 1), wave = tid / kWave;
@@ -468,26 +469,47 @@ __global__ __launch_bounds__(kDdThreads) void dedupe_large_kernel(DedupeArgs arg
     const int n = (int)(hi - lo), base = (int)lo;
     const int runs = (n + kDdCap - 1) / kDdCap;
 
-    // ---- 1. merge the runs
-    for (int e = tid; e < n; e += kDdThreads) {
-        const int r = e / kDdCap;
-        const unsigned key = ws.run_key[base + e];
-        int rank = e - r * kDdCap;
-        for (int r2 = 0; r2 < runs; ++r2) {
-            if (r2 == r) continue;
-            const unsigned *run = ws.run_key + base + r2 * kDdCap;
-            int a = 0, b = min(kDdCap, n - r2 * kDdCap); // keys of run r2 below mine: in [a, b]
-            while (a < b) {
-                const int mid = (a + b) >> 1;
-                const unsigned k2 = run[mid];
-                if (r2 < r ? k2 <= key : k2 < key)
-                    a = mid + 1;
-                else
-                    b = mid;
+    // ---- 1. merge the runs.  Each run in turn is staged in LDS and searched by the items of all other runs, four
+    // searches per thread in step (a fixed number of halvings, no branch); an item's rank is collected in the
+    // workspace (in the list of the segments' heads, which is written only in step 2) by the one thread that owns it.
+    int *rank_of = ws.head_of_seg + base + t;
+    for (int e = tid; e < n; e += kDdThreads) rank_of[e] = e % kDdCap;
+    for (int r2 = 0; r2 < runs; ++r2) {
+        const int len2 = min(kDdCap, n - r2 * kDdCap);
+        __syncthreads(); // (the searches of the previous run are over)
+        for (int i = tid; i < kDdCap; i += kDdThreads) s_run[i] = i < len2 ? ws.run_key[base + r2 * kDdCap + i] : 0xFFFFFFFFu;
+        __syncthreads();
+        for (int e0 = tid; e0 < n; e0 += 4 * kDdThreads) {
+            unsigned key[4];
+            int below[4];
+            bool live[4], ties_below[4];
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const int e = e0 + q * kDdThreads;
+                const int r = min(e, n - 1) / kDdCap;
+                live[q] = e < n && r != r2;
+                ties_below[q] = r2 < r; // equal keys of an earlier run come first
+                key[q] = ws.run_key[base + min(e, n - 1)];
+                below[q] = 0;
             }
-            rank += a;
+#pragma unroll 1
+            for (int step = kDdCap; step >= 1; step >>= 1) {
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    const int idx = below[q] + step; // are the first idx keys of the run all below mine?
+                    const unsigned k2 = s_run[min(idx, kDdCap) - 1];
+                    const bool yes = idx <= len2 && (ties_below[q] ? k2 <= key[q] : k2 < key[q]);
+                    below[q] = yes ? idx : below[q];
+                }
+            }
+#pragma unroll
+            for (int q = 0; q < 4; ++q)
+                if (live[q]) rank_of[e0 + q * kDdThreads] += below[q];
         }
-        ws.merged_key[base + rank] = key;
+    }
+    for (int e = tid; e < n; e += kDdThreads) {
+        const int rank = rank_of[e];
+        ws.merged_key[base + rank] = ws.run_key[base + e];
         ws.merged_pos[base + rank] = ws.run_pos[base + e];
     }
     __syncthreads(); // the runs are not read again: their arrays now take segment index and start of every item

@@ -455,7 +455,7 @@ def main():
         while G < D // 4:
             G *= 2
         # which kernel(s) a call launches, and the algorithmic bytes of one launch
-        dd = "dedupe_kernel + " + ("dedupe_large_kernel + " if N > 16384 and (args.overlap != "ahead" or hp.max_table_lookups > 16384) else "") + "dedupe_finish_kernel"
+        dd = "dedupe_kernel + " + ("dedupe_merge_kernel + dedupe_large_kernel + " if N > 16384 and (args.overlap != "ahead" or hp.max_table_lookups > 16384) else "") + "dedupe_finish_kernel"
         call_kernels = {
             "fwd": (f"embbag_fwd_kernel<{G},{'packed' if packed_fwd else 'master'}>", ab["fwd"]),
             "segment_sum": (f"segment_sum_kernel<{G}>" + ("" if args.fused else " + absmax_finalize_kernel"), ab["segsum"]),

@@ -413,8 +413,10 @@ int32_t dqrm_dedupe_multi(const dqrm_tables_t *tables, int32_t batch, int32_t nu
     // a table of more than kDdCap lookups is sorted in tiles (grid z), which dedupe_large_kernel merges
     const int tiles = (int)std::max<int64_t>(1, (largest + dqrm::kDdCap - 1) / dqrm::kDdCap);
     hipLaunchKernelGGL(dqrm::dedupe_kernel, dim3(T, num_batches, tiles), dim3(dqrm::kDdThreads), 0, st, da);
-    if (tiles > 1)
+    if (tiles > 1) {
+        hipLaunchKernelGGL(dqrm::dedupe_merge_kernel, dim3(T, num_batches, tiles), dim3(dqrm::kDdThreads), 0, st, da);
         hipLaunchKernelGGL(dqrm::dedupe_large_kernel, dim3(T, num_batches), dim3(dqrm::kDdThreads), 0, st, da);
+    }
     hipLaunchKernelGGL(dqrm::dedupe_finish_kernel, dim3(grid_for(max_n, dqrm::kSegThreads, 2), num_batches),
                        dim3(dqrm::kSegThreads), 0, st, da);
     DQRM_HIP_CHECK(hipGetLastError());

@@ -143,7 +143,7 @@ __global__ __launch_bounds__(kDdThreads) void dedupe_kernel(DedupeArgs args)
     const int base = (int)lo;
     // A table of up to kDdCap lookups is this workgroup's (blockIdx.z = 0) from start to end.  A larger one is cut
     // into tiles of kDdCap consecutive lookups: workgroup z sorts tile z and leaves the sorted run in the workspace;
-    // dedupe_large_kernel merges the runs and does the rest.
+    // dedupe_merge_kernel merges the runs and dedupe_large_kernel does the rest.
     const bool large = hi - lo > kDdCap;
     const int tile = (int)blockIdx.z;
     if (!large && tile > 0) return;
@@ -435,15 +435,74 @@ __global__ __launch_bounds__(kDdThreads) void dedupe_kernel(DedupeArgs args)
     if (tid < kAbsmaxSlots) *absmax_slot(ws.absmax_slots, t, tid) = 0.0f;
 }
 
+// Step 1 for a table of more than kDdCap lookups, one workgroup per sorted tile (run): every item of the run finds
+// its place in the table's sorted order on its own -- its index in its own run plus, per other run, the number of
+// that run's keys below it (equal keys of earlier runs count as below, which keeps equal keys in lookup order).
+// Each other run in turn is staged in LDS and searched by the run's items, kept in registers, four searches in step
+// (a fixed number of halvings, no branch).
+__global__ __launch_bounds__(kDdThreads) void dedupe_merge_kernel(DedupeArgs args)
+{
+    const DedupeBatch &bt = args.b[blockIdx.y];
+    const int B = args.B;
+    const int64_t N = bt.N;
+    const BwdWs ws = bt.ws;
+    __shared__ unsigned s_run[kDdCap]; // 64 KB: the run that is being searched
+    constexpr int kItems = kDdCap / kDdThreads; // 16 per thread
+    const int t = blockIdx.x, r = blockIdx.z, tid = threadIdx.x;
+    const long long lo = bt.offsets[(long long)t * B], hi = bt.offsets[(long long)(t + 1) * B];
+    if (lo < 0 || hi > N || lo > hi || hi - lo > bt.limit || hi - lo <= kDdCap) return;
+    const int n = (int)(hi - lo), base = (int)lo;
+    const int runs = (n + kDdCap - 1) / kDdCap;
+    if (r >= runs) return;
+    const int len = min(kDdCap, n - r * kDdCap); // my run
+    unsigned key[kItems];
+    int rank[kItems];
+#pragma unroll
+    for (int q = 0; q < kItems; ++q) {
+        const int j = min(q * kDdThreads + tid, len - 1);
+        key[q] = ws.run_key[base + r * kDdCap + j];
+        rank[q] = j;
+    }
+    for (int r2 = 0; r2 < runs; ++r2) {
+        if (r2 == r) continue; // (block-uniform)
+        const int len2 = min(kDdCap, n - r2 * kDdCap);
+        const bool ties_below = r2 < r;
+        __syncthreads(); // (the searches of the run staged before are over)
+        for (int i = tid; i < kDdCap; i += kDdThreads) s_run[i] = i < len2 ? ws.run_key[base + r2 * kDdCap + i] : 0xFFFFFFFFu;
+        __syncthreads();
+#pragma unroll
+        for (int q0 = 0; q0 < kItems; q0 += 4) {
+            int below[4] = {0, 0, 0, 0};
+#pragma unroll 1
+            for (int step = kDdCap; step >= 1; step >>= 1) {
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    const int idx = below[q] + step; // are the first idx keys of the run all below mine?
+                    const unsigned k2 = s_run[min(idx, kDdCap) - 1];
+                    const bool yes = idx <= len2 && (ties_below ? k2 <= key[q0 + q] : k2 < key[q0 + q]);
+                    below[q] = yes ? idx : below[q];
+                }
+            }
+#pragma unroll
+            for (int q = 0; q < 4; ++q) rank[q0 + q] += below[q];
+        }
+    }
+#pragma unroll
+    for (int q = 0; q < kItems; ++q) {
+        const int j = q * kDdThreads + tid;
+        if (j < len) {
+            ws.merged_key[base + rank[q]] = key[q];
+            ws.merged_pos[base + rank[q]] = ws.run_pos[base + r * kDdCap + j];
+        }
+    }
+}
+
 // ---------------------------------------------------------------------------
-// Tables with more than kDdCap lookups: dedupe_kernel has sorted their tiles of kDdCap consecutive lookups; one
-// workgroup per (table, batch) now
-//  1. merges the runs: every item finds its place in the table's sorted order on its own -- its index in its own
-//     run plus, per other run, the number of that run's keys below it (binary searches in LDS; equal keys of
-//     earlier runs count as below, which keeps equal keys in lookup order);
-//  2. walks the merged order in slabs of one item per thread, carrying the counts from slab to slab: segment
+// Tables with more than kDdCap lookups: dedupe_kernel has sorted their tiles of kDdCap consecutive lookups and
+// dedupe_merge_kernel (above) has merged the runs; one workgroup per (table, batch) now
+//  1. walks the merged order in slabs of one item per thread, carrying the counts from slab to slab: segment
 //     heads, segment index and start of every item, the list of the heads;
-//  3. walks it again for the chunk heads and singles (a segment's end is the next segment's head, known now) and
+//  2. walks it again for the chunk heads and singles (a segment's end is the next segment's head, known now) and
 //     writes the same table-local lists and counts as dedupe_kernel does for a small table.
 // Everything between the steps goes through global memory of the workspace, read back by the same workgroup
 // after a barrier.  Slower per lookup than the in-LDS path; it exists so that no table size up to
@@ -457,7 +516,7 @@ __global__ __launch_bounds__(kDdThreads) void dedupe_large_kernel(DedupeArgs arg
     const BwdWs ws = bt.ws;
     __shared__ int s_w[kDdWaves];
     __shared__ int s_w2[kDdWaves];
-    __shared__ unsigned s_run[kDdCap]; // 64 KB: the run that is being searched
+    constexpr int kLgBatch = 4;        // slabs of kDdThreads items whose data is requested together
 
     const int t = blockIdx.x;
     const int tid = threadIdx.x, lane = tid & (kWave - 1), wave = tid / kWave;
@@ -469,132 +528,115 @@ __global__ __launch_bounds__(kDdThreads) void dedupe_large_kernel(DedupeArgs arg
     const int n = (int)(hi - lo), base = (int)lo;
     const int runs = (n + kDdCap - 1) / kDdCap;
 
-    // ---- 1. merge the runs.  Each run in turn is staged in LDS and searched by the items of all other runs, four
-    // searches per thread in step (a fixed number of halvings, no branch); an item's rank is collected in the
-    // workspace (in the list of the segments' heads, which is written only in step 2) by the one thread that owns it.
-    int *rank_of = ws.head_of_seg + base + t;
-    for (int e = tid; e < n; e += kDdThreads) rank_of[e] = e % kDdCap;
-    for (int r2 = 0; r2 < runs; ++r2) {
-        const int len2 = min(kDdCap, n - r2 * kDdCap);
-        __syncthreads(); // (the searches of the previous run are over)
-        for (int i = tid; i < kDdCap; i += kDdThreads) s_run[i] = i < len2 ? ws.run_key[base + r2 * kDdCap + i] : 0xFFFFFFFFu;
-        __syncthreads();
-        for (int e0 = tid; e0 < n; e0 += 4 * kDdThreads) {
-            unsigned key[4];
-            int below[4];
-            bool live[4], ties_below[4];
-#pragma unroll
-            for (int q = 0; q < 4; ++q) {
-                const int e = e0 + q * kDdThreads;
-                const int r = min(e, n - 1) / kDdCap;
-                live[q] = e < n && r != r2;
-                ties_below[q] = r2 < r; // equal keys of an earlier run come first
-                key[q] = ws.run_key[base + min(e, n - 1)];
-                below[q] = 0;
-            }
-#pragma unroll 1
-            for (int step = kDdCap; step >= 1; step >>= 1) {
-#pragma unroll
-                for (int q = 0; q < 4; ++q) {
-                    const int idx = below[q] + step; // are the first idx keys of the run all below mine?
-                    const unsigned k2 = s_run[min(idx, kDdCap) - 1];
-                    const bool yes = idx <= len2 && (ties_below[q] ? k2 <= key[q] : k2 < key[q]);
-                    below[q] = yes ? idx : below[q];
-                }
-            }
-#pragma unroll
-            for (int q = 0; q < 4; ++q)
-                if (live[q]) rank_of[e0 + q * kDdThreads] += below[q];
-        }
-    }
-    for (int e = tid; e < n; e += kDdThreads) {
-        const int rank = rank_of[e];
-        ws.merged_key[base + rank] = ws.run_key[base + e];
-        ws.merged_pos[base + rank] = ws.run_pos[base + e];
-    }
-    __syncthreads(); // the runs are not read again: their arrays now take segment index and start of every item
+    // (the runs are not read again: their arrays now take segment index and start of every item)
 
-    // ---- 2. segment heads, index and start of every item, slab by slab
+    // ---- 1. segment heads, index and start of every item, slab by slab
     int *seg_idx = reinterpret_cast<int *>(ws.run_key) + base, *seg_start = ws.run_pos + base;
     int *head_of = ws.head_of_seg + base + t;
     int carry_heads = 0, carry_start = -1, n_valid = 0;
-    for (int s0 = 0; s0 < n; s0 += kDdThreads) {
-        const int i = s0 + tid;
-        const unsigned k = i < n ? ws.merged_key[base + i] : rows_t;
-        const unsigned prev = (i > 0 && i < n) ? ws.merged_key[base + i - 1] : 0u;
-        const bool valid = i < n && k < rows_t;
-        const bool head = valid && (i == 0 || prev != k);
-        const int h = wave_incl_scan_add(head ? 1 : 0, lane);
-        const int st = wave_incl_scan_max(head ? i : -1, lane);
-        const int nv = __popcll(__ballot(valid));
-        __syncthreads(); // (s_w / s_w2 of the previous slab have been read)
-        if (lane == kWave - 1) {
-            s_w[wave] = h | (nv << 16); // both at most 64
-            s_w2[wave] = st;
-        }
-        __syncthreads();
-        int heads_before = 0, start_before = -1, heads_slab = 0, valid_slab = 0, start_slab = -1;
+    // (kLgBatch slabs are requested together: a slab's work is short, the round trip for its data is not)
+    for (int g0 = 0; g0 < n; g0 += kLgBatch * kDdThreads) {
+        unsigned k_of[kLgBatch], prev_of[kLgBatch];
 #pragma unroll
-        for (int w = 0; w < kDdWaves; ++w) {
-            const int x = s_w[w];
-            if (w < wave) {
-                heads_before += x & 0xFFFF;
-                start_before = max(start_before, s_w2[w]);
+        for (int q = 0; q < kLgBatch; ++q) {
+            const int i = g0 + q * kDdThreads + tid;
+            k_of[q] = i < n ? ws.merged_key[base + i] : rows_t;
+            prev_of[q] = (i > 0 && i < n) ? ws.merged_key[base + i - 1] : 0u;
+        }
+#pragma unroll
+        for (int q = 0; q < kLgBatch; ++q) {
+            const int s0 = g0 + q * kDdThreads;
+            if (s0 >= n) break; // (block-uniform)
+            const int i = s0 + tid;
+            const unsigned k = k_of[q], prev = prev_of[q];
+            const bool valid = i < n && k < rows_t;
+            const bool head = valid && (i == 0 || prev != k);
+            const int h = wave_incl_scan_add(head ? 1 : 0, lane);
+            const int st = wave_incl_scan_max(head ? i : -1, lane);
+            const int nv = __popcll(__ballot(valid));
+            __syncthreads(); // (s_w / s_w2 of the previous slab have been read)
+            if (lane == kWave - 1) {
+                s_w[wave] = h | (nv << 16); // both at most 64
+                s_w2[wave] = st;
             }
-            heads_slab += x & 0xFFFF;
-            valid_slab += x >> 16;
-            start_slab = max(start_slab, s_w2[w]);
+            __syncthreads();
+            int heads_before = 0, start_before = -1, heads_slab = 0, valid_slab = 0, start_slab = -1;
+#pragma unroll
+            for (int w = 0; w < kDdWaves; ++w) {
+                const int x = s_w[w];
+                if (w < wave) {
+                    heads_before += x & 0xFFFF;
+                    start_before = max(start_before, s_w2[w]);
+                }
+                heads_slab += x & 0xFFFF;
+                valid_slab += x >> 16;
+                start_slab = max(start_slab, s_w2[w]);
+            }
+            if (i < n) {
+                seg_idx[i] = valid ? carry_heads + heads_before + h - 1 : -1;
+                seg_start[i] = max(max(carry_start, start_before), st);
+                if (head) head_of[carry_heads + heads_before + h - 1] = i;
+            }
+            carry_heads += heads_slab;
+            carry_start = max(carry_start, start_slab);
+            n_valid += valid_slab;
         }
-        if (i < n) {
-            seg_idx[i] = valid ? carry_heads + heads_before + h - 1 : -1;
-            seg_start[i] = max(max(carry_start, start_before), st);
-            if (head) head_of[carry_heads + heads_before + h - 1] = i;
-        }
-        carry_heads += heads_slab;
-        carry_start = max(carry_start, start_slab);
-        n_valid += valid_slab;
     }
     const int n_uniq = carry_heads;
     if (tid == 0) head_of[n_uniq] = n_valid; // end of the last segment
     __syncthreads();
 
-    // ---- 3. chunk heads and singles, the table-local lists
+    // ---- 2. chunk heads and singles, the table-local lists
     int carry_single = 0, carry_chunk = 0;
-    for (int s0 = 0; s0 < n; s0 += kDdThreads) {
-        const int i = s0 + tid;
-        int seg = -1, start = 0, p = 0, end = 0;
-        unsigned key = 0;
-        if (i < n) {
-            seg = seg_idx[i];
-            start = seg_start[i];
-            p = ws.merged_pos[base + i];
-            key = ws.merged_key[base + i];
+    for (int g0 = 0; g0 < n; g0 += kLgBatch * kDdThreads) {
+        int seg_of[kLgBatch], start_of[kLgBatch], p_of[kLgBatch], end_of[kLgBatch], bag_of[kLgBatch];
+        unsigned key_of[kLgBatch];
+#pragma unroll
+        for (int q = 0; q < kLgBatch; ++q) {
+            const int i = min(g0 + q * kDdThreads + tid, n - 1);
+            seg_of[q] = seg_idx[i];
+            start_of[q] = seg_start[i];
+            p_of[q] = ws.merged_pos[base + i];
+            key_of[q] = ws.merged_key[base + i];
         }
-        const bool valid = seg >= 0;
-        if (valid) end = head_of[seg + 1];
-        const bool chead = valid && ((i - start) % DQRM_SEG_CHUNK) == 0;
-        const bool single = chead && i == start && end == i + 1;
-        int b = 0;
-        if (i < n) {
-            bt.sorted_pos[base + i] = base + p;
-            if (valid) {
-                b = ws.bag_of_pos[base + p];
-                b = b < 0 ? 0 : (b >= B ? B - 1 : b);
-                ws.sorted_bag[base + i] = b;
+#pragma unroll
+        for (int q = 0; q < kLgBatch; ++q) {
+            if (g0 + q * kDdThreads + tid >= n) seg_of[q] = -1;
+            end_of[q] = head_of[max(seg_of[q], 0) + 1]; // (the list has n_uniq + 1 entries; entry 1 exists even if n_uniq = 0)
+            bag_of[q] = ws.bag_of_pos[base + p_of[q]];
+        }
+#pragma unroll
+        for (int q = 0; q < kLgBatch; ++q) {
+            const int s0 = g0 + q * kDdThreads;
+            if (s0 >= n) break; // (block-uniform)
+            const int i = s0 + tid;
+            const int seg = seg_of[q], start = start_of[q], p = p_of[q], end = end_of[q];
+            const unsigned key = key_of[q];
+            const bool valid = seg >= 0;
+            const bool chead = valid && ((i - start) % DQRM_SEG_CHUNK) == 0;
+            const bool single = chead && i == start && end == i + 1;
+            int b = 0;
+            if (i < n) {
+                bt.sorted_pos[base + i] = base + p;
+                if (valid) {
+                    b = bag_of[q];
+                    b = b < 0 ? 0 : (b >= B ? B - 1 : b);
+                    ws.sorted_bag[base + i] = b;
+                }
             }
+            int tot_single, tot_chunk;
+            const int ex_single = block_excl_scan_add<kDdWaves>(single ? 1 : 0, lane, wave, s_w, &tot_single);
+            const int ex_chunk = block_excl_scan_add<kDdWaves>(chead && !single ? 1 : 0, lane, wave, s_w, &tot_chunk);
+            if (chead && !single) {
+                const int nchunks = (end - start + DQRM_SEG_CHUNK - 1) / DQRM_SEG_CHUNK;
+                ws.chunk_local[base + carry_chunk + ex_chunk] = make_chunk_desc(
+                    base + i, min(DQRM_SEG_CHUNK, end - i), (i - start) / DQRM_SEG_CHUNK, nchunks, seg, key);
+                if (i == start && nchunks > 1) ws.seg_count[(base + i) / DQRM_SEG_CHUNK] = 0;
+            }
+            if (single) ws.single_local[base + carry_single + ex_single] = make_int4(base + i, b, seg, (int)key);
+            carry_single += tot_single;
+            carry_chunk += tot_chunk;
         }
-        int tot_single, tot_chunk;
-        const int ex_single = block_excl_scan_add<kDdWaves>(single ? 1 : 0, lane, wave, s_w, &tot_single);
-        const int ex_chunk = block_excl_scan_add<kDdWaves>(chead && !single ? 1 : 0, lane, wave, s_w, &tot_chunk);
-        if (chead && !single) {
-            const int nchunks = (end - start + DQRM_SEG_CHUNK - 1) / DQRM_SEG_CHUNK;
-            ws.chunk_local[base + carry_chunk + ex_chunk] = make_chunk_desc(
-                base + i, min(DQRM_SEG_CHUNK, end - i), (i - start) / DQRM_SEG_CHUNK, nchunks, seg, key);
-            if (i == start && nchunks > 1) ws.seg_count[(base + i) / DQRM_SEG_CHUNK] = 0;
-        }
-        if (single) ws.single_local[base + carry_single + ex_single] = make_int4(base + i, b, seg, (int)key);
-        carry_single += tot_single;
-        carry_chunk += tot_chunk;
     }
     if (tid == 0) {
         ws.table_base[t] = base;

@@ -110,6 +110,19 @@ def test_large_tables(oracle, B, L):
     full_step_parity(oracle, wl, wl.tables(threads=1), idx, off, wl.grad_normal(0), what=f"large{B}x{L}")
 
 
+@pytest.mark.parametrize("D", [8, 24, 32, 40, 48, 56, 72, 96, 136, 200, 256])
+def test_hot_rows_at_every_row_width(oracle, D):
+    """Segments of hundreds of lookups (many chunks, the combine of parked chunk sums) at every lane-group width and at
+    widths that are not a power of two; rows narrower than a wave share the wave in the combine, wider ones loop."""
+    rng = np.random.default_rng(D)
+    cards = np.concatenate([rng.integers(2, 40, size=4), [3000 + D, 250000]]).astype(np.int64)
+    B = int(rng.integers(1200, 2600))
+    wl = Workload(name=f"hot{D}", T=len(cards), D=D, B=B, alpha=1.15, seed=1000 + D, cards=cards)
+    idx, off = wl.batch(0, pooling="ragged", max_len=3)
+    _say(f"hot rows D={D}: batch {B}, {len(idx)} lookups")
+    full_step_parity(oracle, wl, wl.tables(threads=1), idx, off, wl.grad_normal(0), what=f"hot D={D}")
+
+
 def test_hot_segments_long_chunks(oracle):
     """tiny tables: segments of several hundred to several thousand lookups (many chunks per segment,
     the last-arrival combine), next to a table with no duplicates at all."""

@@ -261,6 +261,10 @@ DENSE_CONFIGS = {
     "small8": dict(num_dense=5, bot=[5, 24, 8], top_hidden=[19, 7, 1]),
     # mid-size, awkward widths: reductions of a few slabs with ragged ends, tiles that end past the edge
     "medium": dict(num_dense=7, bot=[7, 200, 96, 24], top_hidden=[136, 72, 1]),
+    # a bottom MLP of a single layer; a first layer whose width is not a multiple of 4; one with a longer input
+    "one_layer": dict(num_dense=9, bot=[9, 16], top_hidden=[33, 1]),
+    "odd_first": dict(num_dense=6, bot=[6, 30, 16], top_hidden=[21, 1]),
+    "long_first": dict(num_dense=20, bot=[20, 44, 16], top_hidden=[40, 12, 1]),
 }
 
 _STREAM_DENSE = 6

@@ -27,7 +27,8 @@ def _gpu_dense_step(dq, torch, T, D, B, model_np, x, emb, y, lr, dev):
 
 
 @pytest.mark.parametrize("cfg,T,D,B", [("small", 3, 16, 37), ("small8", 5, 8, 200), ("medium", 5, 24, 333),
-                                          ("medium", 5, 24, 1000), ("kaggle", 26, 16, 256), ("kaggle", 26, 16, 2048)])
+                                          ("medium", 5, 24, 1000), ("kaggle", 26, 16, 256), ("kaggle", 26, 16, 2048),
+                                          ("one_layer", 4, 16, 130), ("odd_first", 3, 16, 77), ("long_first", 6, 16, 515)])
 def test_dense_step_matches_oracle(oracle, cfg, T, D, B):
     import torch
     import paper_2410_20046_amd as dq

@@ -160,8 +160,10 @@ class HotPath:
 
     def dedupe(self, k, i, stream=None):
         ix, of = self.batch_of(k)
-        self.dq.dqrm_dedupe(self.tables, ix, of, self.B, self.sps[i], self.urs[i], self.sos[i], self.tuos[i], self.nus[i],
-                            self.wss[i], stream=stream)
+        # (one batch through the multi-batch entry point: it takes the bound on a table's lookups)
+        self.dq.dqrm_dedupe_multi(self.tables, self.B, [(ix, of, self.sps[i], self.urs[i], self.sos[i], self.tuos[i],
+                                                         self.nus[i], self.wss[i])], stream=stream,
+                                  max_table_lookups=self.max_table_lookups)
 
     def dedupe_group(self, ks):
         """dqrm_dedupe_multi for the batches `ks` into the buffers k % nbuf."""
@@ -455,7 +457,7 @@ def main():
         while G < D // 4:
             G *= 2
         # which kernel(s) a call launches, and the algorithmic bytes of one launch
-        dd = "dedupe_kernel + " + ("dedupe_merge_kernel + dedupe_large_kernel + " if N > 16384 and (args.overlap != "ahead" or hp.max_table_lookups > 16384) else "") + "dedupe_finish_kernel"
+        dd = "dedupe_kernel + " + ("dedupe_merge_kernel + dedupe_large_kernel + " if N > 16384 and hp.max_table_lookups > 16384 else "") + "dedupe_finish_kernel"
         call_kernels = {
             "fwd": (f"embbag_fwd_kernel<{G},{'packed' if packed_fwd else 'master'}>", ab["fwd"]),
             "segment_sum": (f"segment_sum_kernel<{G}>" + ("" if args.fused else " + absmax_finalize_kernel"), ab["segsum"]),

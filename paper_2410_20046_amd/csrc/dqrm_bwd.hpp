@@ -6,6 +6,9 @@
 //   registers between passes; ranks come from per-wave digit counters and a
 //   wave-wide match of equal digits), marks segment heads and chunk heads,
 //   and writes table-local segment / chunk lists plus the table's counts.
+//   A table of more than kDdCap lookups is sorted in tiles by several workgroups;
+//   dedupe_merge_kernel merges the sorted tiles and dedupe_large_kernel builds the
+//   same lists from the merged order.
 // Kernel 2 (dedupe_finish_kernel): turns the per-table counts into offsets (T is
 //   small, every workgroup repeats the scan), writes the index-only outputs
 //   (unique rows, segment offsets, table offsets, count) and one dense list of
@@ -18,6 +21,7 @@
 //   chunk that arrives last adds the segment's chunk sums in chunk order.  Which
 //   wave that is depends on scheduling; what it computes does not.
 // Kernel 4 (absmax_finalize_kernel): folds the per-table maxima.
+// segment_sum_multi_kernel / absmax_finalize_multi_kernel: kernels 3 and 4 for several batches in one launch.
 #pragma once
 
 #include "dqrm_device.hpp"
@@ -1170,7 +1174,21 @@ __global__ __launch_bounds__(kSumThreads, 4) void segment_sum_multi_kernel(SegMu
 
 // g_absmax[t] = max over the table's slots
 // (and clears them, so that the segment sums may be repeated on the same dedupe)
-__device__ __forceinline__ void absmax_finalize_body(float *__restrict__ slots, int T, float *__restrict__ g_absmax);
+__device__ __forceinline__ void absmax_finalize_body(float *__restrict__ slots, int T, float *__restrict__ g_absmax)
+{
+    const int t = blockIdx.x * blockDim.x + threadIdx.x;
+    if (t >= T) return;
+    float v[kAbsmaxSlots];
+#pragma unroll
+    for (int k = 0; k < kAbsmaxSlots; ++k) v[k] = *absmax_slot(slots, t, k);
+    float m = 0.0f;
+#pragma unroll
+    for (int k = 0; k < kAbsmaxSlots; ++k) {
+        m = fmaxf(m, v[k]);
+        *absmax_slot(slots, t, k) = 0.0f;
+    }
+    g_absmax[t] = m;
+}
 
 __global__ void absmax_finalize_kernel(float *__restrict__ slots, int T, float *__restrict__ g_absmax)
 {
@@ -1186,22 +1204,6 @@ struct AbsmaxMulti {
 __global__ void absmax_finalize_multi_kernel(AbsmaxMulti m)
 {
     if (m.g_absmax[blockIdx.y]) absmax_finalize_body(m.slots[blockIdx.y], m.T, m.g_absmax[blockIdx.y]);
-}
-
-__device__ __forceinline__ void absmax_finalize_body(float *__restrict__ slots, int T, float *__restrict__ g_absmax)
-{
-    const int t = blockIdx.x * blockDim.x + threadIdx.x;
-    if (t >= T) return;
-    float v[kAbsmaxSlots];
-#pragma unroll
-    for (int k = 0; k < kAbsmaxSlots; ++k) v[k] = *absmax_slot(slots, t, k);
-    float m = 0.0f;
-#pragma unroll
-    for (int k = 0; k < kAbsmaxSlots; ++k) {
-        m = fmaxf(m, v[k]);
-        *absmax_slot(slots, t, k) = 0.0f;
-    }
-    g_absmax[t] = m;
 }
 
 } // namespace dqrm

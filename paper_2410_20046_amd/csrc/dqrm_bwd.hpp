@@ -520,7 +520,6 @@ __global__ __launch_bounds__(kDdThreads) void dedupe_large_kernel(DedupeArgs arg
     const BwdWs ws = bt.ws;
     __shared__ int s_w[kDdWaves];
     __shared__ int s_w2[kDdWaves];
-    constexpr int kLgBatch = 4;        // slabs of kDdThreads items whose data is requested together
 
     const int t = blockIdx.x;
     const int tid = threadIdx.x, lane = tid & (kWave - 1), wave = tid / kWave;
@@ -534,34 +533,41 @@ __global__ __launch_bounds__(kDdThreads) void dedupe_large_kernel(DedupeArgs arg
 
     // (the runs are not read again: their arrays now take segment index and start of every item)
 
-    // ---- 1. segment heads, index and start of every item, slab by slab
+    // A slab is kRounds x kDdThreads consecutive items, wave-striped as in dedupe_kernel: wave w owns the slab's items
+    // w * kRounds * 64 ..., item (round r, lane l) = that + r * 64 + l.  A wave carries its counts from round to round by
+    // itself; the waves meet once per slab.
+    // ---- 1. segment heads, index and start of every item
     int *seg_idx = reinterpret_cast<int *>(ws.run_key) + base, *seg_start = ws.run_pos + base;
     int *head_of = ws.head_of_seg + base + t;
     int carry_heads = 0, carry_start = -1, n_valid = 0;
-    // (kLgBatch slabs are requested together: a slab's work is short, the round trip for its data is not)
-    for (int g0 = 0; g0 < n; g0 += kLgBatch * kDdThreads) {
-        unsigned k_of[kLgBatch], prev_of[kLgBatch];
+    {
+        constexpr int kRounds = 8, kSlab = kRounds * kDdThreads, kPerWave = kRounds * kWave;
+        for (int s0 = 0; s0 < n; s0 += kSlab) {
+            unsigned k_of[kRounds], prev_of[kRounds];
 #pragma unroll
-        for (int q = 0; q < kLgBatch; ++q) {
-            const int i = g0 + q * kDdThreads + tid;
-            k_of[q] = i < n ? ws.merged_key[base + i] : rows_t;
-            prev_of[q] = (i > 0 && i < n) ? ws.merged_key[base + i - 1] : 0u;
-        }
+            for (int r = 0; r < kRounds; ++r) {
+                const int i = s0 + wave * kPerWave + r * kWave + lane;
+                k_of[r] = i < n ? ws.merged_key[base + i] : rows_t;
+                prev_of[r] = (i > 0 && i < n) ? ws.merged_key[base + i - 1] : 0u;
+            }
+            int h_of[kRounds], st_of[kRounds];
+            int wave_heads = 0, wave_start = -1, wave_valid = 0;
 #pragma unroll
-        for (int q = 0; q < kLgBatch; ++q) {
-            const int s0 = g0 + q * kDdThreads;
-            if (s0 >= n) break; // (block-uniform)
-            const int i = s0 + tid;
-            const unsigned k = k_of[q], prev = prev_of[q];
-            const bool valid = i < n && k < rows_t;
-            const bool head = valid && (i == 0 || prev != k);
-            const int h = wave_incl_scan_add(head ? 1 : 0, lane);
-            const int st = wave_incl_scan_max(head ? i : -1, lane);
-            const int nv = __popcll(__ballot(valid));
+            for (int r = 0; r < kRounds; ++r) {
+                const int i = s0 + wave * kPerWave + r * kWave + lane;
+                const bool valid = i < n && k_of[r] < rows_t;
+                const bool head = valid && (i == 0 || prev_of[r] != k_of[r]);
+                h_of[r] = wave_incl_scan_add(head ? 1 : 0, lane) + wave_heads; // heads up to here, this wave and slab
+                st_of[r] = max(wave_incl_scan_max(head ? i : -1, lane), wave_start);
+                wave_heads = wave_last(h_of[r]);
+                wave_start = wave_last(st_of[r]);
+                wave_valid += __popcll(__ballot(valid));
+                h_of[r] = head ? h_of[r] : -h_of[r] - 1; // (the sign tells a head; valid or not is read off k_of)
+            }
             __syncthreads(); // (s_w / s_w2 of the previous slab have been read)
-            if (lane == kWave - 1) {
-                s_w[wave] = h | (nv << 16); // both at most 64
-                s_w2[wave] = st;
+            if (lane == 0) {
+                s_w[wave] = wave_heads | (wave_valid << 16); // both at most 512
+                s_w2[wave] = wave_start;
             }
             __syncthreads();
             int heads_before = 0, start_before = -1, heads_slab = 0, valid_slab = 0, start_slab = -1;
@@ -576,10 +582,16 @@ __global__ __launch_bounds__(kDdThreads) void dedupe_large_kernel(DedupeArgs arg
                 valid_slab += x >> 16;
                 start_slab = max(start_slab, s_w2[w]);
             }
-            if (i < n) {
-                seg_idx[i] = valid ? carry_heads + heads_before + h - 1 : -1;
-                seg_start[i] = max(max(carry_start, start_before), st);
-                if (head) head_of[carry_heads + heads_before + h - 1] = i;
+#pragma unroll
+            for (int r = 0; r < kRounds; ++r) {
+                const int i = s0 + wave * kPerWave + r * kWave + lane;
+                if (i < n) {
+                    const bool valid = k_of[r] < rows_t, head = h_of[r] >= 0;
+                    const int h = head ? h_of[r] : -h_of[r] - 1;
+                    seg_idx[i] = valid ? carry_heads + heads_before + h - 1 : -1;
+                    seg_start[i] = max(max(carry_start, start_before), st_of[r]);
+                    if (head) head_of[carry_heads + heads_before + h - 1] = i;
+                }
             }
             carry_heads += heads_slab;
             carry_start = max(carry_start, start_slab);
@@ -592,54 +604,80 @@ __global__ __launch_bounds__(kDdThreads) void dedupe_large_kernel(DedupeArgs arg
 
     // ---- 2. chunk heads and singles, the table-local lists
     int carry_single = 0, carry_chunk = 0;
-    for (int g0 = 0; g0 < n; g0 += kLgBatch * kDdThreads) {
-        int seg_of[kLgBatch], start_of[kLgBatch], p_of[kLgBatch], end_of[kLgBatch], bag_of[kLgBatch];
-        unsigned key_of[kLgBatch];
+    {
+        constexpr int kRounds = 8, kSlab = kRounds * kDdThreads, kPerWave = kRounds * kWave;
+        for (int s0 = 0; s0 < n; s0 += kSlab) {
+            int seg_of[kRounds], start_of[kRounds], p_of[kRounds], end_of[kRounds], bag_of[kRounds];
+            unsigned key_of[kRounds];
 #pragma unroll
-        for (int q = 0; q < kLgBatch; ++q) {
-            const int i = min(g0 + q * kDdThreads + tid, n - 1);
-            seg_of[q] = seg_idx[i];
-            start_of[q] = seg_start[i];
-            p_of[q] = ws.merged_pos[base + i];
-            key_of[q] = ws.merged_key[base + i];
-        }
+            for (int r = 0; r < kRounds; ++r) {
+                const int i = min(s0 + wave * kPerWave + r * kWave + lane, n - 1);
+                seg_of[r] = seg_idx[i];
+                start_of[r] = seg_start[i];
+                p_of[r] = ws.merged_pos[base + i];
+                key_of[r] = ws.merged_key[base + i];
+            }
 #pragma unroll
-        for (int q = 0; q < kLgBatch; ++q) {
-            if (g0 + q * kDdThreads + tid >= n) seg_of[q] = -1;
-            end_of[q] = head_of[max(seg_of[q], 0) + 1]; // (the list has n_uniq + 1 entries; entry 1 exists even if n_uniq = 0)
-            bag_of[q] = ws.bag_of_pos[base + p_of[q]];
-        }
+            for (int r = 0; r < kRounds; ++r) {
+                if (s0 + wave * kPerWave + r * kWave + lane >= n) seg_of[r] = -1;
+                end_of[r] = head_of[max(seg_of[r], 0) + 1]; // (the list's region has that entry even if n_uniq = 0)
+                bag_of[r] = ws.bag_of_pos[base + p_of[r]];
+            }
+            // one scan counts both kinds (bits 0..15: singles, bits 16..31: the other chunk heads; each <= 8192 a slab)
+            int c_of[kRounds];
+            int wave_count = 0;
 #pragma unroll
-        for (int q = 0; q < kLgBatch; ++q) {
-            const int s0 = g0 + q * kDdThreads;
-            if (s0 >= n) break; // (block-uniform)
-            const int i = s0 + tid;
-            const int seg = seg_of[q], start = start_of[q], p = p_of[q], end = end_of[q];
-            const unsigned key = key_of[q];
-            const bool valid = seg >= 0;
-            const bool chead = valid && ((i - start) % DQRM_SEG_CHUNK) == 0;
-            const bool single = chead && i == start && end == i + 1;
-            int b = 0;
-            if (i < n) {
+            for (int r = 0; r < kRounds; ++r) {
+                const int i = s0 + wave * kPerWave + r * kWave + lane;
+                const bool valid = seg_of[r] >= 0;
+                const bool chead = valid && ((i - start_of[r]) % DQRM_SEG_CHUNK) == 0;
+                const bool single = chead && i == start_of[r] && end_of[r] == i + 1;
+                c_of[r] = wave_incl_scan_add(chead ? (single ? 1 : 0x10000) : 0, lane) + wave_count;
+                wave_count = wave_last(c_of[r]);
+                // what the item itself is rides in p_of's spare bits (a position inside the table is below 2^17)
+                p_of[r] |= chead ? (single ? 1 << 30 : 1 << 29) : 0;
+            }
+            __syncthreads(); // (s_w of the previous slab has been read)
+            if (lane == 0) s_w[wave] = wave_count;
+            __syncthreads();
+            int singles_before = 0, chunks_before = 0, singles_slab = 0, chunks_slab = 0;
+#pragma unroll
+            for (int w = 0; w < kDdWaves; ++w) {
+                const int x = s_w[w];
+                if (w < wave) {
+                    singles_before += x & 0xFFFF;
+                    chunks_before += x >> 16;
+                }
+                singles_slab += x & 0xFFFF;
+                chunks_slab += x >> 16;
+            }
+#pragma unroll
+            for (int r = 0; r < kRounds; ++r) {
+                const int i = s0 + wave * kPerWave + r * kWave + lane;
+                if (i >= n) continue;
+                const int seg = seg_of[r], start = start_of[r], end = end_of[r], p = p_of[r] & 0x1FFFFFFF;
+                const bool is_single = (p_of[r] >> 30) & 1, is_chunk = (p_of[r] >> 29) & 1;
                 bt.sorted_pos[base + i] = base + p;
-                if (valid) {
-                    b = bag_of[q];
+                int b = 0;
+                if (seg >= 0) {
+                    b = bag_of[r];
                     b = b < 0 ? 0 : (b >= B ? B - 1 : b);
                     ws.sorted_bag[base + i] = b;
                 }
+                if (is_chunk) {
+                    const int c = carry_chunk + chunks_before + (c_of[r] >> 16) - 1;
+                    const int nchunks = (end - start + DQRM_SEG_CHUNK - 1) / DQRM_SEG_CHUNK;
+                    ws.chunk_local[base + c] = make_chunk_desc(base + i, min(DQRM_SEG_CHUNK, end - i),
+                                                               (i - start) / DQRM_SEG_CHUNK, nchunks, seg, key_of[r]);
+                    if (i == start && nchunks > 1) ws.seg_count[(base + i) / DQRM_SEG_CHUNK] = 0;
+                }
+                if (is_single) {
+                    const int c = carry_single + singles_before + (c_of[r] & 0xFFFF) - 1;
+                    ws.single_local[base + c] = make_int4(base + i, b, seg, (int)key_of[r]);
+                }
             }
-            int tot_single, tot_chunk;
-            const int ex_single = block_excl_scan_add<kDdWaves>(single ? 1 : 0, lane, wave, s_w, &tot_single);
-            const int ex_chunk = block_excl_scan_add<kDdWaves>(chead && !single ? 1 : 0, lane, wave, s_w, &tot_chunk);
-            if (chead && !single) {
-                const int nchunks = (end - start + DQRM_SEG_CHUNK - 1) / DQRM_SEG_CHUNK;
-                ws.chunk_local[base + carry_chunk + ex_chunk] = make_chunk_desc(
-                    base + i, min(DQRM_SEG_CHUNK, end - i), (i - start) / DQRM_SEG_CHUNK, nchunks, seg, key);
-                if (i == start && nchunks > 1) ws.seg_count[(base + i) / DQRM_SEG_CHUNK] = 0;
-            }
-            if (single) ws.single_local[base + carry_single + ex_single] = make_int4(base + i, b, seg, (int)key);
-            carry_single += tot_single;
-            carry_chunk += tot_chunk;
+            carry_single += singles_slab;
+            carry_chunk += chunks_slab;
         }
     }
     if (tid == 0) {
